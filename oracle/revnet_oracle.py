@@ -1,0 +1,342 @@
+"""CPU oracle for the reversible-residual-network hot path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product (the HIP library and its
+Python binding) may import or call this module; only ``tests/``, the smoke
+check and the benchmark's ``cpu_baseline`` leg do.  It shares no code with the
+GPU path.
+
+What it computes, and where the paper defines it:
+
+* ``func_fwd``      -- a residual function built from the units of Section 2.2
+                       (``a(x) = ReLU(BN(x))``, ``c_k(x) = Conv_kxk(a(x))``,
+                       ``Basic = c3(c3(x))``, ``Bottleneck = c1(c3(c1(x)))``),
+                       storing every intermediate.
+* ``func_bwd``      -- ordinary backprop through it (Section 2.1, the backprop
+                       rule), from the stored intermediates.
+* ``block_fwd``     -- the reversible block, Section 3.1:
+                       ``y1 = x1 + F(x2)``, ``y2 = x2 + G(y1)``.
+* ``block_inverse`` -- its inverse, Section 3.1:
+                       ``x2 = y2 - G(y1)``, ``x1 = y1 - F(x2)``.
+* ``block_bwd_stored`` / ``stack_bwd_stored`` -- the gradient *definition*:
+                       forward pass that keeps all activations, then the
+                       backprop rule node by node.  This is what the method
+                       must reproduce (Section 3.2: the algorithm combines the
+                       reconstruction formulas with the backprop rule, so in
+                       exact arithmetic its result is the ordinary gradient).
+* ``block_reverse`` / ``stack_reverse`` -- Algorithm 1 (Section 3.2) in its own
+                       steps and notation, from ``(y, ybar)`` only; used to pin
+                       Algorithm 1 == stored backprop and to report
+                       reconstruction drift versus depth (Section 3.2
+                       "Numerical error", Section 5.2 "Impact of numerical
+                       error").
+
+The layer operations (direct-loop convolution and its two adjoints, two-pass
+batch norm and its unfused chain-rule backward) are plain C in
+``layer_ops_impl.h``; the precision is that of the arrays passed in
+(float64 for reference values, float32 to mimic the paper's setting).
+
+Readings of points the paper leaves open (all stated in the design notes):
+BN uses batch statistics with the biased variance and ``eps`` added inside the
+square root; ReLU'(0) = 0; every unit, including the first of F and G, is
+BN -> ReLU -> conv; convolutions are zero padded by (k-1)/2 with no bias.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle_layer_ops.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C layer operations with gcc (host only)."""
+    src = os.path.join(_HERE, "layer_ops.c")
+    hdr = os.path.join(_HERE, "layer_ops_impl.h")
+    stale = (not os.path.exists(_LIB_PATH)
+             or os.path.getmtime(_LIB_PATH) < max(os.path.getmtime(src), os.path.getmtime(hdr)))
+    if force or stale:
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", src,
+                               "-o", _LIB_PATH, "-lm"])
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def _sfx(dtype) -> str:
+    if dtype == np.float64:
+        return "_f64"
+    if dtype == np.float32:
+        return "_f32"
+    raise TypeError(f"oracle works in float64 or float32, got {dtype}")
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _real(dtype, v):
+    return ctypes.c_double(v) if dtype == np.float64 else ctypes.c_float(v)
+
+
+# ---------------------------------------------------------------------------
+# layer operations (thin ctypes wrappers over the C definitions)
+# ---------------------------------------------------------------------------
+
+# Number of calls of each convolution routine since the last reset; lets a test
+# check the paper's operation count (Section 3.2 "Computational overhead").
+CONV_CALLS = {"fwd": 0, "dgrad": 0, "wgrad": 0}
+
+
+def reset_conv_calls():
+    for k in CONV_CALLS:
+        CONV_CALLS[k] = 0
+
+
+def conv_fwd(a, w, stride=1):
+    dt = a.dtype
+    a, w = _c(a, dt), _c(w, dt)
+    n, c, h, wd = a.shape
+    k, c2, ks, ks2 = w.shape
+    assert c2 == c and ks == ks2
+    pad = (ks - 1) // 2
+    ho = (h + 2 * pad - ks) // stride + 1
+    wo = (wd + 2 * pad - ks) // stride + 1
+    out = np.empty((n, k, ho, wo), dtype=dt)
+    CONV_CALLS["fwd"] += 1
+    getattr(_load(), "orc_conv_fwd" + _sfx(dt))(_p(a), _p(w), _p(out), n, c, k, h, wd, ks, stride)
+    return out
+
+
+def conv_dgrad(dout, w, in_hw, stride=1):
+    dt = dout.dtype
+    dout, w = _c(dout, dt), _c(w, dt)
+    n, k = dout.shape[:2]
+    k2, c, ks, _ = w.shape
+    assert k2 == k
+    h, wd = in_hw
+    da = np.empty((n, c, h, wd), dtype=dt)
+    CONV_CALLS["dgrad"] += 1
+    getattr(_load(), "orc_conv_dgrad" + _sfx(dt))(_p(dout), _p(w), _p(da), n, c, k, h, wd, ks, stride)
+    return da
+
+
+def conv_wgrad(a, dout, ks, stride=1):
+    dt = a.dtype
+    a, dout = _c(a, dt), _c(dout, dt)
+    n, c, h, wd = a.shape
+    k = dout.shape[1]
+    dw = np.empty((k, c, ks, ks), dtype=dt)
+    CONV_CALLS["wgrad"] += 1
+    getattr(_load(), "orc_conv_wgrad" + _sfx(dt))(_p(a), _p(dout), _p(dw), n, c, k, h, wd, ks, stride)
+    return dw
+
+
+def bn_relu_fwd(x, gamma, beta, eps):
+    """a(x) = ReLU(BN(x)); returns a and everything stored backprop needs."""
+    dt = x.dtype
+    x, gamma, beta = _c(x, dt), _c(gamma, dt), _c(beta, dt)
+    n, c, h, w = x.shape
+    mean = np.empty(c, dt)
+    var = np.empty(c, dt)
+    xhat = np.empty_like(x)
+    u = np.empty_like(x)
+    a = np.empty_like(x)
+    getattr(_load(), "orc_bn_relu_fwd" + _sfx(dt))(
+        _p(x), _p(gamma), _p(beta), _real(dt, eps), _p(mean), _p(var), _p(xhat), _p(u), _p(a),
+        n, c, h, w)
+    return a, dict(x=x, mean=mean, var=var, xhat=xhat, u=u, a=a)
+
+
+def bn_relu_bwd(da, st, gamma, eps):
+    dt = da.dtype
+    da, gamma = _c(da, dt), _c(gamma, dt)
+    n, c, h, w = da.shape
+    dx = np.empty_like(da)
+    dgamma = np.empty(c, dt)
+    dbeta = np.empty(c, dt)
+    getattr(_load(), "orc_bn_relu_bwd" + _sfx(dt))(
+        _p(da), _p(st["x"]), _p(gamma), _real(dt, eps), _p(st["mean"]), _p(st["var"]),
+        _p(st["xhat"]), _p(st["u"]), _p(dx), _p(dgamma), _p(dbeta), n, c, h, w)
+    return dx, dgamma, dbeta
+
+
+# ---------------------------------------------------------------------------
+# residual functions F, G (Section 2.2).  `layers` is a list of dicts with
+# keys w [K,C,k,k], gamma [C], beta [C]; Basic has two 3x3 layers, Bottleneck
+# 1x1 / 3x3 / 1x1.  Optional key "stride" (default 1) exists only for the
+# non-reversible subsampling layers.
+# ---------------------------------------------------------------------------
+
+def func_fwd(x, layers, eps=1e-5):
+    """Apply c_k units in sequence; return output and per-layer stored state."""
+    stored = []
+    h = x
+    for L in layers:
+        a, st = bn_relu_fwd(h, L["gamma"], L["beta"], eps)
+        st["in_hw"] = h.shape[2:]
+        h = conv_fwd(a, L["w"], L.get("stride", 1))
+        stored.append(st)
+    return h, stored
+
+
+def func_bwd(stored, layers, dout, eps=1e-5):
+    """Ordinary backprop through a residual function from stored activations.
+
+    Returns (dx, grads) with grads[l] = dict(w=, gamma=, beta=)."""
+    grads = [None] * len(layers)
+    d = dout
+    for l in range(len(layers) - 1, -1, -1):
+        L, st = layers[l], stored[l]
+        ks = L["w"].shape[2]
+        s = L.get("stride", 1)
+        dw = conv_wgrad(st["a"], d, ks, s)
+        da = conv_dgrad(d, L["w"], st["in_hw"], s)
+        d, dg, db = bn_relu_bwd(da, st, L["gamma"], eps)
+        grads[l] = dict(w=dw, gamma=dg, beta=db)
+    return d, grads
+
+
+# ---------------------------------------------------------------------------
+# reversible block (Section 3.1) and stored-activation backprop (Section 2.1)
+# ---------------------------------------------------------------------------
+
+def block_fwd(x1, x2, P, eps=1e-5):
+    """y1 = x1 + F(x2); y2 = x2 + G(y1).  P = dict(F=layers, G=layers)."""
+    f, st_f = func_fwd(x2, P["F"], eps)
+    y1 = x1 + f
+    g, st_g = func_fwd(y1, P["G"], eps)
+    y2 = x2 + g
+    return y1, y2, dict(F=st_f, G=st_g)
+
+
+def block_inverse(y1, y2, P, eps=1e-5):
+    """x2 = y2 - G(y1); x1 = y1 - F(x2)."""
+    g, _ = func_fwd(y1, P["G"], eps)
+    x2 = y2 - g
+    f, _ = func_fwd(x2, P["F"], eps)
+    x1 = y1 - f
+    return x1, x2
+
+
+def block_bwd_stored(stored, P, dy1, dy2, eps=1e-5):
+    """Backprop rule on the forward graph z1 = x1 + F(x2), y2 = x2 + G(z1),
+    y1 = z1, with every activation taken from the stored forward pass.
+
+    z1 has two children (y1 and, through G, y2); x2 has two (y2 directly and,
+    through F, z1); x1 has one (z1)."""
+    g_in, grads_g = func_bwd(stored["G"], P["G"], dy2, eps)
+    dz1 = dy1 + g_in
+    f_in, grads_f = func_bwd(stored["F"], P["F"], dz1, eps)
+    dx2 = dy2 + f_in
+    dx1 = dz1
+    return dx1, dx2, dict(F=grads_f, G=grads_g)
+
+
+def block_reverse(y1, y2, dy1, dy2, P, eps=1e-5):
+    """Algorithm 1 (Section 3.2): from (y, ybar) alone return the inputs,
+    their total derivatives and the parameter derivatives.
+
+    The Jacobian-transpose products are 'ordinary backprop' through F and G
+    evaluated at the *reconstructed* inputs; the activations of the two
+    reconstruction evaluations are the ones reused for it (Section 5.1, last
+    sentence: this gives the 4N cost)."""
+    z1 = y1
+    g, st_g = func_fwd(z1, P["G"], eps)
+    x2 = y2 - g
+    f, st_f = func_fwd(x2, P["F"], eps)
+    x1 = z1 - f
+    vjp_g, grads_g = func_bwd(st_g, P["G"], dy2, eps)
+    dz1 = dy1 + vjp_g
+    vjp_f, grads_f = func_bwd(st_f, P["F"], dz1, eps)
+    dx2 = dy2 + vjp_f
+    dx1 = dz1
+    return (x1, x2), (dx1, dx2), dict(F=grads_f, G=grads_g)
+
+
+# ---------------------------------------------------------------------------
+# stacks of reversible blocks (Section 3.2, "applying Algorithm 1 repeatedly")
+# ---------------------------------------------------------------------------
+
+def stack_fwd(x1, x2, params, eps=1e-5, keep=False):
+    """Apply blocks params[0..D-1] in order.  With keep=True also return the
+    list of every block's input pair and stored state (the memory-hungry
+    ordinary way)."""
+    inputs, stored = [], []
+    for P in params:
+        if keep:
+            inputs.append((x1, x2))
+        x1, x2, st = block_fwd(x1, x2, P, eps)
+        if keep:
+            stored.append(st)
+    if keep:
+        return x1, x2, inputs, stored
+    return x1, x2
+
+
+def stack_bwd_stored(stored, params, dy1, dy2, eps=1e-5):
+    """Ordinary backprop through the stack from stored activations."""
+    grads = [None] * len(params)
+    for k in range(len(params) - 1, -1, -1):
+        dy1, dy2, grads[k] = block_bwd_stored(stored[k], params[k], dy1, dy2, eps)
+    return dy1, dy2, grads
+
+
+def stack_reverse(y1, y2, dy1, dy2, params, eps=1e-5):
+    """Backprop through the stack given only the top activations and their
+    derivatives.  Also returns the reconstructed input pair of every block
+    (index k = input of block k) for the drift-versus-depth report."""
+    grads = [None] * len(params)
+    recon = [None] * len(params)
+    for k in range(len(params) - 1, -1, -1):
+        (y1, y2), (dy1, dy2), grads[k] = block_reverse(y1, y2, dy1, dy2, params[k], eps)
+        recon[k] = (y1, y2)
+    return (y1, y2), (dy1, dy2), grads, recon
+
+
+# ---------------------------------------------------------------------------
+# error measures used by tests and reports
+# ---------------------------------------------------------------------------
+
+def rel_l2(got, ref) -> float:
+    """Per-tensor relative error ||got - ref||_2 / max(||ref||_2, 1e-30), in float64."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.linalg.norm((got - ref).ravel()) / max(np.linalg.norm(ref.ravel()), 1e-30))
+
+
+def angle_deg(g, h) -> float:
+    """Angle in degrees between two gradients (the quantity of the paper's
+    figure on stored versus reconstructed activations, Section 5.2)."""
+    g = np.asarray(g, dtype=np.float64).ravel()
+    h = np.asarray(h, dtype=np.float64).ravel()
+    c = float(np.dot(g, h) / max(np.linalg.norm(g) * np.linalg.norm(h), 1e-300))
+    return float(np.degrees(np.arccos(min(1.0, max(-1.0, c)))))
+
+
+def flatten_grads(grads_per_block):
+    """Concatenate all parameter gradients of a stack into one vector."""
+    parts = []
+    for gb in grads_per_block:
+        for fn in ("F", "G"):
+            for gl in gb[fn]:
+                parts += [np.ravel(gl["w"]), np.ravel(gl["gamma"]), np.ravel(gl["beta"])]
+    return np.concatenate(parts)

@@ -1,0 +1,397 @@
+"""Pins for the CPU oracle: it is checked here against what the paper and the
+mathematics fix, never against itself and never against the GPU path.
+
+Each test names what it pins and the passage that fixes it.  Together they are
+chosen so that a dropped term, a wrong sign, a wrong index or a transposed
+operand anywhere in the oracle fails at least one of them.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small_stack(seed, kind="basic", n=3, c=6, h=5, w=4, depth=1, width=None, affine="random"):
+    x, params, dy = S.draw_stack(seed, kind, n, c, h, w, depth, width, affine)
+    return x, params, dy
+
+
+def split(t):
+    c = t.shape[1] // 2
+    return np.ascontiguousarray(t[:, :c]), np.ascontiguousarray(t[:, c:])
+
+
+# --------------------------------------------------------------------------
+# convolution: brute force, special cases, adjoint identities
+# --------------------------------------------------------------------------
+
+def conv_python_loops(a, w, stride):
+    """The definition written a second, independent way: gather a zero-padded
+    window and take its elementwise product with the filter."""
+    n, c, h, wd = a.shape
+    k, _, ks, _ = w.shape
+    pad = (ks - 1) // 2
+    ap = np.zeros((n, c, h + 2 * pad, wd + 2 * pad))
+    ap[:, :, pad:pad + h, pad:pad + wd] = a
+    ho = (h + 2 * pad - ks) // stride + 1
+    wo = (wd + 2 * pad - ks) // stride + 1
+    out = np.zeros((n, k, ho, wo))
+    for i, kk, p, q in itertools.product(range(n), range(k), range(ho), range(wo)):
+        win = ap[i, :, p * stride:p * stride + ks, q * stride:q * stride + ks]
+        out[i, kk, p, q] = float((win * w[kk]).sum())
+    return out
+
+
+@pytest.mark.parametrize("ks,stride,h,w", [(3, 1, 4, 5), (1, 1, 3, 4), (3, 2, 6, 5), (1, 2, 4, 4), (7, 2, 9, 8)])
+def test_conv_fwd_brute_force_tiny(oracle, ks, stride, h, w):
+    rng = np.random.default_rng(1)
+    a = rng.standard_normal((2, 3, h, w))
+    wt = rng.standard_normal((4, 3, ks, ks))
+    np.testing.assert_allclose(oracle.conv_fwd(a, wt, stride), conv_python_loops(a, wt, stride),
+                               rtol=1e-12, atol=1e-12)
+
+
+def test_conv_1x1_is_a_per_pixel_matrix_product(oracle):
+    rng = np.random.default_rng(2)
+    a = rng.standard_normal((2, 5, 4, 3))
+    wt = rng.standard_normal((7, 5, 1, 1))
+    ref = np.einsum("kc,nchw->nkhw", wt[:, :, 0, 0], a)
+    np.testing.assert_allclose(oracle.conv_fwd(a, wt), ref, rtol=1e-12, atol=1e-12)
+
+
+def test_conv_3x3_centre_tap_identity_and_shifts(oracle):
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((2, 3, 5, 6))
+    for r, s in itertools.product(range(3), range(3)):
+        wt = np.zeros((3, 3, 3, 3))
+        for c in range(3):
+            wt[c, c, r, s] = 1.0
+        out = oracle.conv_fwd(a, wt)
+        # out[p,q] = a[p+r-1, q+s-1] with zero fill
+        ref = np.zeros_like(a)
+        for p, q in itertools.product(range(5), range(6)):
+            ih, iw = p + r - 1, q + s - 1
+            if 0 <= ih < 5 and 0 <= iw < 6:
+                ref[:, :, p, q] = a[:, :, ih, iw]
+        np.testing.assert_array_equal(out, ref)
+
+
+@pytest.mark.parametrize("ks,stride", [(3, 1), (1, 1), (3, 2), (1, 2)])
+def test_conv_adjoint_identities(oracle, ks, stride):
+    """<conv(a,w), g> = <a, dgrad(g,w)> = <w, wgrad(a,g)> (bilinearity)."""
+    rng = np.random.default_rng(4)
+    a = rng.standard_normal((3, 4, 6, 7))
+    wt = rng.standard_normal((5, 4, ks, ks))
+    out = oracle.conv_fwd(a, wt, stride)
+    g = rng.standard_normal(out.shape)
+    lhs = float((out * g).sum())
+    da = oracle.conv_dgrad(g, wt, a.shape[2:], stride)
+    dw = oracle.conv_wgrad(a, g, ks, stride)
+    assert abs(lhs - float((a * da).sum())) < 1e-10 * abs(lhs) + 1e-10
+    assert abs(lhs - float((wt * dw).sum())) < 1e-10 * abs(lhs) + 1e-10
+
+
+def test_conv_matches_library_routine(oracle):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(5)
+    for ks, stride in [(3, 1), (1, 1), (3, 2), (7, 2)]:
+        a = rng.standard_normal((2, 3, 9, 8))
+        wt = rng.standard_normal((4, 3, ks, ks))
+        ta = torch.tensor(a, requires_grad=True)
+        tw = torch.tensor(wt, requires_grad=True)
+        out = torch.nn.functional.conv2d(ta, tw, stride=stride, padding=(ks - 1) // 2)
+        g = rng.standard_normal(tuple(out.shape))
+        out.backward(torch.tensor(g))
+        np.testing.assert_allclose(oracle.conv_fwd(a, wt, stride), out.detach().numpy(), rtol=1e-11, atol=1e-11)
+        np.testing.assert_allclose(oracle.conv_dgrad(g, wt, a.shape[2:], stride), ta.grad.numpy(), rtol=1e-11, atol=1e-11)
+        np.testing.assert_allclose(oracle.conv_wgrad(a, g, ks, stride), tw.grad.numpy(), rtol=1e-11, atol=1e-11)
+
+
+# --------------------------------------------------------------------------
+# batch norm + ReLU: closed forms and invariants
+# --------------------------------------------------------------------------
+
+def test_bn_output_moments_closed_form(oracle):
+    """Before the ReLU each channel has mean beta and variance gamma^2 var/(var+eps)."""
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((4, 3, 5, 6)) * np.array([0.5, 2.0, 7.0])[None, :, None, None] + 3.0
+    gamma = np.array([0.7, 1.3, -0.9])
+    beta = np.array([0.1, -0.2, 0.3])
+    eps = 1e-5
+    a, st = oracle.bn_relu_fwd(x, gamma, beta, eps)
+    u = st["u"]
+    np.testing.assert_allclose(u.mean(axis=(0, 2, 3)), beta, atol=1e-13)
+    var = x.var(axis=(0, 2, 3))  # numpy's default is the biased estimator
+    np.testing.assert_allclose(st["var"], var, rtol=1e-12)
+    np.testing.assert_allclose(u.var(axis=(0, 2, 3)), gamma ** 2 * var / (var + eps), rtol=1e-12)
+    np.testing.assert_array_equal(a, np.maximum(u, 0))
+
+
+def test_bn_backward_orthogonality(oracle):
+    """dx of train-mode BN sums to zero per channel; its inner product with
+    xhat is gamma*rstd*dgamma*eps/(var+eps), i.e. zero up to the eps term
+    (sum xhat^2 = M var/(var+eps), not M)."""
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((4, 3, 5, 6)) + 1.0
+    gamma = rng.uniform(0.5, 1.5, 3)
+    beta = rng.standard_normal(3) * 0.1
+    a, st = oracle.bn_relu_fwd(x, gamma, beta, 1e-5)
+    da = rng.standard_normal(x.shape)
+    dx, dg, db = oracle.bn_relu_bwd(da, st, gamma, 1e-5)
+    assert np.abs(dx.sum(axis=(0, 2, 3))).max() < 1e-12
+    ve = st["var"] + 1e-5
+    closed = gamma / np.sqrt(ve) * dg * 1e-5 / ve
+    np.testing.assert_allclose((dx * st["xhat"]).sum(axis=(0, 2, 3)), closed, rtol=1e-7, atol=1e-13)
+    mask = st["u"] > 0
+    np.testing.assert_allclose(db, (da * mask).sum(axis=(0, 2, 3)), rtol=1e-12)
+    np.testing.assert_allclose(dg, (da * mask * st["xhat"]).sum(axis=(0, 2, 3)), rtol=1e-12)
+
+
+def test_bn_relu_matches_library_routine(oracle):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((5, 4, 3, 6)) * 2 + 0.5
+    gamma = rng.uniform(0.5, 1.5, 4)
+    beta = rng.standard_normal(4) * 0.1
+    tx = torch.tensor(x, requires_grad=True)
+    tg = torch.tensor(gamma, requires_grad=True)
+    tb = torch.tensor(beta, requires_grad=True)
+    ta = torch.relu(torch.nn.functional.batch_norm(tx, None, None, tg, tb, training=True, eps=1e-5))
+    da = rng.standard_normal(x.shape)
+    ta.backward(torch.tensor(da))
+    a, st = oracle.bn_relu_fwd(x, gamma, beta, 1e-5)
+    dx, dg, db = oracle.bn_relu_bwd(da, st, gamma, 1e-5)
+    np.testing.assert_allclose(a, ta.detach().numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dx, tx.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dg, tg.grad.numpy(), rtol=1e-10)
+    np.testing.assert_allclose(db, tb.grad.numpy(), rtol=1e-10)
+
+
+# --------------------------------------------------------------------------
+# reversible block: inversion, Algorithm 1 == stored backprop, trivial F and G
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 2)])
+def test_inversion_exact_up_to_rounding(oracle, kind, width):
+    """Section 3.1: the inverse formulas recover (x1, x2)."""
+    x, params, _ = small_stack(11, kind=kind, width=width, depth=3)
+    x1, x2 = split(x)
+    y1, y2 = oracle.stack_fwd(x1, x2, params)
+    for P in reversed(params):
+        y1, y2 = oracle.block_inverse(y1, y2, P)
+    assert oracle.rel_l2(y1, x1) < 1e-13 and oracle.rel_l2(y2, x2) < 1e-13
+    # float32: error of a few ulp per block, not zero (Section 3.2, numerical error)
+    p32 = S.cast_params(params, np.float32)
+    a1, a2 = x1.astype(np.float32), x2.astype(np.float32)
+    b1, b2 = oracle.stack_fwd(a1, a2, p32)
+    for P in reversed(p32):
+        b1, b2 = oracle.block_inverse(b1, b2, P)
+    assert oracle.rel_l2(b1, a1) < 1e-5 and oracle.rel_l2(b2, a2) < 1e-5
+
+
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 3)])
+def test_algorithm1_equals_stored_backprop(oracle, kind, width):
+    """Section 3.2: Algorithm 1 from (y, ybar) alone gives the ordinary gradient."""
+    x, params, dy = small_stack(12, kind=kind, width=width, depth=3, n=4, c=8, h=6, w=5)
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    y1, y2, inputs, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, dy1, dy2)
+    (r1, r2), (e1, e2), rgrads, recon = oracle.stack_reverse(y1, y2, dy1, dy2, params)
+    assert oracle.rel_l2(r1, x1) < 1e-12 and oracle.rel_l2(r2, x2) < 1e-12
+    assert oracle.rel_l2(e1, dx1) < 1e-10 and oracle.rel_l2(e2, dx2) < 1e-10
+    assert oracle.rel_l2(oracle.flatten_grads(rgrads), oracle.flatten_grads(grads)) < 1e-10
+    for k in range(len(params)):
+        assert oracle.rel_l2(recon[k][0], inputs[k][0]) < 1e-12
+        assert oracle.rel_l2(recon[k][1], inputs[k][1]) < 1e-12
+
+
+def test_trivial_residual_functions(oracle):
+    """Algorithm 1 does not depend on the form of F and G (Section 3.2,
+    'Modularity'): with all filters zero, y = x, xbar = ybar, and the BN
+    parameter gradients vanish."""
+    x, params, dy = small_stack(13, depth=2)
+    for P in params:
+        for fn in ("F", "G"):
+            for L in P[fn]:
+                L["w"][:] = 0
+                L["beta"][:] = np.abs(L["beta"]) + 0.05
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    y1, y2 = oracle.stack_fwd(x1, x2, params)
+    np.testing.assert_array_equal(y1, x1)
+    np.testing.assert_array_equal(y2, x2)
+    (r1, r2), (e1, e2), grads, _ = oracle.stack_reverse(y1, y2, dy1, dy2, params)
+    np.testing.assert_array_equal(e1, dy1)
+    np.testing.assert_array_equal(e2, dy2)
+    # The last unit of F and G sees h = 0, so BN gives u = beta and a = relu(beta),
+    # constant per channel; the centre-tap filter gradient is then
+    # relu(beta_c) * sum(upstream_k) in closed form (upstream = ybar2 for G, zbar1 = ybar1 for F).
+    for gb, P in zip(grads, params):
+        for fn, up in (("F", dy1), ("G", dy2)):
+            for gl in gb[fn]:
+                assert np.all(gl["gamma"] == 0) and np.all(gl["beta"] == 0)
+            closed = np.outer(up.sum(axis=(0, 2, 3)), np.maximum(P[fn][-1]["beta"], 0))
+            np.testing.assert_allclose(gb[fn][-1]["w"][:, :, 1, 1], closed, rtol=1e-12, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# gradients: finite differences and an automatic-differentiation library
+# --------------------------------------------------------------------------
+
+def objective(oracle, x, params, dy):
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    y1, y2 = oracle.stack_fwd(x1, x2, params)
+    return float((y1 * dy1).sum() + (y2 * dy2).sum())
+
+
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 2)])
+def test_gradients_by_central_differences(oracle, kind, width):
+    """Section 2.1: xbar is the total derivative of the cost.  Cost
+    C = <ybar1, y1> + <ybar2, y2>; every input element and a sample of each
+    parameter tensor are checked by central differences in float64."""
+    x, params, dy = small_stack(14, kind=kind, width=width, n=2, c=4, h=4, w=3, depth=2)
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    y1, y2, _, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, dy1, dy2)
+    dx = np.concatenate([dx1, dx2], axis=1)
+    step = 1e-6
+    rng = np.random.default_rng(0)
+
+    def fd(arr, idx):
+        old = arr[idx]
+        arr[idx] = old + step
+        fp = objective(oracle, x, params, dy)
+        arr[idx] = old - step
+        fm = objective(oracle, x, params, dy)
+        arr[idx] = old
+        return (fp - fm) / (2 * step)
+
+    num = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        num[idx] = fd(x, idx)
+    assert oracle.rel_l2(dx, num) < 1e-6
+    for d, P in enumerate(params):
+        for fn in ("F", "G"):
+            for l, L in enumerate(P[fn]):
+                for key in ("w", "gamma", "beta"):
+                    arr = L[key]
+                    g = grads[d][fn][l][key]
+                    for _ in range(4):
+                        idx = tuple(rng.integers(0, s) for s in arr.shape)
+                        n_ = fd(arr, idx)
+                        assert abs(n_ - g[idx]) < 1e-5 * max(1.0, abs(n_)), (d, fn, l, key, idx, n_, g[idx])
+
+
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 3)])
+def test_block_matches_autograd_library(oracle, kind, width):
+    """The stack built from a library's conv2d / batch_norm / relu and
+    differentiated by its autograd (CPU, float64) gives the same outputs and
+    the same gradients for every tensor."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    x, params, dy = small_stack(15, kind=kind, width=width, n=3, c=6, h=5, w=4, depth=2)
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+
+    tx1 = torch.tensor(x1, requires_grad=True)
+    tx2 = torch.tensor(x2, requires_grad=True)
+    tparams = [{fn: [{k: torch.tensor(v, requires_grad=True) for k, v in L.items()} for L in P[fn]]
+                for fn in ("F", "G")} for P in params]
+
+    def tfunc(h, layers):
+        for L in layers:
+            a = torch.relu(F.batch_norm(h, None, None, L["gamma"], L["beta"], training=True, eps=1e-5))
+            h = F.conv2d(a, L["w"], padding=(L["w"].shape[2] - 1) // 2)
+        return h
+
+    a1, a2 = tx1, tx2
+    for P in tparams:
+        b1 = a1 + tfunc(a2, P["F"])
+        b2 = a2 + tfunc(b1, P["G"])
+        a1, a2 = b1, b2
+    ((a1 * torch.tensor(dy1)).sum() + (a2 * torch.tensor(dy2)).sum()).backward()
+
+    y1, y2, _, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, dy1, dy2)
+    assert oracle.rel_l2(y1, a1.detach().numpy()) < 1e-12
+    assert oracle.rel_l2(y2, a2.detach().numpy()) < 1e-12
+    assert oracle.rel_l2(dx1, tx1.grad.numpy()) < 1e-10
+    assert oracle.rel_l2(dx2, tx2.grad.numpy()) < 1e-10
+    for d in range(len(params)):
+        for fn in ("F", "G"):
+            for l in range(len(params[d][fn])):
+                for key in ("w", "gamma", "beta"):
+                    assert oracle.rel_l2(grads[d][fn][l][key], tparams[d][fn][l][key].grad.numpy()) < 1e-9, (d, fn, l, key)
+
+
+def test_invariance_identities(oracle):
+    """F and G start with a BN, so they ignore a per-channel shift of their
+    input: the part of xbar2 that comes through F, and the part of zbar1 that
+    comes through G, sum to zero over each channel.  Filters that feed a BN are
+    scale invariant, so <w, wbar> ~ 0 for every conv but the last of F and G
+    (exact as eps -> 0)."""
+    x, params, dy = small_stack(16, n=4, c=6, h=6, w=5, depth=1)
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    y1, y2, _, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, dy1, dy2)
+    assert np.abs((dx2 - dy2).sum(axis=(0, 2, 3))).max() < 1e-11
+    assert np.abs((dx1 - dy1).sum(axis=(0, 2, 3))).max() < 1e-11
+    for fn in ("F", "G"):
+        w0 = params[0][fn][0]["w"]
+        g0 = grads[0][fn][0]["w"]
+        assert abs(float((w0 * g0).sum())) < 1e-4 * np.linalg.norm(w0) * np.linalg.norm(g0)
+
+
+def test_operation_count_matches_paper(oracle):
+    """Section 3.2 'Computational overhead': 4N for forward + Algorithm 1
+    against 3N for forward + ordinary backprop (N per conv: one forward, one
+    data gradient, one weight gradient each)."""
+    with open(os.path.join(GOLDEN, "cost_model.json")) as f:
+        gold = json.load(f)
+    x, params, dy = small_stack(17, depth=3)
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    n_conv = sum(len(P["F"]) + len(P["G"]) for P in params)
+
+    oracle.reset_conv_calls()
+    y1, y2, _, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    assert sum(oracle.CONV_CALLS.values()) == gold["ordinary_forward"] * n_conv
+    oracle.stack_bwd_stored(stored, params, dy1, dy2)
+    assert sum(oracle.CONV_CALLS.values()) == gold["ordinary_total"] * n_conv
+
+    oracle.reset_conv_calls()
+    y1, y2 = oracle.stack_fwd(x1, x2, params)
+    assert sum(oracle.CONV_CALLS.values()) == gold["reversible_forward"] * n_conv
+    oracle.stack_reverse(y1, y2, dy1, dy2, params)
+    assert sum(oracle.CONV_CALLS.values()) == gold["reversible_total"] * n_conv
+    assert gold["reversible_total"] * 3 == gold["ordinary_total"] * 4   # "roughly 33% more"
+
+
+def test_float32_drift_grows_but_stays_small(oracle):
+    """Section 3.2 'Numerical error' / Section 5.2: in float32 the reconstruction
+    is not exact, the error accumulates with depth, and the gradient from
+    reconstructed activations stays within a small angle of the stored one."""
+    cfg = dict(kind="basic", n=4, c=8, h=8, w=8, depth=6, width=None, affine="random")
+    x, params, dy = S.draw_stack(18, **cfg)
+    p32 = S.cast_params(params, np.float32)
+    x1, x2 = split(x.astype(np.float32))
+    dy1, dy2 = split(dy.astype(np.float32))
+    y1, y2, inputs, stored = oracle.stack_fwd(x1, x2, p32, keep=True)
+    _, _, g_stored = oracle.stack_bwd_stored(stored, p32, dy1, dy2)
+    _, _, g_rec, recon = oracle.stack_reverse(y1, y2, dy1, dy2, p32)
+    drift = [max(oracle.rel_l2(recon[k][0], inputs[k][0]), oracle.rel_l2(recon[k][1], inputs[k][1]))
+             for k in range(len(params))]
+    assert 0 < drift[-1] < 1e-5          # one block from the top: rounding only
+    assert drift[0] < 1e-4               # bottom of the stack
+    assert drift[0] > drift[-1]          # it accumulates
+    assert oracle.angle_deg(oracle.flatten_grads(g_rec), oracle.flatten_grads(g_stored)) < 0.1
