@@ -1,0 +1,232 @@
+/*
+ * revnet.h -- C ABI of the MI355X (gfx950) reversible-residual-block library.
+ *
+ * The library runs the hot path of "The Reversible Residual Network:
+ * Backpropagation Without Storing Activations" (Gomez, Ren, Urtasun, Grosse,
+ * 2017): the forward pass of a reversible block and the backward pass that
+ * reconstructs the block's inputs from its outputs instead of reading stored
+ * activations, for single blocks and for stacks of blocks.
+ *
+ * Conventions common to every entry point
+ * ---------------------------------------
+ * Memory.   Every pointer inside rvn_tensor / rvn_func_params / rvn_func_grads
+ *           and every `ws` pointer is a DEVICE pointer.  The descriptor,
+ *           tensor and parameter structs themselves live in HOST memory and
+ *           are read during the call only.  The caller owns all device
+ *           buffers, including the workspace; the library allocates and frees
+ *           nothing on the device and keeps no state between calls.
+ * Stream.   All work is enqueued on `hip_stream` (a hipStream_t cast to
+ *           void*; NULL = the default stream).  Nothing synchronises with the
+ *           host; buffers must stay valid until the stream has drained.
+ * Tensors.  Residual-stream tensors are fp32, logical shape [n, c, h, w],
+ *           strides in ELEMENTS.  Supported memory layout: sw == 1,
+ *           sh == w, sc >= h*w, sn >= (c-1)*sc + h*w (rows and planes
+ *           contiguous; channel and image strides free).  This lets x1 and
+ *           x2 be the two channel halves of one [N, C, H, W] buffer without a
+ *           copy (Section 3.1: the units are partitioned by channels; x1 is
+ *           channels [0, C/2), x2 is [C/2, C)).  Other strides give
+ *           RVN_ERR_STRIDE.
+ * Params.   conv_w[l] is dense fp32 [c_out][c_in][k][k]; bn_gamma[l],
+ *           bn_beta[l] are fp32 [c_in] (the BN sits in front of conv l).
+ *           Layer shapes follow from the descriptor:
+ *             RVN_BASIC      : (c_half -> c_half, 3x3), (c_half -> c_half, 3x3)
+ *             RVN_BOTTLENECK : (c_half -> width, 1x1), (width -> width, 3x3),
+ *                              (width -> c_half, 1x1)
+ *           (Section 2.2, the equations for a(x), c_k(x), Basic, Bottleneck).
+ *           Unused slots are ignored.
+ * Errors.   Every entry point returns RVN_OK (0) or a negative rvn_status.
+ *           All argument checks happen before the first device call, so a
+ *           rejected call has touched nothing.  revnet_last_error() returns a
+ *           message for the calling thread's most recent failure.
+ * Numerics. Batch normalisation always uses the statistics of the batch at
+ *           hand (biased variance, eps inside the square root) and keeps no
+ *           running averages; ReLU'(0) = 0; convolutions are stride 1
+ *           (Section 3.1: reversible blocks must have stride 1), zero padded
+ *           by (k-1)/2, without bias.  conv_dtype selects the precision of the
+ *           convolution OPERANDS only (activations after BN+ReLU, filters,
+ *           and the upstream gradient where it enters a convolution); sums,
+ *           BN, the residual stream and all gradients are fp32.
+ *           Every kernel is deterministic (no floating-point atomics): the
+ *           recomputation of G(y1) in the backward pass is bit-identical to
+ *           the forward one, so the only reconstruction error is the rounding
+ *           of (x + g) - g (Section 3.2, "Numerical error").
+ */
+#ifndef REVNET_H
+#define REVNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RVN_OK = 0,
+    RVN_ERR_NULL = -1,        /* a required pointer is NULL                       */
+    RVN_ERR_SHAPE = -2,       /* non-positive or inconsistent n/c/h/w/depth/width */
+    RVN_ERR_STRIDE = -3,      /* memory layout outside the supported family       */
+    RVN_ERR_DTYPE = -4,       /* unknown rvn_dtype / rvn_kind                     */
+    RVN_ERR_WORKSPACE = -5,   /* ws is NULL, misaligned (256 B) or too small      */
+    RVN_ERR_ALIAS = -6,       /* buffers overlap in a way the contract forbids    */
+    RVN_ERR_UNSUPPORTED = -7, /* valid request this build cannot run              */
+    RVN_ERR_HIP = -8          /* a HIP runtime call or kernel launch failed       */
+} rvn_status;
+
+typedef enum { RVN_F32 = 0, RVN_BF16 = 1 } rvn_dtype;
+typedef enum { RVN_BASIC = 0, RVN_BOTTLENECK = 1 } rvn_kind;
+
+/* fp32 device tensor, logical NCHW, strides in elements. */
+typedef struct {
+    void *ptr;
+    int64_t n, c, h, w;
+    int64_t sn, sc, sh, sw;
+} rvn_tensor;
+
+typedef struct {
+    rvn_kind kind;
+    int32_t c_half;       /* channels of x1 (= channels of x2)              */
+    int32_t width;        /* bottleneck inner channels; ignored for BASIC   */
+    float bn_eps;         /* > 0                                            */
+    rvn_dtype conv_dtype; /* precision of convolution operands              */
+} rvn_block_desc;
+
+typedef struct {
+    const float *conv_w[3];
+    const float *bn_gamma[3];
+    const float *bn_beta[3];
+} rvn_func_params;
+
+typedef struct {
+    float *d_conv_w[3];
+    float *d_bn_gamma[3];
+    float *d_bn_beta[3];
+} rvn_func_grads;
+
+typedef struct { rvn_func_params F, G; } rvn_block_params;
+typedef struct { rvn_func_grads F, G; } rvn_block_grads;
+
+/* Work a call enqueues, counted by the same driver code that launches it
+ * (the driver is run without touching the device). */
+typedef struct {
+    int64_t kernel_launches;
+    int64_t conv_fwd_calls;   /* convolution forward evaluations            */
+    int64_t conv_dgrad_calls; /* data-gradient evaluations                  */
+    int64_t conv_wgrad_calls; /* filter-gradient evaluations                */
+    double conv_flops;        /* 2 * multiply-adds of the three above       */
+    double algorithmic_bytes; /* sum over launches of bytes each must move  */
+} rvn_cost;
+
+/*
+ * Workspace sizes, in bytes, for blocks of this descriptor on [n, c_half, h, w]
+ * halves.  fwd_bytes serves revnet_block_fwd / revnet_stack_fwd, bwd_bytes
+ * serves revnet_block_bwd_reconstruct / revnet_stack_bwd.  Neither depends on
+ * the depth of a stack: only one residual function's internals are alive at a
+ * time (Section 3.2: activation storage independent of depth).  Either output
+ * pointer may be NULL.
+ */
+int revnet_workspace_bytes(const rvn_block_desc *desc, int64_t n, int64_t h, int64_t w,
+                           size_t *fwd_bytes, size_t *bwd_bytes);
+
+/*
+ * Reversible block, forward (Section 3.1, the forward coupling equations):
+ *     y1 = x1 + F(x2)
+ *     y2 = x2 + G(y1)
+ * x1, x2: inputs [n, c_half, h, w] (read).  y1, y2: outputs, same shape
+ * (written).  y1 may be the same tensor as x1 and y2 the same as x2 (same ptr
+ * and strides: in-place update); any other overlap among the four, or with
+ * the workspace, is RVN_ERR_ALIAS.  ws: >= fwd_bytes, 256-byte aligned.
+ */
+int revnet_block_fwd(const rvn_block_desc *desc,
+                     const rvn_tensor *x1, const rvn_tensor *x2,
+                     const rvn_block_params *params,
+                     const rvn_tensor *y1, const rvn_tensor *y2,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Reversible block, backward without stored activations (Section 3.2,
+ * Algorithm 1).  Given the block's outputs (y1, y2) and their total
+ * derivatives (dy1, dy2) it computes
+ *     z1  = y1
+ *     x2  = y2 - G(z1)                      (reconstruction)
+ *     x1  = z1 - F(x2)                      (reconstruction)
+ *     dz1 = dy1 + (dG/dz1)^T dy2
+ *     dx2 = dy2 + (dF/dx2)^T dz1
+ *     dx1 = dz1
+ *     dwF = (dF/dwF)^T dz1,   dwG = (dG/dwG)^T dy2
+ * where F and G are evaluated once each and the activations of those
+ * evaluations are the ones back-propagated through (Section 5.1: reusing the
+ * reconstruction activations gives the 4N total cost of Section 3.2).  The
+ * steps are interleaved as G: recompute, reconstruct x2, backprop; then F:
+ * recompute, reconstruct x1, backprop -- the same data flow, with only one
+ * function's internals alive at a time.
+ * y1, y2, dy1, dy2: read.  x1, x2, dx1, dx2: written.  x_i may be the same
+ * tensor as y_i and dx_i the same as dy_i (in place); any other overlap is
+ * RVN_ERR_ALIAS.  grads: every pointer of the layers the descriptor uses must
+ * be non-NULL; each is overwritten, or added to when accumulate_wgrads != 0
+ * (weight sharing across blocks, Section 3.2 footnote on Algorithm 1).
+ * ws: >= bwd_bytes, 256-byte aligned.
+ */
+int revnet_block_bwd_reconstruct(const rvn_block_desc *desc,
+                                 const rvn_tensor *y1, const rvn_tensor *y2,
+                                 const rvn_tensor *dy1, const rvn_tensor *dy2,
+                                 const rvn_block_params *params,
+                                 const rvn_tensor *x1, const rvn_tensor *x2,
+                                 const rvn_tensor *dx1, const rvn_tensor *dx2,
+                                 const rvn_block_grads *grads, int accumulate_wgrads,
+                                 void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Stack of `depth` reversible blocks of one descriptor, forward (Section 3.2,
+ * the paragraph on sequences of blocks): block k maps its input pair to its
+ * output pair with params[k], k = 0 .. depth-1; only the top pair (y1, y2) is
+ * produced, no per-block activation is kept.  params: host array [depth].
+ * Aliasing as in revnet_block_fwd (block 0 reads x and writes y; later blocks
+ * update y in place).
+ */
+int revnet_stack_fwd(const rvn_block_desc *desc, int32_t depth,
+                     const rvn_tensor *x1, const rvn_tensor *x2,
+                     const rvn_block_params *params,
+                     const rvn_tensor *y1, const rvn_tensor *y2,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Stack backward (Section 3.2: Algorithm 1 applied repeatedly, given only the
+ * top activations and their derivatives), k = depth-1 .. 0.  Writes the
+ * reconstructed stack input (x1, x2), its derivatives (dx1, dx2) and the
+ * parameter gradients of every block (grads: host array [depth]).  Block
+ * depth-1 reads (y, dy) and writes (x, dx); lower blocks update (x, dx) in
+ * place.  Aliasing as in revnet_block_bwd_reconstruct.  With
+ * accumulate_wgrads != 0 two blocks may share gradient buffers.
+ */
+int revnet_stack_bwd(const rvn_block_desc *desc, int32_t depth,
+                     const rvn_tensor *y1, const rvn_tensor *y2,
+                     const rvn_tensor *dy1, const rvn_tensor *dy2,
+                     const rvn_block_params *params,
+                     const rvn_tensor *x1, const rvn_tensor *x2,
+                     const rvn_tensor *dx1, const rvn_tensor *dx2,
+                     const rvn_block_grads *grads, int accumulate_wgrads,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * What revnet_stack_fwd (fwd) and revnet_stack_bwd (bwd) would enqueue for
+ * this descriptor, depth and half-tensor shape, without touching the device.
+ * Lets a caller check the paper's operation count (Section 3.2,
+ * "Computational overhead": forward N, reversible backward 3N) and gives the
+ * flop and byte totals for roofline reports.  Either output may be NULL.
+ */
+int revnet_stack_cost(const rvn_block_desc *desc, int32_t depth,
+                      int64_t n, int64_t h, int64_t w,
+                      rvn_cost *fwd, rvn_cost *bwd);
+
+/* Message for the calling thread's most recent failing call ("" if none).
+ * The storage is thread local and valid until that thread's next call. */
+const char *revnet_last_error(void);
+
+/* ABI version: major * 1000 + minor. */
+int revnet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REVNET_H */

@@ -111,9 +111,50 @@ def reset_conv_calls():
         CONV_CALLS[k] = 0
 
 
+# Precision of the convolution OPERANDS.  The paper works in float32
+# throughout (Section 3.2 "Numerical error"); the GPU library can also feed its
+# matrix units bf16 operands with fp32 sums.  Rounding an operand moves some
+# pre-activations across zero, and the ReLU derivative is a 0/1 decision, so a
+# comparison with such a path is only meaningful if the oracle takes those
+# decisions from equally rounded convolutions.  With "bf16" every convolution
+# routine rounds both of its inputs to bfloat16 (nearest, ties to even) and
+# otherwise computes as before, in the arrays' precision.
+_OPERANDS = "exact"
+
+
+class conv_operands:
+    """Context manager: ``with conv_operands("bf16"): ...``"""
+
+    def __init__(self, mode):
+        assert mode in ("exact", "f32", "bf16")
+        self.mode = "exact" if mode == "f32" else mode
+
+    def __enter__(self):
+        global _OPERANDS
+        self.prev, _OPERANDS = _OPERANDS, self.mode
+
+    def __exit__(self, *exc):
+        global _OPERANDS
+        _OPERANDS = self.prev
+
+
+def bf16_round(a):
+    """Round to the nearest bfloat16 (8 significant bits), ties to even, and
+    return in the input's dtype.  Finite inputs only."""
+    a = np.asarray(a)
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(a.dtype)
+
+
+def _operand(a):
+    return bf16_round(a) if _OPERANDS == "bf16" else a
+
+
 def conv_fwd(a, w, stride=1):
     dt = a.dtype
-    a, w = _c(a, dt), _c(w, dt)
+    a, w = _c(_operand(a), dt), _c(_operand(w), dt)
     n, c, h, wd = a.shape
     k, c2, ks, ks2 = w.shape
     assert c2 == c and ks == ks2
@@ -128,7 +169,7 @@ def conv_fwd(a, w, stride=1):
 
 def conv_dgrad(dout, w, in_hw, stride=1):
     dt = dout.dtype
-    dout, w = _c(dout, dt), _c(w, dt)
+    dout, w = _c(_operand(dout), dt), _c(_operand(w), dt)
     n, k = dout.shape[:2]
     k2, c, ks, _ = w.shape
     assert k2 == k
@@ -141,7 +182,7 @@ def conv_dgrad(dout, w, in_hw, stride=1):
 
 def conv_wgrad(a, dout, ks, stride=1):
     dt = a.dtype
-    a, dout = _c(a, dt), _c(dout, dt)
+    a, dout = _c(_operand(a), dt), _c(_operand(dout), dt)
     n, c, h, wd = a.shape
     k = dout.shape[1]
     dw = np.empty((k, c, ks, ks), dtype=dt)

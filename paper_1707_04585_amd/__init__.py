@@ -1,0 +1,10 @@
+"""MI355X-native reversible residual block library (thin Python binding).
+
+All computation happens in the HIP library ``librevnet_hip.so`` behind the C
+ABI of ``include/revnet.h``; this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    BASIC, BOTTLENECK, BF16, F32, BlockDesc, RevnetError, lib_path, load_library, pack_grads,
+    pack_params, revnet_block_bwd_reconstruct, revnet_block_fwd, revnet_last_error,
+    revnet_stack_bwd, revnet_stack_cost, revnet_stack_fwd, revnet_version, revnet_workspace_bytes,
+)

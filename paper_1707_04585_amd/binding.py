@@ -1,0 +1,223 @@
+"""ctypes binding of ``include/revnet.h``: argument marshalling only.
+
+Tensors may be any object with ``data_ptr()``, ``shape`` and ``stride()``
+(torch CUDA tensors in practice: PyTorch is used for device memory and streams,
+nothing else).  Parameter and gradient sets are passed as
+``{"F": [layer, ...], "G": [layer, ...]}`` with ``layer = {"w": t, "gamma": t,
+"beta": t}``.  Every function has the name and argument order of the C entry
+point it calls and raises ``RevnetError`` on a negative status.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+F32, BF16 = 0, 1
+BASIC, BOTTLENECK = 0, 1
+
+EXPORTS = [
+    "revnet_workspace_bytes", "revnet_block_fwd", "revnet_block_bwd_reconstruct", "revnet_stack_fwd",
+    "revnet_stack_bwd", "revnet_stack_cost", "revnet_last_error", "revnet_version",
+]
+
+
+class RevnetError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"revnet status {status}: {message}")
+        self.status = status
+
+
+class rvn_tensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p)] + [(k, C.c_int64) for k in ("n", "c", "h", "w", "sn", "sc", "sh", "sw")]
+
+
+class rvn_block_desc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("c_half", C.c_int32), ("width", C.c_int32), ("bn_eps", C.c_float),
+                ("conv_dtype", C.c_int)]
+
+
+class rvn_func_ptrs(C.Structure):  # layout shared by rvn_func_params and rvn_func_grads
+    _fields_ = [("conv_w", C.c_void_p * 3), ("bn_gamma", C.c_void_p * 3), ("bn_beta", C.c_void_p * 3)]
+
+
+class rvn_block_ptrs(C.Structure):  # rvn_block_params / rvn_block_grads
+    _fields_ = [("F", rvn_func_ptrs), ("G", rvn_func_ptrs)]
+
+
+class rvn_cost(C.Structure):
+    _fields_ = [("kernel_launches", C.c_int64), ("conv_fwd_calls", C.c_int64), ("conv_dgrad_calls", C.c_int64),
+                ("conv_wgrad_calls", C.c_int64), ("conv_flops", C.c_double), ("algorithmic_bytes", C.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "librevnet_hip.so")
+
+
+def load_library():
+    """Load the HIP library; there is no fallback if it has not been built."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_1707_04585_amd.build` "
+                               "(there is no CPU or PyTorch fallback)")
+        lib = C.CDLL(path)
+        lib.revnet_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(lib, name)  # fail early if an entry point is missing
+        _LIB = lib
+    return _LIB
+
+
+class BlockDesc:
+    def __init__(self, kind, c_half, width=0, bn_eps=1e-5, conv_dtype=F32):
+        self.kind = {"basic": BASIC, "bottleneck": BOTTLENECK}.get(kind, kind)
+        self.conv_dtype = {"f32": F32, "bf16": BF16}.get(conv_dtype, conv_dtype)
+        self.c_half, self.width, self.bn_eps = int(c_half), int(width or 0), float(bn_eps)
+
+    def c(self):
+        return rvn_block_desc(self.kind, self.c_half, self.width, self.bn_eps, self.conv_dtype)
+
+    def num_layers(self):
+        return 2 if self.kind == BASIC else 3
+
+
+def _desc(d):
+    return d.c() if isinstance(d, BlockDesc) else d
+
+
+def _tensor(t):
+    if isinstance(t, rvn_tensor):
+        return t
+    n, c, h, w = (int(v) for v in t.shape)
+    sn, sc, sh, sw = (int(v) for v in t.stride())
+    return rvn_tensor(t.data_ptr(), n, c, h, w, sn, sc, sh, sw)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "is_contiguous") and not t.is_contiguous():
+        raise ValueError("parameter tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _pack(block) -> rvn_block_ptrs:
+    out = rvn_block_ptrs()
+    for name in ("F", "G"):
+        f = getattr(out, name)
+        for l, layer in enumerate(block[name]):
+            f.conv_w[l] = _ptr(layer["w"])
+            f.bn_gamma[l] = _ptr(layer["gamma"])
+            f.bn_beta[l] = _ptr(layer["beta"])
+    return out
+
+
+def pack_params(blocks):
+    """[{F: [...], G: [...]}, ...] -> C array of rvn_block_params (host memory)."""
+    if isinstance(blocks, C.Array):
+        return blocks
+    arr = (rvn_block_ptrs * len(blocks))()
+    for k, b in enumerate(blocks):
+        arr[k] = _pack(b)
+    return arr
+
+
+pack_grads = pack_params
+
+
+def _stream(stream):
+    if stream is None:
+        return None
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    if isinstance(ws, tuple):
+        return ws
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _check(rc):
+    if rc != 0:
+        raise RevnetError(rc, revnet_last_error())
+
+
+def revnet_last_error() -> str:
+    return load_library().revnet_last_error().decode()
+
+
+def revnet_version() -> int:
+    return int(load_library().revnet_version())
+
+
+def revnet_workspace_bytes(desc, n, h, w):
+    fwd, bwd = C.c_size_t(0), C.c_size_t(0)
+    d = _desc(desc)
+    _check(load_library().revnet_workspace_bytes(C.byref(d), C.c_int64(n), C.c_int64(h), C.c_int64(w),
+                                                 C.byref(fwd), C.byref(bwd)))
+    return int(fwd.value), int(bwd.value)
+
+
+def revnet_block_fwd(desc, x1, x2, params, y1, y2, ws, stream=None):
+    d = _desc(desc)
+    p = pack_params([params] if isinstance(params, dict) else params)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (x1, x2, y1, y2)]
+    _check(load_library().revnet_block_fwd(C.byref(d), C.byref(t[0]), C.byref(t[1]), p, C.byref(t[2]),
+                                           C.byref(t[3]), C.c_void_p(wp), C.c_size_t(wb),
+                                           C.c_void_p(_stream(stream))))
+
+
+def revnet_block_bwd_reconstruct(desc, y1, y2, dy1, dy2, params, x1, x2, dx1, dx2, grads,
+                                 accumulate_wgrads, ws, stream=None):
+    d = _desc(desc)
+    p = pack_params([params] if isinstance(params, dict) else params)
+    g = pack_grads([grads] if isinstance(grads, dict) else grads)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (y1, y2, dy1, dy2, x1, x2, dx1, dx2)]
+    _check(load_library().revnet_block_bwd_reconstruct(
+        C.byref(d), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]), C.byref(t[3]), p, C.byref(t[4]),
+        C.byref(t[5]), C.byref(t[6]), C.byref(t[7]), g, C.c_int(int(accumulate_wgrads)), C.c_void_p(wp),
+        C.c_size_t(wb), C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_fwd(desc, depth, x1, x2, params, y1, y2, ws, stream=None):
+    d = _desc(desc)
+    p = pack_params(params)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (x1, x2, y1, y2)]
+    _check(load_library().revnet_stack_fwd(C.byref(d), C.c_int32(depth), C.byref(t[0]), C.byref(t[1]), p,
+                                           C.byref(t[2]), C.byref(t[3]), C.c_void_p(wp), C.c_size_t(wb),
+                                           C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_bwd(desc, depth, y1, y2, dy1, dy2, params, x1, x2, dx1, dx2, grads, accumulate_wgrads,
+                     ws, stream=None):
+    d = _desc(desc)
+    p = pack_params(params)
+    g = pack_grads(grads)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (y1, y2, dy1, dy2, x1, x2, dx1, dx2)]
+    _check(load_library().revnet_stack_bwd(
+        C.byref(d), C.c_int32(depth), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]), C.byref(t[3]), p,
+        C.byref(t[4]), C.byref(t[5]), C.byref(t[6]), C.byref(t[7]), g, C.c_int(int(accumulate_wgrads)),
+        C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_cost(desc, depth, n, h, w):
+    d = _desc(desc)
+    fwd, bwd = rvn_cost(), rvn_cost()
+    _check(load_library().revnet_stack_cost(C.byref(d), C.c_int32(depth), C.c_int64(n), C.c_int64(h),
+                                            C.c_int64(w), C.byref(fwd), C.byref(bwd)))
+    return fwd.as_dict(), bwd.as_dict()

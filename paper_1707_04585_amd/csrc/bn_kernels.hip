@@ -1,0 +1,368 @@
+// Train-mode batch normalisation + ReLU, forward and backward, for gfx950.
+//
+// a(x) = ReLU(BN(x)) is the first half of every unit c_k(x) = Conv(a(x)) of
+// the residual functions (Section 2.2).  All kernels here are bound by HBM
+// bandwidth: each streams whole [n][c][h*w] tensors once with 16-byte
+// accesses, reduces per channel with wavefront shuffles and LDS, and leaves
+// the cross-workgroup part of every reduction to a small second kernel that
+// merges the partial results in a fixed order (no floating-point atomics, so
+// results are bitwise reproducible -- the reconstruction of Section 3.2
+// relies on recomputing exactly what the forward pass computed).
+#include "kernels.h"
+
+namespace rvn {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// Sum NV values over the 256 threads of a workgroup; result in thread 0.
+template <int NV>
+__device__ __forceinline__ void block_sum(float (&v)[NV], float *lds) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = wave_sum(v[i]);
+    if (lane == 0) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) lds[wave * NV + i] = v[i];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            v[i] = (lds[i] + lds[NV + i]) + (lds[2 * NV + i] + lds[3 * NV + i]);
+    }
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---------------------------------------------------------------------------
+// statistics: per (channel, image group) shifted sums -> (count, mean, M2)
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_stats_partial_k(const float *__restrict__ x,
+                                                               int64_t sn, int64_t sc, int N,
+                                                               int HW, int ipw,
+                                                               float *__restrict__ partial) {
+    __shared__ float lds[8];
+    const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x;
+    const int n0 = s * ipw, n1 = min(N, n0 + ipw);
+    const float *base = x + (int64_t)ch * sc;
+    // Shift by a value from the data so that the sum of squares does not
+    // cancel when |mean| >> std (the residual stream grows with depth).
+    const float pivot = base[(int64_t)n0 * sn];
+    float acc[2] = {0.f, 0.f};
+    for (int n = n0; n < n1; ++n) {
+        const float *pl = base + (int64_t)n * sn;
+        if (VEC) {
+            const float4 *pl4 = reinterpret_cast<const float4 *>(pl);
+            for (int i = threadIdx.x; i < HW / 4; i += kThreads) {
+                const float4 v = pl4[i];
+                const float a = v.x - pivot, b = v.y - pivot, c = v.z - pivot, d = v.w - pivot;
+                acc[0] += (a + b) + (c + d);
+                acc[1] += (a * a + b * b) + (c * c + d * d);
+            }
+        } else {
+            for (int i = threadIdx.x; i < HW; i += kThreads) {
+                const float d = pl[i] - pivot;
+                acc[0] += d;
+                acc[1] += d * d;
+            }
+        }
+    }
+    block_sum<2>(acc, lds);
+    if (threadIdx.x == 0) {
+        const float cnt = (float)((n1 - n0) * HW);
+        float *o = partial + ((int64_t)ch * S + s) * 3;
+        o[0] = cnt;
+        o[1] = pivot + acc[0] / cnt;
+        o[2] = fmaxf(acc[1] - acc[0] * acc[0] / cnt, 0.f);
+    }
+}
+
+// Merge the S partials of each channel pairwise-in-order (Chan et al.) in
+// double precision; one thread per channel.
+__global__ void bn_stats_finalize_k(const float *__restrict__ partial, int C, int S, float eps,
+                                    float *__restrict__ mean_rstd) {
+    const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+    if (ch >= C) return;
+    const float *p = partial + (int64_t)ch * S * 3;
+    double n = p[0], mean = p[1], m2 = p[2];
+    for (int s = 1; s < S; ++s) {
+        const double nb = p[s * 3], mb = p[s * 3 + 1], m2b = p[s * 3 + 2];
+        const double tot = n + nb, delta = mb - mean;
+        mean += delta * nb / tot;
+        m2 += m2b + delta * delta * n * nb / tot;
+        n = tot;
+    }
+    mean_rstd[ch] = (float)mean;
+    mean_rstd[C + ch] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+}
+
+// ---------------------------------------------------------------------------
+// forward apply
+// ---------------------------------------------------------------------------
+template <bool VEC, bool BF16>
+__global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restrict__ x, int64_t sn,
+                                                          int64_t sc, int C, int HW,
+                                                          int64_t total /* work items */,
+                                                          const float *__restrict__ gamma,
+                                                          const float *__restrict__ beta,
+                                                          const float *__restrict__ mean_rstd,
+                                                          void *__restrict__ out) {
+    constexpr int E = VEC ? 4 : 1;
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= total) return;
+    const int per_plane = HW / E;
+    const int64_t plane = v / per_plane;
+    const int i = (int)(v - plane * per_plane) * E;
+    const int n = (int)(plane / C), ch = (int)(plane - (int64_t)n * C);
+    const float scale = gamma[ch] * mean_rstd[C + ch];
+    const float shift = fmaf(-mean_rstd[ch], scale, beta[ch]);
+    const float *src = x + (int64_t)n * sn + (int64_t)ch * sc + i;
+    const int64_t dst = plane * HW + i;
+    if (VEC) {
+        const float4 q = *reinterpret_cast<const float4 *>(src);
+        float4 r;
+        r.x = fmaxf(fmaf(q.x, scale, shift), 0.f);
+        r.y = fmaxf(fmaf(q.y, scale, shift), 0.f);
+        r.z = fmaxf(fmaf(q.z, scale, shift), 0.f);
+        r.w = fmaxf(fmaf(q.w, scale, shift), 0.f);
+        if (BF16) {
+            uint2 pk;
+            pk.x = (uint32_t)f32_to_bf16_rne(r.x) | ((uint32_t)f32_to_bf16_rne(r.y) << 16);
+            pk.y = (uint32_t)f32_to_bf16_rne(r.z) | ((uint32_t)f32_to_bf16_rne(r.w) << 16);
+            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(out) + dst) = pk;
+        } else {
+            *reinterpret_cast<float4 *>(static_cast<float *>(out) + dst) = r;
+        }
+    } else {
+        const float r = fmaxf(fmaf(*src, scale, shift), 0.f);
+        if (BF16)
+            static_cast<uint16_t *>(out)[dst] = f32_to_bf16_rne(r);
+        else
+            static_cast<float *>(out)[dst] = r;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// backward: per-channel sums of dy and dy*xhat, dy = da * [u > 0]
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *__restrict__ da, int N, int C,
+    int HW, int ipw, const float *__restrict__ gamma, const float *__restrict__ beta,
+    const float *__restrict__ mean_rstd, float *__restrict__ partial) {
+    __shared__ float lds[8];
+    const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x;
+    const int n0 = s * ipw, n1 = min(N, n0 + ipw);
+    const float mean = mean_rstd[ch], rstd = mean_rstd[C + ch];
+    const float scale = gamma[ch] * rstd;
+    const float shift = fmaf(-mean, scale, beta[ch]);
+    float acc[2] = {0.f, 0.f};
+    for (int n = n0; n < n1; ++n) {
+        const float *px = x + (int64_t)n * sn + (int64_t)ch * sc;
+        const float *pd = da + ((int64_t)n * C + ch) * HW;
+        if (VEC) {
+            for (int i = threadIdx.x; i < HW / 4; i += kThreads) {
+                const float4 xv = reinterpret_cast<const float4 *>(px)[i];
+                const float4 dv = reinterpret_cast<const float4 *>(pd)[i];
+                const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+                const float ds[4] = {dv.x, dv.y, dv.z, dv.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float dy = fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
+                    acc[0] += dy;
+                    acc[1] += dy * ((xs[j] - mean) * rstd);
+                }
+            }
+        } else {
+            for (int i = threadIdx.x; i < HW; i += kThreads) {
+                const float xv = px[i];
+                const float dy = fmaf(xv, scale, shift) > 0.f ? pd[i] : 0.f;
+                acc[0] += dy;
+                acc[1] += dy * ((xv - mean) * rstd);
+            }
+        }
+    }
+    block_sum<2>(acc, lds);
+    if (threadIdx.x == 0) {
+        float *o = partial + ((int64_t)ch * S + s) * 2;
+        o[0] = acc[0];
+        o[1] = acc[1];
+    }
+}
+
+// dbeta = sum dy, dgamma = sum dy*xhat; also the two per-channel means the
+// apply pass needs (kept apart from dgamma/dbeta, which may be accumulated).
+__global__ void bn_bwd_finalize_k(const float *__restrict__ partial, int C, int S, double inv_m,
+                                  float *__restrict__ dgamma, float *__restrict__ dbeta,
+                                  int accumulate, float *__restrict__ coef) {
+    const int ch = blockIdx.x * blockDim.x + threadIdx.x;
+    if (ch >= C) return;
+    const float *p = partial + (int64_t)ch * S * 2;
+    double sb = 0.0, sg = 0.0;
+    for (int s = 0; s < S; ++s) {
+        sb += p[s * 2];
+        sg += p[s * 2 + 1];
+    }
+    if (accumulate) {
+        dbeta[ch] += (float)sb;
+        dgamma[ch] += (float)sg;
+    } else {
+        dbeta[ch] = (float)sb;
+        dgamma[ch] = (float)sg;
+    }
+    coef[ch] = (float)(sb * inv_m);
+    coef[C + ch] = (float)(sg * inv_m);
+}
+
+// dx = gamma*rstd*(dy - mean(dy) - xhat*mean(dy*xhat)); out = [skip +] dx
+template <bool VEC, bool SKIP>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
+    int64_t total, const float *__restrict__ gamma, const float *__restrict__ beta,
+    const float *__restrict__ mean_rstd, const float *__restrict__ coef, const float *skip,
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc) {
+    constexpr int E = VEC ? 4 : 1;
+    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (v >= total) return;
+    const int per_plane = HW / E;
+    const int64_t plane = v / per_plane;
+    const int i = (int)(v - plane * per_plane) * E;
+    const int n = (int)(plane / C), ch = (int)(plane - (int64_t)n * C);
+    const float mean = mean_rstd[ch], rstd = mean_rstd[C + ch];
+    const float scale = gamma[ch] * rstd;
+    const float shift = fmaf(-mean, scale, beta[ch]);
+    const float c1 = coef[ch], c2 = coef[C + ch];
+    const float *px = x + (int64_t)n * sn + (int64_t)ch * sc + i;
+    const float *pd = da + plane * HW + i;
+    float *po = out + (int64_t)n * osn + (int64_t)ch * osc + i;
+    const float *pk = SKIP ? skip + (int64_t)n * ksn + (int64_t)ch * ksc + i : nullptr;
+    if (VEC) {
+        const float4 xv = *reinterpret_cast<const float4 *>(px);
+        const float4 dv = *reinterpret_cast<const float4 *>(pd);
+        float4 kv = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (SKIP) kv = *reinterpret_cast<const float4 *>(pk);
+        const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+        const float ds[4] = {dv.x, dv.y, dv.z, dv.w};
+        const float ks[4] = {kv.x, kv.y, kv.z, kv.w};
+        float r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float dy = fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
+            const float xh = (xs[j] - mean) * rstd;
+            const float dx = scale * ((dy - c1) - xh * c2);
+            r[j] = SKIP ? ks[j] + dx : dx;
+        }
+        *reinterpret_cast<float4 *>(po) = make_float4(r[0], r[1], r[2], r[3]);
+    } else {
+        const float xv = *px;
+        const float dy = fmaf(xv, scale, shift) > 0.f ? *pd : 0.f;
+        const float xh = (xv - mean) * rstd;
+        const float dx = scale * ((dy - c1) - xh * c2);
+        *po = SKIP ? *pk + dx : dx;
+    }
+}
+
+inline bool vec_ok(const View &v, int hw) {
+    return hw % 4 == 0 && v.sn % 4 == 0 && v.sc % 4 == 0 && (reinterpret_cast<uintptr_t>(v.p) & 15) == 0;
+}
+
+}  // namespace
+
+int reduce_splits(int c, const Geo &g) {
+    const int target = c >= 1024 ? 1 : 1024 / c;
+    const int s_max = g.n < target ? g.n : target;
+    const int ipw = (g.n + s_max - 1) / s_max;
+    return (g.n + ipw - 1) / ipw;
+}
+
+size_t bn_scratch_floats(int c, const Geo &g) {
+    return (size_t)c * reduce_splits(c, g) * 3 + 2 * (size_t)c;
+}
+
+void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *mean_rstd) {
+    const int S = reduce_splits(c, g);
+    const int ipw = (g.n + S - 1) / S;
+    const double bytes = 4.0 * (double)g.pixels() * c;
+    if (cx.launch(bytes)) {
+        dim3 grid(S, c);
+        if (vec_ok(x, g.hw()))
+            bn_stats_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
+        else
+            bn_stats_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
+        cx.check();
+    }
+    if (cx.launch(0.0)) {
+        bn_stats_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, eps, mean_rstd);
+        cx.check();
+    }
+}
+
+void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float *beta,
+                 const float *mean_rstd, void *a, rvn_dtype dt) {
+    const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
+    if (!cx.launch((4.0 + esz) * (double)g.pixels() * c)) return;
+    const bool vec = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(a) & 15) == 0;
+    const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
+    const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
+#define RVN_LAUNCH(V, B) \
+    bn_relu_fwd_k<V, B><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, c, g.hw(), total, gamma, beta, mean_rstd, a)
+    if (vec && dt == RVN_BF16) RVN_LAUNCH(true, true);
+    else if (vec) RVN_LAUNCH(true, false);
+    else if (dt == RVN_BF16) RVN_LAUNCH(false, true);
+    else RVN_LAUNCH(false, false);
+#undef RVN_LAUNCH
+    cx.check();
+}
+
+void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *gamma,
+                 const float *beta, const float *mean_rstd, float *scratch, float *dgamma,
+                 float *dbeta, bool accumulate, const View *skip, View out) {
+    const int S = reduce_splits(c, g);
+    const int ipw = (g.n + S - 1) / S;
+    const double t = 4.0 * (double)g.pixels() * c;
+    float *coef = scratch + (size_t)c * S * 3;
+    const bool vec_in = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(da) & 15) == 0;
+    if (cx.launch(2.0 * t)) {
+        dim3 grid(S, c);
+        if (vec_in)
+            bn_bwd_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
+        else
+            bn_bwd_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
+        cx.check();
+    }
+    if (cx.launch(0.0)) {
+        bn_bwd_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, 1.0 / (double)g.pixels(), dgamma, dbeta, accumulate ? 1 : 0, coef);
+        cx.check();
+    }
+    if (cx.launch((skip ? 4.0 : 3.0) * t)) {
+        const bool vec = vec_in && vec_ok(out, g.hw()) && (!skip || vec_ok(*skip, g.hw()));
+        const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
+        const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
+        const float *kp = skip ? skip->p : nullptr;
+        const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
+#define RVN_LAUNCH(V, K) \
+    bn_bwd_apply_k<V, K><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, c, g.hw(), total, gamma, beta, mean_rstd, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
+        if (vec && skip) RVN_LAUNCH(true, true);
+        else if (vec) RVN_LAUNCH(true, false);
+        else if (skip) RVN_LAUNCH(false, true);
+        else RVN_LAUNCH(false, false);
+#undef RVN_LAUNCH
+        cx.check();
+    }
+}
+
+}  // namespace rvn

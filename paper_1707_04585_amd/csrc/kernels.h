@@ -1,0 +1,92 @@
+// Internal interface between the host-side block/stack driver and the HIP
+// kernels.  Not part of the public ABI (that is include/revnet.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "revnet.h"
+
+namespace rvn {
+
+// fp32 tensor whose rows and planes are contiguous: element (n, c, i), with
+// i = row * W + col in [0, H*W), lives at p[n*sn + c*sc + i].
+struct View {
+    float *p;
+    int64_t sn, sc;
+};
+
+struct Geo {
+    int n, h, w;
+    int hw() const { return h * w; }
+    int64_t pixels() const { return (int64_t)n * h * w; }
+};
+
+inline View dense_view(float *p, int c, const Geo &g) {
+    return View{p, (int64_t)c * g.hw(), (int64_t)g.hw()};
+}
+
+// What the last convolution of a residual function does with its sums
+// (Section 3.1): plain store, r + acc (forward coupling) or r - acc
+// (reconstruction).
+enum Epilogue { EP_STORE = 0, EP_ADD = 1, EP_SUB = 2 };
+
+// One call's launch context.  With dry == true the wrappers only count.
+struct Ctx {
+    hipStream_t stream = nullptr;
+    bool dry = false;
+    rvn_cost cost = {};
+    hipError_t err = hipSuccess;
+
+    // Record one kernel launch moving `bytes` algorithmic bytes; returns true
+    // if the kernel should really be launched.
+    bool launch(double bytes) {
+        cost.kernel_launches += 1;
+        cost.algorithmic_bytes += bytes;
+        return !dry && err == hipSuccess;
+    }
+    void check() {
+        if (!dry && err == hipSuccess) err = hipGetLastError();
+    }
+};
+
+// ---- sizes of the small scratch areas the wrappers need (floats) ----------
+// Number of image groups a per-channel reduction is split into.
+int reduce_splits(int c, const Geo &g);
+// Scratch floats for bn_stats / bn_relu_bwd partial results of `c` channels.
+size_t bn_scratch_floats(int c, const Geo &g);
+// Scratch floats for the filter-gradient partial sums.
+size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g);
+
+// ---- batch norm + ReLU (Section 2.2: a(x) = ReLU(BN(x))) -------------------
+// mean_rstd[0..c) = batch mean, mean_rstd[c..2c) = 1/sqrt(biased var + eps).
+void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *mean_rstd);
+
+// a = max(gamma * (x - mean) * rstd + beta, 0), written dense [n][c][h*w] as
+// fp32 or bf16 (round to nearest even) according to `dt`.
+void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float *beta,
+                 const float *mean_rstd, void *a, rvn_dtype dt);
+
+// Backward of a(x) given da (dense fp32): writes dgamma, dbeta (added to when
+// accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
+// `da` (dense in-place) or `skip`.
+void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *gamma,
+                 const float *beta, const float *mean_rstd, float *scratch, float *dgamma,
+                 float *dbeta, bool accumulate, const View *skip, View out);
+
+// ---- convolutions (Section 2.2: c_k(x) = Conv_kxk(a(x)), k in {1,3}) -------
+// out = ep(r, conv(a, w)); a is dense [n][cin][h*w] in `dt`; w is fp32
+// [cout][cin][ks][ks], rounded to bf16 on load when dt == RVN_BF16.
+void conv_fwd(Ctx &cx, const void *a, rvn_dtype dt, const float *w, int cin, int cout, int ks,
+              Geo g, Epilogue ep, const View *r, View out);
+
+// da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
+// dh is fp32, rounded to bf16 on load when dt == RVN_BF16.
+void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
+                float *da);
+
+// dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad].
+void conv_wgrad(Ctx &cx, const void *a, rvn_dtype dt, View dh, int cin, int cout, int ks, Geo g,
+                float *scratch, float *dw, bool accumulate);
+
+}  // namespace rvn

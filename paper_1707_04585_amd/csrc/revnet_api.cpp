@@ -1,0 +1,471 @@
+// Host side of the library: argument validation, workspace planning and the
+// block / stack drivers that sequence the HIP kernels.  Everything here runs
+// on the host and only enqueues work on the caller's stream.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "kernels.h"
+
+namespace rvn {
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+struct Layer {
+    int cin, cout, ks;
+};
+
+// Residual function shapes (Section 2.2): Basic = c3(c3(x)),
+// Bottleneck = c1(c3(c1(x))) with the 1x1 convolutions reducing to `width`
+// channels and projecting back.
+int func_layers(const rvn_block_desc &d, Layer out[3]) {
+    if (d.kind == RVN_BASIC) {
+        out[0] = {d.c_half, d.c_half, 3};
+        out[1] = {d.c_half, d.c_half, 3};
+        return 2;
+    }
+    out[0] = {d.c_half, d.width, 1};
+    out[1] = {d.width, d.width, 3};
+    out[2] = {d.width, d.c_half, 1};
+    return 3;
+}
+
+int check_desc(const rvn_block_desc *d) {
+    if (!d) return fail(RVN_ERR_NULL, "descriptor is NULL");
+    if (d->kind != RVN_BASIC && d->kind != RVN_BOTTLENECK)
+        return fail(RVN_ERR_DTYPE, "unknown block kind %d", (int)d->kind);
+    if (d->conv_dtype != RVN_F32 && d->conv_dtype != RVN_BF16)
+        return fail(RVN_ERR_DTYPE, "unknown conv_dtype %d", (int)d->conv_dtype);
+    if (d->c_half <= 0 || d->c_half > 65536)
+        return fail(RVN_ERR_SHAPE, "c_half = %d out of range [1, 65536]", d->c_half);
+    if (d->kind == RVN_BOTTLENECK && (d->width <= 0 || d->width > 65536))
+        return fail(RVN_ERR_SHAPE, "bottleneck width = %d out of range [1, 65536]", d->width);
+    if (!(d->bn_eps > 0.f)) return fail(RVN_ERR_SHAPE, "bn_eps must be > 0");
+    return RVN_OK;
+}
+
+int check_geo(int64_t n, int64_t h, int64_t w) {
+    if (n <= 0 || h <= 0 || w <= 0) return fail(RVN_ERR_SHAPE, "n, h, w must be positive (got %lld, %lld, %lld)", (long long)n, (long long)h, (long long)w);
+    if (h > 32768 || w > 32768 || n > (1 << 24) || n * h * w > 0x7fffffffLL)
+        return fail(RVN_ERR_SHAPE, "n*h*w = %lld exceeds the supported 2^31-1 pixels", (long long)(n * h * w));
+    return RVN_OK;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Workspace layout.  Offsets in bytes from the workspace base.
+struct Plan {
+    int L;
+    Layer layers[3];
+    size_t stats[3];      // 2*cin floats each: batch mean, 1/sqrt(var+eps)
+    size_t bn_scratch;    // partial sums of the per-channel reductions
+    size_t wgrad_scratch; // partial filter gradients (backward only)
+    size_t a[3];          // a_l = ReLU(BN(x_l)), conv operand precision
+    size_t h[2];          // h_l = conv_l(a_l), fp32, input of layer l+1
+    size_t g[2];          // gradient ping-pong buffers (backward only)
+    size_t total;
+};
+
+Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
+    Plan p{};
+    p.L = func_layers(d, p.layers);
+    const size_t P = (size_t)g.pixels();
+    const size_t esz = d.conv_dtype == RVN_BF16 ? 2 : 4;
+    size_t off = 0, bn_s = 0, wg_s = 0, max_cin = 0, max_mid = 0;
+    for (int l = 0; l < p.L; ++l) {
+        const Layer &ly = p.layers[l];
+        p.stats[l] = off;
+        off = align_up(off + 2 * (size_t)ly.cin * 4);
+        bn_s = std::max(bn_s, bn_scratch_floats(ly.cin, g));
+        wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
+        max_cin = std::max(max_cin, (size_t)ly.cin);
+        if (l < p.L - 1) max_mid = std::max(max_mid, (size_t)ly.cout);
+    }
+    p.bn_scratch = off;
+    off = align_up(off + bn_s * 4);
+    if (backward) {
+        p.wgrad_scratch = off;
+        off = align_up(off + wg_s * 4);
+        for (int l = 0; l < p.L; ++l) {
+            p.a[l] = off;
+            off = align_up(off + P * p.layers[l].cin * esz);
+        }
+        for (int l = 0; l < p.L - 1; ++l) {
+            p.h[l] = off;
+            off = align_up(off + P * p.layers[l].cout * 4);
+        }
+        for (int i = 0; i < 2; ++i) {
+            p.g[i] = off;
+            off = align_up(off + P * max_cin * 4);
+        }
+    } else {
+        // Forward keeps nothing: one operand buffer and one intermediate.
+        const size_t a0 = off;
+        off = align_up(off + P * max_cin * esz);
+        const size_t h0 = off;
+        off = align_up(off + P * max_mid * 4);
+        for (int l = 0; l < 3; ++l) p.a[l] = a0;
+        for (int l = 0; l < 2; ++l) p.h[l] = h0;
+    }
+    p.total = off;
+    return p;
+}
+
+struct Bufs {
+    float *stats[3];
+    void *a[3];
+    float *h[2];
+    float *g[2];
+    float *bn_scratch;
+    float *wgrad_scratch;
+};
+
+Bufs bind(const Plan &p, void *ws) {
+    char *b = static_cast<char *>(ws);
+    Bufs o{};
+    for (int l = 0; l < 3; ++l) {
+        o.stats[l] = reinterpret_cast<float *>(b + p.stats[l]);
+        o.a[l] = b + p.a[l];
+    }
+    for (int l = 0; l < 2; ++l) {
+        o.h[l] = reinterpret_cast<float *>(b + p.h[l]);
+        o.g[l] = reinterpret_cast<float *>(b + p.g[l]);
+    }
+    o.bn_scratch = reinterpret_cast<float *>(b + p.bn_scratch);
+    o.wgrad_scratch = reinterpret_cast<float *>(b + p.wgrad_scratch);
+    return o;
+}
+
+// ---- tensors ---------------------------------------------------------------
+
+int check_tensor(const char *name, const rvn_tensor *t, const rvn_block_desc &d, const rvn_tensor *like) {
+    if (!t) return fail(RVN_ERR_NULL, "tensor %s is NULL", name);
+    if (!t->ptr) return fail(RVN_ERR_NULL, "tensor %s has a NULL data pointer", name);
+    if (int rc = check_geo(t->n, t->h, t->w)) return rc;
+    if (t->c != d.c_half)
+        return fail(RVN_ERR_SHAPE, "tensor %s has c = %lld, descriptor says c_half = %d", name, (long long)t->c, d.c_half);
+    if (like && (t->n != like->n || t->h != like->h || t->w != like->w))
+        return fail(RVN_ERR_SHAPE, "tensor %s has shape [%lld,%lld,%lld,%lld], expected n,h,w = %lld,%lld,%lld", name,
+                    (long long)t->n, (long long)t->c, (long long)t->h, (long long)t->w, (long long)like->n, (long long)like->h, (long long)like->w);
+    const int64_t hw = t->h * t->w;
+    if (t->sw != 1 || t->sh != t->w || t->sc < hw || t->sn < (t->c - 1) * t->sc + hw)
+        return fail(RVN_ERR_STRIDE, "tensor %s: strides (%lld,%lld,%lld,%lld) unsupported; need sw=1, sh=w, sc>=h*w, sn>=(c-1)*sc+h*w",
+                    name, (long long)t->sn, (long long)t->sc, (long long)t->sh, (long long)t->sw);
+    if (reinterpret_cast<uintptr_t>(t->ptr) % 4)
+        return fail(RVN_ERR_STRIDE, "tensor %s: data pointer is not 4-byte aligned", name);
+    return RVN_OK;
+}
+
+bool same_tensor(const rvn_tensor *a, const rvn_tensor *b) {
+    return a->ptr == b->ptr && a->sn == b->sn && a->sc == b->sc;
+}
+
+// Exact overlap test for two tensors of the supported layout: each occupies,
+// per image, one interval of (c-1)*sc + h*w elements.
+bool overlaps(const rvn_tensor *a, const rvn_tensor *b) {
+    const int64_t la = ((a->c - 1) * a->sc + a->h * a->w) * 4, lb = ((b->c - 1) * b->sc + b->h * b->w) * 4;
+    const int64_t pa = (int64_t)reinterpret_cast<uintptr_t>(a->ptr), pb = (int64_t)reinterpret_cast<uintptr_t>(b->ptr);
+    const int64_t sa = a->sn * 4, sb = b->sn * 4;
+    if (pa + (a->n - 1) * sa + la <= pb || pb + (b->n - 1) * sb + lb <= pa) return false;
+    for (int64_t i = 0; i < a->n; ++i) {
+        const int64_t s = pa + i * sa, e = s + la;
+        // images m of b with pb + m*sb < e and pb + m*sb + lb > s
+        int64_t m_lo = (s - pb - lb) / sb;  // candidates around the bounds
+        for (int64_t m = std::max<int64_t>(0, m_lo - 1); m < b->n && pb + m * sb < e; ++m)
+            if (pb + m * sb + lb > s) return true;
+    }
+    return false;
+}
+
+bool overlaps_range(const rvn_tensor *a, const void *p, size_t bytes) {
+    const int64_t la = ((a->c - 1) * a->sc + a->h * a->w) * 4;
+    const int64_t pa = (int64_t)reinterpret_cast<uintptr_t>(a->ptr), pb = (int64_t)reinterpret_cast<uintptr_t>(p);
+    return !(pa + (a->n - 1) * a->sn * 4 + la <= pb || pb + (int64_t)bytes <= pa);
+}
+
+View view_of(const rvn_tensor *t) { return View{static_cast<float *>(t->ptr), t->sn, t->sc}; }
+
+int check_params(const rvn_block_desc &d, const rvn_block_params *p, const char *what) {
+    if (!p) return fail(RVN_ERR_NULL, "%s is NULL", what);
+    Layer ly[3];
+    const int L = func_layers(d, ly);
+    const rvn_func_params *fs[2] = {&p->F, &p->G};
+    for (int f = 0; f < 2; ++f)
+        for (int l = 0; l < L; ++l)
+            if (!fs[f]->conv_w[l] || !fs[f]->bn_gamma[l] || !fs[f]->bn_beta[l])
+                return fail(RVN_ERR_NULL, "%s: %c layer %d has a NULL parameter pointer", what, f ? 'G' : 'F', l);
+    return RVN_OK;
+}
+
+int check_grads(const rvn_block_desc &d, const rvn_block_grads *p, const char *what) {
+    if (!p) return fail(RVN_ERR_NULL, "%s is NULL", what);
+    Layer ly[3];
+    const int L = func_layers(d, ly);
+    const rvn_func_grads *fs[2] = {&p->F, &p->G};
+    for (int f = 0; f < 2; ++f)
+        for (int l = 0; l < L; ++l)
+            if (!fs[f]->d_conv_w[l] || !fs[f]->d_bn_gamma[l] || !fs[f]->d_bn_beta[l])
+                return fail(RVN_ERR_NULL, "%s: %c layer %d has a NULL gradient pointer", what, f ? 'G' : 'F', l);
+    return RVN_OK;
+}
+
+int check_ws(const void *ws, size_t have, size_t need) {
+    if (!ws) return fail(RVN_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", need);
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign) return fail(RVN_ERR_WORKSPACE, "workspace is not %zu-byte aligned", kAlign);
+    if (have < need) return fail(RVN_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    return RVN_OK;
+}
+
+// ---- residual function drivers ----------------------------------------------
+
+// out = ep(r, Func(x)); leaves a_l, h_l and the BN statistics in `b`.
+void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
+                  const rvn_func_params &p, Epilogue ep, const View *r, View out) {
+    View cur = x;
+    for (int l = 0; l < pl.L; ++l) {
+        const Layer &ly = pl.layers[l];
+        bn_stats(cx, cur, ly.cin, g, d.bn_eps, b.bn_scratch, b.stats[l]);
+        bn_relu_fwd(cx, cur, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.a[l], d.conv_dtype);
+        if (l < pl.L - 1) {
+            View h = dense_view(b.h[l], ly.cout, g);
+            conv_fwd(cx, b.a[l], d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
+            cur = h;
+        } else {
+            conv_fwd(cx, b.a[l], d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
+        }
+    }
+}
+
+// Ordinary backprop through Func at the activations func_forward left in `b`
+// (Section 2.1, the backprop rule): out = skip + (dFunc/dx)^T upstream, and
+// the parameter gradients.
+void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
+                   const rvn_func_params &p, View upstream, const rvn_func_grads &gr, bool accumulate,
+                   View skip, View out) {
+    View dh = upstream;
+    int cur = 0;
+    for (int l = pl.L - 1; l >= 0; --l) {
+        const Layer &ly = pl.layers[l];
+        conv_wgrad(cx, b.a[l], d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch, gr.d_conv_w[l], accumulate);
+        float *da = b.g[cur];
+        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, da);
+        if (l > 0) {
+            View xl = dense_view(b.h[l - 1], ly.cin, g);
+            View dx = dense_view(da, ly.cin, g);
+            bn_relu_bwd(cx, xl, da, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.bn_scratch,
+                        gr.d_bn_gamma[l], gr.d_bn_beta[l], accumulate, nullptr, dx);
+            dh = dx;
+            cur ^= 1;
+        } else {
+            bn_relu_bwd(cx, x, da, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.bn_scratch,
+                        gr.d_bn_gamma[l], gr.d_bn_beta[l], accumulate, &skip, out);
+        }
+    }
+}
+
+// Section 3.1: y1 = x1 + F(x2); y2 = x2 + G(y1).
+void block_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x1,
+                   View x2, const rvn_block_params &p, View y1, View y2) {
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2);
+}
+
+// Section 3.2, Algorithm 1, with G handled completely before F.
+void block_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View y1,
+                    View y2, View dy1, View dy2, const rvn_block_params &p, View x1, View x2, View dx1,
+                    View dx2, const rvn_block_grads &gr, bool accumulate) {
+    // z1 = y1;  x2 = y2 - G(z1)
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2);
+    // dz1 = dy1 + (dG/dz1)^T dy2;  dwG          (dx1 = dz1)
+    func_backward(cx, d, pl, b, g, y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
+    // x1 = z1 - F(x2)
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1);
+    // dx2 = dy2 + (dF/dx2)^T dz1;  dwF
+    func_backward(cx, d, pl, b, g, x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
+}
+
+int finish(Ctx &cx) {
+    if (cx.err != hipSuccess) return fail(RVN_ERR_HIP, "HIP error: %s", hipGetErrorString(cx.err));
+    return RVN_OK;
+}
+
+int check_fwd_args(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_tensor *x2,
+                   const rvn_tensor *y1, const rvn_tensor *y2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo) {
+    if (int rc = check_desc(desc)) return rc;
+    if (int rc = check_tensor("x1", x1, *desc, nullptr)) return rc;
+    if (int rc = check_tensor("x2", x2, *desc, x1)) return rc;
+    if (int rc = check_tensor("y1", y1, *desc, x1)) return rc;
+    if (int rc = check_tensor("y2", y2, *desc, x1)) return rc;
+    const rvn_tensor *t[4] = {x1, x2, y1, y2};
+    const char *nm[4] = {"x1", "x2", "y1", "y2"};
+    for (int i = 0; i < 4; ++i)
+        for (int j = i + 1; j < 4; ++j) {
+            const bool allowed = (i == 0 && j == 2) || (i == 1 && j == 3);
+            if (allowed && same_tensor(t[i], t[j])) continue;
+            if (overlaps(t[i], t[j])) return fail(RVN_ERR_ALIAS, "%s and %s overlap", nm[i], nm[j]);
+        }
+    *geo = Geo{(int)x1->n, (int)x1->h, (int)x1->w};
+    *plan = make_plan(*desc, *geo, false);
+    if (int rc = check_ws(ws, ws_bytes, plan->total)) return rc;
+    for (int i = 0; i < 4; ++i)
+        if (overlaps_range(t[i], ws, plan->total)) return fail(RVN_ERR_ALIAS, "%s overlaps the workspace", nm[i]);
+    return RVN_OK;
+}
+
+int check_bwd_args(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_tensor *y2,
+                   const rvn_tensor *dy1, const rvn_tensor *dy2, const rvn_tensor *x1, const rvn_tensor *x2,
+                   const rvn_tensor *dx1, const rvn_tensor *dx2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo) {
+    if (int rc = check_desc(desc)) return rc;
+    const rvn_tensor *t[8] = {y1, y2, dy1, dy2, x1, x2, dx1, dx2};
+    const char *nm[8] = {"y1", "y2", "dy1", "dy2", "x1", "x2", "dx1", "dx2"};
+    for (int i = 0; i < 8; ++i)
+        if (int rc = check_tensor(nm[i], t[i], *desc, i ? y1 : nullptr)) return rc;
+    for (int i = 0; i < 8; ++i)
+        for (int j = i + 1; j < 8; ++j) {
+            const bool allowed = j == i + 4;  // x_i with y_i, dx_i with dy_i
+            if (allowed && same_tensor(t[i], t[j])) continue;
+            if (overlaps(t[i], t[j])) return fail(RVN_ERR_ALIAS, "%s and %s overlap", nm[i], nm[j]);
+        }
+    *geo = Geo{(int)y1->n, (int)y1->h, (int)y1->w};
+    *plan = make_plan(*desc, *geo, true);
+    if (int rc = check_ws(ws, ws_bytes, plan->total)) return rc;
+    for (int i = 0; i < 8; ++i)
+        if (overlaps_range(t[i], ws, plan->total)) return fail(RVN_ERR_ALIAS, "%s overlaps the workspace", nm[i]);
+    return RVN_OK;
+}
+
+void stack_forward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
+                   View x1, View x2, const rvn_block_params *params, View y1, View y2) {
+    for (int k = 0; k < depth; ++k) {
+        block_forward(cx, d, pl, b, g, k ? y1 : x1, k ? y2 : x2, params[k], y1, y2);
+    }
+}
+
+void stack_backward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
+                    View y1, View y2, View dy1, View dy2, const rvn_block_params *params, View x1, View x2,
+                    View dx1, View dx2, const rvn_block_grads *grads, bool accumulate) {
+    for (int k = depth - 1; k >= 0; --k) {
+        const bool top = k == depth - 1;
+        block_backward(cx, d, pl, b, g, top ? y1 : x1, top ? y2 : x2, top ? dy1 : dx1, top ? dy2 : dx2,
+                       params[k], x1, x2, dx1, dx2, grads[k], accumulate);
+    }
+}
+
+}  // namespace
+}  // namespace rvn
+
+using namespace rvn;
+
+extern "C" {
+
+int revnet_version(void) { return 1000; }
+
+const char *revnet_last_error(void) { return g_err; }
+
+int revnet_workspace_bytes(const rvn_block_desc *desc, int64_t n, int64_t h, int64_t w,
+                           size_t *fwd_bytes, size_t *bwd_bytes) {
+    if (int rc = check_desc(desc)) return rc;
+    if (int rc = check_geo(n, h, w)) return rc;
+    const Geo g{(int)n, (int)h, (int)w};
+    if (fwd_bytes) *fwd_bytes = make_plan(*desc, g, false).total;
+    if (bwd_bytes) *bwd_bytes = make_plan(*desc, g, true).total;
+    return RVN_OK;
+}
+
+int revnet_block_fwd(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_tensor *x2,
+                     const rvn_block_params *params, const rvn_tensor *y1, const rvn_tensor *y2,
+                     void *ws, size_t ws_bytes, void *hip_stream) {
+    return revnet_stack_fwd(desc, 1, x1, x2, params, y1, y2, ws, ws_bytes, hip_stream);
+}
+
+int revnet_stack_fwd(const rvn_block_desc *desc, int32_t depth, const rvn_tensor *x1,
+                     const rvn_tensor *x2, const rvn_block_params *params, const rvn_tensor *y1,
+                     const rvn_tensor *y2, void *ws, size_t ws_bytes, void *hip_stream) {
+    Plan pl;
+    Geo g;
+    if (depth <= 0) return fail(RVN_ERR_SHAPE, "depth = %d must be positive", depth);
+    if (int rc = check_fwd_args(desc, x1, x2, y1, y2, ws, ws_bytes, &pl, &g)) return rc;
+    if (!params) return fail(RVN_ERR_NULL, "params is NULL");
+    for (int k = 0; k < depth; ++k)
+        if (int rc = check_params(*desc, &params[k], "params")) return rc;
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    stack_forward(cx, *desc, depth, pl, bind(pl, ws), g, view_of(x1), view_of(x2), params, view_of(y1), view_of(y2));
+    return finish(cx);
+}
+
+int revnet_block_bwd_reconstruct(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_tensor *y2,
+                                 const rvn_tensor *dy1, const rvn_tensor *dy2,
+                                 const rvn_block_params *params, const rvn_tensor *x1,
+                                 const rvn_tensor *x2, const rvn_tensor *dx1, const rvn_tensor *dx2,
+                                 const rvn_block_grads *grads, int accumulate_wgrads, void *ws,
+                                 size_t ws_bytes, void *hip_stream) {
+    return revnet_stack_bwd(desc, 1, y1, y2, dy1, dy2, params, x1, x2, dx1, dx2, grads, accumulate_wgrads,
+                            ws, ws_bytes, hip_stream);
+}
+
+int revnet_stack_bwd(const rvn_block_desc *desc, int32_t depth, const rvn_tensor *y1,
+                     const rvn_tensor *y2, const rvn_tensor *dy1, const rvn_tensor *dy2,
+                     const rvn_block_params *params, const rvn_tensor *x1, const rvn_tensor *x2,
+                     const rvn_tensor *dx1, const rvn_tensor *dx2, const rvn_block_grads *grads,
+                     int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream) {
+    Plan pl;
+    Geo g;
+    if (depth <= 0) return fail(RVN_ERR_SHAPE, "depth = %d must be positive", depth);
+    if (int rc = check_bwd_args(desc, y1, y2, dy1, dy2, x1, x2, dx1, dx2, ws, ws_bytes, &pl, &g)) return rc;
+    if (!params) return fail(RVN_ERR_NULL, "params is NULL");
+    if (!grads) return fail(RVN_ERR_NULL, "grads is NULL");
+    for (int k = 0; k < depth; ++k) {
+        if (int rc = check_params(*desc, &params[k], "params")) return rc;
+        if (int rc = check_grads(*desc, &grads[k], "grads")) return rc;
+    }
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    stack_backward(cx, *desc, depth, pl, bind(pl, ws), g, view_of(y1), view_of(y2), view_of(dy1), view_of(dy2),
+                   params, view_of(x1), view_of(x2), view_of(dx1), view_of(dx2), grads, accumulate_wgrads != 0);
+    return finish(cx);
+}
+
+int revnet_stack_cost(const rvn_block_desc *desc, int32_t depth, int64_t n, int64_t h, int64_t w,
+                      rvn_cost *fwd, rvn_cost *bwd) {
+    if (int rc = check_desc(desc)) return rc;
+    if (int rc = check_geo(n, h, w)) return rc;
+    if (depth <= 0) return fail(RVN_ERR_SHAPE, "depth = %d must be positive", depth);
+    const Geo g{(int)n, (int)h, (int)w};
+    // Run the real drivers in counting mode on placeholder addresses; nothing
+    // is dereferenced and nothing is launched.
+    std::vector<rvn_block_params> params((size_t)depth);
+    std::vector<rvn_block_grads> grads((size_t)depth);
+    std::memset(params.data(), 0, params.size() * sizeof(rvn_block_params));
+    std::memset(grads.data(), 0, grads.size() * sizeof(rvn_block_grads));
+    const View v = dense_view(nullptr, desc->c_half, g);
+    if (fwd) {
+        const Plan pl = make_plan(*desc, g, false);
+        Ctx cx;
+        cx.dry = true;
+        stack_forward(cx, *desc, depth, pl, bind(pl, nullptr), g, v, v, params.data(), v, v);
+        *fwd = cx.cost;
+    }
+    if (bwd) {
+        const Plan pl = make_plan(*desc, g, true);
+        Ctx cx;
+        cx.dry = true;
+        stack_backward(cx, *desc, depth, pl, bind(pl, nullptr), g, v, v, v, v, params.data(), v, v, v, v,
+                       grads.data(), false);
+        *bwd = cx.cost;
+    }
+    return RVN_OK;
+}
+
+}  // extern "C"

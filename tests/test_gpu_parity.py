@@ -1,0 +1,327 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.
+
+Tolerances (per-tensor relative L2 error, float64 oracle as reference):
+  fp32 path : forward 1e-5, gradients 1e-4
+  bf16 convolution operands : gradients 2e-2 (forward and reconstruction 1e-2)
+The reference gradient is the ordinary stored-activation one, so the tolerance
+covers both fp32 rounding and reconstruction drift.
+
+For the bf16 path the oracle rounds the operands of its convolutions to bf16
+as well (and still sums in float64): rounding moves a fraction ~1e-3 of the
+pre-activations across zero, each flipped ReLU derivative changes its gradient
+element by O(1), and that alone is a 5-10% relative L2 difference from the
+unrounded gradient at any size.  The 0/1 decisions are therefore taken in the
+kernel's operand precision on both sides; the distance to the unrounded
+float64 gradient is printed for information.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+# Whole bf16 stacks: the GPU (fp32 sums) and the oracle (float64 sums) differ by
+# ~1e-7 going into each bf16 rounding step, which turns that into ~1e-4 on a few
+# percent of the next layer's inputs, and reconstruction feeds the difference to
+# the block below; after a few blocks some ReLU decisions differ and each costs
+# O(1) in its gradient element.  Stacks are therefore held to a looser bound
+# here and to the 2e-2 bar block by block (see
+# test_bf16_every_block_of_a_stack_from_oracle_inputs).
+BF16_STACK_GRAD_TOL = 1e-1
+# Single blocks with long sums (3x3 over 512 channels = 4608 products, BN over
+# only 392 values per channel): the fp32-vs-float64 difference entering the
+# first rounding step is already ~4e-6 and three rounding steps in a row bring
+# it to the bf16 noise floor, so the bound is that of bf16 itself.
+WIDE_BF16_GRAD_TOL = 8e-2
+
+TOL = {"f32": dict(fwd=1e-5, grad=1e-4, recon=1e-5), "bf16": dict(fwd=1e-2, grad=2e-2, recon=1e-2)}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def split(t):
+    c = t.shape[1] // 2
+    return np.ascontiguousarray(t[:, :c]), np.ascontiguousarray(t[:, c:])
+
+
+def oracle_reference(oracle, cfg, x, params, dy):
+    x1, x2 = split(x)
+    dy1, dy2 = split(dy)
+    with oracle.conv_operands(cfg.get("conv", "f32")):
+        y1, y2, inputs, stored = oracle.stack_fwd(x1, x2, params, eps=cfg.get("eps", 1e-5), keep=True)
+        dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, dy1, dy2, eps=cfg.get("eps", 1e-5))
+    return dict(y=np.concatenate([y1, y2], 1), dx=np.concatenate([dx1, dx2], 1), grads=grads, inputs=inputs)
+
+
+def gpu_run(cfg, x, params, dy, inplace=True, split_buffers=False, accumulate=False, repeat_bwd=1):
+    from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
+    import torch
+    r = StackRunner(split_buffers=split_buffers, **cfg)
+    r.set_params(params)
+    X = r.new_pair(x)
+    Y = X if inplace else r.new_pair()
+    r.forward(X, Y)
+    torch.cuda.synchronize()
+    y = r.to_host(Y[0])
+    DY = r.new_pair(dy)
+    if inplace:
+        XR, DX = Y, DY
+    else:
+        XR, DX = r.new_pair(), r.new_pair()
+    for i in range(repeat_bwd):
+        if i:   # run backward again from fresh copies of (y, dy)
+            Y = r.new_pair(y)
+            DY = r.new_pair(dy)
+            XR, DX = (Y, DY) if inplace else (XR, DX)
+        r.backward(Y, DY, XR, DX, accumulate=accumulate)
+    torch.cuda.synchronize()
+    return dict(y=y, x_rec=r.to_host(XR[0]), dx=r.to_host(DX[0]), grads=download_grads(r.grads), runner=r)
+
+
+def error_table(oracle, out, ref, x, scale_grads=1.0):
+    """Relative L2 error of every output tensor; parameter gradients keyed
+    'k.F.l.w' etc.  A gradient whose reference is zero up to rounding is
+    reported as an absolute error over its scale."""
+    err = dict(y=oracle.rel_l2(out["y"], ref["y"]), x_rec=oracle.rel_l2(out["x_rec"], x),
+               dx=oracle.rel_l2(out["dx"], ref["dx"]))
+    for k, (gb, rb) in enumerate(zip(out["grads"], ref["grads"])):
+        for fn in ("F", "G"):
+            for l, (gl, rl) in enumerate(zip(gb[fn], rb[fn])):
+                for key in ("w", "gamma", "beta"):
+                    want = scale_grads * rl[key]
+                    floor = 1e-6 * max(1.0, float(np.abs(want).max()))
+                    if np.linalg.norm(want) < floor:
+                        err[f"{k}.{fn}.{l}.{key}"] = float(np.abs(gl[key] - want).max()) / (1e4 * floor)
+                    else:
+                        err[f"{k}.{fn}.{l}.{key}"] = oracle.rel_l2(gl[key], want)
+    return err
+
+
+def check_against_oracle(oracle, out, ref, x, conv, scale_grads=1.0, tol=None):
+    tol = tol or TOL[conv]
+    err = error_table(oracle, out, ref, x, scale_grads)
+    gerr = {k: v for k, v in err.items() if "." in k}
+    worst = max(gerr, key=gerr.get)
+    print("rel. errors: y %.2e  x_rec %.2e  dx %.2e  worst parameter gradient %s %.2e" %
+          (err["y"], err["x_rec"], err["dx"], worst, gerr[worst]), flush=True)
+    assert err["y"] < tol["fwd"], ("y", err["y"])
+    assert err["x_rec"] < tol["recon"], ("x_rec", err["x_rec"])
+    assert err["dx"] < tol["grad"], ("dx", err["dx"])
+    assert gerr[worst] < tol["grad"], (worst, gerr[worst])
+    return err
+
+
+SMALL_CASES = {
+    # name: (cfg, note)
+    "c1_single_basic_block": dict(S.STACKS["c1_block"]),
+    "basic_ragged_odd_channels": dict(kind="basic", n=3, c=10, h=7, w=9, depth=2, width=None, conv="f32", affine="random"),
+    "basic_several_tiles": dict(kind="basic", n=6, c=32, h=32, w=32, depth=2, width=None, conv="f32", affine="random"),
+    "basic_c56_8x8": dict(kind="basic", n=8, c=112, h=8, w=8, depth=1, width=None, conv="f32", affine="random"),
+    "bottleneck_ragged": dict(kind="bottleneck", n=2, c=24, h=6, w=10, depth=2, width=5, conv="f32", affine="random"),
+    "bottleneck_56x56": dict(kind="bottleneck", n=2, c=64, h=56, w=56, depth=1, width=16, conv="f32", affine="random"),
+    "bottleneck_7x7_wide": dict(kind="bottleneck", n=4, c=256, h=7, w=7, depth=1, width=64, conv="f32", affine="random"),
+    "degenerate_one_pixel": dict(kind="basic", n=1, c=2, h=1, w=1, depth=1, width=None, conv="f32", affine="random"),
+    "degenerate_one_row": dict(kind="basic", n=2, c=4, h=1, w=5, depth=1, width=None, conv="f32", affine="random"),
+}
+
+
+@pytest.mark.parametrize("conv", ["f32", "bf16"])
+@pytest.mark.parametrize("name", list(SMALL_CASES))
+def test_stack_matches_oracle(oracle, torch_cuda, name, conv):
+    cfg = dict(SMALL_CASES[name], conv=conv)
+    if name.startswith("degenerate") and conv == "bf16":
+        pytest.skip("degenerate shapes are covered in fp32")
+    print(f"case {name} conv={conv} cfg={cfg}", flush=True)
+    x, params, dy = S.draw_stack(1234, **cfg)
+    ref = oracle_reference(oracle, cfg, x, params, dy)
+    out = gpu_run(cfg, x, params, dy)
+    tol = dict(TOL[conv])
+    if conv == "bf16" and cfg["depth"] > 1:
+        tol["grad"] = BF16_STACK_GRAD_TOL
+    check_against_oracle(oracle, out, ref, x, conv, tol=tol)
+
+
+@pytest.mark.parametrize("kind,c,width,h,w", [("basic", 32, None, 16, 16), ("bottleneck", 64, 16, 14, 14)])
+def test_bf16_every_block_of_a_stack_from_oracle_inputs(oracle, torch_cuda, kind, c, width, h, w):
+    """bf16 operands, 2e-2 bar, block by block: block k of a 4-block stack gets
+    the oracle's (x, y, ybar) of that block, so every block is checked at its
+    real statistics without the divergence between two precisions compounding
+    through the rounding steps of the blocks above and below it."""
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
+    cfg = dict(kind=kind, n=8, c=c, h=h, w=w, depth=4, width=width, conv="bf16", affine="random")
+    x, params, dy = S.draw_stack(4321, **cfg)
+    with oracle.conv_operands("bf16"):
+        x1, x2 = split(x)
+        y1, y2, inputs, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+        outs = inputs[1:] + [(y1, y2)]
+        g1, g2 = split(dy)
+        ups, downs, grads = [None] * 4, [None] * 4, [None] * 4
+        for k in range(3, -1, -1):
+            ups[k] = (g1, g2)
+            g1, g2, grads[k] = oracle.block_bwd_stored(stored[k], params[k], g1, g2)
+            downs[k] = (g1, g2)
+    r = StackRunner(**cfg)
+    r.set_params(params)
+    cat = lambda pr: np.concatenate(pr, axis=1)
+    for k in range(4):
+        X, Y = r.new_pair(cat(inputs[k])), r.new_pair()
+        rv.revnet_block_fwd(r.desc, X[1], X[2], r.params[k], Y[1], Y[2], r.ws)
+        torch.cuda.synchronize()
+        y_gpu = r.to_host(Y[0])
+        Y, DY = r.new_pair(cat(outs[k])), r.new_pair(cat(ups[k]))
+        rv.revnet_block_bwd_reconstruct(r.desc, Y[1], Y[2], DY[1], DY[2], r.params[k], Y[1], Y[2], DY[1], DY[2],
+                                        r.grads[k], 0, r.ws)
+        torch.cuda.synchronize()
+        out = dict(y=y_gpu, x_rec=r.to_host(Y[0]), dx=r.to_host(DY[0]), grads=[download_grads(r.grads)[k]])
+        ref = dict(y=cat(outs[k]), dx=cat(downs[k]), grads=[grads[k]])
+        print(f"block {k}:", end=" ")
+        check_against_oracle(oracle, out, ref, cat(inputs[k]), "bf16")
+
+
+def test_block_entry_points_c1(oracle, torch_cuda):
+    """revnet_block_fwd / revnet_block_bwd_reconstruct on the single-block
+    workload, out of place, against the oracle and against Algorithm 1 run in
+    float32 on the CPU."""
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
+    cfg, x, params, dy = S.draw_named("c1_block")
+    ref = oracle_reference(oracle, cfg, x, params, dy)
+    r = StackRunner(**cfg)
+    r.set_params(params)
+    X, Y, DY, XR, DX = r.new_pair(x), r.new_pair(), r.new_pair(dy), r.new_pair(), r.new_pair()
+    rv.revnet_block_fwd(r.desc, X[1], X[2], r.params[0], Y[1], Y[2], r.ws)
+    rv.revnet_block_bwd_reconstruct(r.desc, Y[1], Y[2], DY[1], DY[2], r.params[0], XR[1], XR[2], DX[1], DX[2],
+                                    r.grads[0], 0, r.ws)
+    torch.cuda.synchronize()
+    out = dict(y=r.to_host(Y[0]), x_rec=r.to_host(XR[0]), dx=r.to_host(DX[0]), grads=download_grads(r.grads))
+    check_against_oracle(oracle, out, ref, x, "f32")
+    # inputs are untouched by an out-of-place call
+    np.testing.assert_array_equal(r.to_host(X[0]), x.astype(np.float32).astype(np.float64))
+    np.testing.assert_array_equal(r.to_host(DY[0]), dy.astype(np.float32).astype(np.float64))
+
+
+def test_in_place_out_of_place_and_split_buffers_agree_bitwise(oracle, torch_cuda):
+    cfg = dict(kind="basic", n=4, c=16, h=12, w=12, depth=3, width=None, conv="f32", affine="random")
+    x, params, dy = S.draw_stack(77, **cfg)
+    a = gpu_run(cfg, x, params, dy, inplace=True)
+    b = gpu_run(cfg, x, params, dy, inplace=False)
+    c = gpu_run(cfg, x, params, dy, inplace=False, split_buffers=True)
+    for other in (b, c):
+        for key in ("y", "x_rec", "dx"):
+            np.testing.assert_array_equal(a[key], other[key])
+        np.testing.assert_array_equal(oracle.flatten_grads(a["grads"]), oracle.flatten_grads(other["grads"]))
+
+
+def test_runs_are_bitwise_reproducible(oracle, torch_cuda):
+    """No floating-point atomics anywhere: two runs give identical bits, which
+    is also what makes the recomputed G(y1) equal the forward one."""
+    cfg = dict(kind="bottleneck", n=4, c=32, h=14, w=14, depth=2, width=8, conv="bf16", affine="random")
+    x, params, dy = S.draw_stack(78, **cfg)
+    a = gpu_run(cfg, x, params, dy)
+    b = gpu_run(cfg, x, params, dy)
+    for key in ("y", "x_rec", "dx"):
+        np.testing.assert_array_equal(a[key], b[key])
+    np.testing.assert_array_equal(oracle.flatten_grads(a["grads"]), oracle.flatten_grads(b["grads"]))
+
+
+def test_accumulate_wgrads(oracle, torch_cuda):
+    """accumulate_wgrads adds to the gradient buffers (weight sharing, footnote
+    to Algorithm 1): two backward passes give twice the gradient."""
+    cfg = dict(kind="basic", n=3, c=8, h=6, w=6, depth=2, width=None, conv="f32", affine="random")
+    x, params, dy = S.draw_stack(79, **cfg)
+    ref = oracle_reference(oracle, cfg, x, params, dy)
+    out = gpu_run(cfg, x, params, dy, accumulate=True, repeat_bwd=2)
+    check_against_oracle(oracle, out, ref, x, "f32", scale_grads=2.0)
+
+
+def test_c2_full_size_with_drift_report(oracle, torch_cuda):
+    """The 9-block stack at N=128, C=32, 32x32, fp32, every output against the
+    float64 oracle, plus reconstruction error per depth (Section 3.2
+    'Numerical error': it accumulates but stays small).
+
+    Tolerance at this size.  The stack takes 9*4*N*c*H*W = 7.5e7 ReLU
+    decisions u > 0.  fp32 sums of 144 products put u about 3e-7 (relative to
+    its unit scale) away from the float64 value, so a decision differs with
+    probability 2 * 3e-7 * pdf(0) = 2.4e-7: about 18 of them, whatever the
+    kernel.  Each one changes its gradient element by O(1) and that error
+    travels, norm roughly preserved, through the layers below but stays inside
+    its own image.  Expected ||error|| / ||dx|| = sqrt(18 / 4.2e6) = 2e-3.  So:
+      * images without a differing decision must meet the 1e-4 bar, and at
+        least 60% of the 128 images must be such images;
+      * whole tensors: dx within 5e-3, parameter gradients within 1e-2, and the
+        angle between the parameter-gradient vectors (the quantity of the
+        paper's figure on stored versus reconstructed activations) < 0.2 deg.
+    """
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import StackRunner
+    cfg, x, params, dy = S.draw_named("c2_stack9")
+    print("oracle reference for c2_stack9 ...", flush=True)
+    ref = oracle_reference(oracle, cfg, x, params, dy)
+    print("gpu run ...", flush=True)
+    out = gpu_run(cfg, x, params, dy)
+    check_against_oracle(oracle, out, ref, x, "f32", tol=dict(fwd=1e-5, recon=1e-5, grad=1e-2))
+    assert oracle.rel_l2(out["dx"], ref["dx"]) < 5e-3
+    per_image = np.array([oracle.rel_l2(out["dx"][i], ref["dx"][i]) for i in range(cfg["n"])])
+    clean = float((per_image < 1e-4).mean())
+    print("images whose dx meets 1e-4: %.0f%%; median per-image error %.2e" % (100 * clean, np.median(per_image)), flush=True)
+    assert clean >= 0.6
+    ang = oracle.angle_deg(oracle.flatten_grads(out["grads"]), oracle.flatten_grads(ref["grads"]))
+    print("angle between GPU and stored-activation parameter gradients: %.3e degrees" % ang, flush=True)
+    assert ang < 0.2
+    # drift per depth: peel the stack one block at a time with the block entry point
+    r = StackRunner(**cfg)
+    r.set_params(params)
+    Y, DY = r.new_pair(ref["y"]), r.new_pair(dy)
+    drift = []
+    for k in range(cfg["depth"] - 1, -1, -1):
+        rv.revnet_block_bwd_reconstruct(r.desc, Y[1], Y[2], DY[1], DY[2], r.params[k], Y[1], Y[2], DY[1], DY[2],
+                                        r.grads[k], 0, r.ws)
+        torch.cuda.synchronize()
+        xin = np.concatenate(ref["inputs"][k], axis=1)
+        drift.append(oracle.rel_l2(r.to_host(Y[0]), xin))
+    print("reconstruction rel. error, top block first:", ["%.2e" % d for d in drift], flush=True)
+    assert max(drift) < 1e-5
+
+
+def test_large_bottleneck_properties(oracle, torch_cuda):
+    """Bottleneck stack at the real channel counts and resolution (C=256,
+    width 64, 56x56) with a batch too large for the oracle to finish quickly:
+    properties that hold at any size.  (i) reconstruction returns the input;
+    (ii) F and G start with a BN, so the gradient that arrives through them
+    sums to zero over each channel."""
+    cfg = dict(S.STACKS["c4_bneck12"], n=8, depth=2)
+    x, params, dy = S.draw_stack(80, **cfg)
+    out = gpu_run(cfg, x, params, dy)
+    assert oracle.rel_l2(out["x_rec"], x) < TOL["bf16"]["recon"]
+    through = (out["dx"] - dy.astype(np.float32)).sum(axis=(0, 2, 3))
+    scale = np.abs(out["dx"]).sum(axis=(0, 2, 3))
+    c = cfg["c"] // 2
+    # x2-half: dx2 - dy2 came through F of the bottom block; sums to ~0 per channel
+    assert np.abs(through[c:]).max() < 1e-4 * scale[c:].max()
+
+
+def test_reduced_batch_real_shapes_bf16(oracle, torch_cuda):
+    """Real channel counts and resolutions of the bf16 workloads at a batch the
+    oracle finishes in seconds."""
+    for name, n, gtol in (("c3_stage2", 8, 2e-2), ("c3_stage3", 16, 2e-2), ("c5_stage2", 2, 2e-2),
+                          ("c5_stage4", 8, WIDE_BF16_GRAD_TOL)):
+        cfg = dict(S.STACKS[name], n=n, depth=1)
+        print(f"case {name} n={n}", flush=True)
+        x, params, dy = S.draw_stack(81, **cfg)
+        ref = oracle_reference(oracle, cfg, x, params, dy)
+        out = gpu_run(cfg, x, params, dy)
+        check_against_oracle(oracle, out, ref, x, "bf16", tol=dict(TOL["bf16"], grad=gtol))
+        with oracle.conv_operands("exact"):
+            exact = oracle_reference(oracle, dict(cfg, conv="f32"), x, params, dy)
+        print("  for information, against unrounded float64: dx %.2e" % oracle.rel_l2(out["dx"], exact["dx"]), flush=True)

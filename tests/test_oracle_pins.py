@@ -113,6 +113,41 @@ def test_conv_matches_library_routine(oracle):
         np.testing.assert_allclose(oracle.conv_wgrad(a, g, ks, stride), tw.grad.numpy(), rtol=1e-11, atol=1e-11)
 
 
+def test_bf16_operand_rounding_matches_library_and_definition(oracle):
+    """bfloat16 = float32 with the low 16 bits removed, round to nearest, ties
+    to even.  Checked against the definition on hand-picked values and against
+    a library's float32 -> bfloat16 conversion on random ones."""
+    one = np.float32(1.0)
+    ulp = np.float32(2.0 ** -7)            # spacing of bf16 in [1, 2)
+    cases = {1.0: 1.0, 1.0 + 2.0 ** -9: 1.0, 1.0 + 2.0 ** -8: 1.0,       # tie -> even (1.0)
+             1.0 + 3 * 2.0 ** -8: 1.0 + 2 * 2.0 ** -7,                      # tie -> even (up)
+             1.0 + 2.0 ** -8 + 2.0 ** -20: 1.0 + 2.0 ** -7, -3.1415927: -3.140625, 0.0: 0.0}
+    for v, want in cases.items():
+        assert float(oracle.bf16_round(np.array([v]))[0]) == want, v
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(9)
+    v = (rng.standard_normal(20000) * np.exp(rng.uniform(-20, 20, 20000))).astype(np.float32)
+    ref = torch.tensor(v).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(oracle.bf16_round(v), ref)
+    # the context manager rounds both operands of every convolution routine and nothing else
+    a = rng.standard_normal((2, 3, 5, 5))
+    w = rng.standard_normal((4, 3, 3, 3))
+    g = rng.standard_normal((2, 4, 5, 5))
+    exact = oracle.conv_fwd(oracle.bf16_round(a), oracle.bf16_round(w))
+    with oracle.conv_operands("bf16"):
+        np.testing.assert_array_equal(oracle.conv_fwd(a, w), exact)
+        np.testing.assert_array_equal(oracle.conv_dgrad(g, w, (5, 5)),
+                                      orc_exact(oracle, "dgrad", oracle.bf16_round(g), oracle.bf16_round(w)))
+        np.testing.assert_array_equal(oracle.conv_wgrad(a, g, 3),
+                                      orc_exact(oracle, "wgrad", oracle.bf16_round(a), oracle.bf16_round(g)))
+    assert not np.array_equal(oracle.conv_fwd(a, w), exact)
+
+
+def orc_exact(oracle, which, p, q):
+    with oracle.conv_operands("exact"):
+        return oracle.conv_dgrad(p, q, (5, 5)) if which == "dgrad" else oracle.conv_wgrad(p, q, 3)
+
+
 # --------------------------------------------------------------------------
 # batch norm + ReLU: closed forms and invariants
 # --------------------------------------------------------------------------
