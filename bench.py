@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the reversible-stack hot path on one MI355X.
+
+One step = revnet_stack_fwd + revnet_stack_bwd (reconstructing backward) over
+one synthetic batch that is already resident in HBM.  Default workload: the
+9-block basic stack at N=128, C=32 (16+16), 32x32, fp32 ("c2_stack9").
+
+Prints ONE JSON line: images/s, the roofline of the dominant kernel (per-launch
+duration measured with HIP events on the launch stream, in a separate profiled
+pass of the same steps), the CPU oracle timed beside it on a bounded sample,
+peak activation bytes versus depth and reconstruction error versus depth.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks.
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2500.0, "TFLOP/s"),
+        "alu_f32": (157.3, "TFLOP/s")}
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (profiles/), keyed by (workload, kernel family); None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def bound_of(family: str, conv: str):
+    """Which roof a kernel family is held against."""
+    if family in ("conv_fwd", "conv_dgrad", "conv_wgrad"):
+        return ("mfma", "mfma_bf16" if conv == "bf16" else "mfma_f32")
+    return ("hbm", "hbm")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_stack9")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-n", type=int, default=32, help="batch of the oracle timing sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import StackRunner
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    rv.load_library()  # fails loudly if the HIP library is missing
+
+    cfg, x, params, dy = S.draw_named(args.workload)
+    n, c, h, w, depth, conv = cfg["n"], cfg["c"], cfg["h"], cfg["w"], cfg["depth"], cfg["conv"]
+    r = StackRunner(**cfg)
+    r.set_params(params)
+    torch.cuda.reset_peak_memory_stats()
+    base_alloc = torch.cuda.memory_allocated()
+    X, DY = r.new_pair(x), r.new_pair(dy)     # inputs, read only in every step
+    Y, DX = r.new_pair(), r.new_pair()        # top activations (reconstructed in place), gradients
+    stream = torch.cuda.current_stream()
+
+    def step():
+        r.forward(X, Y, stream)               # x -> y, nothing else kept
+        r.backward(Y, DY, Y, DX, stream=stream)   # y -> x in place; dy -> dx
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = max(wall_ms, ev0.elapsed_time(ev1) / args.steps)
+    peak_alloc = torch.cuda.max_memory_allocated() - base_alloc
+
+    # ---- profiled pass: per-kernel durations with HIP events on the launch stream
+    rv.revnet_profile_begin()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    stats = rv.revnet_profile_end()
+    kern = {}
+    for name, st in stats.items():
+        avg_us = st["total_ms"] * 1e3 / st["launches"]
+        kern[name] = dict(launches_per_step=st["launches"] / args.steps, avg_us=round(avg_us, 3),
+                          ms_per_step=round(st["total_ms"] / args.steps, 4),
+                          GBps=round(st["algorithmic_bytes"] / st["total_ms"] / 1e6, 1) if st["total_ms"] else None,
+                          TFLOPs=round(st["flops"] / st["total_ms"] / 1e9, 2) if st["flops"] else None)
+    dom = max(stats, key=lambda k: stats[k]["total_ms"])
+    bound, peak_key = bound_of(dom, conv)
+    peak, unit = PEAK[peak_key]
+    d = stats[dom]
+    per_launch_s = d["total_ms"] * 1e-3 / d["launches"]
+    quantity = (d["flops"] / 1e12 if bound != "hbm" else d["algorithmic_bytes"] / 1e9) / d["launches"]
+    achieved = quantity / per_launch_s
+    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 2), peak=peak, unit=unit,
+                    frac=round(achieved / peak, 4), avg_launch_us=round(per_launch_s * 1e6, 3),
+                    traffic=MEASURED_TRAFFIC.get((args.workload, dom)))
+
+    # ---- the same totals against the rooflines, whole step
+    fwd_cost, bwd_cost = rv.revnet_stack_cost(r.desc, depth, n, h, w)
+    step_flops = fwd_cost["conv_flops"] + bwd_cost["conv_flops"]
+    step_bytes = fwd_cost["algorithmic_bytes"] + bwd_cost["algorithmic_bytes"]
+
+    # ---- reconstruction error versus depth (input of block k, top block first)
+    drift = None
+    if depth > 1:
+        drift = []
+        fwd_only = []
+        cur = r.new_pair(x)
+        nxt = r.new_pair()
+        for k in range(depth):               # block inputs from a forward pass, one block at a time
+            fwd_only.append(r.to_host(cur[0]).astype(np.float32))
+            rv.revnet_block_fwd(r.desc, cur[1], cur[2], r.params[k], nxt[1], nxt[2], r.ws, stream)
+            cur, nxt = nxt, cur
+        G = r.new_pair(dy)
+        for k in range(depth - 1, -1, -1):
+            rv.revnet_block_bwd_reconstruct(r.desc, cur[1], cur[2], G[1], G[2], r.params[k], cur[1], cur[2],
+                                            G[1], G[2], r.grads[k], 0, r.ws, stream)
+            torch.cuda.synchronize()
+            rec = r.to_host(cur[0])
+            ref = fwd_only[k].astype(np.float64)
+            drift.append(float(np.linalg.norm(rec - ref) / np.linalg.norm(ref)))
+
+    # ---- activation memory versus depth (the workspace query has no depth argument)
+    act = r.activation_bytes()
+    act_vs_depth = {}
+    esz = 2 if conv == "bf16" else 4
+    per_block_stored = 2 * sum(n * h * w * cin * (4 + esz) for cin, _, _ in S.func_layers(cfg["kind"], c // 2, cfg["width"]))
+    for dd in (1, 2, 4, 9, 18, 36):
+        assert rv.revnet_workspace_bytes(r.desc, n, h, w) == (r.fwd_bytes, r.bwd_bytes)
+        act_vs_depth[str(dd)] = {"reversible": act["total"],
+                                 "stored_activation_backprop": 2 * act["stream"] + dd * per_block_stored}
+
+    out = {
+        "metric": "images/sec reversible fwd+bwd per stack on 1 MI355X; peak activation HBM bytes",
+        "value": round(n / (ms_per_step * 1e-3), 1),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if conv == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "kind": cfg["kind"], "n": n, "c": c, "h": h, "w": w,
+                   "depth": depth, "width": cfg["width"], "conv_operands": conv},
+        "roofline": roofline,
+        "step_totals": {"conv_TFLOP": round(step_flops / 1e12, 4), "algorithmic_GB": round(step_bytes / 1e9, 3),
+                        "kernel_launches": fwd_cost["kernel_launches"] + bwd_cost["kernel_launches"],
+                        "achieved_TFLOPs": round(step_flops / 1e12 / (ms_per_step * 1e-3), 2),
+                        "achieved_GBps": round(step_bytes / 1e9 / (ms_per_step * 1e-3), 1)},
+        "kernels": kern,
+        "peak_activation_bytes": {"analytic": act, "torch_max_allocated_over_params": int(peak_alloc),
+                                  "vs_depth": act_vs_depth},
+        "reconstruction_rel_error_top_block_first": drift,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import revnet_oracle as O
+        ns = min(args.cpu_sample_n, n)
+        c2 = c // 2
+        xs, dys = x[:ns], dy[:ns]
+        sp = lambda t: (np.ascontiguousarray(t[:, :c2]), np.ascontiguousarray(t[:, c2:]))
+        O.build()
+        with O.conv_operands(conv):
+            tc0 = time.perf_counter()
+            y1, y2, _, stored = O.stack_fwd(*sp(xs), params, keep=True)
+            O.stack_bwd_stored(stored, params, *sp(dys))
+            tc1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": round(ns / (tc1 - tc0), 2), "unit": "images/s", "cores": O.num_threads(),
+                               "kind": "oracle", "seconds": round(tc1 - tc0, 2),
+                               "sample": f"first {ns} of {n} images, same C/H/W/depth, one forward + "
+                                         "stored-activation backward in float64"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

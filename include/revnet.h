@@ -219,6 +219,29 @@ int revnet_stack_cost(const rvn_block_desc *desc, int32_t depth,
                       int64_t n, int64_t h, int64_t w,
                       rvn_cost *fwd, rvn_cost *bwd);
 
+/*
+ * Per-kernel timing for roofline reports (not part of the paper's method).
+ * Between revnet_profile_begin() and revnet_profile_end() every kernel the
+ * library launches is bracketed by HIP events on the stream it is launched
+ * on.  revnet_profile_end() waits for those events and returns, per kernel
+ * family that ran, the number of launches, their summed duration, and the
+ * summed algorithmic bytes and flops (the same figures revnet_stack_cost
+ * counts).  stats: host array of max_stats entries; *n_stats receives the
+ * number of families that ran.  `name` points to static storage.  Process
+ * wide; events cost a few microseconds per launch, so time throughput in a
+ * separate pass.
+ */
+typedef struct {
+    const char *name;
+    int64_t launches;
+    double total_ms;
+    double algorithmic_bytes;
+    double flops;
+} rvn_kernel_stat;
+
+int revnet_profile_begin(void);
+int revnet_profile_end(rvn_kernel_stat *stats, int32_t max_stats, int32_t *n_stats);
+
 /* Message for the calling thread's most recent failing call ("" if none).
  * The storage is thread local and valid until that thread's next call. */
 const char *revnet_last_error(void);

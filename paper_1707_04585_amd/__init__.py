@@ -5,6 +5,6 @@ ABI of ``include/revnet.h``; this package only marshals arguments.
 """
 from .binding import (  # noqa: F401
     BASIC, BOTTLENECK, BF16, F32, BlockDesc, RevnetError, lib_path, load_library, pack_grads,
-    pack_params, revnet_block_bwd_reconstruct, revnet_block_fwd, revnet_last_error,
+    pack_params, revnet_block_bwd_reconstruct, revnet_block_fwd, revnet_last_error, revnet_profile_begin, revnet_profile_end,
     revnet_stack_bwd, revnet_stack_cost, revnet_stack_fwd, revnet_version, revnet_workspace_bytes,
 )

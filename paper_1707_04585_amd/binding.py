@@ -21,6 +21,7 @@ BASIC, BOTTLENECK = 0, 1
 EXPORTS = [
     "revnet_workspace_bytes", "revnet_block_fwd", "revnet_block_bwd_reconstruct", "revnet_stack_fwd",
     "revnet_stack_bwd", "revnet_stack_cost", "revnet_last_error", "revnet_version",
+    "revnet_profile_begin", "revnet_profile_end",
 ]
 
 
@@ -53,6 +54,11 @@ class rvn_cost(C.Structure):
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class rvn_kernel_stat(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int64), ("total_ms", C.c_double),
+                ("algorithmic_bytes", C.c_double), ("flops", C.c_double)]
 
 
 def lib_path() -> str:
@@ -221,3 +227,19 @@ def revnet_stack_cost(desc, depth, n, h, w):
     _check(load_library().revnet_stack_cost(C.byref(d), C.c_int32(depth), C.c_int64(n), C.c_int64(h),
                                             C.c_int64(w), C.byref(fwd), C.byref(bwd)))
     return fwd.as_dict(), bwd.as_dict()
+
+
+def revnet_profile_begin():
+    _check(load_library().revnet_profile_begin())
+
+
+def revnet_profile_end():
+    """-> {kernel family: dict(launches, total_ms, algorithmic_bytes, flops)}"""
+    stats = (rvn_kernel_stat * 32)()
+    n = C.c_int32(0)
+    rc = load_library().revnet_profile_end(stats, C.c_int32(32), C.byref(n))
+    if rc != 0:
+        raise RevnetError(rc, "event timing failed")
+    return {stats[i].name.decode(): dict(launches=stats[i].launches, total_ms=stats[i].total_ms,
+                                         algorithmic_bytes=stats[i].algorithmic_bytes, flops=stats[i].flops)
+            for i in range(min(n.value, 32))}

@@ -297,7 +297,7 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *m
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double bytes = 4.0 * (double)g.pixels() * c;
-    if (cx.launch(bytes)) {
+    if (cx.launch(K_BN_STATS, bytes)) {
         dim3 grid(S, c);
         if (vec_ok(x, g.hw()))
             bn_stats_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
@@ -305,7 +305,7 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *m
             bn_stats_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
         cx.check();
     }
-    if (cx.launch(0.0)) {
+    if (cx.launch(K_BN_STATS_FINALIZE, 0.0)) {
         bn_stats_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, eps, mean_rstd);
         cx.check();
     }
@@ -314,7 +314,7 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *m
 void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float *beta,
                  const float *mean_rstd, void *a, rvn_dtype dt) {
     const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
-    if (!cx.launch((4.0 + esz) * (double)g.pixels() * c)) return;
+    if (!cx.launch(K_BN_RELU_FWD, (4.0 + esz) * (double)g.pixels() * c)) return;
     const bool vec = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(a) & 15) == 0;
     const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
     const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
@@ -336,7 +336,7 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *ga
     const double t = 4.0 * (double)g.pixels() * c;
     float *coef = scratch + (size_t)c * S * 3;
     const bool vec_in = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(da) & 15) == 0;
-    if (cx.launch(2.0 * t)) {
+    if (cx.launch(K_BN_BWD_REDUCE, 2.0 * t)) {
         dim3 grid(S, c);
         if (vec_in)
             bn_bwd_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
@@ -344,11 +344,11 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *ga
             bn_bwd_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
         cx.check();
     }
-    if (cx.launch(0.0)) {
+    if (cx.launch(K_BN_BWD_FINALIZE, 0.0)) {
         bn_bwd_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, 1.0 / (double)g.pixels(), dgamma, dbeta, accumulate ? 1 : 0, coef);
         cx.check();
     }
-    if (cx.launch((skip ? 4.0 : 3.0) * t)) {
+    if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : 3.0) * t)) {
         const bool vec = vec_in && vec_ok(out, g.hw()) && (!skip || vec_ok(*skip, g.hw()));
         const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
         const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);

@@ -227,9 +227,10 @@ void conv_fwd(Ctx &cx, const void *a, rvn_dtype dt, const float *w, int cin, int
               Geo g, Epilogue ep, const View *r, View out) {
     const double P = (double)g.pixels();
     const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
+    const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_fwd_calls += 1;
-    cx.cost.conv_flops += 2.0 * P * cin * cout * ks * ks;
-    if (!cx.launch(P * cin * esz + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0))) return;
+    cx.cost.conv_flops += flops;
+    if (!cx.launch(K_CONV_FWD, P * cin * esz + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
     conv_common(cx, a, dt == RVN_BF16, (int64_t)cin * g.hw(), g.hw(), false, dt == RVN_BF16, false, w,
                 cin, cout, ks, g, ep, r, out);
 }
@@ -237,9 +238,10 @@ void conv_fwd(Ctx &cx, const void *a, rvn_dtype dt, const float *w, int cin, int
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
                 float *da) {
     const double P = (double)g.pixels();
+    const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_dgrad_calls += 1;
-    cx.cost.conv_flops += 2.0 * P * cin * cout * ks * ks;
-    if (!cx.launch(P * cout * 4.0 + P * cin * 4.0)) return;
+    cx.cost.conv_flops += flops;
+    if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops)) return;
     // The "input" of this convolution is dh with `cout` channels; it produces `cin` channels.
     conv_common(cx, dh.p, false, dh.sn, dh.sc, dt == RVN_BF16, dt == RVN_BF16, true, w, cout, cin, ks, g,
                 EP_STORE, nullptr, dense_view(da, cin, g));
@@ -249,11 +251,12 @@ void conv_wgrad(Ctx &cx, const void *a, rvn_dtype dt, View dh, int cin, int cout
                 float *scratch, float *dw, bool accumulate) {
     const double P = (double)g.pixels();
     const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
+    const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_wgrad_calls += 1;
-    cx.cost.conv_flops += 2.0 * P * cin * cout * ks * ks;
+    cx.cost.conv_flops += flops;
     const int S = wgrad_splits(cin, cout, g);
     const int ipw = (g.n + S - 1) / S;
-    if (cx.launch(P * cin * esz + P * cout * 4.0)) {
+    if (cx.launch(K_CONV_WGRAD, P * cin * esz + P * cout * 4.0, flops)) {
         dim3 grid(cout, (cin + kCT - 1) / kCT, S);
 #define RVN_LAUNCH(KS, T)                                                                   \
     wgrad_direct_partial_k<KS, T><<<grid, kThreads, 0, cx.stream>>>(                        \
@@ -269,7 +272,7 @@ void conv_wgrad(Ctx &cx, const void *a, rvn_dtype dt, View dh, int cin, int cout
 #undef RVN_LAUNCH
         cx.check();
     }
-    if (cx.launch(0.0)) {
+    if (cx.launch(K_WGRAD_REDUCE, 0.0)) {
         const int64_t count = (int64_t)cin * cout * ks * ks;
         reduce_partials_k<<<(unsigned)((count + 255) / 256), 256, 0, cx.stream>>>(scratch, count, S, dw, accumulate ? 1 : 0);
         cx.check();

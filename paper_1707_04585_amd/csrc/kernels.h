@@ -31,21 +31,54 @@ inline View dense_view(float *p, int c, const Geo &g) {
 // (reconstruction).
 enum Epilogue { EP_STORE = 0, EP_ADD = 1, EP_SUB = 2 };
 
+// Kernel families, for launch accounting and the optional event profiler.
+enum KernelId {
+    K_BN_STATS = 0,
+    K_BN_STATS_FINALIZE,
+    K_BN_RELU_FWD,
+    K_CONV_FWD,
+    K_CONV_DGRAD,
+    K_CONV_WGRAD,
+    K_WGRAD_REDUCE,
+    K_BN_BWD_REDUCE,
+    K_BN_BWD_FINALIZE,
+    K_BN_BWD_APPLY,
+    K_COUNT
+};
+const char *kernel_name(int id);
+
+// Optional per-launch timing with HIP events on the caller's stream
+// (revnet_profile_begin / revnet_profile_end).
+void profile_mark_begin(int id, double bytes, double flops, hipStream_t stream);
+void profile_mark_end(hipStream_t stream);
+bool profile_enabled();
+
 // One call's launch context.  With dry == true the wrappers only count.
 struct Ctx {
     hipStream_t stream = nullptr;
     bool dry = false;
     rvn_cost cost = {};
     hipError_t err = hipSuccess;
+    bool marked = false;
 
-    // Record one kernel launch moving `bytes` algorithmic bytes; returns true
-    // if the kernel should really be launched.
-    bool launch(double bytes) {
+    // Record one kernel launch of family `id` that must move `bytes`
+    // algorithmic bytes and perform `flops`; returns true if the kernel should
+    // really be launched (then call check() right after the launch).
+    bool launch(int id, double bytes, double flops = 0.0) {
         cost.kernel_launches += 1;
         cost.algorithmic_bytes += bytes;
-        return !dry && err == hipSuccess;
+        const bool go = !dry && err == hipSuccess;
+        if (go && profile_enabled()) {
+            profile_mark_begin(id, bytes, flops, stream);
+            marked = true;
+        }
+        return go;
     }
     void check() {
+        if (marked) {
+            profile_mark_end(stream);
+            marked = false;
+        }
         if (!dry && err == hipSuccess) err = hipGetLastError();
     }
 };

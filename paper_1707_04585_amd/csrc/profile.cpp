@@ -1,0 +1,108 @@
+// Optional per-kernel timing with HIP events, for roofline reports.
+//
+// While enabled, every kernel launch of the library is bracketed by a pair of
+// events recorded on the stream the kernel is launched on.  The events come
+// from a pool that grows on demand (host allocations only; no device memory).
+// Profiling perturbs timing slightly and is meant for a separate pass.
+#include <mutex>
+#include <vector>
+
+#include "kernels.h"
+
+namespace rvn {
+namespace {
+
+struct Mark {
+    int id;
+    double bytes, flops;
+    hipEvent_t start, stop;
+};
+
+std::mutex g_mu;
+bool g_on = false;
+std::vector<Mark> g_marks;
+std::vector<hipEvent_t> g_pool;
+
+hipEvent_t take_event() {
+    if (!g_pool.empty()) {
+        hipEvent_t e = g_pool.back();
+        g_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+const char *const kNames[K_COUNT] = {
+    "bn_stats_partial_k", "bn_stats_finalize_k", "bn_relu_fwd_k", "conv_fwd", "conv_dgrad",
+    "conv_wgrad", "reduce_partials_k", "bn_bwd_partial_k", "bn_bwd_finalize_k", "bn_bwd_apply_k",
+};
+
+}  // namespace
+
+const char *kernel_name(int id) { return id >= 0 && id < K_COUNT ? kNames[id] : "?"; }
+
+bool profile_enabled() { return g_on; }
+
+void profile_mark_begin(int id, double bytes, double flops, hipStream_t stream) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    Mark m{id, bytes, flops, take_event(), take_event()};
+    (void)hipEventRecord(m.start, stream);
+    g_marks.push_back(m);
+}
+
+void profile_mark_end(hipStream_t stream) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_marks.empty()) (void)hipEventRecord(g_marks.back().stop, stream);
+}
+
+}  // namespace rvn
+
+using namespace rvn;
+
+extern "C" {
+
+int revnet_profile_begin(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (Mark &m : g_marks) {
+        g_pool.push_back(m.start);
+        g_pool.push_back(m.stop);
+    }
+    g_marks.clear();
+    g_on = true;
+    return RVN_OK;
+}
+
+int revnet_profile_end(rvn_kernel_stat *stats, int32_t max_stats, int32_t *n_stats) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_on = false;
+    rvn_kernel_stat acc[K_COUNT] = {};
+    hipError_t err = hipSuccess;
+    for (Mark &m : g_marks) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(m.stop);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, m.start, m.stop);
+        if (e != hipSuccess) err = e;
+        acc[m.id].launches += 1;
+        acc[m.id].total_ms += ms;
+        acc[m.id].algorithmic_bytes += m.bytes;
+        acc[m.id].flops += m.flops;
+        g_pool.push_back(m.start);
+        g_pool.push_back(m.stop);
+    }
+    g_marks.clear();
+    int32_t n = 0;
+    for (int id = 0; id < K_COUNT; ++id) {
+        if (!acc[id].launches) continue;
+        if (stats && n < max_stats) {
+            acc[id].name = kernel_name(id);
+            stats[n] = acc[id];
+        }
+        ++n;
+    }
+    if (n_stats) *n_stats = n;
+    return err == hipSuccess ? RVN_OK : RVN_ERR_HIP;
+}
+
+}  // extern "C"
