@@ -94,7 +94,8 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_k(const float *__re
 // Merge the S partials of each channel pairwise-in-order (Chan et al.) in
 // double precision; one thread per channel.
 __global__ void bn_stats_finalize_k(const float *__restrict__ partial, int C, int S, float eps,
-                                    float *__restrict__ mean_rstd) {
+                                    const float *__restrict__ gamma, const float *__restrict__ beta,
+                                    float *__restrict__ stats) {
     const int ch = blockIdx.x * blockDim.x + threadIdx.x;
     if (ch >= C) return;
     const float *p = partial + (int64_t)ch * S * 3;
@@ -106,8 +107,13 @@ __global__ void bn_stats_finalize_k(const float *__restrict__ partial, int C, in
         m2 += m2b + delta * delta * n * nb / tot;
         n = tot;
     }
-    mean_rstd[ch] = (float)mean;
-    mean_rstd[C + ch] = (float)(1.0 / sqrt(m2 / n + (double)eps));
+    const float mean_f = (float)mean;
+    const float rstd_f = (float)(1.0 / sqrt(m2 / n + (double)eps));
+    const float scale = gamma[ch] * rstd_f;
+    stats[ch] = mean_f;
+    stats[C + ch] = rstd_f;
+    stats[2 * C + ch] = scale;
+    stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
 }
 
 // ---------------------------------------------------------------------------
@@ -117,9 +123,7 @@ template <bool VEC, bool BF16>
 __global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restrict__ x, int64_t sn,
                                                           int64_t sc, int C, int HW,
                                                           int64_t total /* work items */,
-                                                          const float *__restrict__ gamma,
-                                                          const float *__restrict__ beta,
-                                                          const float *__restrict__ mean_rstd,
+                                                          const float *__restrict__ stats,
                                                           void *__restrict__ out) {
     constexpr int E = VEC ? 4 : 1;
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -128,8 +132,7 @@ __global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restric
     const int64_t plane = v / per_plane;
     const int i = (int)(v - plane * per_plane) * E;
     const int n = (int)(plane / C), ch = (int)(plane - (int64_t)n * C);
-    const float scale = gamma[ch] * mean_rstd[C + ch];
-    const float shift = fmaf(-mean_rstd[ch], scale, beta[ch]);
+    const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
     const float *src = x + (int64_t)n * sn + (int64_t)ch * sc + i;
     const int64_t dst = plane * HW + i;
     if (VEC) {
@@ -162,14 +165,12 @@ __global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restric
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_partial_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *__restrict__ da, int N, int C,
-    int HW, int ipw, const float *__restrict__ gamma, const float *__restrict__ beta,
-    const float *__restrict__ mean_rstd, float *__restrict__ partial) {
+    int HW, int ipw, const float *__restrict__ stats, float *__restrict__ partial) {
     __shared__ float lds[8];
     const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x;
     const int n0 = s * ipw, n1 = min(N, n0 + ipw);
-    const float mean = mean_rstd[ch], rstd = mean_rstd[C + ch];
-    const float scale = gamma[ch] * rstd;
-    const float shift = fmaf(-mean, scale, beta[ch]);
+    const float mean = stats[ch], rstd = stats[C + ch];
+    const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
     float acc[2] = {0.f, 0.f};
     for (int n = n0; n < n1; ++n) {
         const float *px = x + (int64_t)n * sn + (int64_t)ch * sc;
@@ -232,8 +233,7 @@ __global__ void bn_bwd_finalize_k(const float *__restrict__ partial, int C, int 
 template <bool VEC, bool SKIP>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
-    int64_t total, const float *__restrict__ gamma, const float *__restrict__ beta,
-    const float *__restrict__ mean_rstd, const float *__restrict__ coef, const float *skip,
+    int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
     int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc) {
     constexpr int E = VEC ? 4 : 1;
     const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -242,9 +242,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const int64_t plane = v / per_plane;
     const int i = (int)(v - plane * per_plane) * E;
     const int n = (int)(plane / C), ch = (int)(plane - (int64_t)n * C);
-    const float mean = mean_rstd[ch], rstd = mean_rstd[C + ch];
-    const float scale = gamma[ch] * rstd;
-    const float shift = fmaf(-mean, scale, beta[ch]);
+    const float mean = stats[ch], rstd = stats[C + ch];
+    const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
     const float c1 = coef[ch], c2 = coef[C + ch];
     const float *px = x + (int64_t)n * sn + (int64_t)ch * sc + i;
     const float *pd = da + plane * HW + i;
@@ -293,7 +292,8 @@ size_t bn_scratch_floats(int c, const Geo &g) {
     return (size_t)c * reduce_splits(c, g) * 3 + 2 * (size_t)c;
 }
 
-void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *mean_rstd) {
+void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
+              float *scratch, float *stats) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double bytes = 4.0 * (double)g.pixels() * c;
@@ -306,20 +306,19 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *m
         cx.check();
     }
     if (cx.launch(K_BN_STATS_FINALIZE, 0.0)) {
-        bn_stats_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, eps, mean_rstd);
+        bn_stats_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, eps, gamma, beta, stats);
         cx.check();
     }
 }
 
-void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float *beta,
-                 const float *mean_rstd, void *a, rvn_dtype dt) {
+void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn_dtype dt) {
     const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
     if (!cx.launch(K_BN_RELU_FWD, (4.0 + esz) * (double)g.pixels() * c)) return;
     const bool vec = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(a) & 15) == 0;
     const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
     const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
 #define RVN_LAUNCH(V, B) \
-    bn_relu_fwd_k<V, B><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, c, g.hw(), total, gamma, beta, mean_rstd, a)
+    bn_relu_fwd_k<V, B><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, c, g.hw(), total, stats, a)
     if (vec && dt == RVN_BF16) RVN_LAUNCH(true, true);
     else if (vec) RVN_LAUNCH(true, false);
     else if (dt == RVN_BF16) RVN_LAUNCH(false, true);
@@ -328,9 +327,8 @@ void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float 
     cx.check();
 }
 
-void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *gamma,
-                 const float *beta, const float *mean_rstd, float *scratch, float *dgamma,
-                 float *dbeta, bool accumulate, const View *skip, View out) {
+void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
+                 float *dgamma, float *dbeta, bool accumulate, const View *skip, View out) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double t = 4.0 * (double)g.pixels() * c;
@@ -339,9 +337,9 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *ga
     if (cx.launch(K_BN_BWD_REDUCE, 2.0 * t)) {
         dim3 grid(S, c);
         if (vec_in)
-            bn_bwd_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
+            bn_bwd_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch);
         else
-            bn_bwd_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, gamma, beta, mean_rstd, scratch);
+            bn_bwd_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch);
         cx.check();
     }
     if (cx.launch(K_BN_BWD_FINALIZE, 0.0)) {
@@ -355,7 +353,7 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *ga
         const float *kp = skip ? skip->p : nullptr;
         const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
 #define RVN_LAUNCH(V, K) \
-    bn_bwd_apply_k<V, K><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, c, g.hw(), total, gamma, beta, mean_rstd, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
+    bn_bwd_apply_k<V, K><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);

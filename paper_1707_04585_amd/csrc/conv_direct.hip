@@ -1,11 +1,9 @@
-// Shape-generic direct convolutions (vector ALU, no matrix cores) for gfx950.
+// Shape-generic filter gradient on the vector ALU (no matrix cores) for gfx950.
 //
-// These kernels accept every (c_in, c_out, k in {1,3}, h, w) the residual
-// functions of Section 2.2 can ask for.  They are the path for shapes the
-// matrix-core kernels do not cover.  Operands of a bf16 convolution are
-// rounded to bf16 (nearest even) and multiplied in fp32, which is what a
-// bf16 matrix instruction with fp32 accumulation computes up to summation
-// order.
+// Accepts every (c_in, c_out, k in {1,3}, h, w) the residual functions of
+// Section 2.2 can ask for.  Operands of a bf16 convolution are rounded to bf16
+// (nearest even) and multiplied in fp32, which is what a bf16 matrix
+// instruction with fp32 accumulation computes up to summation order.
 #include "kernels.h"
 
 namespace rvn {
@@ -13,8 +11,6 @@ namespace rvn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kCoT = 8;      // output channels per thread
-constexpr int kCiChunk = 32; // input channels staged per LDS round
 
 __device__ __forceinline__ float bf16_round(float f) {
     uint32_t u = __float_as_uint(f);
@@ -32,87 +28,6 @@ __device__ __forceinline__ float load_elem<float>(const float *p, int64_t i) {
 template <>
 __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t *p, int64_t i) {
     return __uint_as_float((uint32_t)p[i] << 16);
-}
-
-// out[n, o, p, q] = ep(r, sum_{i,r,s} in[n, i, p+r-pad, q+s-pad] * wt(o, i, r, s))
-// with wt(o,i,r,s) = w[o][i][r][s]                       (forward,  TRANSPOSED = false)
-//                  = w[i][o][KS-1-r][KS-1-s]             (data grad, TRANSPOSED = true)
-// The data gradient of a stride-1 "same" convolution is itself such a
-// convolution of the upstream gradient with the transposed, flipped filter.
-template <int KS, typename TIN, bool TRANSPOSED>
-__global__ __launch_bounds__(kThreads) void conv_direct_k(
-    const TIN *__restrict__ in, int64_t isn, int64_t isc, int round_in, int round_w,
-    const float *__restrict__ w, int CI, int CO, int N, int H, int W, int ep, const float *r,
-    int64_t rsn, int64_t rsc, float *out, int64_t osn, int64_t osc) {
-    __shared__ float wl[kCiChunk * KS * KS * kCoT];
-    const int HW = H * W;
-    const int64_t pix = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const bool live = pix < (int64_t)N * HW;
-    const int n = live ? (int)(pix / HW) : 0;
-    const int i_pl = live ? (int)(pix - (int64_t)n * HW) : 0;
-    const int row = i_pl / W, col = i_pl - row * W;
-    const int o0 = blockIdx.y * kCoT;
-    constexpr int PAD = (KS - 1) / 2;
-
-    float acc[kCoT];
-#pragma unroll
-    for (int j = 0; j < kCoT; ++j) acc[j] = 0.f;
-
-    for (int c0 = 0; c0 < CI; c0 += kCiChunk) {
-        const int cn = min(kCiChunk, CI - c0);
-        __syncthreads();
-        for (int e = threadIdx.x; e < cn * KS * KS * kCoT; e += kThreads) {
-            const int j = e % kCoT;
-            const int t = (e / kCoT) % (KS * KS);
-            const int ci = e / (kCoT * KS * KS);
-            const int o = o0 + j, i = c0 + ci;
-            float v = 0.f;
-            if (o < CO) {
-                if (TRANSPOSED) {
-                    const int rr = KS - 1 - t / KS, ss = KS - 1 - t % KS;
-                    v = w[((int64_t)i * CO + o) * (KS * KS) + rr * KS + ss];
-                } else {
-                    v = w[((int64_t)o * CI + i) * (KS * KS) + t];
-                }
-                if (round_w) v = bf16_round(v);
-            }
-            wl[e] = v;
-        }
-        __syncthreads();
-        if (live) {
-            const TIN *src = in + (int64_t)n * isn + (int64_t)c0 * isc;
-            for (int ci = 0; ci < cn; ++ci) {
-#pragma unroll
-                for (int rr = 0; rr < KS; ++rr) {
-                    const int ih = row + rr - PAD;
-#pragma unroll
-                    for (int ss = 0; ss < KS; ++ss) {
-                        const int iw = col + ss - PAD;
-                        float v = 0.f;
-                        if (ih >= 0 && ih < H && iw >= 0 && iw < W) {
-                            v = load_elem<TIN>(src, (int64_t)ci * isc + ih * W + iw);
-                            if (round_in) v = bf16_round(v);
-                        }
-                        const float *wp = &wl[(ci * KS * KS + rr * KS + ss) * kCoT];
-#pragma unroll
-                        for (int j = 0; j < kCoT; ++j) acc[j] = fmaf(v, wp[j], acc[j]);
-                    }
-                }
-            }
-        }
-    }
-    if (!live) return;
-#pragma unroll
-    for (int j = 0; j < kCoT; ++j) {
-        const int o = o0 + j;
-        if (o >= CO) break;
-        float v = acc[j];
-        if (ep != EP_STORE) {
-            const float rv = r[(int64_t)n * rsn + (int64_t)o * rsc + i_pl];
-            v = ep == EP_ADD ? rv + v : rv - v;
-        }
-        out[(int64_t)n * osn + (int64_t)o * osc + i_pl] = v;
-    }
 }
 
 // Filter gradient, partial over an image group:
@@ -198,53 +113,6 @@ int wgrad_splits(int cin, int cout, const Geo &g) {
 
 size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g) {
     return (size_t)wgrad_splits(cin, cout, g) * cin * cout * ks * ks;
-}
-
-static void conv_common(Ctx &cx, const void *in, bool in_bf16_storage, int64_t isn, int64_t isc,
-                        bool round_in, bool round_w, bool transposed, const float *w, int ci, int co,
-                        int ks, Geo g, Epilogue ep, const View *r, View out) {
-    dim3 grid((unsigned)((g.pixels() + kThreads - 1) / kThreads), (co + kCoT - 1) / kCoT);
-    const float *rp = r ? r->p : nullptr;
-    const int64_t rsn = r ? r->sn : 0, rsc = r ? r->sc : 0;
-#define RVN_LAUNCH(KS, T, TR)                                                                      \
-    conv_direct_k<KS, T, TR><<<grid, kThreads, 0, cx.stream>>>(                                    \
-        static_cast<const T *>(in), isn, isc, round_in ? 1 : 0, round_w ? 1 : 0, w, ci, co, g.n, g.h, \
-        g.w, (int)ep, rp, rsn, rsc, out.p, out.sn, out.sc)
-    if (ks == 3) {
-        if (transposed) RVN_LAUNCH(3, float, true);
-        else if (in_bf16_storage) RVN_LAUNCH(3, uint16_t, false);
-        else RVN_LAUNCH(3, float, false);
-    } else {
-        if (transposed) RVN_LAUNCH(1, float, true);
-        else if (in_bf16_storage) RVN_LAUNCH(1, uint16_t, false);
-        else RVN_LAUNCH(1, float, false);
-    }
-#undef RVN_LAUNCH
-    cx.check();
-}
-
-void conv_fwd(Ctx &cx, const void *a, rvn_dtype dt, const float *w, int cin, int cout, int ks,
-              Geo g, Epilogue ep, const View *r, View out) {
-    const double P = (double)g.pixels();
-    const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
-    const double flops = 2.0 * P * cin * cout * ks * ks;
-    cx.cost.conv_fwd_calls += 1;
-    cx.cost.conv_flops += flops;
-    if (!cx.launch(K_CONV_FWD, P * cin * esz + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
-    conv_common(cx, a, dt == RVN_BF16, (int64_t)cin * g.hw(), g.hw(), false, dt == RVN_BF16, false, w,
-                cin, cout, ks, g, ep, r, out);
-}
-
-void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
-                float *da) {
-    const double P = (double)g.pixels();
-    const double flops = 2.0 * P * cin * cout * ks * ks;
-    cx.cost.conv_dgrad_calls += 1;
-    cx.cost.conv_flops += flops;
-    if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops)) return;
-    // The "input" of this convolution is dh with `cout` channels; it produces `cin` channels.
-    conv_common(cx, dh.p, false, dh.sn, dh.sc, dt == RVN_BF16, dt == RVN_BF16, true, w, cout, cin, ks, g,
-                EP_STORE, nullptr, dense_view(da, cin, g));
 }
 
 void conv_wgrad(Ctx &cx, const void *a, rvn_dtype dt, View dh, int cin, int cout, int ks, Geo g,

@@ -92,26 +92,32 @@ size_t bn_scratch_floats(int c, const Geo &g);
 size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g);
 
 // ---- batch norm + ReLU (Section 2.2: a(x) = ReLU(BN(x))) -------------------
-// mean_rstd[0..c) = batch mean, mean_rstd[c..2c) = 1/sqrt(biased var + eps).
-void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, float *scratch, float *mean_rstd);
+// Per-channel statistics of x and the affine map they imply.  stats holds four
+// arrays of c floats: batch mean, rstd = 1/sqrt(biased var + eps),
+// scale = gamma*rstd, shift = beta - mean*scale, so that
+// a(x) = max(x*scale + shift, 0).  Every consumer evaluates that one
+// expression (one fma), which keeps the ReLU decisions of the forward pass, the
+// recomputation and the backward pass identical.
+constexpr int kStatsArrays = 4;
+void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
+              float *scratch, float *stats);
 
-// a = max(gamma * (x - mean) * rstd + beta, 0), written dense [n][c][h*w] as
-// fp32 or bf16 (round to nearest even) according to `dt`.
-void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *gamma, const float *beta,
-                 const float *mean_rstd, void *a, rvn_dtype dt);
+// a = max(x*scale + shift, 0), written dense [n][c][h*w] as fp32 or bf16
+// (round to nearest even) according to `dt`.
+void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn_dtype dt);
 
 // Backward of a(x) given da (dense fp32): writes dgamma, dbeta (added to when
 // accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
 // `da` (dense in-place) or `skip`.
-void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *gamma,
-                 const float *beta, const float *mean_rstd, float *scratch, float *dgamma,
-                 float *dbeta, bool accumulate, const View *skip, View out);
+void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
+                 float *dgamma, float *dbeta, bool accumulate, const View *skip, View out);
 
 // ---- convolutions (Section 2.2: c_k(x) = Conv_kxk(a(x)), k in {1,3}) -------
-// out = ep(r, conv(a, w)); a is dense [n][cin][h*w] in `dt`; w is fp32
-// [cout][cin][ks][ks], rounded to bf16 on load when dt == RVN_BF16.
-void conv_fwd(Ctx &cx, const void *a, rvn_dtype dt, const float *w, int cin, int cout, int ks,
-              Geo g, Epilogue ep, const View *r, View out);
+// out = ep(r, conv(a(x), w)) with a(x) = max(x*scale + shift, 0) formed on the
+// fly from stats (scale_shift = stats + 2*cin); w is fp32 [cout][cin][ks][ks].
+// With dt == RVN_BF16 both operands are rounded to bf16 before multiplying.
+void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, int cin,
+              int cout, int ks, Geo g, Epilogue ep, const View *r, View out);
 
 // da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
 // dh is fp32, rounded to bf16 on load when dt == RVN_BF16.

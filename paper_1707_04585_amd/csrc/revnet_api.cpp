@@ -68,7 +68,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Plan {
     int L;
     Layer layers[3];
-    size_t stats[3];      // 2*cin floats each: batch mean, 1/sqrt(var+eps)
+    size_t stats[3];      // kStatsArrays*cin floats each: mean, rstd, scale, shift
     size_t bn_scratch;    // partial sums of the per-channel reductions
     size_t wgrad_scratch; // partial filter gradients (backward only)
     size_t a[3];          // a_l = ReLU(BN(x_l)), conv operand precision
@@ -86,7 +86,7 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     for (int l = 0; l < p.L; ++l) {
         const Layer &ly = p.layers[l];
         p.stats[l] = off;
-        off = align_up(off + 2 * (size_t)ly.cin * 4);
+        off = align_up(off + kStatsArrays * (size_t)ly.cin * 4);
         bn_s = std::max(bn_s, bn_scratch_floats(ly.cin, g));
         wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
         max_cin = std::max(max_cin, (size_t)ly.cin);
@@ -110,13 +110,14 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
             off = align_up(off + P * max_cin * 4);
         }
     } else {
-        // Forward keeps nothing: one operand buffer and one intermediate.
-        const size_t a0 = off;
-        off = align_up(off + P * max_cin * esz);
+        // Forward keeps nothing: a(x) is formed inside the convolution, and one
+        // intermediate buffer is enough (h_l is dead once conv l+1 has run).
         const size_t h0 = off;
         off = align_up(off + P * max_mid * 4);
-        for (int l = 0; l < 3; ++l) p.a[l] = a0;
-        for (int l = 0; l < 2; ++l) p.h[l] = h0;
+        const size_t h1 = off;
+        if (p.L > 2) off = align_up(off + P * max_mid * 4);
+        p.h[0] = h0;
+        p.h[1] = p.L > 2 ? h1 : h0;
     }
     p.total = off;
     return p;
@@ -229,20 +230,22 @@ int check_ws(const void *ws, size_t have, size_t need) {
 
 // ---- residual function drivers ----------------------------------------------
 
-// out = ep(r, Func(x)); leaves a_l, h_l and the BN statistics in `b`.
+// out = ep(r, Func(x)); leaves h_l and the BN statistics in `b` (and, when
+// keep_a, the conv operands a_l the filter-gradient kernel reads).
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
-                  const rvn_func_params &p, Epilogue ep, const View *r, View out) {
+                  const rvn_func_params &p, Epilogue ep, const View *r, View out, bool keep_a) {
     View cur = x;
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
-        bn_stats(cx, cur, ly.cin, g, d.bn_eps, b.bn_scratch, b.stats[l]);
-        bn_relu_fwd(cx, cur, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.a[l], d.conv_dtype);
+        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.stats[l]);
+        if (keep_a) bn_relu_fwd(cx, cur, ly.cin, g, b.stats[l], b.a[l], d.conv_dtype);
+        const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
-            conv_fwd(cx, b.a[l], d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
             cur = h;
         } else {
-            conv_fwd(cx, b.a[l], d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
         }
     }
 }
@@ -263,13 +266,13 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         if (l > 0) {
             View xl = dense_view(b.h[l - 1], ly.cin, g);
             View dx = dense_view(da, ly.cin, g);
-            bn_relu_bwd(cx, xl, da, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.bn_scratch,
-                        gr.d_bn_gamma[l], gr.d_bn_beta[l], accumulate, nullptr, dx);
+            bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+                        accumulate, nullptr, dx);
             dh = dx;
             cur ^= 1;
         } else {
-            bn_relu_bwd(cx, x, da, ly.cin, g, p.bn_gamma[l], p.bn_beta[l], b.stats[l], b.bn_scratch,
-                        gr.d_bn_gamma[l], gr.d_bn_beta[l], accumulate, &skip, out);
+            bn_relu_bwd(cx, x, da, ly.cin, g, b.stats[l], b.bn_scratch, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+                        accumulate, &skip, out);
         }
     }
 }
@@ -277,8 +280,8 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
 // Section 3.1: y1 = x1 + F(x2); y2 = x2 + G(y1).
 void block_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x1,
                    View x2, const rvn_block_params &p, View y1, View y2) {
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1);
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2);
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1, false);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2, false);
 }
 
 // Section 3.2, Algorithm 1, with G handled completely before F.
@@ -286,11 +289,11 @@ void block_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs
                     View y2, View dy1, View dy2, const rvn_block_params &p, View x1, View x2, View dx1,
                     View dx2, const rvn_block_grads &gr, bool accumulate) {
     // z1 = y1;  x2 = y2 - G(z1)
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2, true);
     // dz1 = dy1 + (dG/dz1)^T dy2;  dwG          (dx1 = dz1)
     func_backward(cx, d, pl, b, g, y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
     // x1 = z1 - F(x2)
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1);
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1, true);
     // dx2 = dy2 + (dF/dx2)^T dz1;  dwF
     func_backward(cx, d, pl, b, g, x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
 }
