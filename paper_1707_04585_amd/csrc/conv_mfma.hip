@@ -78,11 +78,6 @@ __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
     const int co0 = blockIdx.y * (MT * 16);
     const int HW = p.H * p.W;
 
-    // Zero the whole input area once: halo columns and the columns right of
-    // the image are never written by the staging loop.
-    for (int i = tid * 4; i < p.IMGS * p.img_stride; i += kThreads * 4)
-        *reinterpret_cast<float4 *>(in_lds + i) = make_float4(0.f, 0.f, 0.f, 0.f);
-
     // Per-tile LDS base address of this lane's pixel (B operand) and validity.
     const int tcols = 1 << p.tcols_log2;
     const int l16 = lane & 15, kq = lane >> 4;
@@ -111,63 +106,115 @@ __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
     const int rows_per_pass = kThreads >> p.tpr_log2;
     const int total_rows = p.IMGS * KC * p.lrows;
 
+    // Right-hand zero quad of a staged row (3x3 only): the column just right of
+    // the image must read as zero; it lies in the quad after the last data quad
+    // unless W is not a multiple of 4 (then the masked tail of the data quad
+    // covers it).
+    const int quads = (p.W + 3) >> 2;
+    const bool right_quad = KS == 3 && (p.W & 3) == 0;
+    constexpr int RB = 4;                          // rows a thread loads before it stores
+    constexpr int WITER = (WCHUNK + kThreads - 1) / kThreads;
+
     for (int c0 = 0; c0 < p.CI; c0 += KC) {
-        __syncthreads();  // previous chunk fully consumed (also orders the zero fill)
-        // ---- stage the input band: a = max(x*scale + shift, 0), zero outside the image
-        for (int rho = ty; rho < total_rows; rho += rows_per_pass) {
-            const int pl = (int)(((float)rho + 0.5f) * p.inv_lrows);  // rho / lrows
-            const int lr = rho - pl * p.lrows;
-            const int img = pl / KC, c = pl - img * KC;
-            const int n = n0 + img, ch = c0 + c, row = row0 - PAD + lr;
-            const int col = tx * 4;
-            if (col >= p.W) continue;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (n < p.N && ch < p.CI && row >= 0 && row < p.H) {
-                const float *src = p.in + (int64_t)n * p.isn + (int64_t)ch * p.isc + row * p.W + col;
-                if (vec) {
-                    const float4 q = *reinterpret_cast<const float4 *>(src);
-                    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-                } else {
+        __syncthreads();  // previous chunk fully consumed
+        // ---- filter chunk: read global memory in its own order (runs of
+        //      KC*KS2 floats per output channel, or MT*16*KS2 per input channel
+        //      when transposed), all loads in flight before the first store.
+        float wv[WITER];
+        int wdst[WITER];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (col + j < p.W) v[j] = src[j];
+        for (int i = 0; i < WITER; ++i) {
+            const int e = tid + i * kThreads;
+            int kol, cl, t;
+            if (p.transposed) {
+                cl = e / (MT * 16 * KS2);
+                const int rem = e - cl * (MT * 16 * KS2);
+                kol = rem / KS2;
+                t = rem - kol * KS2;
+            } else {
+                kol = e / (KC * KS2);
+                const int rem = e - kol * (KC * KS2);
+                cl = rem / KS2;
+                t = rem - cl * KS2;
+            }
+            const int ko = co0 + kol, ch = c0 + cl;
+            float v = 0.f;
+            if (e < WCHUNK && ko < p.CO && ch < p.CI) {
+                v = p.transposed ? p.w[((int64_t)ch * p.CO + ko) * KS2 + t]
+                                 : p.w[((int64_t)ko * p.CI + ch) * KS2 + t];
+            }
+            wv[i] = v;
+            // A-operand order; the transposed (data-gradient) filter is also flipped.
+            const int tt = p.transposed ? KS2 - 1 - t : t;
+            wdst[i] = e < WCHUNK ? ((((cl >> 2) * KS2 + tt) * MT + (kol >> 4)) * 64 + (cl & 3) * 16 + (kol & 15)) : -1;
+        }
+        // ---- input band: a = max(x*scale + shift, 0), zero outside the image
+        for (int rbase = 0; rbase < total_rows; rbase += RB * rows_per_pass) {
+            float4 q[RB];
+            int dsti[RB];
+            float sc[RB], sh[RB];
+            bool live[RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) {
+                const int rho = rbase + i * rows_per_pass + ty;
+                const int pl = (int)(((float)rho + 0.5f) * p.inv_lrows);  // rho / lrows
+                const int lr = rho - pl * p.lrows;
+                const int img = pl / KC, c = pl - img * KC;
+                const int n = n0 + img, ch = c0 + c, row = row0 - PAD + lr;
+                const int col = tx * 4;
+                dsti[i] = (rho < total_rows && tx < quads) ? img * p.img_stride + c * p.plane + lr * p.pitch + LP + col : -1;
+                live[i] = dsti[i] >= 0 && n < p.N && ch < p.CI && row >= 0 && row < p.H;
+                q[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                sc[i] = 1.f;
+                sh[i] = 0.f;
+                if (live[i]) {
+                    const float *src = p.in + (int64_t)n * p.isn + (int64_t)ch * p.isc + row * p.W + col;
+                    if (vec) {
+                        q[i] = *reinterpret_cast<const float4 *>(src);
+                    } else {
+                        q[i].x = src[0];
+                        if (col + 1 < p.W) q[i].y = src[1];
+                        if (col + 2 < p.W) q[i].z = src[2];
+                        if (col + 3 < p.W) q[i].w = src[3];
+                    }
+                    if (p.scale_shift) {
+                        sc[i] = p.scale_shift[ch];
+                        sh[i] = p.scale_shift[p.CI + ch];
+                    }
                 }
-                if (p.scale_shift) {
-                    const float sc = p.scale_shift[ch], sh = p.scale_shift[p.CI + ch];
+            }
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = fmaxf(fmaf(v[j], sc, sh), 0.f);
+            for (int i = 0; i < RB; ++i) {
+                if (dsti[i] < 0) continue;
+                float v[4] = {q[i].x, q[i].y, q[i].z, q[i].w};
+                if (live[i]) {
+                    if (p.scale_shift) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = fmaxf(fmaf(v[j], sc[i], sh[i]), 0.f);
+                    }
+                    if (p.round_bf16) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = bf16_round_dev(v[j]);
+                    }
                     if (!vec) {
+                        const int col = tx * 4;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
+                        for (int j = 1; j < 4; ++j)
                             if (col + j >= p.W) v[j] = 0.f;
                     }
                 }
-                if (p.round_bf16) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) v[j] = bf16_round_dev(v[j]);
+                float *dst = in_lds + dsti[i];
+                *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                if (KS == 3) {
+                    if (tx == 0) *reinterpret_cast<float4 *>(dst - 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (right_quad && tx == quads - 1)
+                        *reinterpret_cast<float4 *>(dst + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             }
-            float *dst = in_lds + img * p.img_stride + c * p.plane + lr * p.pitch + LP + col;
-            *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         }
-        // ---- stage the filter chunk in A-operand order:
-        //      w_lds[((c4*KS2 + t)*MT + m)*64 + (c%4)*16 + ko%16]
-        for (int e = tid; e < WCHUNK; e += kThreads) {
-            const int ko16 = e & 15, cq = (e >> 4) & 3;
-            const int rest = e >> 6;
-            const int m = rest % MT, t = (rest / MT) % KS2, c4 = rest / (MT * KS2);
-            const int ko = co0 + m * 16 + ko16, ch = c0 + c4 * 4 + cq;
-            float v = 0.f;
-            if (ko < p.CO && ch < p.CI) {
-                if (p.transposed) {
-                    const int tf = KS2 - 1 - t;  // (KS-1-r)*KS + (KS-1-s)
-                    v = p.w[((int64_t)ch * p.CO + ko) * KS2 + tf];
-                } else {
-                    v = p.w[((int64_t)ko * p.CI + ch) * KS2 + t];
-                }
-                if (p.round_bf16) v = bf16_round_dev(v);
-            }
-            w_lds[e] = v;
+#pragma unroll
+        for (int i = 0; i < WITER; ++i) {
+            if (wdst[i] >= 0) w_lds[wdst[i]] = p.round_bf16 ? bf16_round_dev(wv[i]) : wv[i];
         }
         __syncthreads();
         // ---- multiply
