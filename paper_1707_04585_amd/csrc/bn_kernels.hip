@@ -3,11 +3,12 @@
 // a(x) = ReLU(BN(x)) is the first half of every unit c_k(x) = Conv(a(x)) of
 // the residual functions (Section 2.2).  All kernels here are bound by HBM
 // bandwidth: each streams whole [n][c][h*w] tensors once with 16-byte
-// accesses, reduces per channel with wavefront shuffles and LDS, and leaves
-// the cross-workgroup part of every reduction to a small second kernel that
-// merges the partial results in a fixed order (no floating-point atomics, so
-// results are bitwise reproducible -- the reconstruction of Section 3.2
-// relies on recomputing exactly what the forward pass computed).
+// accesses and reduces per channel with wavefront shuffles and LDS.  The
+// cross-workgroup part of a reduction is finished by the workgroup that
+// arrives last at a per-channel ticket counter; the merge itself runs in a
+// fixed order (no floating-point atomics), so results are bitwise
+// reproducible -- the reconstruction of Section 3.2 relies on recomputing
+// exactly what the forward pass computed.
 #include "kernels.h"
 
 namespace rvn {
@@ -47,16 +48,57 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
     return (uint16_t)(u >> 16);
 }
 
+// Partial results cross workgroups (and XCDs, whose L2s are not coherent with
+// each other inside a kernel) through device-scope accesses: a device-scope
+// store is written through to the memory side, a device-scope load is served
+// from there.  That avoids device-scope fences, which write back and
+// invalidate a whole L2 each time.
+__device__ __forceinline__ void publish(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float fetch(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Ticket: thread 0 (which has publish()ed this workgroup's partial result)
+// waits until those stores have completed and takes a ticket; the workgroup
+// holding the last of `expected` tickets returns true for all its threads and
+// has put the counter back to zero for the next use.  It must read the other
+// workgroups' results with fetch().
+__device__ __forceinline__ bool arrive_last(int *counter, int expected, int *flag_lds) {
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt: stores done
+        const int prev = atomicAdd(counter, 1);
+        const int last = prev == expected - 1;
+        if (last) atomicExch(counter, 0);
+        *flag_lds = last;
+    }
+    __syncthreads();
+    return *flag_lds != 0;
+}
+
+__device__ __forceinline__ double shfl_down_f64(double v, int off) {
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_down(lo, off, 64);
+    hi = __shfl_down(hi, off, 64);
+    return __hiloint2double(hi, lo);
+}
+
 // ---------------------------------------------------------------------------
-// statistics: per (channel, image group) shifted sums -> (count, mean, M2)
+// statistics: per (channel, image group) shifted sums -> (count, mean, M2);
+// the last workgroup of a channel merges them and writes the four per-channel
+// arrays mean, rstd, scale, shift.
 // ---------------------------------------------------------------------------
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void bn_stats_partial_k(const float *__restrict__ x,
-                                                               int64_t sn, int64_t sc, int N,
-                                                               int HW, int ipw,
-                                                               float *__restrict__ partial) {
+__global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__ x, int64_t sn,
+                                                       int64_t sc, int N, int HW, int ipw,
+                                                       float *partial, int *counters, float eps,
+                                                       const float *__restrict__ gamma,
+                                                       const float *__restrict__ beta,
+                                                       float *__restrict__ stats) {
     __shared__ float lds[8];
-    const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x;
+    __shared__ int flag;
+    const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x, C = gridDim.y;
     const int n0 = s * ipw, n1 = min(N, n0 + ipw);
     const float *base = x + (int64_t)ch * sc;
     // Shift by a value from the data so that the sum of squares does not
@@ -85,39 +127,46 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial_k(const float *__re
     if (threadIdx.x == 0) {
         const float cnt = (float)((n1 - n0) * HW);
         float *o = partial + ((int64_t)ch * S + s) * 3;
-        o[0] = cnt;
-        o[1] = pivot + acc[0] / cnt;
-        o[2] = fmaxf(acc[1] - acc[0] * acc[0] / cnt, 0.f);
+        publish(o, cnt);
+        publish(o + 1, pivot + acc[0] / cnt);
+        publish(o + 2, fmaxf(acc[1] - acc[0] * acc[0] / cnt, 0.f));
     }
-}
-
-// Merge the S partials of each channel pairwise-in-order (Chan et al.) in
-// double precision; one thread per channel.
-__global__ void bn_stats_finalize_k(const float *__restrict__ partial, int C, int S, float eps,
-                                    const float *__restrict__ gamma, const float *__restrict__ beta,
-                                    float *__restrict__ stats) {
-    const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-    if (ch >= C) return;
-    const float *p = partial + (int64_t)ch * S * 3;
-    double n = p[0], mean = p[1], m2 = p[2];
-    for (int s = 1; s < S; ++s) {
-        const double nb = p[s * 3], mb = p[s * 3 + 1], m2b = p[s * 3 + 2];
-        const double tot = n + nb, delta = mb - mean;
-        mean += delta * nb / tot;
-        m2 += m2b + delta * delta * n * nb / tot;
+    if (!arrive_last(counters + ch * kCounterStride, S, &flag)) return;
+    // Merge the S <= 64 partials (Chan et al.) in a fixed shuffle tree, in
+    // double precision; lane s holds partial s.
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    double n = 0.0, mean = 0.0, m2 = 0.0;
+    if (lane < S) {
+        const float *q = partial + ((int64_t)ch * S + lane) * 3;
+        n = fetch(q);
+        mean = fetch(q + 1);
+        m2 = fetch(q + 2);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double nb = shfl_down_f64(n, off), mb = shfl_down_f64(mean, off), m2b = shfl_down_f64(m2, off);
+        const double tot = n + nb;
+        if (tot > 0.0) {
+            const double delta = mb - mean, fb = nb / tot;
+            mean += delta * fb;
+            m2 += m2b + delta * delta * n * fb;
+        }
         n = tot;
     }
-    const float mean_f = (float)mean;
-    const float rstd_f = (float)(1.0 / sqrt(m2 / n + (double)eps));
-    const float scale = gamma[ch] * rstd_f;
-    stats[ch] = mean_f;
-    stats[C + ch] = rstd_f;
-    stats[2 * C + ch] = scale;
-    stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
+    if (lane == 0) {
+        const float mean_f = (float)mean;
+        const float rstd_f = (float)(1.0 / sqrt(m2 / n + (double)eps));
+        const float scale = gamma[ch] * rstd_f;
+        stats[ch] = mean_f;
+        stats[C + ch] = rstd_f;
+        stats[2 * C + ch] = scale;
+        stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
+    }
 }
 
 // ---------------------------------------------------------------------------
-// forward apply
+// forward apply (only where a(x) is needed as a tensor)
 // ---------------------------------------------------------------------------
 template <bool VEC, bool BF16>
 __global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restrict__ x, int64_t sn,
@@ -160,13 +209,18 @@ __global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restric
 }
 
 // ---------------------------------------------------------------------------
-// backward: per-channel sums of dy and dy*xhat, dy = da * [u > 0]
+// backward, reduce pass: per-channel sums of dy and dy*xhat, dy = da * [u > 0];
+// the last workgroup of a channel writes dbeta = sum dy, dgamma = sum dy*xhat
+// and the two per-channel means the apply pass needs (kept apart from
+// dgamma/dbeta, which may be accumulated into).
 // ---------------------------------------------------------------------------
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void bn_bwd_partial_k(
+__global__ __launch_bounds__(kThreads) void bn_bwd_reduce_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *__restrict__ da, int N, int C,
-    int HW, int ipw, const float *__restrict__ stats, float *__restrict__ partial) {
+    int HW, int ipw, const float *__restrict__ stats, float *partial, int *counters, double inv_m,
+    float *__restrict__ dgamma, float *__restrict__ dbeta, int accumulate, float *__restrict__ coef) {
     __shared__ float lds[8];
+    __shared__ int flag;
     const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x;
     const int n0 = s * ipw, n1 = min(N, n0 + ipw);
     const float mean = stats[ch], rstd = stats[C + ch];
@@ -200,33 +254,34 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial_k(
     block_sum<2>(acc, lds);
     if (threadIdx.x == 0) {
         float *o = partial + ((int64_t)ch * S + s) * 2;
-        o[0] = acc[0];
-        o[1] = acc[1];
+        publish(o, acc[0]);
+        publish(o + 1, acc[1]);
     }
-}
-
-// dbeta = sum dy, dgamma = sum dy*xhat; also the two per-channel means the
-// apply pass needs (kept apart from dgamma/dbeta, which may be accumulated).
-__global__ void bn_bwd_finalize_k(const float *__restrict__ partial, int C, int S, double inv_m,
-                                  float *__restrict__ dgamma, float *__restrict__ dbeta,
-                                  int accumulate, float *__restrict__ coef) {
-    const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-    if (ch >= C) return;
-    const float *p = partial + (int64_t)ch * S * 2;
+    if (!arrive_last(counters + ch * kCounterStride, S, &flag)) return;
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
     double sb = 0.0, sg = 0.0;
-    for (int s = 0; s < S; ++s) {
-        sb += p[s * 2];
-        sg += p[s * 2 + 1];
+    if (lane < S) {
+        const float *q = partial + ((int64_t)ch * S + lane) * 2;
+        sb = fetch(q);
+        sg = fetch(q + 1);
     }
-    if (accumulate) {
-        dbeta[ch] += (float)sb;
-        dgamma[ch] += (float)sg;
-    } else {
-        dbeta[ch] = (float)sb;
-        dgamma[ch] = (float)sg;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        sb += shfl_down_f64(sb, off);
+        sg += shfl_down_f64(sg, off);
     }
-    coef[ch] = (float)(sb * inv_m);
-    coef[C + ch] = (float)(sg * inv_m);
+    if (lane == 0) {
+        if (accumulate) {
+            dbeta[ch] += (float)sb;
+            dgamma[ch] += (float)sg;
+        } else {
+            dbeta[ch] = (float)sb;
+            dgamma[ch] = (float)sg;
+        }
+        coef[ch] = (float)(sb * inv_m);
+        coef[C + ch] = (float)(sg * inv_m);
+    }
 }
 
 // dx = gamma*rstd*(dy - mean(dy) - xhat*mean(dy*xhat)); out = [skip +] dx
@@ -275,6 +330,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     }
 }
 
+__global__ void clear_counters_k(int *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
 inline bool vec_ok(const View &v, int hw) {
     return hw % 4 == 0 && v.sn % 4 == 0 && v.sc % 4 == 0 && (reinterpret_cast<uintptr_t>(v.p) & 15) == 0;
 }
@@ -282,33 +342,35 @@ inline bool vec_ok(const View &v, int hw) {
 }  // namespace
 
 int reduce_splits(int c, const Geo &g) {
-    const int target = c >= 1024 ? 1 : 1024 / c;
+    int target = c >= 1024 ? 1 : 1024 / c;
+    if (target > 64) target = 64;  // the finishing workgroup merges one partial per lane
     const int s_max = g.n < target ? g.n : target;
     const int ipw = (g.n + s_max - 1) / s_max;
     return (g.n + ipw - 1) / ipw;
 }
 
+// Scratch layout (floats): [c*S*3 partials][2c per-channel means for the apply pass].
 size_t bn_scratch_floats(int c, const Geo &g) {
     return (size_t)c * reduce_splits(c, g) * 3 + 2 * (size_t)c;
 }
 
+void clear_counters(Ctx &cx, int *counters, int n) {
+    if (!cx.launch(K_CLEAR_COUNTERS, 0.0)) return;
+    clear_counters_k<<<(n + 255) / 256, 256, 0, cx.stream>>>(counters, n);
+    cx.check();
+}
+
 void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
-              float *scratch, float *stats) {
+              float *scratch, int *counters, float *stats) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
-    const double bytes = 4.0 * (double)g.pixels() * c;
-    if (cx.launch(K_BN_STATS, bytes)) {
-        dim3 grid(S, c);
-        if (vec_ok(x, g.hw()))
-            bn_stats_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
-        else
-            bn_stats_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch);
-        cx.check();
-    }
-    if (cx.launch(K_BN_STATS_FINALIZE, 0.0)) {
-        bn_stats_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, eps, gamma, beta, stats);
-        cx.check();
-    }
+    if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c)) return;
+    dim3 grid(S, c);
+    if (vec_ok(x, g.hw()))
+        bn_stats_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
+    else
+        bn_stats_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
+    cx.check();
 }
 
 void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn_dtype dt) {
@@ -328,7 +390,7 @@ void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn
 }
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
-                 float *dgamma, float *dbeta, bool accumulate, const View *skip, View out) {
+                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double t = 4.0 * (double)g.pixels() * c;
@@ -336,14 +398,11 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
     const bool vec_in = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(da) & 15) == 0;
     if (cx.launch(K_BN_BWD_REDUCE, 2.0 * t)) {
         dim3 grid(S, c);
+        const double inv_m = 1.0 / (double)g.pixels();
         if (vec_in)
-            bn_bwd_partial_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch);
+            bn_bwd_reduce_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
         else
-            bn_bwd_partial_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch);
-        cx.check();
-    }
-    if (cx.launch(K_BN_BWD_FINALIZE, 0.0)) {
-        bn_bwd_finalize_k<<<(c + 63) / 64, 64, 0, cx.stream>>>(scratch, c, S, 1.0 / (double)g.pixels(), dgamma, dbeta, accumulate ? 1 : 0, coef);
+            bn_bwd_reduce_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
         cx.check();
     }
     if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : 3.0) * t)) {

@@ -34,14 +34,13 @@ enum Epilogue { EP_STORE = 0, EP_ADD = 1, EP_SUB = 2 };
 // Kernel families, for launch accounting and the optional event profiler.
 enum KernelId {
     K_BN_STATS = 0,
-    K_BN_STATS_FINALIZE,
+    K_CLEAR_COUNTERS,
     K_BN_RELU_FWD,
     K_CONV_FWD,
     K_CONV_DGRAD,
     K_CONV_WGRAD,
     K_WGRAD_REDUCE,
     K_BN_BWD_REDUCE,
-    K_BN_BWD_FINALIZE,
     K_BN_BWD_APPLY,
     K_COUNT
 };
@@ -99,8 +98,17 @@ size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g);
 // expression (one fma), which keeps the ReLU decisions of the forward pass, the
 // recomputation and the backward pass identical.
 constexpr int kStatsArrays = 4;
+// `counters`: c * kCounterStride zero-initialised ints (ticket counters of the
+// cross-workgroup reduction, one per channel, each on a cache line of its own
+// so that the atomics of different channels do not serialise; left at zero
+// again).
+constexpr int kCounterStride = 32;
 void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
-              float *scratch, float *stats);
+              float *scratch, int *counters, float *stats);
+
+// Zero n ticket counters (once per library call; the workspace is caller
+// memory with unknown contents).
+void clear_counters(Ctx &cx, int *counters, int n);
 
 // a = max(x*scale + shift, 0), written dense [n][c][h*w] as fp32 or bf16
 // (round to nearest even) according to `dt`.
@@ -110,7 +118,7 @@ void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn
 // accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
 // `da` (dense in-place) or `skip`.
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
-                 float *dgamma, float *dbeta, bool accumulate, const View *skip, View out);
+                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out);
 
 // ---- convolutions (Section 2.2: c_k(x) = Conv_kxk(a(x)), k in {1,3}) -------
 // out = ep(r, conv(a(x), w)) with a(x) = max(x*scale + shift, 0) formed on the

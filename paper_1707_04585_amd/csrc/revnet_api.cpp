@@ -69,6 +69,8 @@ struct Plan {
     int L;
     Layer layers[3];
     size_t stats[3];      // kStatsArrays*cin floats each: mean, rstd, scale, shift
+    size_t counters;      // ticket counters of the cross-workgroup reductions (ints)
+    int n_counters;
     size_t bn_scratch;    // partial sums of the per-channel reductions
     size_t wgrad_scratch; // partial filter gradients (backward only)
     size_t a[3];          // a_l = ReLU(BN(x_l)), conv operand precision
@@ -92,6 +94,9 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
         max_cin = std::max(max_cin, (size_t)ly.cin);
         if (l < p.L - 1) max_mid = std::max(max_mid, (size_t)ly.cout);
     }
+    p.counters = off;
+    p.n_counters = (int)std::max(max_cin, (size_t)1) * kCounterStride;
+    off = align_up(off + (size_t)p.n_counters * 4);
     p.bn_scratch = off;
     off = align_up(off + bn_s * 4);
     if (backward) {
@@ -130,6 +135,7 @@ struct Bufs {
     float *g[2];
     float *bn_scratch;
     float *wgrad_scratch;
+    int *counters;
 };
 
 Bufs bind(const Plan &p, void *ws) {
@@ -144,6 +150,7 @@ Bufs bind(const Plan &p, void *ws) {
         o.g[l] = reinterpret_cast<float *>(b + p.g[l]);
     }
     o.bn_scratch = reinterpret_cast<float *>(b + p.bn_scratch);
+    o.counters = reinterpret_cast<int *>(b + p.counters);
     o.wgrad_scratch = reinterpret_cast<float *>(b + p.wgrad_scratch);
     return o;
 }
@@ -237,7 +244,7 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
     View cur = x;
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
-        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.stats[l]);
+        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
         if (keep_a) bn_relu_fwd(cx, cur, ly.cin, g, b.stats[l], b.a[l], d.conv_dtype);
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
@@ -266,12 +273,12 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         if (l > 0) {
             View xl = dense_view(b.h[l - 1], ly.cin, g);
             View dx = dense_view(da, ly.cin, g);
-            bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+            bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, nullptr, dx);
             dh = dx;
             cur ^= 1;
         } else {
-            bn_relu_bwd(cx, x, da, ly.cin, g, b.stats[l], b.bn_scratch, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+            bn_relu_bwd(cx, x, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, &skip, out);
         }
     }
@@ -350,6 +357,7 @@ int check_bwd_args(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_t
 
 void stack_forward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
                    View x1, View x2, const rvn_block_params *params, View y1, View y2) {
+    clear_counters(cx, b.counters, pl.n_counters);
     for (int k = 0; k < depth; ++k) {
         block_forward(cx, d, pl, b, g, k ? y1 : x1, k ? y2 : x2, params[k], y1, y2);
     }
@@ -358,6 +366,7 @@ void stack_forward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, 
 void stack_backward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
                     View y1, View y2, View dy1, View dy2, const rvn_block_params *params, View x1, View x2,
                     View dx1, View dx2, const rvn_block_grads *grads, bool accumulate) {
+    clear_counters(cx, b.counters, pl.n_counters);
     for (int k = depth - 1; k >= 0; --k) {
         const bool top = k == depth - 1;
         block_backward(cx, d, pl, b, g, top ? y1 : x1, top ? y2 : x2, top ? dy1 : dx1, top ? dy2 : dx2,

@@ -140,5 +140,6 @@ def test_workspace_does_not_depend_on_depth_and_scales_with_batch():
     assert 1.9 < b2 / b1 < 2.1
     c1 = rv.revnet_stack_cost(d, 1, 8, 32, 32)
     c50 = rv.revnet_stack_cost(d, 50, 8, 32, 32)
-    assert c50[1]["kernel_launches"] == 50 * c1[1]["kernel_launches"]
+    # one launch per call clears the reduction counters; the rest is per block
+    assert c50[1]["kernel_launches"] - 1 == 50 * (c1[1]["kernel_launches"] - 1)
     assert abs(c50[1]["algorithmic_bytes"] - 50 * c1[1]["algorithmic_bytes"]) < 1e-6 * c50[1]["algorithmic_bytes"]
