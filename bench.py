@@ -27,7 +27,11 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (profiles/), keyed by (workload, kernel family); None = not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # conv_mfma_f32_k at c2_stack9: (FETCH_SIZE 6395.7 KiB x 2.0 + WRITE_SIZE 8192.0 KiB x 1.0) per dispatch,
+    # averaged over forward, recompute and data-gradient launches (profiles/c2_stack9_hbm_traffic.txt)
+    ("c2_stack9", "conv_fwd"): 21485512,
+}
 
 
 def bound_of(family: str, conv: str):
@@ -45,6 +49,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_stack9")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-n", type=int, default=32, help="batch of the oracle timing sample")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run a plain elementwise copy of this many MiB (read + write that many each), "
+                         "the reference reading for rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -114,6 +121,14 @@ def main() -> int:
     roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 2), peak=peak, unit=unit,
                     frac=round(achieved / peak, 4), avg_launch_us=round(per_launch_s * 1e6, 3),
                     traffic=MEASURED_TRAFFIC.get((args.workload, dom)))
+
+    if args.copy_probe_mib:
+        src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device=r.device).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)   # one elementwise kernel: reads and writes copy_probe_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the same totals against the rooflines, whole step
     fwd_cost, bwd_cost = rv.revnet_stack_cost(r.desc, depth, n, h, w)

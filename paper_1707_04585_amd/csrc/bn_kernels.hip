@@ -41,13 +41,6 @@ __device__ __forceinline__ void block_sum(float (&v)[NV], float *lds) {
     }
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
 // Partial results cross workgroups (and XCDs, whose L2s are not coherent with
 // each other inside a kernel) through device-scope accesses: a device-scope
 // store is written through to the memory side, a device-scope load is served
@@ -162,49 +155,6 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
         stats[C + ch] = rstd_f;
         stats[2 * C + ch] = scale;
         stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// forward apply (only where a(x) is needed as a tensor)
-// ---------------------------------------------------------------------------
-template <bool VEC, bool BF16>
-__global__ __launch_bounds__(kThreads) void bn_relu_fwd_k(const float *__restrict__ x, int64_t sn,
-                                                          int64_t sc, int C, int HW,
-                                                          int64_t total /* work items */,
-                                                          const float *__restrict__ stats,
-                                                          void *__restrict__ out) {
-    constexpr int E = VEC ? 4 : 1;
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (v >= total) return;
-    const int per_plane = HW / E;
-    const int64_t plane = v / per_plane;
-    const int i = (int)(v - plane * per_plane) * E;
-    const int n = (int)(plane / C), ch = (int)(plane - (int64_t)n * C);
-    const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
-    const float *src = x + (int64_t)n * sn + (int64_t)ch * sc + i;
-    const int64_t dst = plane * HW + i;
-    if (VEC) {
-        const float4 q = *reinterpret_cast<const float4 *>(src);
-        float4 r;
-        r.x = fmaxf(fmaf(q.x, scale, shift), 0.f);
-        r.y = fmaxf(fmaf(q.y, scale, shift), 0.f);
-        r.z = fmaxf(fmaf(q.z, scale, shift), 0.f);
-        r.w = fmaxf(fmaf(q.w, scale, shift), 0.f);
-        if (BF16) {
-            uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16_rne(r.x) | ((uint32_t)f32_to_bf16_rne(r.y) << 16);
-            pk.y = (uint32_t)f32_to_bf16_rne(r.z) | ((uint32_t)f32_to_bf16_rne(r.w) << 16);
-            *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(out) + dst) = pk;
-        } else {
-            *reinterpret_cast<float4 *>(static_cast<float *>(out) + dst) = r;
-        }
-    } else {
-        const float r = fmaxf(fmaf(*src, scale, shift), 0.f);
-        if (BF16)
-            static_cast<uint16_t *>(out)[dst] = f32_to_bf16_rne(r);
-        else
-            static_cast<float *>(out)[dst] = r;
     }
 }
 
@@ -370,22 +320,6 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
         bn_stats_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
     else
         bn_stats_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
-    cx.check();
-}
-
-void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn_dtype dt) {
-    const double esz = dt == RVN_BF16 ? 2.0 : 4.0;
-    if (!cx.launch(K_BN_RELU_FWD, (4.0 + esz) * (double)g.pixels() * c)) return;
-    const bool vec = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(a) & 15) == 0;
-    const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
-    const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
-#define RVN_LAUNCH(V, B) \
-    bn_relu_fwd_k<V, B><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, c, g.hw(), total, stats, a)
-    if (vec && dt == RVN_BF16) RVN_LAUNCH(true, true);
-    else if (vec) RVN_LAUNCH(true, false);
-    else if (dt == RVN_BF16) RVN_LAUNCH(false, true);
-    else RVN_LAUNCH(false, false);
-#undef RVN_LAUNCH
     cx.check();
 }
 

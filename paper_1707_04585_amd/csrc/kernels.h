@@ -35,7 +35,6 @@ enum Epilogue { EP_STORE = 0, EP_ADD = 1, EP_SUB = 2 };
 enum KernelId {
     K_BN_STATS = 0,
     K_CLEAR_COUNTERS,
-    K_BN_RELU_FWD,
     K_CONV_FWD,
     K_CONV_DGRAD,
     K_CONV_WGRAD,
@@ -110,10 +109,6 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
 // memory with unknown contents).
 void clear_counters(Ctx &cx, int *counters, int n);
 
-// a = max(x*scale + shift, 0), written dense [n][c][h*w] as fp32 or bf16
-// (round to nearest even) according to `dt`.
-void bn_relu_fwd(Ctx &cx, View x, int c, Geo g, const float *stats, void *a, rvn_dtype dt);
-
 // Backward of a(x) given da (dense fp32): writes dgamma, dbeta (added to when
 // accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
 // `da` (dense in-place) or `skip`.
@@ -132,8 +127,10 @@ void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const flo
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
                 float *da);
 
-// dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad].
-void conv_wgrad(Ctx &cx, const void *a, rvn_dtype dt, View dh, int cin, int cout, int ks, Geo g,
-                float *scratch, float *dw, bool accumulate);
+// dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad], with
+// a(x) = max(x*scale + shift, 0) formed on the fly from the layer input x as in
+// conv_fwd; with dt == RVN_BF16 a and dh are rounded to bf16 before multiplying.
+void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
+                int ks, Geo g, float *scratch, float *dw, bool accumulate);
 
 }  // namespace rvn

@@ -35,8 +35,8 @@ hipEvent_t take_event() {
 }
 
 const char *const kNames[K_COUNT] = {
-    "bn_stats_k", "clear_counters_k", "bn_relu_fwd_k", "conv_fwd", "conv_dgrad",
-    "conv_wgrad", "reduce_partials_k", "bn_bwd_reduce_k", "bn_bwd_apply_k",
+    "bn_stats_k", "clear_counters_k", "conv_fwd", "conv_dgrad",
+    "conv_wgrad", "wgrad_reduce_k", "bn_bwd_reduce_k", "bn_bwd_apply_k",
 };
 
 }  // namespace

@@ -73,7 +73,6 @@ struct Plan {
     int n_counters;
     size_t bn_scratch;    // partial sums of the per-channel reductions
     size_t wgrad_scratch; // partial filter gradients (backward only)
-    size_t a[3];          // a_l = ReLU(BN(x_l)), conv operand precision
     size_t h[2];          // h_l = conv_l(a_l), fp32, input of layer l+1
     size_t g[2];          // gradient ping-pong buffers (backward only)
     size_t total;
@@ -83,7 +82,6 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     Plan p{};
     p.L = func_layers(d, p.layers);
     const size_t P = (size_t)g.pixels();
-    const size_t esz = d.conv_dtype == RVN_BF16 ? 2 : 4;
     size_t off = 0, bn_s = 0, wg_s = 0, max_cin = 0, max_mid = 0;
     for (int l = 0; l < p.L; ++l) {
         const Layer &ly = p.layers[l];
@@ -102,10 +100,8 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     if (backward) {
         p.wgrad_scratch = off;
         off = align_up(off + wg_s * 4);
-        for (int l = 0; l < p.L; ++l) {
-            p.a[l] = off;
-            off = align_up(off + P * p.layers[l].cin * esz);
-        }
+        // a_l = ReLU(BN(x_l)) is never stored: every convolution kernel forms it
+        // from x_l (the function input or h_{l-1}) while staging its operands.
         for (int l = 0; l < p.L - 1; ++l) {
             p.h[l] = off;
             off = align_up(off + P * p.layers[l].cout * 4);
@@ -130,7 +126,6 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
 
 struct Bufs {
     float *stats[3];
-    void *a[3];
     float *h[2];
     float *g[2];
     float *bn_scratch;
@@ -143,7 +138,6 @@ Bufs bind(const Plan &p, void *ws) {
     Bufs o{};
     for (int l = 0; l < 3; ++l) {
         o.stats[l] = reinterpret_cast<float *>(b + p.stats[l]);
-        o.a[l] = b + p.a[l];
     }
     for (int l = 0; l < 2; ++l) {
         o.h[l] = reinterpret_cast<float *>(b + p.h[l]);
@@ -237,15 +231,13 @@ int check_ws(const void *ws, size_t have, size_t need) {
 
 // ---- residual function drivers ----------------------------------------------
 
-// out = ep(r, Func(x)); leaves h_l and the BN statistics in `b` (and, when
-// keep_a, the conv operands a_l the filter-gradient kernel reads).
+// out = ep(r, Func(x)); leaves the layer inputs h_l and the BN statistics in `b`.
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
-                  const rvn_func_params &p, Epilogue ep, const View *r, View out, bool keep_a) {
+                  const rvn_func_params &p, Epilogue ep, const View *r, View out) {
     View cur = x;
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
         bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
-        if (keep_a) bn_relu_fwd(cx, cur, ly.cin, g, b.stats[l], b.a[l], d.conv_dtype);
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
@@ -267,11 +259,12 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
     int cur = 0;
     for (int l = pl.L - 1; l >= 0; --l) {
         const Layer &ly = pl.layers[l];
-        conv_wgrad(cx, b.a[l], d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch, gr.d_conv_w[l], accumulate);
+        const View xl = l > 0 ? dense_view(b.h[l - 1], ly.cin, g) : x;
+        conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
+                   gr.d_conv_w[l], accumulate);
         float *da = b.g[cur];
         conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, da);
         if (l > 0) {
-            View xl = dense_view(b.h[l - 1], ly.cin, g);
             View dx = dense_view(da, ly.cin, g);
             bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, nullptr, dx);
@@ -287,8 +280,8 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
 // Section 3.1: y1 = x1 + F(x2); y2 = x2 + G(y1).
 void block_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x1,
                    View x2, const rvn_block_params &p, View y1, View y2) {
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1, false);
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2, false);
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2);
 }
 
 // Section 3.2, Algorithm 1, with G handled completely before F.
@@ -296,11 +289,11 @@ void block_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs
                     View y2, View dy1, View dy2, const rvn_block_params &p, View x1, View x2, View dx1,
                     View dx2, const rvn_block_grads &gr, bool accumulate) {
     // z1 = y1;  x2 = y2 - G(z1)
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2, true);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2);
     // dz1 = dy1 + (dG/dz1)^T dy2;  dwG          (dx1 = dz1)
     func_backward(cx, d, pl, b, g, y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
     // x1 = z1 - F(x2)
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1, true);
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1);
     // dx2 = dy2 + (dF/dx2)^T dz1;  dwF
     func_backward(cx, d, pl, b, g, x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
 }
