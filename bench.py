@@ -48,7 +48,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2_stack9")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-n", type=int, default=32, help="batch of the oracle timing sample")
+    ap.add_argument("--cpu-sample-n", type=int, default=0,
+                    help="batch of the oracle timing sample (0: the whole batch if one pass takes under ~30 s, "
+                         "else the largest power-of-two fraction that does)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (read + write that many each), "
                          "the reference reading for rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -189,20 +191,32 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         from oracle import revnet_oracle as O
-        ns = min(args.cpu_sample_n, n)
         c2 = c // 2
-        xs, dys = x[:ns], dy[:ns]
         sp = lambda t: (np.ascontiguousarray(t[:, :c2]), np.ascontiguousarray(t[:, c2:]))
         O.build()
-        with O.conv_operands(conv):
-            tc0 = time.perf_counter()
-            y1, y2, _, stored = O.stack_fwd(*sp(xs), params, keep=True)
-            O.stack_bwd_stored(stored, params, *sp(dys))
-            tc1 = time.perf_counter()
-        out["cpu_baseline"] = {"value": round(ns / (tc1 - tc0), 2), "unit": "images/s", "cores": O.num_threads(),
-                               "kind": "oracle", "seconds": round(tc1 - tc0, 2),
-                               "sample": f"first {ns} of {n} images, same C/H/W/depth, one forward + "
-                                         "stored-activation backward in float64"}
+
+        def oracle_pass(ns):
+            with O.conv_operands(conv):
+                t0 = time.perf_counter()
+                y1, y2, _, stored = O.stack_fwd(*sp(x[:ns]), params, keep=True)
+                O.stack_bwd_stored(stored, params, *sp(dy[:ns]))
+                return time.perf_counter() - t0
+
+        # Bounded sample: 10-30 s of oracle work.  Probe on 2 images, then take the
+        # largest batch that one pass finishes in ~30 s and repeat it up to ~10 s.
+        ns = min(args.cpu_sample_n, n) if args.cpu_sample_n else n
+        if not args.cpu_sample_n:
+            per_image = oracle_pass(min(2, n)) / min(2, n)
+            while ns > 1 and per_image * ns > 30.0:
+                ns //= 2
+        secs, passes = 0.0, 0
+        while passes == 0 or (secs < 10.0 and passes < 8):
+            secs += oracle_pass(ns)
+            passes += 1
+        out["cpu_baseline"] = {"value": round(ns * passes / secs, 2), "unit": "images/s", "cores": O.num_threads(),
+                               "kind": "oracle", "seconds": round(secs, 2),
+                               "sample": f"first {ns} of {n} images, same C/H/W/depth, {passes} pass(es) of one "
+                                         "forward + stored-activation backward in float64"}
     print(json.dumps(out))
     return 0
 

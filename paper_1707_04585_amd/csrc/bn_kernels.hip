@@ -306,8 +306,7 @@ size_t bn_scratch_floats(int c, const Geo &g) {
 
 void clear_counters(Ctx &cx, int *counters, int n) {
     if (!cx.launch(K_CLEAR_COUNTERS, 0.0)) return;
-    clear_counters_k<<<(n + 255) / 256, 256, 0, cx.stream>>>(counters, n);
-    cx.check();
+    cx.run(clear_counters_k, dim3((n + 255) / 256), dim3(256), 0, counters, n);
 }
 
 void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
@@ -317,10 +316,9 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
     if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c)) return;
     dim3 grid(S, c);
     if (vec_ok(x, g.hw()))
-        bn_stats_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
+        cx.run(bn_stats_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
     else
-        bn_stats_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
-    cx.check();
+        cx.run(bn_stats_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
 }
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
@@ -334,10 +332,9 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         dim3 grid(S, c);
         const double inv_m = 1.0 / (double)g.pixels();
         if (vec_in)
-            bn_bwd_reduce_k<true><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
+            cx.run(bn_bwd_reduce_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
         else
-            bn_bwd_reduce_k<false><<<grid, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
-        cx.check();
+            cx.run(bn_bwd_reduce_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
     }
     if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : 3.0) * t)) {
         const bool vec = vec_in && vec_ok(out, g.hw()) && (!skip || vec_ok(*skip, g.hw()));
@@ -346,13 +343,12 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         const float *kp = skip ? skip->p : nullptr;
         const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
 #define RVN_LAUNCH(V, K) \
-    bn_bwd_apply_k<V, K><<<blocks, kThreads, 0, cx.stream>>>(x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
+    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);
         else RVN_LAUNCH(false, false);
 #undef RVN_LAUNCH
-        cx.check();
     }
 }
 

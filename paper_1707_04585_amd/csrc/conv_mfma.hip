@@ -339,7 +339,7 @@ template <int KS, int KC>
 void launch_conv(Ctx &cx, ConvArgs &a, const Tiling &tl, int mt, dim3 grid) {
 #define RVN_CASE(MT_, NT_)                                                                    \
     if (mt == MT_ && tl.NT == NT_) {                                                          \
-        conv_mfma_f32_k<KS, MT_, NT_, KC><<<grid, kThreads, tl.lds_bytes, cx.stream>>>(a);    \
+        cx.run(conv_mfma_f32_k<KS, MT_, NT_, KC>, grid, dim3(kThreads), tl.lds_bytes, a);     \
         return;                                                                               \
     }
     RVN_CASE(1, 4) RVN_CASE(2, 4) RVN_CASE(4, 4)
@@ -353,7 +353,7 @@ void conv_mfma(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
     const int kc = ks == 3 ? (mt == 4 ? 8 : 16) : 16;
     const Tiling tl = choose_tiling(g, ks, kc, mt);
     if (tl.NT == 0) {  // no tiling fits (image rows too wide for LDS)
-        cx.err = hipErrorInvalidConfiguration;
+        cx.fail(hipErrorInvalidConfiguration);
         return;
     }
     ConvArgs a{};
@@ -378,7 +378,6 @@ void conv_mfma(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
     } else {
         launch_conv<1, 16>(cx, a, tl, mt, grid);
     }
-    cx.check();
 }
 
 }  // namespace

@@ -412,8 +412,7 @@ void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh
     const WgradPlan w = plan_wgrad(cin, cout, ks, g);
     if (cx.launch(K_CONV_WGRAD, P * cin * 4.0 + P * cout * 4.0, flops)) {
         if (!w.ok) {  // image rows too wide for LDS
-            cx.err = hipErrorInvalidConfiguration;
-            cx.check();
+            cx.fail(hipErrorInvalidConfiguration);
             return;
         }
         WgradArgs a{};
@@ -439,18 +438,16 @@ void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh
                          (reinterpret_cast<uintptr_t>(dh.p) & 15) == 0;
 #define RVN_CASE(KS_, MT_, CT_)                                                                    \
     if (ks == KS_ && w.MT == MT_ && w.CT == CT_) {                                                 \
-        if (vec) conv_wgrad_mfma_k<KS_, MT_, CT_, true><<<grid, kThreads, w.lds_bytes, cx.stream>>>(a);  \
-        else conv_wgrad_mfma_k<KS_, MT_, CT_, false><<<grid, kThreads, w.lds_bytes, cx.stream>>>(a);     \
+        if (vec) cx.run(conv_wgrad_mfma_k<KS_, MT_, CT_, true>, grid, dim3(kThreads), w.lds_bytes, a);   \
+        else cx.run(conv_wgrad_mfma_k<KS_, MT_, CT_, false>, grid, dim3(kThreads), w.lds_bytes, a);      \
     }
         RVN_CASE(3, 1, 1) RVN_CASE(3, 1, 2) RVN_CASE(3, 2, 1) RVN_CASE(3, 2, 2)
         RVN_CASE(1, 1, 1) RVN_CASE(1, 1, 2) RVN_CASE(1, 2, 1) RVN_CASE(1, 2, 2)
 #undef RVN_CASE
-        cx.check();
     }
     if (cx.launch(K_WGRAD_REDUCE, 0.0)) {
-        wgrad_reduce_k<<<(unsigned)((w.part_stride + 31) / 32), kThreads, 0, cx.stream>>>(
-            scratch, w.part_stride, w.S, ks * ks, w.MT, w.CT, w.tiles_c, cout, cin, dw, accumulate ? 1 : 0);
-        cx.check();
+        cx.run(wgrad_reduce_k, dim3((unsigned)((w.part_stride + 31) / 32)), dim3(kThreads), 0, scratch,
+               w.part_stride, w.S, ks * ks, w.MT, w.CT, w.tiles_c, cout, cin, dw, accumulate ? 1 : 0);
     }
 }
 

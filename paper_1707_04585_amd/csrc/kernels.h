@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "revnet.h"
@@ -45,10 +46,10 @@ enum KernelId {
 };
 const char *kernel_name(int id);
 
-// Optional per-launch timing with HIP events on the caller's stream
-// (revnet_profile_begin / revnet_profile_end).
-void profile_mark_begin(int id, double bytes, double flops, hipStream_t stream);
-void profile_mark_end(hipStream_t stream);
+// Optional per-launch timing (revnet_profile_begin / revnet_profile_end): a
+// pair of HIP events that the launch itself stamps with the kernel's start and
+// end on the stream it runs on.
+void profile_new_mark(int id, double bytes, double flops, hipEvent_t *start, hipEvent_t *stop);
 bool profile_enabled();
 
 // One call's launch context.  With dry == true the wrappers only count.
@@ -57,27 +58,33 @@ struct Ctx {
     bool dry = false;
     rvn_cost cost = {};
     hipError_t err = hipSuccess;
-    bool marked = false;
+    hipEvent_t ev_start = nullptr, ev_stop = nullptr;  // set while a profiled launch is pending
 
     // Record one kernel launch of family `id` that must move `bytes`
     // algorithmic bytes and perform `flops`; returns true if the kernel should
-    // really be launched (then call check() right after the launch).
+    // really be launched (then call run() for it).
     bool launch(int id, double bytes, double flops = 0.0) {
         cost.kernel_launches += 1;
         cost.algorithmic_bytes += bytes;
         const bool go = !dry && err == hipSuccess;
-        if (go && profile_enabled()) {
-            profile_mark_begin(id, bytes, flops, stream);
-            marked = true;
-        }
+        if (go && profile_enabled()) profile_new_mark(id, bytes, flops, &ev_start, &ev_stop);
         return go;
     }
-    void check() {
-        if (marked) {
-            profile_mark_end(stream);
-            marked = false;
+    // Enqueue `kernel` on the stream and record the launch status.
+    template <typename... KArgs, typename... Args>
+    void run(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, Args... args) {
+        if (ev_start) {
+            hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, ev_start, ev_stop, 0,
+                                  static_cast<KArgs>(args)...);
+            ev_start = ev_stop = nullptr;
+        } else {
+            kernel<<<grid, block, lds_bytes, stream>>>(static_cast<KArgs>(args)...);
         }
-        if (!dry && err == hipSuccess) err = hipGetLastError();
+        if (err == hipSuccess) err = hipGetLastError();
+    }
+    void fail(hipError_t e) {
+        ev_start = ev_stop = nullptr;
+        if (err == hipSuccess) err = e;
     }
 };
 

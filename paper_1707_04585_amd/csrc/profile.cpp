@@ -1,9 +1,11 @@
 // Optional per-kernel timing with HIP events, for roofline reports.
 //
-// While enabled, every kernel launch of the library is bracketed by a pair of
-// events recorded on the stream the kernel is launched on.  The events come
-// from a pool that grows on demand (host allocations only; no device memory).
-// Profiling perturbs timing slightly and is meant for a separate pass.
+// While enabled, every kernel launch of the library carries a pair of events
+// that the dispatch itself stamps with the kernel's start and end times on the
+// stream it runs on (hipExtLaunchKernelGGL), so the elapsed time between them
+// is the kernel's own duration.  The events come from a pool that grows on
+// demand (host allocations only; no device memory).  Profiling perturbs the
+// gaps between kernels and is meant for a separate pass.
 #include <mutex>
 #include <vector>
 
@@ -45,16 +47,12 @@ const char *kernel_name(int id) { return id >= 0 && id < K_COUNT ? kNames[id] : 
 
 bool profile_enabled() { return g_on; }
 
-void profile_mark_begin(int id, double bytes, double flops, hipStream_t stream) {
+void profile_new_mark(int id, double bytes, double flops, hipEvent_t *start, hipEvent_t *stop) {
     std::lock_guard<std::mutex> lk(g_mu);
     Mark m{id, bytes, flops, take_event(), take_event()};
-    (void)hipEventRecord(m.start, stream);
     g_marks.push_back(m);
-}
-
-void profile_mark_end(hipStream_t stream) {
-    std::lock_guard<std::mutex> lk(g_mu);
-    if (!g_marks.empty()) (void)hipEventRecord(g_marks.back().stop, stream);
+    *start = m.start;
+    *stop = m.stop;
 }
 
 }  // namespace rvn
