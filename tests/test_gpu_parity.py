@@ -19,22 +19,27 @@ import numpy as np
 import pytest
 
 import synth_inputs as S
+from bf16_floor import bf16_grad_floor
 
 pytestmark = pytest.mark.gpu
 
-# Whole bf16 stacks: the GPU (fp32 sums) and the oracle (float64 sums) differ by
-# ~1e-7 going into each bf16 rounding step, which turns that into ~1e-4 on a few
-# percent of the next layer's inputs, and reconstruction feeds the difference to
-# the block below; after a few blocks some ReLU decisions differ and each costs
-# O(1) in its gradient element.  Stacks are therefore held to a looser bound
-# here and to the 2e-2 bar block by block (see
-# test_bf16_every_block_of_a_stack_from_oracle_inputs).
-BF16_STACK_GRAD_TOL = 1e-1
-# Single blocks with long sums (3x3 over 512 channels = 4608 products, BN over
-# only 392 values per channel): the fp32-vs-float64 difference entering the
-# first rounding step is already ~4e-6 and three rounding steps in a row bring
-# it to the bf16 noise floor, so the bound is that of bf16 itself.
-WIDE_BF16_GRAD_TOL = 8e-2
+# bf16 operands make a residual function ill-conditioned with respect to
+# summation order: a relative difference d entering a rounding step (fp32 sums on
+# the GPU, float64 sums in the oracle: d ~ 1e-7) moves a fraction d / 2^-8 of the
+# values to the neighbouring bf16 number, i.e. leaves a relative difference
+# sqrt(d * 2^-8); three layers take 1e-7 to 2e-5, 3e-4 and 1e-3, and at 1e-3 about
+# one ReLU decision in a thousand differs, each an O(1) change of its gradient
+# element: sqrt(1e-3) = 3e-2.  No kernel can be closer to a float64-summing oracle
+# than another correct summation order is.  That floor is measured, on the CPU
+# and with the oracle alone, as the distance between the oracle run in float32
+# and in float64 (both with bf16 operands); the GPU must stay within the 2e-2 bar
+# or, where the floor is above it, within 3x the floor.
+def bf16_grad_tol(oracle, cfg, x, params, dy, ref):
+    floor = bf16_grad_floor(oracle, cfg, x, params, dy, ref)
+    tol = max(TOL["bf16"]["grad"], 3.0 * floor)
+    print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol), flush=True)
+    return tol
+
 
 TOL = {"f32": dict(fwd=1e-5, grad=1e-4, recon=1e-5), "bf16": dict(fwd=1e-2, grad=2e-2, recon=1e-2)}
 
@@ -143,8 +148,8 @@ def test_stack_matches_oracle(oracle, torch_cuda, name, conv):
     ref = oracle_reference(oracle, cfg, x, params, dy)
     out = gpu_run(cfg, x, params, dy)
     tol = dict(TOL[conv])
-    if conv == "bf16" and cfg["depth"] > 1:
-        tol["grad"] = BF16_STACK_GRAD_TOL
+    if conv == "bf16":
+        tol["grad"] = bf16_grad_tol(oracle, cfg, x, params, dy, ref)
     check_against_oracle(oracle, out, ref, x, conv, tol=tol)
 
 
@@ -314,13 +319,13 @@ def test_large_bottleneck_properties(oracle, torch_cuda):
 def test_reduced_batch_real_shapes_bf16(oracle, torch_cuda):
     """Real channel counts and resolutions of the bf16 workloads at a batch the
     oracle finishes in seconds."""
-    for name, n, gtol in (("c3_stage2", 8, 2e-2), ("c3_stage3", 16, 2e-2), ("c5_stage2", 2, 2e-2),
-                          ("c5_stage4", 8, WIDE_BF16_GRAD_TOL)):
+    for name, n in (("c3_stage2", 8), ("c3_stage3", 16), ("c5_stage2", 2), ("c5_stage4", 8)):
         cfg = dict(S.STACKS[name], n=n, depth=1)
         print(f"case {name} n={n}", flush=True)
         x, params, dy = S.draw_stack(81, **cfg)
         ref = oracle_reference(oracle, cfg, x, params, dy)
         out = gpu_run(cfg, x, params, dy)
+        gtol = bf16_grad_tol(oracle, cfg, x, params, dy, ref)
         check_against_oracle(oracle, out, ref, x, "bf16", tol=dict(TOL["bf16"], grad=gtol))
         with oracle.conv_operands("exact"):
             exact = oracle_reference(oracle, dict(cfg, conv="f32"), x, params, dy)

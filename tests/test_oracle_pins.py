@@ -430,3 +430,33 @@ def test_float32_drift_grows_but_stays_small(oracle):
     assert drift[0] < 1e-4               # bottom of the stack
     assert drift[0] > drift[-1]          # it accumulates
     assert oracle.angle_deg(oracle.flatten_grads(g_rec), oracle.flatten_grads(g_stored)) < 0.1
+
+
+def test_bf16_operands_make_gradients_sensitive_to_summation_order(oracle):
+    """With bf16 operands a residual function amplifies a summation-order
+    difference d to sqrt(d / 256) per layer, and ReLU decisions taken from such
+    values differ in about one case per thousand after three layers.  Measured
+    with the oracle alone (float32 against float64, same bf16 operand
+    rounding): percent-level gradient differences for a bottleneck block, while
+    the same block with exact operands agrees to float32 rounding.  The GPU
+    parity tests take their bf16 gradient tolerance from this floor."""
+    from bf16_floor import bf16_grad_floor
+    cfg = dict(S.STACKS["c5_stage2"], n=2, depth=1)
+    x, params, dy = S.draw_stack(81, **cfg)
+    c = cfg["c"] // 2
+    sp = lambda t: (np.ascontiguousarray(t[:, :c]), np.ascontiguousarray(t[:, c:]))
+
+    def ref_dx(mode):
+        with oracle.conv_operands(mode):
+            y1, y2, _, stored = oracle.stack_fwd(*sp(x), params, keep=True)
+            dx1, dx2, _ = oracle.stack_bwd_stored(stored, params, *sp(dy))
+        return dict(dx=np.concatenate([dx1, dx2], 1))
+
+    floor_bf16 = bf16_grad_floor(oracle, cfg, x, params, dy, ref_dx("bf16"))
+    assert 5e-3 < floor_bf16 < 1e-1
+    # same comparison with exact operands: plain float32 rounding
+    p32 = S.cast_params(params, np.float32)
+    f32 = lambda t: tuple(np.ascontiguousarray(h, dtype=np.float32) for h in sp(t))
+    y1, y2, _, stored = oracle.stack_fwd(*f32(x), p32, eps=np.float32(1e-5), keep=True)
+    dx1, dx2, _ = oracle.stack_bwd_stored(stored, p32, *f32(dy), eps=np.float32(1e-5))
+    assert oracle.rel_l2(np.concatenate([dx1, dx2], 1), ref_dx("exact")["dx"]) < 1e-3
