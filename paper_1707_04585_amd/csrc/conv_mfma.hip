@@ -389,6 +389,7 @@ void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const flo
     cx.cost.conv_fwd_calls += 1;
     cx.cost.conv_flops += flops;
     if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
+    if (dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, false, cin, cout, ks, g, ep, r, out)) return;
     conv_mfma(cx, x, scale_shift, w, false, cin, cout, ks, g, dt == RVN_BF16, ep, r, out);
 }
 
@@ -401,6 +402,8 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cou
     if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops)) return;
     // A stride-1 "same" convolution of dh (cout channels) with the transposed,
     // flipped filter, producing cin channels.
+    if (dt == RVN_BF16 && conv_bf16(cx, dh, nullptr, w, true, cout, cin, ks, g, EP_STORE, nullptr, dense_view(da, cin, g)))
+        return;
     conv_mfma(cx, dh, nullptr, w, true, cout, cin, ks, g, dt == RVN_BF16, EP_STORE, nullptr,
               dense_view(da, cin, g));
 }

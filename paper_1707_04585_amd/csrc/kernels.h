@@ -129,6 +129,13 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
 void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, int cin,
               int cout, int ks, Geo g, Epilogue ep, const View *r, View out);
 
+// The same convolution on bf16 matrix instructions (operands rounded to bf16,
+// fp32 accumulation); `transposed`: w is [ci][co][ks][ks] and is read transposed
+// and flipped (data gradient).  Returns false if no tiling fits (nothing is
+// launched then).
+bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, bool transposed, int ci, int co,
+               int ks, Geo g, Epilogue ep, const View *r, View out);
+
 // da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
 // dh is fp32, rounded to bf16 on load when dt == RVN_BF16.
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
