@@ -44,6 +44,8 @@ struct Bf16Args {
     int64_t isn, isc;
     const float *scale_shift;  // [2*CI]: a = max(in*scale + shift, 0); null = use `in` as is
     const float *w;            // [CO][CI][KS][KS] forward; [CI][CO][KS][KS] read transposed+flipped otherwise
+    const uint16_t *wq;        // or null: the same filter already in bf16 and K order, [CO][KS*KS][CIP]
+    int CIP;                   // channel pitch of wq (a multiple of 8)
     const float *r;            // skip operand of the epilogue (may alias out)
     int64_t rsn, rsc;
     float *out;
@@ -64,7 +66,14 @@ __device__ __forceinline__ uint32_t bf16_bits(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
 }
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+// Two floats to a pair of bf16 (nearest even): one v_cvt_pk_bf16_f32.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const float2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
 
 template <int KS, int MT, int NT, int KC>
 __global__ __launch_bounds__(kThreads) void conv_bf16_k(const Bf16Args p) {
@@ -163,26 +172,38 @@ __global__ __launch_bounds__(kThreads) void conv_bf16_k(const Bf16Args p) {
             }
         }
         // ---- filter tile: item = (ko, tap, channel octet) -> 8 K-consecutive values
-        for (int e = tid; e < W_ITEMS; e += kThreads) {
-            const int oc = e % octs;
-            int t = e / octs;
-            const int tap = t % KS2, kol = t / KS2;
-            const int ko = co0 + kol, chb = c0 + oc * 8;
-            float v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                v[k] = 0.f;
-                const int ch = chb + k;
-                if (ko < CO && ch < CI)
-                    v[k] = p.transposed ? p.w[((int64_t)ch * CO + ko) * KS2 + (KS2 - 1 - tap)]
-                                        : p.w[((int64_t)ko * CI + ch) * KS2 + tap];
+        if (p.wq) {
+            for (int e = tid; e < W_ITEMS; e += kThreads) {
+                const int oc = e % octs;
+                const int t = e / octs;  // = kol * KS2 + tap
+                const int ko = co0 + t / KS2, chb = c0 + oc * 8;
+                uint4 rec = make_uint4(0u, 0u, 0u, 0u);
+                if (ko < CO && chb < p.CIP)
+                    rec = *reinterpret_cast<const uint4 *>(p.wq + ((int64_t)co0 * KS2 + t) * p.CIP + chb);
+                *reinterpret_cast<uint4 *>(w_lds + t * REC + oc * 8) = rec;
             }
-            uint4 rec;
-            rec.x = pack2(v[0], v[1]);
-            rec.y = pack2(v[2], v[3]);
-            rec.z = pack2(v[4], v[5]);
-            rec.w = pack2(v[6], v[7]);
-            *reinterpret_cast<uint4 *>(w_lds + (kol * KS2 + tap) * REC + oc * 8) = rec;
+        } else {
+            for (int e = tid; e < W_ITEMS; e += kThreads) {
+                const int oc = e % octs;
+                int t = e / octs;
+                const int tap = t % KS2, kol = t / KS2;
+                const int ko = co0 + kol, chb = c0 + oc * 8;
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    v[k] = 0.f;
+                    const int ch = chb + k;
+                    if (ko < CO && ch < CI)
+                        v[k] = p.transposed ? p.w[((int64_t)ch * CO + ko) * KS2 + (KS2 - 1 - tap)]
+                                            : p.w[((int64_t)ko * CI + ch) * KS2 + tap];
+                }
+                uint4 rec;
+                rec.x = pack2(v[0], v[1]);
+                rec.y = pack2(v[2], v[3]);
+                rec.z = pack2(v[4], v[5]);
+                rec.w = pack2(v[6], v[7]);
+                *reinterpret_cast<uint4 *>(w_lds + (kol * KS2 + tap) * REC + oc * 8) = rec;
+            }
         }
         __syncthreads();
         // ---- multiply
@@ -244,50 +265,95 @@ struct Bf16Plan {
 Bf16Plan plan_bf16(int ci, int co, int ks, const Geo &g) {
     Bf16Plan best{};
     best.ok = false;
-    const int mt = co <= 32 ? 1 : 2;
-    const int kc = ci <= 16 ? 16 : 32;
-    const int rec = kc + kPadK;
     double best_score = -1.0;
-    for (int nt : {1, 2, 4}) {
-        const int slots = kWaves * nt * 32;
-        for (int imgs = 1; imgs <= 16 && imgs <= g.n; ++imgs) {
-            for (int tr = imgs > 1 ? g.h : 1; tr <= g.h; ++tr) {
-                const int npix = imgs * tr * g.w;
-                if (npix > slots) break;
-                const int lrows = tr + ks - 1, lcols = g.w + ks - 1;
-                const size_t bytes = ((size_t)imgs * lrows * lcols + (size_t)mt * 32 * ks * ks) * rec * 2;
-                if (bytes > 64 * 1024) break;
-                const int bands = (g.h + tr - 1) / tr, groups = (g.n + imgs - 1) / imgs;
-                const double useful = (double)g.n * g.h * g.w, issued = (double)groups * bands * slots;
-                double score = useful / issued;
-                // enough workgroups for every compute unit; larger blocks reuse the filter tile more
-                const double wgs = (double)groups * bands * ((co + mt * 32 - 1) / (mt * 32));
-                if (wgs < 512) score *= 0.5 + 0.5 * wgs / 512;
-                score *= 1.0 + 0.02 * nt;
-                if (score > best_score) {
-                    best_score = score;
-                    best.MT = mt; best.NT = nt; best.KC = kc; best.TR = tr; best.IMGS = imgs; best.bands = bands;
-                    best.lrows = lrows; best.lcols = lcols; best.Wq = (g.w + 3) / 4;
-                    best.in_items = imgs * lrows * best.Wq * (kc / 8);
-                    best.lds_bytes = bytes;
-                    best.ok = true;
+    // Channels per chunk: as many as the problem has, up to 128 (1x1) / 64 (3x3),
+    // if the tiles still fit; fewer, larger chunks mean fewer barriers per result.
+    for (int kc : {16, 32, 64, 128}) {
+    if (kc > 16 && kc / 2 >= ci) continue;
+    if (ks == 3 && kc > 64) continue;
+    const int rec = kc + kPadK;
+    for (int mt : {1, 2, 4}) {
+        if (mt > 1 && co <= (mt / 2) * 32) continue;
+        const int groups_y = (co + mt * 32 - 1) / (mt * 32);
+        for (int nt : {1, 2, 4}) {
+            if (mt * nt > 4) continue;  // 64 accumulator registers at most: three workgroups per compute unit
+            const int slots = kWaves * nt * 32;
+            for (int imgs = 1; imgs <= 16 && imgs <= g.n; ++imgs) {
+                for (int tr = imgs > 1 ? g.h : 1; tr <= g.h; ++tr) {
+                    const int npix = imgs * tr * g.w;
+                    if (npix > slots) break;
+                    const int lrows = tr + ks - 1, lcols = g.w + ks - 1;
+                    const size_t bytes = ((size_t)imgs * lrows * lcols + (size_t)mt * 32 * ks * ks) * rec * 2;
+                    if (bytes > 64 * 1024) break;
+                    const int bands = (g.h + tr - 1) / tr, groups = (g.n + imgs - 1) / imgs;
+                    // useful results over issued matrix-instruction results, whole problem
+                    const double useful = (double)g.n * g.h * g.w * co;
+                    const double issued = (double)groups * bands * slots * groups_y * mt * 32;
+                    double score = useful / issued;
+                    // first enough workgroups to give every compute unit two; then
+                    // larger tiles, which re-read input and filter tiles less often
+                    const double wgs = (double)groups * bands * groups_y;
+                    if (wgs < 512) score *= 0.25 + 0.75 * wgs / 512;
+                    score *= 1.0 + 0.03 * nt + 0.03 * mt + (kc >= 128 ? 0.09 : kc >= 64 ? 0.06 : kc >= 32 ? 0.03 : 0.0);
+                    if (score > best_score) {
+                        best_score = score;
+                        best.MT = mt; best.NT = nt; best.KC = kc; best.TR = tr; best.IMGS = imgs; best.bands = bands;
+                        best.lrows = lrows; best.lcols = lcols; best.Wq = (g.w + 3) / 4;
+                        best.in_items = imgs * lrows * best.Wq * (kc / 8);
+                        best.lds_bytes = bytes;
+                        best.ok = true;
+                    }
                 }
             }
         }
     }
+    }
     return best;
+}
+
+// Filter in bf16 and K order for conv_bf16_k: qf[ko][tap][c] = w[ko][c][tap]
+// (forward), qb[c][tap][ko] = w[ko][c][k*k-1-tap] (data gradient: transposed and
+// flipped); channel pitches CIP, COP (multiples of 8, zero padded).
+__global__ __launch_bounds__(kThreads) void prep_filter_k(const float *__restrict__ w, int CO, int CI, int KS2,
+                                                          uint16_t *__restrict__ qf, int CIP,
+                                                          uint16_t *__restrict__ qb, int COP) {
+    const int64_t nf = (int64_t)CO * KS2 * CIP, nb = qb ? (int64_t)CI * KS2 * COP : 0;
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < nf) {
+        const int c = (int)(i % CIP);
+        const int64_t t = i / CIP;
+        const int tap = (int)(t % KS2), ko = (int)(t / KS2);
+        qf[i] = c < CI ? (uint16_t)bf16_bits(w[((int64_t)ko * CI + c) * KS2 + tap]) : (uint16_t)0;
+    } else if (i - nf < nb) {
+        const int64_t j = i - nf;
+        const int ko = (int)(j % COP);
+        const int64_t t = j / COP;
+        const int tap = (int)(t % KS2), c = (int)(t / KS2);
+        qb[j] = ko < CO ? (uint16_t)bf16_bits(w[((int64_t)ko * CI + c) * KS2 + (KS2 - 1 - tap)]) : (uint16_t)0;
+    }
 }
 
 }  // namespace
 
-bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, bool transposed, int ci, int co,
-               int ks, Geo g, Epilogue ep, const View *r, View out) {
+size_t filter_bf16_elems(int rows, int cols_k, int ks) { return (size_t)rows * ks * ks * ((cols_k + 7) / 8 * 8); }
+
+void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, uint16_t *qf, uint16_t *qb) {
+    const int cip = (cin + 7) / 8 * 8, cop = (cout + 7) / 8 * 8;
+    const int64_t n = (int64_t)cout * ks * ks * cip + (qb ? (int64_t)cin * ks * ks * cop : 0);
+    if (!cx.launch(K_PREP_FILTER, 4.0 * cin * cout * ks * ks + 2.0 * n)) return;
+    cx.run(prep_filter_k, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, w, cout, cin, ks * ks,
+           qf, cip, qb, cop);
+}
+
+bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,
+               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out) {
     const Bf16Plan pl = plan_bf16(ci, co, ks, g);
     if (!pl.ok) return false;
     Bf16Args a{};
     a.in = in.p; a.isn = in.sn; a.isc = in.sc;
     a.scale_shift = scale_shift;
     a.w = w;
+    a.wq = wq; a.CIP = (ci + 7) / 8 * 8;
     a.r = r ? r->p : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
     a.out = out.p; a.osn = out.sn; a.osc = out.sc;
     a.N = g.n; a.H = g.h; a.W = g.w; a.CI = ci; a.CO = co;
@@ -303,8 +369,8 @@ bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
     }
 #define RVN_CASES(KS_, KC_)                                                                              \
     RVN_CASE(KS_, 1, 1, KC_) RVN_CASE(KS_, 1, 2, KC_) RVN_CASE(KS_, 1, 4, KC_)                           \
-    RVN_CASE(KS_, 2, 1, KC_) RVN_CASE(KS_, 2, 2, KC_) RVN_CASE(KS_, 2, 4, KC_)
-    RVN_CASES(3, 16) RVN_CASES(3, 32) RVN_CASES(1, 16) RVN_CASES(1, 32)
+    RVN_CASE(KS_, 2, 1, KC_) RVN_CASE(KS_, 2, 2, KC_) RVN_CASE(KS_, 4, 1, KC_)
+    RVN_CASES(3, 16) RVN_CASES(3, 32) RVN_CASES(3, 64) RVN_CASES(1, 16) RVN_CASES(1, 32) RVN_CASES(1, 64) RVN_CASES(1, 128)
 #undef RVN_CASES
 #undef RVN_CASE
     return false;

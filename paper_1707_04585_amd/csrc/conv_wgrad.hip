@@ -400,7 +400,8 @@ WgradPlan plan_wgrad(int cin, int cout, int ks, const Geo &g) {
 
 size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g) {
     const WgradPlan w = plan_wgrad(cin, cout, ks, g);
-    return w.ok ? (size_t)w.S * w.part_stride : 0;
+    const size_t a = w.ok ? (size_t)w.S * w.part_stride : 0, b = wgrad_bf16_scratch_floats(cin, cout, ks, g);
+    return a > b ? a : b;
 }
 
 void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
@@ -409,6 +410,10 @@ void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_wgrad_calls += 1;
     cx.cost.conv_flops += flops;
+    if (dt == RVN_BF16 &&
+        conv_wgrad_bf16(cx, x, scale_shift, dh, cin, cout, ks, g, scratch, dw, accumulate,
+                        P * cin * 4.0 + P * cout * 4.0, flops))
+        return;
     const WgradPlan w = plan_wgrad(cin, cout, ks, g);
     if (cx.launch(K_CONV_WGRAD, P * cin * 4.0 + P * cout * 4.0, flops)) {
         if (!w.ok) {  // image rows too wide for LDS

@@ -42,6 +42,7 @@ enum KernelId {
     K_WGRAD_REDUCE,
     K_BN_BWD_REDUCE,
     K_BN_BWD_APPLY,
+    K_PREP_FILTER,
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -95,6 +96,7 @@ int reduce_splits(int c, const Geo &g);
 size_t bn_scratch_floats(int c, const Geo &g);
 // Scratch floats for the filter-gradient partial sums.
 size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g);
+size_t wgrad_bf16_scratch_floats(int cin, int cout, int ks, const Geo &g);
 
 // ---- batch norm + ReLU (Section 2.2: a(x) = ReLU(BN(x))) -------------------
 // Per-channel statistics of x and the affine map they imply.  stats holds four
@@ -126,24 +128,38 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
 // out = ep(r, conv(a(x), w)) with a(x) = max(x*scale + shift, 0) formed on the
 // fly from stats (scale_shift = stats + 2*cin); w is fp32 [cout][cin][ks][ks].
 // With dt == RVN_BF16 both operands are rounded to bf16 before multiplying.
-void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, int cin,
+void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, const uint16_t *wq, int cin,
               int cout, int ks, Geo g, Epilogue ep, const View *r, View out);
 
 // The same convolution on bf16 matrix instructions (operands rounded to bf16,
 // fp32 accumulation); `transposed`: w is [ci][co][ks][ks] and is read transposed
 // and flipped (data gradient).  Returns false if no tiling fits (nothing is
 // launched then).
-bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, bool transposed, int ci, int co,
-               int ks, Geo g, Epilogue ep, const View *r, View out);
+bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,
+               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out);
+
+// The filter w [cout][cin][ks][ks] in bf16 and in the order the bf16 kernel
+// consumes it: qf [cout][ks*ks][cin padded to 8] for the forward convolution and
+// (if qb != nullptr) qb [cin][ks*ks][cout padded to 8], transposed and flipped,
+// for the data gradient.  filter_bf16_elems(rows, k_channels, ks) = elements of
+// such a buffer.
+size_t filter_bf16_elems(int rows, int k_channels, int ks);
+void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, uint16_t *qf, uint16_t *qb);
 
 // da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
 // dh is fp32, rounded to bf16 on load when dt == RVN_BF16.
-void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, int cin, int cout, int ks, Geo g,
-                float *da);
+void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *wq, int cin, int cout, int ks,
+                Geo g, float *da);
 
 // dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad], with
 // a(x) = max(x*scale + shift, 0) formed on the fly from the layer input x as in
 // conv_fwd; with dt == RVN_BF16 a and dh are rounded to bf16 before multiplying.
+// The same with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
+// to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the
+// caller accounts for the launch.  Returns false (nothing launched) when no
+// plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.
+bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
+                     float *scratch, float *dw, bool accumulate, double bytes, double flops);
 void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
                 int ks, Geo g, float *scratch, float *dw, bool accumulate);
 

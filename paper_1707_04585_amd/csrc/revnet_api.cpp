@@ -75,8 +75,19 @@ struct Plan {
     size_t wgrad_scratch; // partial filter gradients (backward only)
     size_t h[2];          // h_l = conv_l(a_l), fp32, input of layer l+1
     size_t g[2];          // gradient ping-pong buffers (backward only)
+    // bf16 convolutions with large filters: the filters of the function at hand
+    // in bf16 and K order, for the forward convolution and (backward only) for
+    // the data gradient; `prep[l]` says whether layer l uses them
+    size_t wq_f[3], wq_b[3];
+    bool prep[3];
     size_t total;
 };
+
+// Filters this large are converted once per function evaluation instead of in
+// every workgroup of the convolution.
+bool wants_prep(const rvn_block_desc &d, const Layer &ly) {
+    return d.conv_dtype == RVN_BF16 && (int64_t)ly.cin * ly.cout * ly.ks * ly.ks >= 16384;
+}
 
 Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     Plan p{};
@@ -91,6 +102,17 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
         wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
         max_cin = std::max(max_cin, (size_t)ly.cin);
         if (l < p.L - 1) max_mid = std::max(max_mid, (size_t)ly.cout);
+    }
+    for (int l = 0; l < p.L; ++l) {
+        const Layer &ly = p.layers[l];
+        p.prep[l] = wants_prep(d, ly);
+        if (!p.prep[l]) continue;
+        p.wq_f[l] = off;
+        off = align_up(off + filter_bf16_elems(ly.cout, ly.cin, ly.ks) * 2);
+        if (backward) {
+            p.wq_b[l] = off;
+            off = align_up(off + filter_bf16_elems(ly.cin, ly.cout, ly.ks) * 2);
+        }
     }
     p.counters = off;
     p.n_counters = (int)std::max(max_cin, (size_t)1) * kCounterStride;
@@ -131,6 +153,7 @@ struct Bufs {
     float *bn_scratch;
     float *wgrad_scratch;
     int *counters;
+    uint16_t *wq_f[3], *wq_b[3];  // null where the layer does not use converted filters
 };
 
 Bufs bind(const Plan &p, void *ws) {
@@ -138,6 +161,8 @@ Bufs bind(const Plan &p, void *ws) {
     Bufs o{};
     for (int l = 0; l < 3; ++l) {
         o.stats[l] = reinterpret_cast<float *>(b + p.stats[l]);
+        o.wq_f[l] = p.prep[l] ? reinterpret_cast<uint16_t *>(b + p.wq_f[l]) : nullptr;
+        o.wq_b[l] = p.prep[l] && p.wq_b[l] ? reinterpret_cast<uint16_t *>(b + p.wq_b[l]) : nullptr;
     }
     for (int l = 0; l < 2; ++l) {
         o.h[l] = reinterpret_cast<float *>(b + p.h[l]);
@@ -235,16 +260,18 @@ int check_ws(const void *ws, size_t have, size_t need) {
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
                   const rvn_func_params &p, Epilogue ep, const View *r, View out) {
     View cur = x;
+    for (int l = 0; l < pl.L; ++l)
+        if (b.wq_f[l]) prep_filter_bf16(cx, p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]);
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
         bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
             cur = h;
         } else {
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
         }
     }
 }
@@ -263,7 +290,7 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                    gr.d_conv_w[l], accumulate);
         float *da = b.g[cur];
-        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], ly.cin, ly.cout, ly.ks, g, da);
+        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da);
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
             bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
