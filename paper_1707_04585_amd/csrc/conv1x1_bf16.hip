@@ -1,0 +1,379 @@
+// 1x1 convolution (forward and data gradient) with bf16 operands on the CDNA4
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation), for the 1x1 units
+// of the bottleneck residual function (Section 2.2, Eq. 3) when the block
+// descriptor asks for bf16 convolution operands.
+//
+// A 1x1 convolution has no halo, so the activation operand never needs LDS: the
+// image plane of a channel is a contiguous run of H*W floats, and a lane loads
+// 4 consecutive pixels of 8 consecutive channels (8 coalesced 16-byte loads per
+// 16-channel step).  Element j of those loads, over the 8 channels, is exactly
+// the B operand of one matrix instruction for the lane's pixel 4*q + j, so a
+// wavefront covers 32 groups of 4 pixels with 4 matrix instructions per step
+// and its results come out as 4 consecutive pixels per lane and channel:
+// 16-byte stores, 512-byte runs per channel.  BN scale/shift, ReLU and the bf16
+// rounding are applied in registers between the load and the multiply; the
+// coupling y = r + acc / reconstruction x = r - acc of Section 3.1 is applied in
+// the accumulator registers.
+//
+// The filter is read from a copy laid out in operand order (one contiguous
+// 1 KB block per 32 output channels x 16 input channels, lane-major), so the A
+// operand is a single coalesced 16-byte load per lane that stays in L1/L2.
+// The loads of step s+1 are issued before the arithmetic of step s.  There is
+// no LDS and no barrier: the four wavefronts of a workgroup are independent
+// and are arranged as PW pixel tiles x CW output-channel tiles so that those
+// which share input data run on the same compute unit.
+#include <algorithm>
+#include <cstdlib>
+#include <type_traits>
+
+#include "kernels.h"
+
+namespace rvn {
+
+namespace {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef float f4a_t __attribute__((ext_vector_type(4)));              // 16-byte aligned
+typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));  // only element aligned
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+
+struct C1Args {
+    const float *in;  // x (forward) or upstream gradient (data gradient), fp32, planes of HW floats
+    int64_t isn, isc;
+    const float *scale_shift;  // [2*CI]: a = max(in*scale + shift, 0); null = use `in` as is
+    const uint16_t *wq;        // filter in operand order: [mtiles][ksteps][64 lanes][8]
+    const float *r;            // skip operand of the epilogue (may alias out)
+    int64_t rsn, rsc;
+    float *out;
+    int64_t osn, osc;
+    int HW, CI, CO;
+    int ep;
+    int gpi, groups;  // 4-pixel groups per image and in total
+    int ksteps;       // CI / 16
+    int mtiles;       // ceil(CO / 32)
+    int PW, CW, KW;   // wavefronts of a workgroup: pixel tiles x output-channel tiles x shares of the channels
+    int npt, ncg;     // workgroup grid: pixel tiles / PW, output-channel tiles / CW
+    uint32_t m_gpi;   // fast-division multiplier (see fdiv)
+};
+
+__device__ __forceinline__ int fdiv(int e, uint32_t m) { return m ? (int)__umulhi((uint32_t)e, m) : e; }
+
+// Two floats to a pair of bf16 (nearest even): one v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const float2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
+
+// MTW: 32-channel output tiles per wavefront.  GEN: planes need not be 16-byte
+// aligned and H*W need not be a multiple of 4 (the last group of an image is
+// then loaded from H*W - 4 and shifted into place).
+template <int MTW, bool GEN>
+__global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
+    using F4 = typename std::conditional<GEN, f4u_t, f4a_t>::type;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l32 = lane & 31, kg = lane >> 5;
+
+    // Workgroup ids go round-robin over the 8 dies; give every die a contiguous
+    // range of the (pixel tile, channel tile) space so that workgroups sharing
+    // input data also share an L2.
+    const int per_die = gridDim.x >> 3;
+    const int logical = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
+    const int cg = logical % p.ncg, pt = logical / p.ncg;
+    if (pt >= p.npt) return;
+    const int pw = wave % p.PW, cw = (wave / p.PW) % p.CW, kw = wave / (p.PW * p.CW);
+    const int mt0 = (cg * p.CW + cw) * MTW;
+    const bool idle = mt0 >= p.mtiles;  // no output tile: only keeps the barrier company
+
+    const int HW = p.HW;
+    const int g = (pt * p.PW + pw) * 32 + l32;
+    const bool live = g < p.groups;
+    const int gg = live ? g : 0;
+    const int n = fdiv(gg, p.m_gpi), q = gg - n * p.gpi;
+    const int pix = 4 * q;
+    const int valid = GEN ? min(4, HW - pix) : 4;
+    const int shift = 4 - valid;
+    // Addresses are a wavefront-uniform 64-bit part (channel, step) plus a 32-bit
+    // per-lane byte offset (image, pixel, channel octet half): the host keeps
+    // every tensor slice handed to one launch below 4 GB.
+    const uint32_t in_off = (uint32_t)(((int64_t)n * p.isn + (pix - shift) + (int64_t)(kg * 8) * p.isc) * 4);
+    const char *const in_base = reinterpret_cast<const char *>(p.in);
+    const int64_t isc_b = p.isc * 4;
+    const char *const w_base = reinterpret_cast<const char *>(p.wq) + (int64_t)mt0 * p.ksteps * 1024;
+    const uint32_t w_off = (uint32_t)lane * 16;
+    const int64_t tile_w = (int64_t)p.ksteps * 1024;
+    const bool bn = p.scale_shift != nullptr;
+    const int CI = p.CI;
+
+    float16_t acc[MTW][4];
+#pragma unroll
+    for (int m = 0; m < MTW; ++m)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[m][j][i] = 0.f;
+
+    struct Buf {
+        F4 v[8];
+        uint4_t a[MTW];
+    };
+    auto load = [&](Buf &b, int ks) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            b.v[k] = *reinterpret_cast<const F4 *>(in_base + (int64_t)(ks * 16 + k) * isc_b + in_off);
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) {
+            const bool has = mt0 + m < p.mtiles;
+            b.a[m] = *reinterpret_cast<const uint4_t *>(w_base + (has ? m * tile_w : 0) + (int64_t)ks * 1024 + w_off);
+        }
+    };
+    auto compute = [&](Buf &b, int ks) {
+        float v[8][4];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float x0 = b.v[k][0], x1 = b.v[k][1], x2 = b.v[k][2], x3 = b.v[k][3];
+            if (GEN) {  // the last group of an image was loaded `shift` pixels early
+                const float y0 = shift == 0 ? x0 : shift == 1 ? x1 : shift == 2 ? x2 : x3;
+                const float y1 = shift == 0 ? x1 : shift == 1 ? x2 : shift == 2 ? x3 : 0.f;
+                const float y2 = shift == 0 ? x2 : shift == 1 ? x3 : 0.f;
+                const float y3 = shift == 0 ? x3 : 0.f;
+                x0 = y0; x1 = y1; x2 = y2; x3 = y3;
+            }
+            if (bn) {
+                const int c = ks * 16 + k;  // wavefront-uniform: scalar loads
+                const float s_lo = p.scale_shift[c], s_hi = p.scale_shift[c + 8];
+                const float h_lo = p.scale_shift[CI + c], h_hi = p.scale_shift[CI + c + 8];
+                const float sc = kg ? s_hi : s_lo, sh = kg ? h_hi : h_lo;
+                x0 = fmaxf(fmaf(x0, sc, sh), 0.f);
+                x1 = fmaxf(fmaf(x1, sc, sh), 0.f);
+                x2 = fmaxf(fmaf(x2, sc, sh), 0.f);
+                x3 = fmaxf(fmaf(x3, sc, sh), 0.f);
+                if (GEN) {  // pixels past the end of the image stay zero
+                    x1 = valid > 1 ? x1 : 0.f;
+                    x2 = valid > 2 ? x2 : 0.f;
+                    x3 = valid > 3 ? x3 : 0.f;
+                }
+            }
+            v[k][0] = x0; v[k][1] = x1; v[k][2] = x2; v[k][3] = x3;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4_t bq = {pack2(v[0][j], v[1][j]), pack2(v[2][j], v[3][j]), pack2(v[4][j], v[5][j]),
+                                pack2(v[6][j], v[7][j])};
+            const bf16x8_t bo = *reinterpret_cast<const bf16x8_t *>(&bq);
+#pragma unroll
+            for (int m = 0; m < MTW; ++m)
+                acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t *>(&b.a[m]), bo,
+                                                                    acc[m][j], 0, 0, 0);
+        }
+    };
+
+    // This wavefront's share of the reduction (KW wavefronts split the channels).
+    Buf b0, b1;
+    const int ks0 = idle ? 0 : kw * p.ksteps / p.KW;
+    const int ksteps = idle ? 0 : (kw + 1) * p.ksteps / p.KW;
+    if (ks0 < ksteps) load(b0, ks0);
+    for (int ks = ks0; ks < ksteps; ks += 2) {
+        if (ks + 1 < ksteps) load(b1, ks + 1);
+        compute(b0, ks);
+        if (ks + 1 < ksteps) {
+            if (ks + 2 < ksteps) load(b0, ks + 2);
+            compute(b1, ks + 1);
+        }
+    }
+
+    // ---- epilogue: register i of accumulator (m, j) is channel
+    //      (mt0 + m)*32 + 8*(i/4) + 4*kg + i%4 at pixel pix + j
+    if (p.KW > 1) {  // sum the KW partial tiles in wavefront kw = 0, in a fixed order
+        extern __shared__ float red[];  // [KW - 1][PW * CW][MTW * 64 registers][64 lanes]
+        const int slot = wave % (p.PW * p.CW), slots = p.PW * p.CW;
+        if (kw > 0) {
+            float *dst = red + ((int64_t)((kw - 1) * slots + slot) * (MTW * 64)) * 64 + lane;
+#pragma unroll
+            for (int m = 0; m < MTW; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) dst[((m * 4 + j) * 16 + i) * 64] = acc[m][j][i];
+        }
+        __syncthreads();
+        if (kw > 0) return;
+        for (int k = 1; k < p.KW; ++k) {
+            const float *srcp = red + ((int64_t)((k - 1) * slots + slot) * (MTW * 64)) * 64 + lane;
+#pragma unroll
+            for (int m = 0; m < MTW; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[m][j][i] += srcp[((m * 4 + j) * 16 + i) * 64];
+        }
+    }
+    if (!live || idle) return;
+    //      Channels are handled 8 at a time; the skip values of the next 8 are
+    //      requested before the current 8 are stored (r may alias out, element
+    //      for element, so a lane reads an address before it writes it).
+    const uint32_t o_off = (uint32_t)(((int64_t)n * p.osn + pix + (int64_t)(4 * kg) * p.osc) * 4);
+    const uint32_t r_off = (uint32_t)(((int64_t)n * p.rsn + pix + (int64_t)(4 * kg) * p.rsc) * 4);
+    char *const o_base = reinterpret_cast<char *>(p.out);
+    const char *const r_base = reinterpret_cast<const char *>(p.r);
+    const bool full = !GEN || valid == 4;
+    const bool skip = p.ep != EP_STORE;
+    constexpr int NB = MTW * 2;  // batches of 8 channels
+    F4 rv[2][8];
+    // channel of element e of batch b, without the lane's 4*kg
+    auto chan = [&](int b, int e) { return (mt0 + (b >> 1)) * 32 + 16 * (b & 1) + 8 * (e >> 2) + (e & 3); };
+    auto fetch = [&](F4 *dst, int b) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int ku = chan(b, e);
+            dst[e] = F4{0.f, 0.f, 0.f, 0.f};
+            if (ku + 4 * kg < p.CO) {
+                const float *rp = reinterpret_cast<const float *>(r_base + (int64_t)ku * p.rsc * 4 + r_off);
+                if (full) {
+                    dst[e] = *reinterpret_cast<const F4 *>(rp);
+                } else {
+                    dst[e][0] = rp[0];
+                    if (valid > 1) dst[e][1] = rp[1];
+                    if (valid > 2) dst[e][2] = rp[2];
+                }
+            }
+        }
+    };
+    if (skip) fetch(rv[0], 0);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (skip && b + 1 < NB) fetch(rv[(b + 1) & 1], b + 1);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int ku = chan(b, e);
+            if (ku + 4 * kg >= p.CO) continue;
+            const int m = b >> 1, i = 8 * (b & 1) + e;
+            F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
+            if (skip) t = p.ep == EP_ADD ? rv[b & 1][e] + t : rv[b & 1][e] - t;
+            float *op = reinterpret_cast<float *>(o_base + (int64_t)ku * p.osc * 4 + o_off);
+            if (full) {
+                *reinterpret_cast<F4 *>(op) = t;
+            } else {
+                op[0] = t[0];
+                if (valid > 1) op[1] = t[1];
+                if (valid > 2) op[2] = t[2];
+            }
+        }
+    }
+}
+
+// qf[mt][ks][lane][e] = W[row = mt*32 + lane%32][col = ks*16 + (lane/32)*8 + e],
+// W[row][col] = w[row][col] (forward: rows = cout, cols = cin) or w[col][row]
+// (data gradient: rows = cin, cols = cout); zero outside the filter.
+__global__ __launch_bounds__(kThreads) void prep_filter_1x1_k(const float *__restrict__ w, int CO, int CI,
+                                                              uint16_t *__restrict__ qf, int ks_f, int64_t n_f,
+                                                              uint16_t *__restrict__ qb, int ks_b, int64_t n_b) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const bool fwd = i < n_f;
+    const int64_t j = fwd ? i : i - n_f;
+    if (!fwd && j >= n_b) return;
+    const int ksteps = fwd ? ks_f : ks_b;
+    const int e = (int)(j & 7), ln = (int)((j >> 3) & 63);
+    const int64_t blk = j >> 9;
+    const int ks = (int)(blk % ksteps), mt = (int)(blk / ksteps);
+    const int row = mt * 32 + (ln & 31), col = ks * 16 + (ln >> 5) * 8 + e;
+    float v = 0.f;
+    if (fwd) {
+        if (row < CO && col < CI) v = w[(int64_t)row * CI + col];
+    } else {
+        if (row < CI && col < CO) v = w[(int64_t)col * CI + row];
+    }
+    const uint32_t q = pack2(v, 0.f);
+    (fwd ? qf : qb)[j] = (uint16_t)(q & 0xffffu);
+}
+
+uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
+
+size_t operand_elems(int rows, int cols) { return (size_t)((rows + 31) / 32) * 32 * ((cols + 15) / 16) * 16; }
+
+}  // namespace
+
+bool conv1x1_direct_ok(int k_channels, const Geo &g) {
+    return k_channels % 16 == 0 && (int64_t)g.h * g.w >= 4 && (int64_t)g.n * ((g.h * g.w + 3) / 4) < (1 << 30);
+}
+
+size_t filter_1x1_elems(int rows, int k_channels) { return operand_elems(rows, k_channels); }
+
+void prep_filter_1x1(Ctx &cx, const float *w, int cin, int cout, uint16_t *qf, uint16_t *qb) {
+    const int64_t n_f = qf ? (int64_t)operand_elems(cout, cin) : 0, n_b = qb ? (int64_t)operand_elems(cin, cout) : 0;
+    if (!cx.launch(K_PREP_FILTER, 4.0 * cin * cout + 2.0 * (n_f + n_b))) return;
+    cx.run(prep_filter_1x1_k, dim3((unsigned)((n_f + n_b + kThreads - 1) / kThreads)), dim3(kThreads), 0, w, cout, cin,
+           qf, (cin + 15) / 16, n_f, qb, (cout + 15) / 16, n_b);
+}
+
+bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
+                  Epilogue ep, const View *r, View out) {
+    if (!wq || !conv1x1_direct_ok(ci, g)) return false;
+    const int HW = g.h * g.w;
+    // Lane offsets are 32-bit byte offsets from the tensor base: launch per slice
+    // of images small enough for that.
+    const int64_t img_bytes = 4 * std::max(std::max(in.sn, out.sn), r ? r->sn : (int64_t)0);
+    const int64_t tail_bytes = 4 * ((int64_t)HW + std::max(std::max((int64_t)ci * in.sc, (int64_t)co * out.sc),
+                                                           r ? (int64_t)co * r->sc : (int64_t)0));
+    const int64_t room = ((int64_t)1 << 32) - tail_bytes;
+    if (room < img_bytes) {  // one image alone is too large
+        cx.fail(hipErrorInvalidValue);
+        return true;
+    }
+    const int slice_n = (int)std::min<int64_t>(g.n, room / std::max<int64_t>(img_bytes, 1));
+    for (int n0 = 0; n0 < g.n; n0 += slice_n) {
+        const int ns = std::min(slice_n, g.n - n0);
+        C1Args a{};
+        a.in = in.p + (int64_t)n0 * in.sn; a.isn = in.sn; a.isc = in.sc;
+        a.scale_shift = scale_shift;
+        a.wq = wq;
+        a.r = r ? r->p + (int64_t)n0 * r->sn : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
+        a.out = out.p + (int64_t)n0 * out.sn; a.osn = out.sn; a.osc = out.sc;
+        a.HW = HW; a.CI = ci; a.CO = co;
+        a.ep = (int)ep;
+        a.gpi = (HW + 3) / 4;
+        a.groups = ns * a.gpi;
+        a.ksteps = ci / 16;
+        a.mtiles = (co + 31) / 32;
+        a.m_gpi = fdiv_magic(a.gpi);
+        const int ptiles = (a.groups + 31) / 32;
+        // With few tiles, the wavefronts of a workgroup split the input channels
+        // (shorter dependent chains, more loads in flight).  Otherwise two output
+        // tiles per wavefront halve the passes over the input, as long as that
+        // still leaves two wavefronts for every SIMD.
+        const int64_t tiles = (int64_t)ptiles * a.mtiles;
+        a.KW = 1;
+        if (tiles < 1024 && a.ksteps >= 8) a.KW = tiles < 512 && a.ksteps >= 16 ? 4 : 2;
+        int mtw = a.KW == 1 && a.mtiles >= 2 && (int64_t)ptiles * ((a.mtiles + 1) / 2) >= 2048 ? 2 : 1;
+        if (const char *e = getenv("RVN_1X1_KW")) a.KW = atoi(e), mtw = 1;
+        const int cot = (a.mtiles + mtw - 1) / mtw;
+        const int rest = 4 / a.KW;
+        a.CW = cot >= rest ? rest : cot >= 2 ? 2 : 1;
+        a.PW = rest / a.CW;
+        a.npt = (ptiles + a.PW - 1) / a.PW;
+        a.ncg = (cot + a.CW - 1) / a.CW;
+        const int64_t wgs = ((int64_t)a.npt * a.ncg + 7) / 8 * 8;
+        const bool gen = (HW & 3) != 0 || (in.sn & 3) != 0 || (in.sc & 3) != 0 || (out.sn & 3) != 0 ||
+                         (out.sc & 3) != 0 || (reinterpret_cast<uintptr_t>(in.p) & 15) != 0 ||
+                         (reinterpret_cast<uintptr_t>(out.p) & 15) != 0 ||
+                         (r && ((r->sn & 3) != 0 || (r->sc & 3) != 0 || (reinterpret_cast<uintptr_t>(r->p) & 15) != 0));
+        const dim3 grid((unsigned)wgs);
+        const size_t lds = a.KW > 1 ? (size_t)(a.KW - 1) * (a.PW * a.CW) * mtw * 64 * 64 * 4 : 0;
+        if (mtw == 2) {
+            if (gen) cx.run(conv1x1_bf16_k<2, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<2, false>, grid, dim3(kThreads), lds, a);
+        } else {
+            if (gen) cx.run(conv1x1_bf16_k<1, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<1, false>, grid, dim3(kThreads), lds, a);
+        }
+    }
+    return true;
+}
+
+}  // namespace rvn

@@ -26,6 +26,8 @@
 // full rows of IMGS images, at most 4*NT*32 pixels) and MT*32 output channels;
 // wavefront w takes the pixel groups w*NT .. w*NT+NT-1.  Input channels are
 // consumed KC at a time.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace rvn {
@@ -317,7 +319,7 @@ Bf16Plan plan_bf16(int ci, int co, int ks, const Geo &g) {
 __global__ __launch_bounds__(kThreads) void prep_filter_k(const float *__restrict__ w, int CO, int CI, int KS2,
                                                           uint16_t *__restrict__ qf, int CIP,
                                                           uint16_t *__restrict__ qb, int COP) {
-    const int64_t nf = (int64_t)CO * KS2 * CIP, nb = qb ? (int64_t)CI * KS2 * COP : 0;
+    const int64_t nf = qf ? (int64_t)CO * KS2 * CIP : 0, nb = qb ? (int64_t)CI * KS2 * COP : 0;
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i < nf) {
         const int c = (int)(i % CIP);
@@ -335,11 +337,22 @@ __global__ __launch_bounds__(kThreads) void prep_filter_k(const float *__restric
 
 }  // namespace
 
-size_t filter_bf16_elems(int rows, int cols_k, int ks) { return (size_t)rows * ks * ks * ((cols_k + 7) / 8 * 8); }
+size_t filter_bf16_elems(int rows, int cols_k, int ks) {
+    const size_t n = (size_t)rows * ks * ks * ((cols_k + 7) / 8 * 8);
+    return ks == 1 ? std::max(n, filter_1x1_elems(rows, cols_k)) : n;
+}
 
-void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, uint16_t *qf, uint16_t *qb) {
+void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, Geo g, uint16_t *qf, uint16_t *qb) {
+    if (ks == 1) {  // operand order for the filters conv1x1_bf16 will take
+        uint16_t *const df = qf && conv1x1_direct_ok(cin, g) ? qf : nullptr;
+        uint16_t *const db = qb && conv1x1_direct_ok(cout, g) ? qb : nullptr;
+        if (df || db) prep_filter_1x1(cx, w, cin, cout, df, db);
+        if (df) qf = nullptr;
+        if (db) qb = nullptr;
+        if (!qf && !qb) return;
+    }
     const int cip = (cin + 7) / 8 * 8, cop = (cout + 7) / 8 * 8;
-    const int64_t n = (int64_t)cout * ks * ks * cip + (qb ? (int64_t)cin * ks * ks * cop : 0);
+    const int64_t n = (qf ? (int64_t)cout * ks * ks * cip : 0) + (qb ? (int64_t)cin * ks * ks * cop : 0);
     if (!cx.launch(K_PREP_FILTER, 4.0 * cin * cout * ks * ks + 2.0 * n)) return;
     cx.run(prep_filter_k, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, w, cout, cin, ks * ks,
            qf, cip, qb, cop);
@@ -347,6 +360,7 @@ void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, uint16
 
 bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,
                int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out) {
+    if (ks == 1 && wq && conv1x1_direct_ok(ci, g)) return conv1x1_bf16(cx, in, scale_shift, wq, ci, co, g, ep, r, out);
     const Bf16Plan pl = plan_bf16(ci, co, ks, g);
     if (!pl.ok) return false;
     Bf16Args a{};

@@ -143,8 +143,22 @@ bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const
 // (if qb != nullptr) qb [cin][ks*ks][cout padded to 8], transposed and flipped,
 // for the data gradient.  filter_bf16_elems(rows, k_channels, ks) = elements of
 // such a buffer.
+//
+// 1x1 filters whose reduction length (cin forward, cout for the data gradient)
+// passes conv1x1_direct_ok are stored instead in the operand order of
+// conv1x1_bf16: [rows / 32][k_channels / 16][64 lanes][8], zero padded.
 size_t filter_bf16_elems(int rows, int k_channels, int ks);
-void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, uint16_t *qf, uint16_t *qb);
+void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, Geo g, uint16_t *qf, uint16_t *qb);
+
+// 1x1 convolution without LDS: activations go from HBM to the matrix
+// instruction's registers directly.  Needs the filter in operand order (wq from
+// prep_filter_1x1) and conv1x1_direct_ok(ci, g); returns false (nothing
+// launched) otherwise.
+bool conv1x1_direct_ok(int k_channels, const Geo &g);
+size_t filter_1x1_elems(int rows, int k_channels);
+void prep_filter_1x1(Ctx &cx, const float *w, int cin, int cout, uint16_t *qf, uint16_t *qb);
+bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
+                  Epilogue ep, const View *r, View out);
 
 // da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
 // dh is fp32, rounded to bf16 on load when dt == RVN_BF16.
@@ -154,13 +168,14 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *
 // dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad], with
 // a(x) = max(x*scale + shift, 0) formed on the fly from the layer input x as in
 // conv_fwd; with dt == RVN_BF16 a and dh are rounded to bf16 before multiplying.
+void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
+                int ks, Geo g, float *scratch, float *dw, bool accumulate);
+
 // The same with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
 // to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the
 // caller accounts for the launch.  Returns false (nothing launched) when no
 // plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.
 bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
                      float *scratch, float *dw, bool accumulate, double bytes, double flops);
-void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
-                int ks, Geo g, float *scratch, float *dw, bool accumulate);
 
 }  // namespace rvn

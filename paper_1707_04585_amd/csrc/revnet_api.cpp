@@ -85,8 +85,10 @@ struct Plan {
 
 // Filters this large are converted once per function evaluation instead of in
 // every workgroup of the convolution.
-bool wants_prep(const rvn_block_desc &d, const Layer &ly) {
-    return d.conv_dtype == RVN_BF16 && (int64_t)ly.cin * ly.cout * ly.ks * ly.ks >= 16384;
+bool wants_prep(const rvn_block_desc &d, const Layer &ly, const Geo &g) {
+    if (d.conv_dtype != RVN_BF16) return false;
+    if (ly.ks == 1 && (conv1x1_direct_ok(ly.cin, g) || conv1x1_direct_ok(ly.cout, g))) return true;
+    return (int64_t)ly.cin * ly.cout * ly.ks * ly.ks >= 16384;
 }
 
 Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
@@ -105,7 +107,7 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     }
     for (int l = 0; l < p.L; ++l) {
         const Layer &ly = p.layers[l];
-        p.prep[l] = wants_prep(d, ly);
+        p.prep[l] = wants_prep(d, ly, g);
         if (!p.prep[l]) continue;
         p.wq_f[l] = off;
         off = align_up(off + filter_bf16_elems(ly.cout, ly.cin, ly.ks) * 2);
@@ -261,7 +263,7 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
                   const rvn_func_params &p, Epilogue ep, const View *r, View out) {
     View cur = x;
     for (int l = 0; l < pl.L; ++l)
-        if (b.wq_f[l]) prep_filter_bf16(cx, p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]);
+        if (b.wq_f[l]) prep_filter_bf16(cx, p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, g, b.wq_f[l], b.wq_b[l]);
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
         bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
