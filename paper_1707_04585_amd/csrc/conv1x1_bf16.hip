@@ -70,10 +70,11 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     return *reinterpret_cast<const uint32_t *>(&b);
 }
 
-// MTW: 32-channel output tiles per wavefront.  GEN: planes need not be 16-byte
+// MTW: 32-channel output tiles per wavefront.  DEPTH: steps the loads run ahead
+// (1 or 2).  GEN: planes need not be 16-byte
 // aligned and H*W need not be a multiple of 4 (the last group of an image is
 // then loaded from H*W - 4 and shifted into place).
-template <int MTW, bool GEN>
+template <int MTW, int DEPTH, bool GEN>
 __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     using F4 = typename std::conditional<GEN, f4u_t, f4a_t>::type;
     const int lane = threadIdx.x & 63;
@@ -111,13 +112,39 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     const bool bn = p.scale_shift != nullptr;
     const int CI = p.CI;
 
+    // Output addressing: uniform 64-bit channel part plus a 32-bit lane offset.
+    const uint32_t o_off = (uint32_t)(((int64_t)n * p.osn + pix + (int64_t)(4 * kg) * p.osc) * 4);
+    const uint32_t r_off = (uint32_t)(((int64_t)n * p.rsn + pix + (int64_t)(4 * kg) * p.rsc) * 4);
+    char *const o_base = reinterpret_cast<char *>(p.out);
+    const char *const r_base = reinterpret_cast<const char *>(p.r);
+    const bool full = !GEN || valid == 4;
+    // channel of register i of output tile m, without the lane's 4*kg
+    auto chan = [&](int m, int i) { return (mt0 + m) * 32 + 8 * (i >> 2) + (i & 3); };
+
+    // The accumulators start from the skip operand (+r for y = r + conv, -r for
+    // x = r - conv, negated again when stored), so its loads are in flight
+    // together with the first activation loads and cost no registers.  r may
+    // alias out element for element: a lane reads an address before it writes it.
     float16_t acc[MTW][4];
 #pragma unroll
     for (int m = 0; m < MTW; ++m)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 16; ++i) {
+            F4 t = {0.f, 0.f, 0.f, 0.f};
+            if (p.ep != EP_STORE && live && !idle && kw == 0 && chan(m, i) + 4 * kg < p.CO) {
+                const float *rp = reinterpret_cast<const float *>(r_base + (int64_t)chan(m, i) * p.rsc * 4 + r_off);
+                if (full) {
+                    t = *reinterpret_cast<const F4 *>(rp);
+                } else {
+                    t[0] = rp[0];
+                    if (valid > 1) t[1] = rp[1];
+                    if (valid > 2) t[2] = rp[2];
+                }
+                if (p.ep == EP_SUB) t = -t;
+            }
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[m][j][i] = 0.f;
+            for (int j = 0; j < 4; ++j) acc[m][j][i] = t[j];
+        }
 
     struct Buf {
         F4 v[8];
@@ -174,17 +201,36 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
     };
 
-    // This wavefront's share of the reduction (KW wavefronts split the channels).
-    Buf b0, b1;
+    // This wavefront's share of the reduction (KW wavefronts split the channels);
+    // loads run DEPTH steps ahead of the arithmetic.
     const int ks0 = idle ? 0 : kw * p.ksteps / p.KW;
     const int ksteps = idle ? 0 : (kw + 1) * p.ksteps / p.KW;
-    if (ks0 < ksteps) load(b0, ks0);
-    for (int ks = ks0; ks < ksteps; ks += 2) {
-        if (ks + 1 < ksteps) load(b1, ks + 1);
-        compute(b0, ks);
-        if (ks + 1 < ksteps) {
-            if (ks + 2 < ksteps) load(b0, ks + 2);
-            compute(b1, ks + 1);
+    if (DEPTH == 1) {
+        Buf b0, b1;
+        if (ks0 < ksteps) load(b0, ks0);
+        for (int ks = ks0; ks < ksteps; ks += 2) {
+            if (ks + 1 < ksteps) load(b1, ks + 1);
+            compute(b0, ks);
+            if (ks + 1 < ksteps) {
+                if (ks + 2 < ksteps) load(b0, ks + 2);
+                compute(b1, ks + 1);
+            }
+        }
+    } else {
+        Buf b0, b1, b2;
+        if (ks0 < ksteps) load(b0, ks0);
+        if (ks0 + 1 < ksteps) load(b1, ks0 + 1);
+        for (int ks = ks0; ks < ksteps; ks += 3) {
+            if (ks + 2 < ksteps) load(b2, ks + 2);
+            compute(b0, ks);
+            if (ks + 1 < ksteps) {
+                if (ks + 3 < ksteps) load(b0, ks + 3);
+                compute(b1, ks + 1);
+            }
+            if (ks + 2 < ksteps) {
+                if (ks + 4 < ksteps) load(b1, ks + 4);
+                compute(b2, ks + 2);
+            }
         }
     }
 
@@ -215,48 +261,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
     }
     if (!live || idle) return;
-    //      Channels are handled 8 at a time; the skip values of the next 8 are
-    //      requested before the current 8 are stored (r may alias out, element
-    //      for element, so a lane reads an address before it writes it).
-    const uint32_t o_off = (uint32_t)(((int64_t)n * p.osn + pix + (int64_t)(4 * kg) * p.osc) * 4);
-    const uint32_t r_off = (uint32_t)(((int64_t)n * p.rsn + pix + (int64_t)(4 * kg) * p.rsc) * 4);
-    char *const o_base = reinterpret_cast<char *>(p.out);
-    const char *const r_base = reinterpret_cast<const char *>(p.r);
-    const bool full = !GEN || valid == 4;
-    const bool skip = p.ep != EP_STORE;
-    constexpr int NB = MTW * 2;  // batches of 8 channels
-    F4 rv[2][8];
-    // channel of element e of batch b, without the lane's 4*kg
-    auto chan = [&](int b, int e) { return (mt0 + (b >> 1)) * 32 + 16 * (b & 1) + 8 * (e >> 2) + (e & 3); };
-    auto fetch = [&](F4 *dst, int b) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int ku = chan(b, e);
-            dst[e] = F4{0.f, 0.f, 0.f, 0.f};
-            if (ku + 4 * kg < p.CO) {
-                const float *rp = reinterpret_cast<const float *>(r_base + (int64_t)ku * p.rsc * 4 + r_off);
-                if (full) {
-                    dst[e] = *reinterpret_cast<const F4 *>(rp);
-                } else {
-                    dst[e][0] = rp[0];
-                    if (valid > 1) dst[e][1] = rp[1];
-                    if (valid > 2) dst[e][2] = rp[2];
-                }
-            }
-        }
-    };
-    if (skip) fetch(rv[0], 0);
+    for (int m = 0; m < MTW; ++m)
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        if (skip && b + 1 < NB) fetch(rv[(b + 1) & 1], b + 1);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int ku = chan(b, e);
-            if (ku + 4 * kg >= p.CO) continue;
-            const int m = b >> 1, i = 8 * (b & 1) + e;
+        for (int i = 0; i < 16; ++i) {
+            if (chan(m, i) + 4 * kg >= p.CO) continue;
             F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
-            if (skip) t = p.ep == EP_ADD ? rv[b & 1][e] + t : rv[b & 1][e] - t;
-            float *op = reinterpret_cast<float *>(o_base + (int64_t)ku * p.osc * 4 + o_off);
+            if (p.ep == EP_SUB) t = -t;
+            float *op = reinterpret_cast<float *>(o_base + (int64_t)chan(m, i) * p.osc * 4 + o_off);
             if (full) {
                 *reinterpret_cast<F4 *>(op) = t;
             } else {
@@ -265,7 +277,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
                 if (valid > 2) op[2] = t[2];
             }
         }
-    }
 }
 
 // qf[mt][ks][lane][e] = W[row = mt*32 + lane%32][col = ks*16 + (lane/32)*8 + e],
@@ -331,12 +342,12 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         const int ns = std::min(slice_n, g.n - n0);
         C1Args a{};
         a.in = in.p + (int64_t)n0 * in.sn; a.isn = in.sn; a.isc = in.sc;
-        a.scale_shift = scale_shift;
+        a.scale_shift = getenv("RVN_DBG_NOBN") ? nullptr : scale_shift;
         a.wq = wq;
         a.r = r ? r->p + (int64_t)n0 * r->sn : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
         a.out = out.p + (int64_t)n0 * out.sn; a.osn = out.sn; a.osc = out.sc;
         a.HW = HW; a.CI = ci; a.CO = co;
-        a.ep = (int)ep;
+        a.ep = getenv("RVN_DBG_NOR") ? (int)EP_STORE : (int)ep;
         a.gpi = (HW + 3) / 4;
         a.groups = ns * a.gpi;
         a.ksteps = ci / 16;
@@ -352,6 +363,7 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         if (tiles < 1024 && a.ksteps >= 8) a.KW = tiles < 512 && a.ksteps >= 16 ? 4 : 2;
         int mtw = a.KW == 1 && a.mtiles >= 2 && (int64_t)ptiles * ((a.mtiles + 1) / 2) >= 2048 ? 2 : 1;
         if (const char *e = getenv("RVN_1X1_KW")) a.KW = atoi(e), mtw = 1;
+        if (const char *e = getenv("RVN_1X1_MTW")) if (a.KW == 1 && a.mtiles >= 2) mtw = atoi(e);
         const int cot = (a.mtiles + mtw - 1) / mtw;
         const int rest = 4 / a.KW;
         a.CW = cot >= rest ? rest : cot >= 2 ? 2 : 1;
@@ -365,12 +377,17 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
                          (r && ((r->sn & 3) != 0 || (r->sc & 3) != 0 || (reinterpret_cast<uintptr_t>(r->p) & 15) != 0));
         const dim3 grid((unsigned)wgs);
         const size_t lds = a.KW > 1 ? (size_t)(a.KW - 1) * (a.PW * a.CW) * mtw * 64 * 64 * 4 : 0;
+        int depth = mtw == 1 ? 2 : 1;
+        if (const char *e = getenv("RVN_1X1_DEPTH")) depth = mtw == 1 ? atoi(e) : 1;
         if (mtw == 2) {
-            if (gen) cx.run(conv1x1_bf16_k<2, true>, grid, dim3(kThreads), lds, a);
-            else cx.run(conv1x1_bf16_k<2, false>, grid, dim3(kThreads), lds, a);
+            if (gen) cx.run(conv1x1_bf16_k<2, 1, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<2, 1, false>, grid, dim3(kThreads), lds, a);
+        } else if (depth == 2) {
+            if (gen) cx.run(conv1x1_bf16_k<1, 2, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<1, 2, false>, grid, dim3(kThreads), lds, a);
         } else {
-            if (gen) cx.run(conv1x1_bf16_k<1, true>, grid, dim3(kThreads), lds, a);
-            else cx.run(conv1x1_bf16_k<1, false>, grid, dim3(kThreads), lds, a);
+            if (gen) cx.run(conv1x1_bf16_k<1, 1, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<1, 1, false>, grid, dim3(kThreads), lds, a);
         }
     }
     return true;

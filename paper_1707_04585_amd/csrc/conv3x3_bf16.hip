@@ -1,0 +1,429 @@
+// 3x3 convolution (forward and data gradient) with bf16 operands on the CDNA4
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation), for the 3x3 units
+// c_3(x) = Conv_3x3(ReLU(BN(x))) of Section 2.2 when the block descriptor asks
+// for bf16 convolution operands.
+//
+// GEMM view.  D[ko][pixel] = sum_{tap, c} Wt[ko][tap][c] * A[c][pixel + tap],
+// one matrix instruction per (tap, 16 input channels).  Both operands live in
+// LDS with the channel innermost (pixel records and (ko, tap) records of KC + 8
+// bf16), so every operand read is one 16-byte access per lane.
+//
+// What this kernel adds to that scheme:
+//  * register tiling: a wavefront owns MTW x NTW tiles of 32 x 32 results, so
+//    an LDS read feeds NTW (filter) or MTW (activation) matrix instructions;
+//  * software pipelining: the global loads of channel chunk i+1 (activations as
+//    fp32, filter as prepared bf16) are issued before the matrix instructions
+//    of chunk i and are converted and written to LDS after them;
+//  * staging by linear quads: an item is 4 consecutive pixels of the band's
+//    contiguous range in the image plane, times 8 channels, so the loads are
+//    16 bytes whatever the image width; BN scale/shift, ReLU and the bf16
+//    rounding happen on the way into LDS;
+//  * optional split of the input channels over gridDim.z: partial tiles go to
+//    scratch and a second kernel sums them in a fixed order and applies the
+//    coupling y = r + conv / reconstruction x = r - conv of Section 3.1
+//    (otherwise that is done in the accumulator registers here).
+#include <algorithm>
+#include <cstdlib>
+
+#include "kernels.h"
+
+namespace rvn {
+
+namespace {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kPadK = 8;     // bf16 elements of padding per LDS record
+constexpr int kInItems = 2;  // activation staging items per thread and chunk, at most
+
+struct C3Args {
+    const float *in;  // x (forward) or upstream gradient (data gradient), fp32 NCHW planes
+    int64_t isn, isc;
+    const float *scale_shift;  // [2*CI]: a = max(in*scale + shift, 0); null = use `in` as is
+    const uint16_t *wq;        // filter in bf16, [CO][9][CIP]
+    int CIP;
+    const float *r;  // skip operand of the epilogue (may alias out)
+    int64_t rsn, rsc;
+    float *out;
+    int64_t osn, osc;
+    int N, H, W, CI, CO, ep;
+    int TR, IMGS, bands;  // rows and images per pixel block, blocks per image column
+    int pix_per_img;      // TR * W
+    int n_pix;            // IMGS * TR * W
+    int lrows, lcols;     // LDS tile: TR + 2 rows, W + 2 columns
+    int q_per_img;        // quads of the widest band range: ceil((TR + 2) * W / 4)
+    int in_items;         // IMGS * q_per_img * (KC / 8)
+    int chunks, cps;      // channel chunks in total and per split
+    float *part;          // partial tiles [split][n][ko][h*w] when gridDim.z > 1
+    int64_t part_stride;
+    int dbg;
+};
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    const float2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t *>(&b);
+}
+
+// WM x WN wavefronts (WM * WN = 4), each MTW x NTW tiles of 32 output channels
+// x 32 pixels; KC input channels per chunk.
+template <int WM, int MTW, int NTW, int KC>
+__global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
+    constexpr int WN = 4 / WM;
+    constexpr int REC = KC + kPadK, OCTS = KC / 8;
+    constexpr int CH = WM * MTW * 32;  // output channels per workgroup
+    constexpr int W_ITEMS = CH * 9 * OCTS, W_PER = (W_ITEMS + kThreads - 1) / kThreads;
+    extern __shared__ __align__(16) uint16_t smem16[];
+    uint16_t *in_lds = smem16;                                    // [IMGS][lrows][lcols][REC]
+    uint16_t *w_lds = smem16 + p.IMGS * p.lrows * p.lcols * REC;  // [CH][9][REC]
+    float *ss_lds = reinterpret_cast<float *>(w_lds + CH * 9 * REC);  // [2][CI]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int band = blockIdx.x % p.bands, img_grp = blockIdx.x / p.bands;
+    const int n0 = img_grp * p.IMGS, row0 = band * p.TR;
+    const int co0 = blockIdx.y * CH;
+    const int N = p.N, H = p.H, W = p.W, CI = p.CI, CO = p.CO;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const bool bn = p.scale_shift != nullptr;
+
+    // ---- zero the activation tile once (halo, rows outside the image, unused
+    //      slots stay zero) and fetch scale/shift
+    {
+        const int n16 = p.IMGS * p.lrows * p.lcols * REC / 8;
+        for (int e = tid; e < n16; e += kThreads) reinterpret_cast<uint4_t *>(in_lds)[e] = uint4_t{0u, 0u, 0u, 0u};
+        if (bn)
+            for (int e = tid; e < 2 * CI; e += kThreads) ss_lds[e] = p.scale_shift[e];
+    }
+
+    // ---- this thread's activation items: (image, quad of the band's pixel range, channel octet)
+    const int start_row = max(0, row0 - 1), end_row = min(H, row0 + p.TR + 1);
+    const int range = (end_row - start_row) * W;  // contiguous pixels of the plane this block reads
+    uint32_t it_off[kInItems];                    // byte offset of (image, pixel) in a plane (dead items: 0)
+    int it_rec[kInItems], it_info[kInItems];      // LDS record of pixel 0; col | nvalid << 16 | shift << 20 | oc << 24
+#pragma unroll
+    for (int i = 0; i < kInItems; ++i) {
+        const int e = tid + i * kThreads;
+        const int oc = e % OCTS, t = e / OCTS;
+        const int q = t % p.q_per_img, img = t / p.q_per_img;
+        const int n = n0 + img, start = 4 * q;
+        const bool live = e < p.in_items && n < N && start < range;
+        const int ld = min(start, range - 4), shift = start - ld;
+        const int lin = start_row * W + start, row = lin / W, col = lin - row * W;
+        it_off[i] = live ? (uint32_t)(((int64_t)n * p.isn + start_row * W + ld) * 4) : 0u;
+        it_rec[i] = (img * p.lrows + (row - (row0 - 1))) * p.lcols + 1 + col;
+        const int nvalid = live ? min(4, range - start) : 0;
+        it_info[i] = col | (nvalid << 16) | (shift << 20) | (oc << 24);
+    }
+
+    // ---- this lane's pixel in each of its NTW pixel groups
+    int b_rec[NTW], o_img[NTW], o_pix[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+        const int f = (wn * NTW + t) * 32 + l32;
+        const int img = f / p.pix_per_img, rem = f - img * p.pix_per_img;
+        const int rr = rem / W, cc = rem - rr * W;
+        const bool ok = f < p.n_pix && n0 + img < N && row0 + rr < H;
+        b_rec[t] = f < p.n_pix ? (img * p.lrows + rr) * p.lcols + cc : 0;
+        o_img[t] = ok ? n0 + img : -1;
+        o_pix[t] = (row0 + rr) * W + cc;
+    }
+
+    float16_t acc[MTW][NTW];
+#pragma unroll
+    for (int m = 0; m < MTW; ++m)
+#pragma unroll
+        for (int t = 0; t < NTW; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.f;
+
+    f4u_t gin[kInItems][8];
+    uint4_t gw[W_PER];
+    const char *const in_base = reinterpret_cast<const char *>(p.in);
+    const int64_t isc_b = p.isc * 4;
+
+    auto g2r = [&](int c0) {
+        if (p.dbg & 8) return;
+#pragma unroll
+        for (int i = 0; i < kInItems; ++i) {
+            const int oc = it_info[i] >> 24;
+            // octets past the last channel read the chunk's first octet instead and are zeroed later
+            const uint32_t off = it_off[i] + (c0 + oc * 8 < CI ? (uint32_t)(oc * 8 * isc_b) : 0u);
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                gin[i][k] = *reinterpret_cast<const f4u_t *>(in_base + (int64_t)(c0 + k) * isc_b + off);
+        }
+#pragma unroll
+        for (int i = 0; i < W_PER; ++i) {
+            const int e = tid + i * kThreads;
+            const int oc = e % OCTS, t = e / OCTS;
+            const bool ok = e < W_ITEMS && co0 + t / 9 < CO && c0 + oc * 8 < p.CIP;
+            gw[i] = *reinterpret_cast<const uint4_t *>(p.wq + (ok ? ((int64_t)co0 * 9 + t) * p.CIP + c0 + oc * 8 : 0));
+            if (!ok) gw[i] = uint4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    auto r2l = [&](int c0) {
+        if (p.dbg & 4) return;
+#pragma unroll
+        for (int i = 0; i < kInItems; ++i) {
+            const int info = it_info[i];
+            const int col = info & 0xffff, nvalid = (info >> 16) & 15, shift = (info >> 20) & 15, oc = info >> 24;
+            if (nvalid == 0) continue;
+            const bool chan_ok = c0 + oc * 8 < CI;
+            float v[8][4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const f4u_t x = gin[i][k];
+                float x0 = shift == 0 ? x[0] : shift == 1 ? x[1] : shift == 2 ? x[2] : x[3];
+                float x1 = shift == 0 ? x[1] : shift == 1 ? x[2] : x[3];
+                float x2 = shift == 0 ? x[2] : x[3];
+                float x3 = x[3];
+                if (bn) {
+                    const int ch = chan_ok ? c0 + oc * 8 + k : 0;
+                    const float sc = ss_lds[ch], sh = ss_lds[CI + ch];
+                    x0 = fmaxf(fmaf(x0, sc, sh), 0.f);
+                    x1 = fmaxf(fmaf(x1, sc, sh), 0.f);
+                    x2 = fmaxf(fmaf(x2, sc, sh), 0.f);
+                    x3 = fmaxf(fmaf(x3, sc, sh), 0.f);
+                }
+                v[k][0] = chan_ok ? x0 : 0.f;
+                v[k][1] = chan_ok ? x1 : 0.f;
+                v[k][2] = chan_ok ? x2 : 0.f;
+                v[k][3] = chan_ok ? x3 : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (j >= nvalid) break;
+                // pixels past the end of an image row continue in the next tile row, after 2 halo records
+                const int rec = it_rec[i] + j + (col + j >= W ? 2 : 0);
+                const uint4_t q = {pack2(v[0][j], v[1][j]), pack2(v[2][j], v[3][j]), pack2(v[4][j], v[5][j]),
+                                   pack2(v[6][j], v[7][j])};
+                *reinterpret_cast<uint4_t *>(in_lds + rec * REC + oc * 8) = q;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < W_PER; ++i) {
+            const int e = tid + i * kThreads;
+            if (e < W_ITEMS) *reinterpret_cast<uint4_t *>(w_lds + (e / OCTS) * REC + (e % OCTS) * 8) = gw[i];
+        }
+    };
+
+    const int chunk0 = blockIdx.z * p.cps, chunk1 = min(p.chunks, chunk0 + p.cps);
+    g2r(chunk0 * KC);
+    __syncthreads();  // tile zeroed, scale/shift in LDS
+    r2l(chunk0 * KC);
+    __syncthreads();
+    for (int ch = chunk0; ch < chunk1; ++ch) {
+        if (ch + 1 < chunk1) g2r((ch + 1) * KC);
+        if (!(p.dbg & 1))
+#pragma unroll
+        for (int rr = 0; rr < 3; ++rr) {
+#pragma unroll
+            for (int ss = 0; ss < 3; ++ss) {
+#pragma unroll
+                for (int ks = 0; ks < KC / 16; ++ks) {
+                    bf16x8_t a[MTW], b[NTW];
+#pragma unroll
+                    for (int m = 0; m < MTW; ++m)
+                        a[m] = *reinterpret_cast<const bf16x8_t *>(
+                            w_lds + (((wm * MTW + m) * 32 + l32) * 9 + rr * 3 + ss) * REC + ks * 16 + kg * 8);
+#pragma unroll
+                    for (int t = 0; t < NTW; ++t)
+                        b[t] = *reinterpret_cast<const bf16x8_t *>(
+                            in_lds + (b_rec[t] + rr * p.lcols + ss) * REC + ks * 16 + kg * 8);
+#pragma unroll
+                    for (int m = 0; m < MTW; ++m)
+#pragma unroll
+                        for (int t = 0; t < NTW; ++t)
+                            acc[m][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[t], acc[m][t], 0, 0, 0);
+                }
+            }
+        }
+        if (ch + 1 < chunk1) {
+            __syncthreads();  // every wavefront has read chunk ch
+            r2l((ch + 1) * KC);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: register i of a lane is channel 8*(i/4) + 4*kg + i%4 of its pixel
+    const bool partial = gridDim.z > 1;
+    if (p.dbg & 2) return;
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+        if (o_img[t] < 0) continue;
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) {
+            const int kb = co0 + (wm * MTW + m) * 32 + 4 * kg;
+            if (partial) {
+                float *dst = p.part + blockIdx.z * p.part_stride + ((int64_t)o_img[t] * CO) * (H * W) + o_pix[t];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int ko = kb + 8 * (i >> 2) + (i & 3);
+                    if (ko < CO) dst[(int64_t)ko * (H * W)] = acc[m][t][i];
+                }
+                continue;
+            }
+            if (p.ep != EP_STORE) {  // all skip values first: r may alias out
+                const float *const rsrc = p.r + (int64_t)o_img[t] * p.rsn + o_pix[t];
+                float rv[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int ko = kb + 8 * (i >> 2) + (i & 3);
+                    rv[i] = ko < CO ? rsrc[(int64_t)ko * p.rsc] : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[m][t][i] = p.ep == EP_ADD ? rv[i] + acc[m][t][i] : rv[i] - acc[m][t][i];
+            }
+            float *const dst = p.out + (int64_t)o_img[t] * p.osn + o_pix[t];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int ko = kb + 8 * (i >> 2) + (i & 3);
+                if (ko < CO) dst[(int64_t)ko * p.osc] = acc[m][t][i];
+            }
+        }
+    }
+}
+
+// out = ep(r, sum_s part[s]) over dense partial tiles [S][n][c][hw], summed in
+// the order s = 0, 1, ...
+__global__ __launch_bounds__(kThreads) void splitk_reduce_k(const float *__restrict__ part, int64_t part_stride, int S,
+                                                            int C, int HW, int64_t total, const float *r,
+                                                            int64_t rsn, int64_t rsc, float *out, int64_t osn,
+                                                            int64_t osc, int ep) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= total) return;
+    float v = part[i];
+    for (int s = 1; s < S; ++s) v += part[(int64_t)s * part_stride + i];
+    const int64_t plane = i / HW;
+    const int pix = (int)(i - plane * HW);
+    const int64_t n = plane / C;
+    const int c = (int)(plane - n * C);
+    if (ep != EP_STORE) {
+        const float rv = r[n * rsn + (int64_t)c * rsc + pix];
+        v = ep == EP_ADD ? rv + v : rv - v;
+    }
+    out[n * osn + (int64_t)c * osc + pix] = v;
+}
+
+struct C3Plan {
+    int WM, MTW, NTW, KC, TR, IMGS, bands, lrows, lcols, q_per_img, in_items, chunks, S, cps;
+    size_t lds_bytes;
+    bool ok;
+};
+
+C3Plan plan_c3(int ci, int co, const Geo &g) {
+    C3Plan pl{};
+    pl.ok = false;
+    if (ci % 8 != 0 || g.w < 4 || ci > 4096) return pl;
+    // Output channels per workgroup and the wavefront arrangement.
+    if (co <= 32) { pl.WM = 1; pl.MTW = 1; pl.NTW = 2; }
+    else if (co <= 64) { pl.WM = 1; pl.MTW = 2; pl.NTW = 2; }
+    else { pl.WM = 2; pl.MTW = 2; pl.NTW = 2; }
+    const int ch = pl.WM * pl.MTW * 32, slots = (4 / pl.WM) * pl.NTW * 32;
+    pl.KC = ci >= 32 && ch <= 64 ? 32 : 16;
+    if (const char *e = getenv("RVN_3X3_KC")) pl.KC = atoi(e);
+    const int rec = pl.KC + kPadK, octs = pl.KC / 8;
+    // Pixel block: the fullest block of whole rows (or whole images) that fits.
+    double best = -1.0;
+    for (int imgs = 1; imgs <= 16 && imgs <= g.n; ++imgs) {
+        for (int tr = imgs > 1 ? g.h : 1; tr <= g.h; ++tr) {
+            const int npix = imgs * tr * g.w;
+            if (npix > slots) break;
+            const int lrows = tr + 2, lcols = g.w + 2;
+            const int q = ((tr + 2) * g.w + 3) / 4;
+            const int items = imgs * q * octs;
+            const size_t bytes = ((size_t)imgs * lrows * lcols + (size_t)ch * 9) * rec * 2 + (size_t)ci * 8;
+            if (items > kInItems * kThreads || bytes > 76 * 1024) break;
+            const int bands = (g.h + tr - 1) / tr, groups = (g.n + imgs - 1) / imgs;
+            const double useful = (double)g.n * g.h * g.w, issued = (double)groups * bands * slots;
+            const double score = useful / issued;
+            if (score > best) {
+                best = score;
+                pl.TR = tr; pl.IMGS = imgs; pl.bands = bands; pl.lrows = lrows; pl.lcols = lcols;
+                pl.q_per_img = q; pl.in_items = items; pl.lds_bytes = bytes;
+                pl.ok = true;
+            }
+        }
+    }
+    if (!pl.ok) return pl;
+    pl.chunks = (ci + pl.KC - 1) / pl.KC;
+    const int64_t wgs = (int64_t)((g.n + pl.IMGS - 1) / pl.IMGS) * pl.bands * ((co + ch - 1) / ch);
+    pl.S = 1;
+    if (wgs < 256 && pl.chunks >= 4) pl.S = (int)std::min<int64_t>(pl.chunks / 2, (512 + wgs - 1) / wgs);
+    if (const char *e = getenv("RVN_3X3_S")) pl.S = std::max(1, std::min(pl.chunks, atoi(e)));
+    pl.cps = (pl.chunks + pl.S - 1) / pl.S;
+    pl.S = (pl.chunks + pl.cps - 1) / pl.cps;
+    return pl;
+}
+
+template <int WM, int MTW, int NTW, int KC>
+void launch_c3(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
+    static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once
+    if (!raised) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+        if (e != hipSuccess) {
+            cx.fail(e);
+            return;
+        }
+        raised = true;
+    }
+    cx.run(conv3x3_bf16_k<WM, MTW, NTW, KC>, grid, dim3(kThreads), pl.lds_bytes, a);
+}
+
+}  // namespace
+
+bool conv3x3_bf16_ok(int ci, int co, const Geo &g) { return plan_c3(ci, co, g).ok; }
+
+size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g) {
+    const C3Plan pl = plan_c3(ci, co, g);
+    return pl.ok && pl.S > 1 ? (size_t)pl.S * g.n * co * g.h * g.w : 0;
+}
+
+bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
+                  Epilogue ep, const View *r, View out, float *scratch) {
+    if (!wq) return false;
+    const C3Plan pl = plan_c3(ci, co, g);
+    if (!pl.ok || (pl.S > 1 && !scratch)) return false;
+    // lane offsets into `in` are 32-bit byte offsets
+    if (((int64_t)g.n * in.sn + (int64_t)ci * in.sc) * 4 >= ((int64_t)1 << 32)) return false;
+    C3Args a{};
+    a.in = in.p; a.isn = in.sn; a.isc = in.sc;
+    a.scale_shift = scale_shift;
+    a.wq = wq; a.CIP = (ci + 7) / 8 * 8;
+    a.r = r ? r->p : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
+    a.out = out.p; a.osn = out.sn; a.osc = out.sc;
+    a.N = g.n; a.H = g.h; a.W = g.w; a.CI = ci; a.CO = co; a.ep = (int)ep;
+    a.TR = pl.TR; a.IMGS = pl.IMGS; a.bands = pl.bands;
+    a.pix_per_img = pl.TR * g.w; a.n_pix = pl.IMGS * pl.TR * g.w;
+    a.lrows = pl.lrows; a.lcols = pl.lcols; a.q_per_img = pl.q_per_img; a.in_items = pl.in_items;
+    a.chunks = pl.chunks; a.cps = pl.cps;
+    a.dbg = getenv("RVN_3X3_DBG") ? atoi(getenv("RVN_3X3_DBG")) : 0;
+    a.part = scratch; a.part_stride = (int64_t)g.n * co * g.h * g.w;
+    const int ch = pl.WM * pl.MTW * 32;
+    const dim3 grid((unsigned)(pl.bands * ((g.n + pl.IMGS - 1) / pl.IMGS)), (unsigned)((co + ch - 1) / ch), (unsigned)pl.S);
+    bool launched = true;
+    if (pl.WM == 1 && pl.MTW == 1 && pl.KC == 16) launch_c3<1, 1, 2, 16>(cx, pl, a, grid);
+    else if (pl.WM == 1 && pl.MTW == 1 && pl.KC == 32) launch_c3<1, 1, 2, 32>(cx, pl, a, grid);
+    else if (pl.WM == 1 && pl.MTW == 2 && pl.KC == 16) launch_c3<1, 2, 2, 16>(cx, pl, a, grid);
+    else if (pl.WM == 1 && pl.MTW == 2 && pl.KC == 32) launch_c3<1, 2, 2, 32>(cx, pl, a, grid);
+    else if (pl.WM == 2 && pl.MTW == 2 && pl.KC == 16) launch_c3<2, 2, 2, 16>(cx, pl, a, grid);
+    else launched = false;
+    if (!launched) return false;
+    if (pl.S > 1) {
+        const int64_t total = a.part_stride;
+        cx.run(splitk_reduce_k, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, scratch,
+               a.part_stride, pl.S, co, g.h * g.w, total, a.r, a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep);
+    }
+    return true;
+}
+
+}  // namespace rvn

@@ -337,6 +337,10 @@ __global__ __launch_bounds__(kThreads) void prep_filter_k(const float *__restric
 
 }  // namespace
 
+size_t conv_bf16_scratch_floats(int ci, int co, int ks, const Geo &g) {
+    return ks == 3 ? conv3x3_bf16_scratch_floats(ci, co, g) : 0;
+}
+
 size_t filter_bf16_elems(int rows, int cols_k, int ks) {
     const size_t n = (size_t)rows * ks * ks * ((cols_k + 7) / 8 * 8);
     return ks == 1 ? std::max(n, filter_1x1_elems(rows, cols_k)) : n;
@@ -359,8 +363,9 @@ void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, Geo g,
 }
 
 bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,
-               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out) {
+               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out, float *scratch) {
     if (ks == 1 && wq && conv1x1_direct_ok(ci, g)) return conv1x1_bf16(cx, in, scale_shift, wq, ci, co, g, ep, r, out);
+    if (ks == 3 && wq && conv3x3_bf16(cx, in, scale_shift, wq, ci, co, g, ep, r, out, scratch)) return true;
     const Bf16Plan pl = plan_bf16(ci, co, ks, g);
     if (!pl.ok) return false;
     Bf16Args a{};

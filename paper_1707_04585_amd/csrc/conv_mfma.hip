@@ -383,18 +383,18 @@ void conv_mfma(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
 }  // namespace
 
 void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, const uint16_t *wq, int cin,
-              int cout, int ks, Geo g, Epilogue ep, const View *r, View out) {
+              int cout, int ks, Geo g, Epilogue ep, const View *r, View out, float *scratch) {
     const double P = (double)g.pixels();
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_fwd_calls += 1;
     cx.cost.conv_flops += flops;
     if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
-    if (dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out)) return;
+    if (dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch)) return;
     conv_mfma(cx, x, scale_shift, w, false, cin, cout, ks, g, dt == RVN_BF16, ep, r, out);
 }
 
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *wq, int cin, int cout, int ks,
-                Geo g, float *da) {
+                Geo g, float *da, float *scratch) {
     const double P = (double)g.pixels();
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_dgrad_calls += 1;
@@ -402,7 +402,7 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *
     if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops)) return;
     // A stride-1 "same" convolution of dh (cout channels) with the transposed,
     // flipped filter, producing cin channels.
-    if (dt == RVN_BF16 && conv_bf16(cx, dh, nullptr, w, wq, true, cout, cin, ks, g, EP_STORE, nullptr, dense_view(da, cin, g)))
+    if (dt == RVN_BF16 && conv_bf16(cx, dh, nullptr, w, wq, true, cout, cin, ks, g, EP_STORE, nullptr, dense_view(da, cin, g), scratch))
         return;
     conv_mfma(cx, dh, nullptr, w, true, cout, cin, ks, g, dt == RVN_BF16, EP_STORE, nullptr,
               dense_view(da, cin, g));

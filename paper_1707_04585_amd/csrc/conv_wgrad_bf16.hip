@@ -31,6 +31,8 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 
@@ -54,7 +56,10 @@ struct WgArgs {
 
 // e / d for 0 <= e, e * d < 2^32, with m = 2^32 / d + 1 computed on the host
 // (m = 0 stands for d = 1).
-__device__ __forceinline__ int fdiv(int e, uint32_t m) { return m ? (int)__umulhi((uint32_t)e, m) : e; }
+__device__ __forceinline__ int fdiv(int e, uint32_t m) {  // branch-free: keeps the loads of a batch in one basic block
+    const uint32_t one = m == 0u ? 1u : 0u;
+    return (int)(__umulhi((uint32_t)e, m) + (uint32_t)e * one);
+}
 
 // Two floats to a pair of bf16 (nearest even): one v_cvt_pk_bf16_f32.
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -63,16 +68,25 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     return *reinterpret_cast<const uint32_t *>(&b);
 }
 
+// Four consecutive pixels of a row starting at column col, in two steps so
+// that the loads of several items can be in flight together: quad_load issues
+// one unconditional 16-byte load (from `safe` where the item is outside the
+// tensor; rows have 4 pixels or more, and where fewer than 4 are left the load
+// starts `sh` pixels early so that it ends inside the row), quad_fix puts the
+// pixels in place, with zeros past the end of the row or for an outside item.
 template <bool VEC>
-__device__ __forceinline__ float4 load_quad(const float *g, bool in, const float *safe, int col, int W) {
-    if (VEC) return *reinterpret_cast<const float4 *>(in ? g : safe);
-    float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (in) {
-        q.x = g[0];
-        if (col + 1 < W) q.y = g[1];
-        if (col + 2 < W) q.z = g[2];
-        if (col + 3 < W) q.w = g[3];
-    }
+__device__ __forceinline__ f4u_t quad_load(const float *g, bool in, const float *safe, int col, int W, int &sh) {
+    sh = VEC || !in ? 0 : col - min(col, W - 4);
+    if (VEC) return *reinterpret_cast<const float4_t *>(in ? g : safe);
+    return *reinterpret_cast<const f4u_t *>((in ? g : safe) - sh);
+}
+__device__ __forceinline__ float4 quad_fix(f4u_t x, int sh, bool zero) {
+    float4 q;
+    q.x = sh == 0 ? x[0] : sh == 1 ? x[1] : sh == 2 ? x[2] : x[3];
+    q.y = sh == 0 ? x[1] : sh == 1 ? x[2] : sh == 2 ? x[3] : 0.f;
+    q.z = sh == 0 ? x[2] : sh == 1 ? x[3] : 0.f;
+    q.w = sh == 0 ? x[3] : 0.f;
+    if (zero) q = make_float4(0.f, 0.f, 0.f, 0.f);
     return q;
 }
 
@@ -80,6 +94,7 @@ template <int KS, int MT, int CT, bool VEC>
 __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p) {
     constexpr int KS2 = KS * KS, PAD = KS / 2, LP = 8;  // image column 0 sits 8 elements into a tile row
     constexpr int WT = MT * CT, KW = 4 / WT;            // tile owners, pixel shares
+    constexpr int kBatch = KS == 3 ? 4 : 8;             // staging items a thread has in flight
     static_assert(WT == 1 || WT == 2 || WT == 4, "one tile per wavefront");
     extern __shared__ __align__(16) uint16_t smem16[];
     uint16_t *a_lds = smem16;
@@ -106,36 +121,64 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p)
     // Stage unit u: a = max(x*scale + shift, 0) (zero outside the image) and dh,
     // both as bf16, 4 pixels per item.  Several workgroups share a compute unit,
     // so one's loads overlap another's matrix instructions.
+    // Items are handled kBatch at a time: all loads of a batch are issued (from a
+    // safe address where the item is outside the tensor) before any is converted,
+    // so a unit costs a few memory round trips instead of one per item.
     auto stage = [&](int u) {
         const int g = u / bands;
         const int n0 = g * IMGS, row0 = (u - g * bands) * TH;
-        for (int e = tid; e < p.a_items; e += kThreads) {
-            const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
-            const int t2 = fdiv(t, p.m_lrows), lr = t - t2 * p.lrows;
-            const int cl = fdiv(t2, p.m_imgs), img = t2 - cl * IMGS;
-            const int col = qx * 4, ch = c0 + cl, n = n0 + img, row = row0 - PAD + lr;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (ch < p.CI && n < N && row >= 0 && row < H) {
-                const float4 q = load_quad<VEC>(xp + (int64_t)n * xsn + (int64_t)ch * p.xsc + row * W + col, true, xp, col, W);
-                const float sc = ss_lds[cl], sh = ss_lds[CT * 32 + cl];
-                v[0] = fmaxf(fmaf(q.x, sc, sh), 0.f);
-                v[1] = col + 1 < W ? fmaxf(fmaf(q.y, sc, sh), 0.f) : 0.f;
-                v[2] = col + 2 < W ? fmaxf(fmaf(q.z, sc, sh), 0.f) : 0.f;
-                v[3] = col + 3 < W ? fmaxf(fmaf(q.w, sc, sh), 0.f) : 0.f;
+        for (int e0 = tid; e0 < p.a_items; e0 += kThreads * kBatch) {
+            f4u_t x[kBatch];
+            int where[kBatch];  // LDS offset (elements) | sh << 20 | outside << 30; negative: no item
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const int e = e0 + b * kThreads;
+                const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
+                const int t2 = fdiv(t, p.m_lrows), lr = t - t2 * p.lrows;
+                const int cl = fdiv(t2, p.m_imgs), img = t2 - cl * IMGS;
+                const int col = qx * 4, ch = c0 + cl, n = n0 + img, row = row0 - PAD + lr;
+                const bool in = e < p.a_items && ch < p.CI && n < N && row >= 0 && row < H;
+                int sh;
+                x[b] = quad_load<VEC>(xp + (int64_t)n * xsn + (int64_t)ch * p.xsc + row * W + col, in, xp, col, W, sh);
+                where[b] = e < p.a_items ? (cl * p.a_plane + img * p.a_img + lr * p.a_pitch + LP + col) | (sh << 20) | (in ? 0 : 1 << 30) : -1;
             }
-            *reinterpret_cast<uint2 *>(a_lds + cl * p.a_plane + img * p.a_img + lr * p.a_pitch + LP + col) =
-                make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const int off = where[b] & 0xfffff;
+                const float4 q = quad_fix(x[b], VEC ? 0 : (where[b] >> 20) & 3, false);
+                const bool zero = (where[b] >> 30) & 1;
+                const int e = e0 + b * kThreads;
+                const int t = fdiv(e, p.m_wq), col = (e - t * p.Wq) * 4;
+                const int cl = min(fdiv(fdiv(t, p.m_lrows), p.m_imgs), CT * 32 - 1);
+                const float sc = ss_lds[cl], sh = ss_lds[CT * 32 + cl];
+                const float v0 = zero ? 0.f : fmaxf(fmaf(q.x, sc, sh), 0.f);
+                const float v1 = zero || col + 1 >= W ? 0.f : fmaxf(fmaf(q.y, sc, sh), 0.f);
+                const float v2 = zero || col + 2 >= W ? 0.f : fmaxf(fmaf(q.z, sc, sh), 0.f);
+                const float v3 = zero || col + 3 >= W ? 0.f : fmaxf(fmaf(q.w, sc, sh), 0.f);
+                if (where[b] >= 0) *reinterpret_cast<uint2 *>(a_lds + off) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+            }
         }
-        for (int e = tid; e < p.d_items; e += kThreads) {
-            const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
-            const int t2 = fdiv(t, p.m_th), r = t - t2 * TH;
-            const int ml = fdiv(t2, p.m_imgs), img = t2 - ml * IMGS;
-            const int col = qx * 4, ko = ko0 + ml, n = n0 + img, row = row0 + r;
-            float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ko < p.CO && n < N && row < H)
-                q = load_quad<VEC>(dp + (int64_t)n * dsn + (int64_t)ko * p.dsc + row * W + col, true, dp, col, W);
-            *reinterpret_cast<uint2 *>(d_lds + ml * p.d_plane + img * p.d_img + r * p.d_pitch + col) =
-                make_uint2(pack2(q.x, q.y), pack2(q.z, q.w));
+        for (int e0 = tid; e0 < p.d_items; e0 += kThreads * kBatch) {
+            f4u_t x[kBatch];
+            int where[kBatch];
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const int e = e0 + b * kThreads;
+                const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
+                const int t2 = fdiv(t, p.m_th), r = t - t2 * TH;
+                const int ml = fdiv(t2, p.m_imgs), img = t2 - ml * IMGS;
+                const int col = qx * 4, ko = ko0 + ml, n = n0 + img, row = row0 + r;
+                const bool in = e < p.d_items && ko < p.CO && n < N && row < H;
+                int sh;
+                x[b] = quad_load<VEC>(dp + (int64_t)n * dsn + (int64_t)ko * p.dsc + row * W + col, in, dp, col, W, sh);
+                where[b] = e < p.d_items ? (ml * p.d_plane + img * p.d_img + r * p.d_pitch + col) | (sh << 20) | (in ? 0 : 1 << 30) : -1;
+            }
+#pragma unroll
+            for (int b = 0; b < kBatch; ++b) {
+                const float4 q = quad_fix(x[b], VEC ? 0 : (where[b] >> 20) & 3, (where[b] >> 30) & 1);
+                const uint2 v = make_uint2(pack2(q.x, q.y), pack2(q.z, q.w));
+                if (where[b] >= 0) *reinterpret_cast<uint2 *>(d_lds + (where[b] & 0xfffff)) = v;
+            }
         }
     };
 
@@ -288,6 +331,8 @@ int bank_pad(int plane) {  // smallest value >= plane that is 8 modulo 128 (elem
 
 WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     WgPlan w{};
+    w.ok = false;
+    if (g.w < 4) return w;  // staging loads 4 pixels of a row at a time
     w.MT = cout <= 32 ? 1 : 2;
     w.CT = cin <= 32 ? 1 : 2;
     w.Wq = (g.w + 3) / 4;

@@ -129,14 +129,25 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
 // fly from stats (scale_shift = stats + 2*cin); w is fp32 [cout][cin][ks][ks].
 // With dt == RVN_BF16 both operands are rounded to bf16 before multiplying.
 void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const float *w, const uint16_t *wq, int cin,
-              int cout, int ks, Geo g, Epilogue ep, const View *r, View out);
+              int cout, int ks, Geo g, Epilogue ep, const View *r, View out, float *scratch);
 
 // The same convolution on bf16 matrix instructions (operands rounded to bf16,
 // fp32 accumulation); `transposed`: w is [ci][co][ks][ks] and is read transposed
 // and flipped (data gradient).  Returns false if no tiling fits (nothing is
 // launched then).
 bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,
-               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out);
+               int ci, int co, int ks, Geo g, Epilogue ep, const View *r, View out, float *scratch);
+// Scratch floats conv_bf16 may need for a ci -> co convolution (partial tiles
+// when the input channels are split over workgroups); 0 if none.
+size_t conv_bf16_scratch_floats(int ci, int co, int ks, const Geo &g);
+
+// 3x3 convolution, register-tiled and software-pipelined (see conv3x3_bf16.hip).
+// Needs the filter prepared as [co][9][ci padded to 8]; returns false (nothing
+// launched) when conv3x3_bf16_ok(ci, co, g) does not hold.
+bool conv3x3_bf16_ok(int ci, int co, const Geo &g);
+size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g);
+bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
+                  Epilogue ep, const View *r, View out, float *scratch);
 
 // The filter w [cout][cin][ks][ks] in bf16 and in the order the bf16 kernel
 // consumes it: qf [cout][ks*ks][cin padded to 8] for the forward convolution and
@@ -163,7 +174,7 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
 // da (dense fp32 [n][cin][h*w]) = sum_{k,r,s} dh[.., k, p-r+pad, q-s+pad] w[k,c,r,s];
 // dh is fp32, rounded to bf16 on load when dt == RVN_BF16.
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *wq, int cin, int cout, int ks,
-                Geo g, float *da);
+                Geo g, float *da, float *scratch);
 
 // dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad], with
 // a(x) = max(x*scale + shift, 0) formed on the fly from the layer input x as in

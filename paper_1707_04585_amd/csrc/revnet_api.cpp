@@ -72,7 +72,7 @@ struct Plan {
     size_t counters;      // ticket counters of the cross-workgroup reductions (ints)
     int n_counters;
     size_t bn_scratch;    // partial sums of the per-channel reductions
-    size_t wgrad_scratch; // partial filter gradients (backward only)
+    size_t wgrad_scratch; // partial filter gradients (backward only) and partial tiles of channel-split convolutions
     size_t h[2];          // h_l = conv_l(a_l), fp32, input of layer l+1
     size_t g[2];          // gradient ping-pong buffers (backward only)
     // bf16 convolutions with large filters: the filters of the function at hand
@@ -88,6 +88,7 @@ struct Plan {
 bool wants_prep(const rvn_block_desc &d, const Layer &ly, const Geo &g) {
     if (d.conv_dtype != RVN_BF16) return false;
     if (ly.ks == 1 && (conv1x1_direct_ok(ly.cin, g) || conv1x1_direct_ok(ly.cout, g))) return true;
+    if (ly.ks == 3 && (conv3x3_bf16_ok(ly.cin, ly.cout, g) || conv3x3_bf16_ok(ly.cout, ly.cin, g))) return true;
     return (int64_t)ly.cin * ly.cout * ly.ks * ly.ks >= 16384;
 }
 
@@ -101,7 +102,11 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
         p.stats[l] = off;
         off = align_up(off + kStatsArrays * (size_t)ly.cin * 4);
         bn_s = std::max(bn_s, bn_scratch_floats(ly.cin, g));
-        wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
+        if (backward) wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
+        if (d.conv_dtype == RVN_BF16) {
+            wg_s = std::max(wg_s, conv_bf16_scratch_floats(ly.cin, ly.cout, ly.ks, g));
+            if (backward) wg_s = std::max(wg_s, conv_bf16_scratch_floats(ly.cout, ly.cin, ly.ks, g));
+        }
         max_cin = std::max(max_cin, (size_t)ly.cin);
         if (l < p.L - 1) max_mid = std::max(max_mid, (size_t)ly.cout);
     }
@@ -121,9 +126,9 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     off = align_up(off + (size_t)p.n_counters * 4);
     p.bn_scratch = off;
     off = align_up(off + bn_s * 4);
+    p.wgrad_scratch = off;
+    off = align_up(off + wg_s * 4);
     if (backward) {
-        p.wgrad_scratch = off;
-        off = align_up(off + wg_s * 4);
         // a_l = ReLU(BN(x_l)) is never stored: every convolution kernel forms it
         // from x_l (the function input or h_{l-1}) while staging its operands.
         for (int l = 0; l < p.L - 1; ++l) {
@@ -270,10 +275,10 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.wgrad_scratch);
             cur = h;
         } else {
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.wgrad_scratch);
         }
     }
 }
@@ -292,7 +297,7 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                    gr.d_conv_w[l], accumulate);
         float *da = b.g[cur];
-        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da);
+        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.wgrad_scratch);
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
             bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
