@@ -92,7 +92,7 @@ __device__ __forceinline__ float4 quad_fix(f4u_t x, int sh, bool zero) {
 
 template <int KS, int MT, int CT, bool VEC>
 __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p) {
-    constexpr int KS2 = KS * KS, PAD = KS / 2, LP = 8;  // image column 0 sits 8 elements into a tile row
+    constexpr int KS2 = KS * KS, PAD = KS / 2, LP = KS == 3 ? 8 : 0;  // 3x3: image column 0 sits 8 elements into a tile row
     constexpr int WT = MT * CT, KW = 4 / WT;            // tile owners, pixel shares
     constexpr int kBatch = KS == 3 ? 4 : 8;             // staging items a thread has in flight
     static_assert(WT == 1 || WT == 2 || WT == 4, "one tile per wavefront");
@@ -325,9 +325,9 @@ struct WgPlan {
 
 uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
 
-int bank_pad(int plane) {  // smallest value >= plane that is 8 modulo 128 (elements)
-    return plane + ((8 - plane % 128) + 128) % 128;
-}
+// Smallest value >= plane that is 8 modulo 16 (elements): planes an odd multiple
+// of 16 bytes apart put the 16-byte reads of 8 neighbouring lanes on distinct banks.
+int bank_pad(int plane) { return plane + ((8 - plane % 16) + 16) % 16; }
 
 WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     WgPlan w{};
@@ -337,7 +337,7 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     w.CT = cin <= 32 ? 1 : 2;
     w.Wq = (g.w + 3) / 4;
     w.cpr = (g.w + 7) / 8;
-    w.a_pitch = 8 + w.cpr * 8 + 8;
+    w.a_pitch = ks == 3 ? 8 + w.cpr * 8 + 8 : w.cpr * 8;  // 3x3: 8 zero elements before and after every row
     w.d_pitch = w.cpr * 8;
     w.tiles_ko = (cout + w.MT * 32 - 1) / (w.MT * 32);
     w.tiles_c = (cin + w.CT * 32 - 1) / (w.CT * 32);
@@ -350,7 +350,7 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
         const int a_items = w.CT * 32 * imgs * lrows * w.Wq;
         const int d_items = w.MT * 32 * imgs * th * w.Wq;
         const size_t bytes = ((size_t)w.CT * 32 * a_plane + (size_t)w.MT * 32 * d_plane) * 2;
-        if (bytes > 60 * 1024 || imgs > 255 || lrows > 4000) return false;
+        if (bytes > 64 * 1024 || imgs > 255 || lrows > 4000) return false;
         w.TH = th; w.IMGS = imgs; w.lrows = lrows;
         w.a_img = a_img; w.d_img = d_img; w.a_plane = a_plane; w.d_plane = d_plane;
         w.a_items = a_items; w.d_items = d_items;
@@ -358,7 +358,7 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
         return true;
     };
     w.ok = false;
-    for (int imgs = g.n < 8 ? g.n : 8; imgs >= 1 && !w.ok; --imgs) w.ok = fits(g.h, imgs);
+    for (int imgs = g.n < 16 ? g.n : 16; imgs >= 1 && !w.ok; --imgs) w.ok = fits(g.h, imgs);
     for (int th = g.h - 1; th >= 1 && !w.ok; --th) w.ok = fits(th, 1);
     if (!w.ok) return w;
     if (w.IMGS == 1) {  // equal bands: no taller than what fits, as few as that allows
