@@ -23,7 +23,6 @@
 // and are arranged as PW pixel tiles x CW output-channel tiles so that those
 // which share input data run on the same compute unit.
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "kernels.h"
@@ -279,31 +278,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
 }
 
-// qf[mt][ks][lane][e] = W[row = mt*32 + lane%32][col = ks*16 + (lane/32)*8 + e],
-// W[row][col] = w[row][col] (forward: rows = cout, cols = cin) or w[col][row]
-// (data gradient: rows = cin, cols = cout); zero outside the filter.
-__global__ __launch_bounds__(kThreads) void prep_filter_1x1_k(const float *__restrict__ w, int CO, int CI,
-                                                              uint16_t *__restrict__ qf, int ks_f, int64_t n_f,
-                                                              uint16_t *__restrict__ qb, int ks_b, int64_t n_b) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const bool fwd = i < n_f;
-    const int64_t j = fwd ? i : i - n_f;
-    if (!fwd && j >= n_b) return;
-    const int ksteps = fwd ? ks_f : ks_b;
-    const int e = (int)(j & 7), ln = (int)((j >> 3) & 63);
-    const int64_t blk = j >> 9;
-    const int ks = (int)(blk % ksteps), mt = (int)(blk / ksteps);
-    const int row = mt * 32 + (ln & 31), col = ks * 16 + (ln >> 5) * 8 + e;
-    float v = 0.f;
-    if (fwd) {
-        if (row < CO && col < CI) v = w[(int64_t)row * CI + col];
-    } else {
-        if (row < CI && col < CO) v = w[(int64_t)col * CI + row];
-    }
-    const uint32_t q = pack2(v, 0.f);
-    (fwd ? qf : qb)[j] = (uint16_t)(q & 0xffffu);
-}
-
 uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
 
 size_t operand_elems(int rows, int cols) { return (size_t)((rows + 31) / 32) * 32 * ((cols + 15) / 16) * 16; }
@@ -315,13 +289,6 @@ bool conv1x1_direct_ok(int k_channels, const Geo &g) {
 }
 
 size_t filter_1x1_elems(int rows, int k_channels) { return operand_elems(rows, k_channels); }
-
-void prep_filter_1x1(Ctx &cx, const float *w, int cin, int cout, uint16_t *qf, uint16_t *qb) {
-    const int64_t n_f = qf ? (int64_t)operand_elems(cout, cin) : 0, n_b = qb ? (int64_t)operand_elems(cin, cout) : 0;
-    if (!cx.launch(K_PREP_FILTER, 4.0 * cin * cout + 2.0 * (n_f + n_b))) return;
-    cx.run(prep_filter_1x1_k, dim3((unsigned)((n_f + n_b + kThreads - 1) / kThreads)), dim3(kThreads), 0, w, cout, cin,
-           qf, (cin + 15) / 16, n_f, qb, (cout + 15) / 16, n_b);
-}
 
 bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
                   Epilogue ep, const View *r, View out) {
@@ -342,12 +309,12 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         const int ns = std::min(slice_n, g.n - n0);
         C1Args a{};
         a.in = in.p + (int64_t)n0 * in.sn; a.isn = in.sn; a.isc = in.sc;
-        a.scale_shift = getenv("RVN_DBG_NOBN") ? nullptr : scale_shift;
+        a.scale_shift = scale_shift;
         a.wq = wq;
         a.r = r ? r->p + (int64_t)n0 * r->sn : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
         a.out = out.p + (int64_t)n0 * out.sn; a.osn = out.sn; a.osc = out.sc;
         a.HW = HW; a.CI = ci; a.CO = co;
-        a.ep = getenv("RVN_DBG_NOR") ? (int)EP_STORE : (int)ep;
+        a.ep = (int)ep;
         a.gpi = (HW + 3) / 4;
         a.groups = ns * a.gpi;
         a.ksteps = ci / 16;
@@ -362,8 +329,6 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         a.KW = 1;
         if (tiles < 1024 && a.ksteps >= 8) a.KW = tiles < 512 && a.ksteps >= 16 ? 4 : 2;
         int mtw = a.KW == 1 && a.mtiles >= 2 && (int64_t)ptiles * ((a.mtiles + 1) / 2) >= 2048 ? 2 : 1;
-        if (const char *e = getenv("RVN_1X1_KW")) a.KW = atoi(e), mtw = 1;
-        if (const char *e = getenv("RVN_1X1_MTW")) if (a.KW == 1 && a.mtiles >= 2) mtw = atoi(e);
         const int cot = (a.mtiles + mtw - 1) / mtw;
         const int rest = 4 / a.KW;
         a.CW = cot >= rest ? rest : cot >= 2 ? 2 : 1;
@@ -377,8 +342,7 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
                          (r && ((r->sn & 3) != 0 || (r->sc & 3) != 0 || (reinterpret_cast<uintptr_t>(r->p) & 15) != 0));
         const dim3 grid((unsigned)wgs);
         const size_t lds = a.KW > 1 ? (size_t)(a.KW - 1) * (a.PW * a.CW) * mtw * 64 * 64 * 4 : 0;
-        int depth = mtw == 1 ? 2 : 1;
-        if (const char *e = getenv("RVN_1X1_DEPTH")) depth = mtw == 1 ? atoi(e) : 1;
+        const int depth = mtw == 1 ? 2 : 1;
         if (mtw == 2) {
             if (gen) cx.run(conv1x1_bf16_k<2, 1, true>, grid, dim3(kThreads), lds, a);
             else cx.run(conv1x1_bf16_k<2, 1, false>, grid, dim3(kThreads), lds, a);

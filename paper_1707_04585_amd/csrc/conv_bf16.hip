@@ -313,26 +313,58 @@ Bf16Plan plan_bf16(int ci, int co, int ks, const Geo &g) {
     return best;
 }
 
-// Filter in bf16 and K order for conv_bf16_k: qf[ko][tap][c] = w[ko][c][tap]
-// (forward), qb[c][tap][ko] = w[ko][c][k*k-1-tap] (data gradient: transposed and
-// flipped); channel pitches CIP, COP (multiples of 8, zero padded).
-__global__ __launch_bounds__(kThreads) void prep_filter_k(const float *__restrict__ w, int CO, int CI, int KS2,
-                                                          uint16_t *__restrict__ qf, int CIP,
-                                                          uint16_t *__restrict__ qb, int COP) {
-    const int64_t nf = qf ? (int64_t)CO * KS2 * CIP : 0, nb = qb ? (int64_t)CI * KS2 * COP : 0;
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i < nf) {
-        const int c = (int)(i % CIP);
-        const int64_t t = i / CIP;
+// One launch converts every filter of a residual function.  A job is one
+// destination buffer:
+//   kind 0: q[ko][tap][c]  = w[ko][c][tap]           (forward, channel pitch KP)
+//   kind 1: q[c][tap][ko]  = w[ko][c][k*k-1-tap]     (data gradient: transposed and flipped, pitch KP)
+//   kind 2: q[mt][ks][lane][e] = w[row][col]         (1x1 forward, operand order of conv1x1_bf16:
+//   kind 3: q[mt][ks][lane][e] = w[col][row]          row = mt*32 + lane%32, col = ks*16 + (lane/32)*8 + e)
+// with zeros outside the filter.
+struct PrepJob {
+    const float *w;  // [CO][CI][KS2]
+    uint16_t *q;
+    int CO, CI, KS2, kind;
+    int KP;       // channel pitch (kinds 0, 1) or 16-channel steps per row tile (kinds 2, 3)
+    int block0;   // first workgroup of this job
+    int64_t n;    // elements to write
+};
+struct PrepArgs {
+    PrepJob job[6];
+    int jobs;
+};
+
+__global__ __launch_bounds__(kThreads) void prep_filter_k(const PrepArgs p) {
+    int j = 0;
+#pragma unroll
+    for (int i = 1; i < 6; ++i)
+        if (i < p.jobs && (int)blockIdx.x >= p.job[i].block0) j = i;
+    const PrepJob &jb = p.job[j];
+    const int64_t i = (int64_t)(blockIdx.x - jb.block0) * kThreads + threadIdx.x;
+    if (i >= jb.n) return;
+    const int CO = jb.CO, CI = jb.CI, KS2 = jb.KS2;
+    float v = 0.f;
+    if (jb.kind == 0) {
+        const int c = (int)(i % jb.KP);
+        const int64_t t = i / jb.KP;
         const int tap = (int)(t % KS2), ko = (int)(t / KS2);
-        qf[i] = c < CI ? (uint16_t)bf16_bits(w[((int64_t)ko * CI + c) * KS2 + tap]) : (uint16_t)0;
-    } else if (i - nf < nb) {
-        const int64_t j = i - nf;
-        const int ko = (int)(j % COP);
-        const int64_t t = j / COP;
+        if (c < CI) v = jb.w[((int64_t)ko * CI + c) * KS2 + tap];
+    } else if (jb.kind == 1) {
+        const int ko = (int)(i % jb.KP);
+        const int64_t t = i / jb.KP;
         const int tap = (int)(t % KS2), c = (int)(t / KS2);
-        qb[j] = ko < CO ? (uint16_t)bf16_bits(w[((int64_t)ko * CI + c) * KS2 + (KS2 - 1 - tap)]) : (uint16_t)0;
+        if (ko < CO) v = jb.w[((int64_t)ko * CI + c) * KS2 + (KS2 - 1 - tap)];
+    } else {
+        const int e = (int)(i & 7), ln = (int)((i >> 3) & 63);
+        const int64_t blk = i >> 9;
+        const int ks = (int)(blk % jb.KP), mt = (int)(blk / jb.KP);
+        const int row = mt * 32 + (ln & 31), col = ks * 16 + (ln >> 5) * 8 + e;
+        if (jb.kind == 2) {
+            if (row < CO && col < CI) v = jb.w[(int64_t)row * CI + col];
+        } else {
+            if (row < CI && col < CO) v = jb.w[(int64_t)col * CI + row];
+        }
     }
+    jb.q[i] = (uint16_t)(pack2(v, 0.f) & 0xffffu);
 }
 
 }  // namespace
@@ -346,20 +378,38 @@ size_t filter_bf16_elems(int rows, int cols_k, int ks) {
     return ks == 1 ? std::max(n, filter_1x1_elems(rows, cols_k)) : n;
 }
 
-void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, Geo g, uint16_t *qf, uint16_t *qb) {
-    if (ks == 1) {  // operand order for the filters conv1x1_bf16 will take
-        uint16_t *const df = qf && conv1x1_direct_ok(cin, g) ? qf : nullptr;
-        uint16_t *const db = qb && conv1x1_direct_ok(cout, g) ? qb : nullptr;
-        if (df || db) prep_filter_1x1(cx, w, cin, cout, df, db);
-        if (df) qf = nullptr;
-        if (db) qb = nullptr;
-        if (!qf && !qb) return;
+void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g) {
+    PrepArgs a{};
+    int blocks = 0;
+    double bytes = 0.0;
+    auto add = [&](const FilterPrep &fp, uint16_t *q, int kind, int kp, int64_t n) {
+        PrepJob &jb = a.job[a.jobs++];
+        jb.w = fp.w; jb.q = q; jb.CO = fp.cout; jb.CI = fp.cin; jb.KS2 = fp.ks * fp.ks; jb.kind = kind; jb.KP = kp;
+        jb.block0 = blocks; jb.n = n;
+        blocks += (int)((n + kThreads - 1) / kThreads);
+        bytes += 2.0 * n;
+    };
+    for (int i = 0; i < count && i < 3; ++i) {
+        const FilterPrep &fp = f[i];
+        if (!fp.qf && !fp.qb) continue;
+        bytes += 4.0 * fp.cin * fp.cout * fp.ks * fp.ks;
+        const int cip = (fp.cin + 7) / 8 * 8, cop = (fp.cout + 7) / 8 * 8, ks2 = fp.ks * fp.ks;
+        if (fp.qf) {
+            if (fp.ks == 1 && conv1x1_direct_ok(fp.cin, g))
+                add(fp, fp.qf, 2, (fp.cin + 15) / 16, (int64_t)filter_1x1_elems(fp.cout, fp.cin));
+            else
+                add(fp, fp.qf, 0, cip, (int64_t)fp.cout * ks2 * cip);
+        }
+        if (fp.qb) {
+            if (fp.ks == 1 && conv1x1_direct_ok(fp.cout, g))
+                add(fp, fp.qb, 3, (fp.cout + 15) / 16, (int64_t)filter_1x1_elems(fp.cin, fp.cout));
+            else
+                add(fp, fp.qb, 1, cop, (int64_t)fp.cin * ks2 * cop);
+        }
     }
-    const int cip = (cin + 7) / 8 * 8, cop = (cout + 7) / 8 * 8;
-    const int64_t n = (qf ? (int64_t)cout * ks * ks * cip : 0) + (qb ? (int64_t)cin * ks * ks * cop : 0);
-    if (!cx.launch(K_PREP_FILTER, 4.0 * cin * cout * ks * ks + 2.0 * n)) return;
-    cx.run(prep_filter_k, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, w, cout, cin, ks * ks,
-           qf, cip, qb, cop);
+    if (a.jobs == 0) return;
+    if (!cx.launch(K_PREP_FILTER, bytes)) return;
+    cx.run(prep_filter_k, dim3((unsigned)blocks), dim3(kThreads), 0, a);
 }
 
 bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,

@@ -159,15 +159,20 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
 // passes conv1x1_direct_ok are stored instead in the operand order of
 // conv1x1_bf16: [rows / 32][k_channels / 16][64 lanes][8], zero padded.
 size_t filter_bf16_elems(int rows, int k_channels, int ks);
-void prep_filter_bf16(Ctx &cx, const float *w, int cin, int cout, int ks, Geo g, uint16_t *qf, uint16_t *qb);
+struct FilterPrep {
+    const float *w;  // [cout][cin][ks][ks]
+    int cin, cout, ks;
+    uint16_t *qf, *qb;  // destinations (either may be null)
+};
+// Converts the filters of up to three layers in one launch.
+void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g);
 
 // 1x1 convolution without LDS: activations go from HBM to the matrix
 // instruction's registers directly.  Needs the filter in operand order (wq from
-// prep_filter_1x1) and conv1x1_direct_ok(ci, g); returns false (nothing
+// prep_filters_bf16) and conv1x1_direct_ok(ci, g); returns false (nothing
 // launched) otherwise.
 bool conv1x1_direct_ok(int k_channels, const Geo &g);
 size_t filter_1x1_elems(int rows, int k_channels);
-void prep_filter_1x1(Ctx &cx, const float *w, int cin, int cout, uint16_t *qf, uint16_t *qb);
 bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
                   Epilogue ep, const View *r, View out);
 

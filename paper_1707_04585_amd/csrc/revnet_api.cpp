@@ -267,8 +267,10 @@ int check_ws(const void *ws, size_t have, size_t need) {
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
                   const rvn_func_params &p, Epilogue ep, const View *r, View out) {
     View cur = x;
+    FilterPrep prep[3];
     for (int l = 0; l < pl.L; ++l)
-        if (b.wq_f[l]) prep_filter_bf16(cx, p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, g, b.wq_f[l], b.wq_b[l]);
+        prep[l] = FilterPrep{p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]};
+    prep_filters_bf16(cx, prep, pl.L, g);
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
         bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
