@@ -70,6 +70,12 @@ __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *fla
     return *flag_lds != 0;
 }
 
+// e / d with a host-made multiplier m = 2^32 / d + 1 (exact while e * d < 2^32;
+// the host passes m = 0 when it cannot promise that, and d is divided by then).
+__device__ __forceinline__ int idiv(int e, int d, uint32_t m) { return m ? (int)__umulhi((uint32_t)e, m) : e / d; }
+
+constexpr int kFly = 4;  // items a thread requests before it uses the first
+
 __device__ __forceinline__ double shfl_down_f64(double v, int off) {
     int lo = __double2loint(v), hi = __double2hiint(v);
     lo = __shfl_down(lo, off, 64);
@@ -84,7 +90,7 @@ __device__ __forceinline__ double shfl_down_f64(double v, int off) {
 // ---------------------------------------------------------------------------
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__ x, int64_t sn,
-                                                       int64_t sc, int N, int HW, int ipw,
+                                                       int64_t sc, int N, int HW, int ipw, uint32_t m_per,
                                                        float *partial, int *counters, float eps,
                                                        const float *__restrict__ gamma,
                                                        const float *__restrict__ beta,
@@ -98,19 +104,34 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
     // cancel when |mean| >> std (the residual stream grows with depth).
     const float pivot = base[(int64_t)n0 * sn];
     float acc[2] = {0.f, 0.f};
-    for (int n = n0; n < n1; ++n) {
-        const float *pl = base + (int64_t)n * sn;
-        if (VEC) {
-            const float4 *pl4 = reinterpret_cast<const float4 *>(pl);
-            for (int i = threadIdx.x; i < HW / 4; i += kThreads) {
-                const float4 v = pl4[i];
-                const float a = v.x - pivot, b = v.y - pivot, c = v.z - pivot, d = v.w - pivot;
+    // The workgroup's images as one index space (quads if VEC), kFly loads in
+    // flight per thread; indices past the end re-read a valid item and add 0.
+    const int per = VEC ? HW / 4 : HW, total = (n1 - n0) * per;
+    for (int q0 = threadIdx.x; q0 < total; q0 += kFly * kThreads) {
+        float4 v[kFly];
+        bool ok[kFly];
+#pragma unroll
+        for (int k = 0; k < kFly; ++k) {
+            const int q = q0 + k * kThreads;
+            ok[k] = q < total;
+            const int qc = ok[k] ? q : q0;
+            const int n = idiv(qc, per, m_per), i = qc - n * per;
+            const float *pl = base + (int64_t)(n0 + n) * sn;
+            if (VEC) {
+                v[k] = reinterpret_cast<const float4 *>(pl)[i];
+            } else {
+                v[k].x = pl[i];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < kFly; ++k) {
+            if (VEC) {
+                const float a = ok[k] ? v[k].x - pivot : 0.f, b = ok[k] ? v[k].y - pivot : 0.f;
+                const float c = ok[k] ? v[k].z - pivot : 0.f, d = ok[k] ? v[k].w - pivot : 0.f;
                 acc[0] += (a + b) + (c + d);
                 acc[1] += (a * a + b * b) + (c * c + d * d);
-            }
-        } else {
-            for (int i = threadIdx.x; i < HW; i += kThreads) {
-                const float d = pl[i] - pivot;
+            } else {
+                const float d = ok[k] ? v[k].x - pivot : 0.f;
                 acc[0] += d;
                 acc[1] += d * d;
             }
@@ -167,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *__restrict__ da, int N, int C,
-    int HW, int ipw, const float *__restrict__ stats, float *partial, int *counters, double inv_m,
+    int HW, int ipw, uint32_t m_per, const float *__restrict__ stats, float *partial, int *counters, double inv_m,
     float *__restrict__ dgamma, float *__restrict__ dbeta, int accumulate, float *__restrict__ coef) {
     __shared__ float lds[8];
     __shared__ int flag;
@@ -176,28 +197,35 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_k(
     const float mean = stats[ch], rstd = stats[C + ch];
     const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
     float acc[2] = {0.f, 0.f};
-    for (int n = n0; n < n1; ++n) {
-        const float *px = x + (int64_t)n * sn + (int64_t)ch * sc;
-        const float *pd = da + ((int64_t)n * C + ch) * HW;
-        if (VEC) {
-            for (int i = threadIdx.x; i < HW / 4; i += kThreads) {
-                const float4 xv = reinterpret_cast<const float4 *>(px)[i];
-                const float4 dv = reinterpret_cast<const float4 *>(pd)[i];
-                const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
-                const float ds[4] = {dv.x, dv.y, dv.z, dv.w};
+    const int per = VEC ? HW / 4 : HW, total = (n1 - n0) * per;
+    for (int q0 = threadIdx.x; q0 < total; q0 += kFly * kThreads) {
+        float4 xv[kFly], dv[kFly];
+        bool ok[kFly];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float dy = fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
-                    acc[0] += dy;
-                    acc[1] += dy * ((xs[j] - mean) * rstd);
-                }
+        for (int k = 0; k < kFly; ++k) {
+            const int q = q0 + k * kThreads;
+            ok[k] = q < total;
+            const int qc = ok[k] ? q : q0;
+            const int n = idiv(qc, per, m_per), i = qc - n * per;
+            const float *px = x + (int64_t)(n0 + n) * sn + (int64_t)ch * sc;
+            const float *pd = da + ((int64_t)(n0 + n) * C + ch) * HW;
+            if (VEC) {
+                xv[k] = reinterpret_cast<const float4 *>(px)[i];
+                dv[k] = reinterpret_cast<const float4 *>(pd)[i];
+            } else {
+                xv[k].x = px[i];
+                dv[k].x = pd[i];
             }
-        } else {
-            for (int i = threadIdx.x; i < HW; i += kThreads) {
-                const float xv = px[i];
-                const float dy = fmaf(xv, scale, shift) > 0.f ? pd[i] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < kFly; ++k) {
+            const float xs[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
+            const float ds[4] = {dv[k].x, dv[k].y, dv[k].z, dv[k].w};
+#pragma unroll
+            for (int j = 0; j < (VEC ? 4 : 1); ++j) {
+                const float dy = ok[k] && fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
                 acc[0] += dy;
-                acc[1] += dy * ((xv - mean) * rstd);
+                acc[1] += dy * ((xs[j] - mean) * rstd);
             }
         }
     }
@@ -289,6 +317,14 @@ inline bool vec_ok(const View &v, int hw) {
     return hw % 4 == 0 && v.sn % 4 == 0 && v.sc % 4 == 0 && (reinterpret_cast<uintptr_t>(v.p) & 15) == 0;
 }
 
+// Multiplier for idiv: indices run up to images * per, and the shortcut is
+// exact while index * per < 2^32.
+uint32_t div_magic(int images, int per) {
+    if (per <= 1) return 0u;
+    if ((uint64_t)images * per * per >= (1ull << 32)) return 0u;
+    return (uint32_t)((1ull << 32) / (uint64_t)per + 1ull);
+}
+
 }  // namespace
 
 int reduce_splits(int c, const Geo &g) {
@@ -316,9 +352,9 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
     if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c)) return;
     dim3 grid(S, c);
     if (vec_ok(x, g.hw()))
-        cx.run(bn_stats_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
+        cx.run(bn_stats_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw() / 4), scratch, counters, eps, gamma, beta, stats);
     else
-        cx.run(bn_stats_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, scratch, counters, eps, gamma, beta, stats);
+        cx.run(bn_stats_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw()), scratch, counters, eps, gamma, beta, stats);
 }
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
@@ -332,9 +368,9 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         dim3 grid(S, c);
         const double inv_m = 1.0 / (double)g.pixels();
         if (vec_in)
-            cx.run(bn_bwd_reduce_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
+            cx.run(bn_bwd_reduce_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, div_magic(ipw, g.hw() / 4), stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
         else
-            cx.run(bn_bwd_reduce_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
+            cx.run(bn_bwd_reduce_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, div_magic(ipw, g.hw()), stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
     }
     if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : 3.0) * t)) {
         const bool vec = vec_in && vec_ok(out, g.hw()) && (!skip || vec_ok(*skip, g.hw()));
