@@ -30,14 +30,26 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2
 MEASURED_TRAFFIC = {
     # conv_mfma_f32_k at c2_stack9: (FETCH_SIZE 6395.7 KiB x 2.0 + WRITE_SIZE 8192.0 KiB x 1.0) per dispatch,
     # averaged over forward, recompute and data-gradient launches (profiles/c2_stack9_hbm_traffic.txt)
-    ("c2_stack9", "conv_fwd"): 21485512,
+    ("c2_stack9", "conv_fwd"): 21485479,
+    # c4_bneck12: conv1x1_bf16_k (128->64), conv3x3_bf16_k, conv1x1_bf16_k (64->128), same averaging
+    # (profiles/c4_bneck12_hbm_traffic.txt)
+    ("c4_bneck12", "conv_fwd"): 170811376,
+    # c5_stage3: the two conv1x1_bf16_k shapes and conv3x3_bf16_k + its splitk_reduce_k
+    # (profiles/c5_stage3_hbm_traffic.txt)
+    ("c5_stage3", "conv_fwd"): 52166418,
 }
 
 
-def bound_of(family: str, conv: str):
-    """Which roof a kernel family is held against."""
+def bound_of(family: str, conv: str, flops: float, nbytes: float):
+    """Which roof a kernel family is held against: a convolution family whose
+    algorithmic flops per algorithmic byte (summed over its launches in this
+    workload) lie above the ridge of its matrix unit is matrix-bound, every
+    other kernel is bound by HBM."""
     if family in ("conv_fwd", "conv_dgrad", "conv_wgrad"):
-        return ("mfma", "mfma_bf16" if conv == "bf16" else "mfma_f32")
+        key = "mfma_bf16" if conv == "bf16" else "mfma_f32"
+        ridge = PEAK[key][0] * 1e12 / (PEAK["hbm"][0] * 1e9)
+        if nbytes > 0 and flops / nbytes >= ridge:
+            return ("mfma", key)
     return ("hbm", "hbm")
 
 
@@ -114,7 +126,7 @@ def main() -> int:
                           GBps=round(st["algorithmic_bytes"] / st["total_ms"] / 1e6, 1) if st["total_ms"] else None,
                           TFLOPs=round(st["flops"] / st["total_ms"] / 1e9, 2) if st["flops"] else None)
     dom = max(stats, key=lambda k: stats[k]["total_ms"])
-    bound, peak_key = bound_of(dom, conv)
+    bound, peak_key = bound_of(dom, conv, stats[dom]["flops"], stats[dom]["algorithmic_bytes"])
     peak, unit = PEAK[peak_key]
     d = stats[dom]
     per_launch_s = d["total_ms"] * 1e-3 / d["launches"]
