@@ -241,28 +241,50 @@ __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
         }
     }
 
-    // ---- epilogue: lane holds channels co0 + m*16 + 4*kq + j (j = 0..3) of its pixel
+    // ---- epilogue: lane holds channels co0 + m*16 + 4*kq + j (j = 0..3) of its pixel.
+    //      r may alias out (element for element), so the compiler cannot move a
+    //      skip load above an earlier store: all skip values are requested first.
+    int64_t e_off[NT];  // offset of (image, pixel) in out / r, -1: nothing to write
+    int64_t e_roff[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int tile = wave + kWaves * t;
-        if (tile >= p.n_tiles) continue;
         const int img = tile / p.tiles_per_img, rem = tile - img * p.tiles_per_img;
         const int tr = rem / p.ctl, tc = rem - tr * p.ctl;
         const int n = n0 + img, row = row0 + tr * p.trows + dr, col = (tc << p.tcols_log2) + dc;
-        if (n >= p.N || row >= p.H || row >= row0 + p.TH || col >= p.W) continue;
+        const bool ok = tile < p.n_tiles && n < p.N && row < p.H && row < row0 + p.TH && col < p.W;
         const int pix = row * p.W + col;
+        e_off[t] = ok ? (int64_t)n * p.osn + pix : -1;
+        e_roff[t] = (int64_t)n * p.rsn + pix;
+    }
+    if (p.ep != EP_STORE) {
+        float rv[NT][MT][4];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ko = co0 + m * 16 + kq * 4 + j;
+                    rv[t][m][j] = e_off[t] >= 0 && ko < p.CO ? p.r[e_roff[t] + (int64_t)ko * p.rsc] : 0.f;
+                }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[m][t][j] = p.ep == EP_ADD ? rv[t][m][j] + acc[m][t][j] : rv[t][m][j] - acc[m][t][j];
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        if (e_off[t] < 0) continue;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int ko = co0 + m * 16 + kq * 4 + j;
-                if (ko >= p.CO) continue;
-                float v = acc[m][t][j];
-                if (p.ep != EP_STORE) {
-                    const float rv = p.r[(int64_t)n * p.rsn + (int64_t)ko * p.rsc + pix];
-                    v = p.ep == EP_ADD ? rv + v : rv - v;
-                }
-                p.out[(int64_t)n * p.osn + (int64_t)ko * p.osc + pix] = v;
+                if (ko < p.CO) p.out[e_off[t] + (int64_t)ko * p.osc] = acc[m][t][j];
             }
         }
     }
