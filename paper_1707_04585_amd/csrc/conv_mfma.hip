@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
     // covers it).
     const int quads = (p.W + 3) >> 2;
     const bool right_quad = KS == 3 && (p.W & 3) == 0;
-    constexpr int RB = 4;                          // rows a thread loads before it stores
+    constexpr int RB = 6;                          // rows a thread loads before it stores
     constexpr int WITER = (WCHUNK + kThreads - 1) / kThreads;
 
     for (int c0 = 0; c0 < p.CI; c0 += KC) {
