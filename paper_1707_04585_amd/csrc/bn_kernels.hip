@@ -10,6 +10,7 @@
 // reproducible -- the reconstruction of Section 3.2 relies on recomputing
 // exactly what the forward pass computed.
 #include "kernels.h"
+#include "wgrad_reduce.h"
 
 namespace rvn {
 
@@ -267,9 +268,17 @@ template <bool VEC, bool SKIP>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
-    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc) {
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry) {
+    // The first carry.blocks workgroups sum a filter gradient's partial results
+    // (independent work that would otherwise be a launch of its own; first, so
+    // that its dependent loads run under the streaming of the others).
+    if ((int)blockIdx.x < carry.blocks) {
+        __shared__ float lds[kThreads];
+        wgrad_reduce_body(carry, blockIdx.x, lds);
+        return;
+    }
     constexpr int E = VEC ? 4 : 1;
-    const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t v = (int64_t)(blockIdx.x - carry.blocks) * kThreads + threadIdx.x;
     if (v >= total) return;
     const int per_plane = HW / E;
     const int64_t plane = v / per_plane;
@@ -358,7 +367,8 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
 }
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
-                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out) {
+                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out,
+                 const WgradReduce *carry) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double t = 4.0 * (double)g.pixels() * c;
@@ -378,8 +388,12 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
         const float *kp = skip ? skip->p : nullptr;
         const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
+        WgradReduce red{};
+        if (carry) red = *carry;
+        if (red.blocks < 0) red.blocks = 0;
+        const unsigned extra = (unsigned)red.blocks;
 #define RVN_LAUNCH(V, K) \
-    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc)
+    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);

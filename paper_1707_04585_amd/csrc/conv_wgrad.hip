@@ -22,6 +22,7 @@
 // them.  The workgroups' partial results are summed by a second kernel in a
 // fixed order (no floating-point atomics: results are bitwise reproducible).
 #include "kernels.h"
+#include "wgrad_reduce.h"
 
 namespace rvn {
 
@@ -290,49 +291,9 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_mfma_k(const WgradArgs p)
     }
 }
 
-// dw (+)= sum_s part[s]: a workgroup handles 32 consecutive partial-result
-// slots; 8 slices of s are summed in order by 8 groups of 32 threads, then
-// combined in order, and the slot is mapped from register order to
-// dw[ko][c][tap].
-__global__ __launch_bounds__(kThreads) void wgrad_reduce_k(const float *__restrict__ part, int part_stride,
-                                                           int S, int KS2, int MT, int CT, int tiles_c,
-                                                           int CO, int CI, float *__restrict__ dw,
-                                                           int accumulate) {
+__global__ __launch_bounds__(kThreads) void wgrad_reduce_k(const WgradReduce r) {
     __shared__ float lds[kThreads];
-    const int o = blockIdx.x * 32 + (threadIdx.x & 31), sl = threadIdx.x >> 5;
-    const int per = (S + 7) / 8;
-    const int s0 = sl * per, s1 = min(S, s0 + per);
-    float v = 0.f;
-    if (o < part_stride) {
-        const float *q = part + o;
-        int s = s0;
-        for (; s + 4 <= s1; s += 4) {
-            const float a = q[(int64_t)s * part_stride], b = q[(int64_t)(s + 1) * part_stride];
-            const float c = q[(int64_t)(s + 2) * part_stride], d = q[(int64_t)(s + 3) * part_stride];
-            v += (a + b) + (c + d);
-        }
-        for (; s < s1; ++s) v += q[(int64_t)s * part_stride];
-    }
-    lds[threadIdx.x] = v;
-    __syncthreads();
-    if (sl == 0 && o < part_stride) {
-        const int l = threadIdx.x;
-        const float t = ((lds[l] + lds[32 + l]) + (lds[64 + l] + lds[96 + l])) +
-                        ((lds[128 + l] + lds[160 + l]) + (lds[192 + l] + lds[224 + l]));
-        const int WT = MT * CT;
-        const int ln = o & 63, j = (o >> 6) & 3;
-        int r = o >> 8;
-        const int tap = r % KS2;
-        r /= KS2;
-        const int tl = r % WT, grp = r / WT;
-        const int gy = grp / tiles_c, gz = grp - gy * tiles_c;
-        const int mm = tl / CT, cc = tl - mm * CT;
-        const int ko = (gy * MT + mm) * 16 + 4 * (ln >> 4) + j, c = (gz * CT + cc) * 16 + (ln & 15);
-        if (ko < CO && c < CI) {
-            const int64_t i = ((int64_t)ko * CI + c) * KS2 + tap;
-            dw[i] = accumulate ? dw[i] + t : t;
-        }
-    }
+    wgrad_reduce_body(r, blockIdx.x, lds);
 }
 
 struct WgradPlan {
@@ -405,14 +366,15 @@ size_t wgrad_scratch_floats(int cin, int cout, int ks, const Geo &g) {
 }
 
 void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
-                int ks, Geo g, float *scratch, float *dw, bool accumulate) {
+                int ks, Geo g, float *scratch, float *dw, bool accumulate, WgradReduce *defer) {
+    if (defer) defer->blocks = 0;
     const double P = (double)g.pixels();
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_wgrad_calls += 1;
     cx.cost.conv_flops += flops;
     if (dt == RVN_BF16 &&
         conv_wgrad_bf16(cx, x, scale_shift, dh, cin, cout, ks, g, scratch, dw, accumulate,
-                        P * cin * 4.0 + P * cout * 4.0, flops))
+                        P * cin * 4.0 + P * cout * 4.0, flops, defer))
         return;
     const WgradPlan w = plan_wgrad(cin, cout, ks, g);
     if (cx.launch(K_CONV_WGRAD, P * cin * 4.0 + P * cout * 4.0, flops)) {
@@ -450,10 +412,18 @@ void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh
         RVN_CASE(1, 1, 1) RVN_CASE(1, 1, 2) RVN_CASE(1, 2, 1) RVN_CASE(1, 2, 2)
 #undef RVN_CASE
     }
-    if (cx.launch(K_WGRAD_REDUCE, 0.0)) {
-        cx.run(wgrad_reduce_k, dim3((unsigned)((w.part_stride + 31) / 32)), dim3(kThreads), 0, scratch,
-               w.part_stride, w.S, ks * ks, w.MT, w.CT, w.tiles_c, cout, cin, dw, accumulate ? 1 : 0);
-    }
+    WgradReduce red{};
+    red.part = scratch; red.dw = dw;
+    red.part_stride = w.part_stride; red.S = w.S; red.KS2 = ks * ks; red.MT = w.MT; red.CT = w.CT;
+    red.tiles_c = w.tiles_c; red.CO = cout; red.CI = cin; red.accumulate = accumulate ? 1 : 0;
+    red.tile = 16; red.blocks = (w.part_stride + 31) / 32;
+    if (defer) *defer = red;
+    else wgrad_reduce(cx, red);
+}
+
+void wgrad_reduce(Ctx &cx, const WgradReduce &r) {
+    if (r.blocks <= 0) return;
+    if (cx.launch(K_WGRAD_REDUCE, 0.0)) cx.run(wgrad_reduce_k, dim3((unsigned)r.blocks), dim3(kThreads), 0, r);
 }
 
 }  // namespace rvn

@@ -19,7 +19,9 @@
 // images; workgroup s walks over a contiguous range of units with its partial
 // sums in registers; every wavefront owns one 32x32 (ko, c) tile for all k*k
 // taps and a 1/KW share of the 16-pixel steps; a(x) = max(x*scale + shift, 0) is
-// formed (and rounded to bf16) on the way into LDS.  Partial results are summed by a second kernel in a fixed order.
+// formed (and rounded to bf16) on the way into LDS.  Partial results are summed
+// in a fixed order by wgrad_reduce_body, in a launch of its own or carried by
+// another kernel.
 #include "kernels.h"
 
 namespace rvn {
@@ -271,50 +273,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p)
     }
 }
 
-// dw (+)= sum_s part[s], mapping register order to dw[ko][c][tap]; a workgroup
-// handles 32 consecutive slots, 8 slices of s summed in order by 8 groups of 32
-// threads, then combined in order.
-__global__ __launch_bounds__(kThreads) void wgrad_bf16_reduce_k(const float *__restrict__ part, int part_stride,
-                                                                int S, int KS2, int MT, int CT, int tiles_c,
-                                                                int CO, int CI, float *__restrict__ dw,
-                                                                int accumulate) {
-    __shared__ float lds[kThreads];
-    const int o = blockIdx.x * 32 + (threadIdx.x & 31), sl = threadIdx.x >> 5;
-    const int per = (S + 7) / 8;
-    const int s0 = sl * per, s1 = min(S, s0 + per);
-    float v = 0.f;
-    if (o < part_stride) {
-        const float *q = part + o;
-        int s = s0;
-        for (; s + 4 <= s1; s += 4) {
-            const float a = q[(int64_t)s * part_stride], b = q[(int64_t)(s + 1) * part_stride];
-            const float c = q[(int64_t)(s + 2) * part_stride], d = q[(int64_t)(s + 3) * part_stride];
-            v += (a + b) + (c + d);
-        }
-        for (; s < s1; ++s) v += q[(int64_t)s * part_stride];
-    }
-    lds[threadIdx.x] = v;
-    __syncthreads();
-    if (sl == 0 && o < part_stride) {
-        const int l = threadIdx.x;
-        const float t = ((lds[l] + lds[32 + l]) + (lds[64 + l] + lds[96 + l])) +
-                        ((lds[128 + l] + lds[160 + l]) + (lds[192 + l] + lds[224 + l]));
-        const int WT = MT * CT;
-        const int ln = o & 63, i = (o >> 6) & 15;
-        int r = o >> 10;
-        const int tap = r % KS2;
-        r /= KS2;
-        const int tl = r % WT, grp = r / WT;
-        const int gy = grp / tiles_c, gz = grp - gy * tiles_c;
-        const int mm = tl / CT, cc = tl - mm * CT;
-        const int ko = (gy * MT + mm) * 32 + 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3), c = (gz * CT + cc) * 32 + (ln & 31);
-        if (ko < CO && c < CI) {
-            const int64_t k = ((int64_t)ko * CI + c) * KS2 + tap;
-            dw[k] = accumulate ? dw[k] + t : t;
-        }
-    }
-}
-
 struct WgPlan {
     int MT, CT, TH, IMGS, bands, units, S, upw, Wq, cpr, lrows;
     int a_pitch, a_img, a_plane, d_pitch, d_img, d_plane, a_items, d_items;
@@ -385,7 +343,7 @@ size_t wgrad_bf16_scratch_floats(int cin, int cout, int ks, const Geo &g) {
 }
 
 bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
-                     float *scratch, float *dw, bool accumulate, double bytes, double flops) {
+                     float *scratch, float *dw, bool accumulate, double bytes, double flops, WgradReduce *defer) {
     const WgPlan w = plan_wg(cin, cout, ks, g);
     if (!w.ok) return false;
     WgArgs a{};
@@ -415,10 +373,13 @@ bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin
         RVN_CASE(1, 1, 1) RVN_CASE(1, 1, 2) RVN_CASE(1, 2, 1) RVN_CASE(1, 2, 2)
 #undef RVN_CASE
     }
-    if (cx.launch(K_WGRAD_REDUCE, 0.0)) {
-        cx.run(wgrad_bf16_reduce_k, dim3((unsigned)((w.part_stride + 31) / 32)), dim3(kThreads), 0, scratch,
-               w.part_stride, w.S, ks * ks, w.MT, w.CT, w.tiles_c, cout, cin, dw, accumulate ? 1 : 0);
-    }
+    WgradReduce red{};
+    red.part = scratch; red.dw = dw;
+    red.part_stride = w.part_stride; red.S = w.S; red.KS2 = ks * ks; red.MT = w.MT; red.CT = w.CT;
+    red.tiles_c = w.tiles_c; red.CO = cout; red.CI = cin; red.accumulate = accumulate ? 1 : 0;
+    red.tile = 32; red.blocks = (w.part_stride + 31) / 32;
+    if (defer) *defer = red;
+    else wgrad_reduce(cx, red);
     return true;
 }
 

@@ -89,6 +89,17 @@ struct Ctx {
     }
 };
 
+// The second half of a filter gradient: the ordered sum of its partial results.
+// conv_wgrad either launches it or hands it to the caller, who lets another
+// launch carry it (bn_relu_bwd's apply pass).  blocks == 0: nothing to do.
+struct WgradReduce {
+    const float *part;  // [S][part_stride]
+    float *dw;          // [CO][CI][KS2]
+    int part_stride, S, KS2, MT, CT, tiles_c, CO, CI, accumulate;
+    int tile;    // 16 (fp32 instruction) or 32 (bf16 instruction): edge of a result tile
+    int blocks;  // workgroups of 256 threads it needs
+};
+
 // ---- sizes of the small scratch areas the wrappers need (floats) ----------
 // Number of image groups a per-channel reduction is split into.
 int reduce_splits(int c, const Geo &g);
@@ -120,9 +131,11 @@ void clear_counters(Ctx &cx, int *counters, int n);
 
 // Backward of a(x) given da (dense fp32): writes dgamma, dbeta (added to when
 // accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
-// `da` (dense in-place) or `skip`.
+// `da` (dense in-place) or `skip`.  `carry`: a pending filter-gradient sum that
+// rides in the apply launch (extra workgroups).
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
-                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out);
+                 int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out,
+                 const WgradReduce *carry = nullptr);
 
 // ---- convolutions (Section 2.2: c_k(x) = Conv_kxk(a(x)), k in {1,3}) -------
 // out = ep(r, conv(a(x), w)) with a(x) = max(x*scale + shift, 0) formed on the
@@ -184,14 +197,17 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *
 // dw[k,c,r,s] (+)= sum_{n,p,q} dh[n,k,p,q] a[n,c,p+r-pad,q+s-pad], with
 // a(x) = max(x*scale + shift, 0) formed on the fly from the layer input x as in
 // conv_fwd; with dt == RVN_BF16 a and dh are rounded to bf16 before multiplying.
+// With `defer` the ordered sum of the partial results is not launched but
+// described in *defer for the caller to run (before `scratch` is reused).
 void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
-                int ks, Geo g, float *scratch, float *dw, bool accumulate);
+                int ks, Geo g, float *scratch, float *dw, bool accumulate, WgradReduce *defer = nullptr);
+void wgrad_reduce(Ctx &cx, const WgradReduce &r);
 
 // The same with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
 // to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the
 // caller accounts for the launch.  Returns false (nothing launched) when no
 // plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.
 bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
-                     float *scratch, float *dw, bool accumulate, double bytes, double flops);
+                     float *scratch, float *dw, bool accumulate, double bytes, double flops, WgradReduce *defer);
 
 }  // namespace rvn

@@ -72,7 +72,9 @@ struct Plan {
     size_t counters;      // ticket counters of the cross-workgroup reductions (ints)
     int n_counters;
     size_t bn_scratch;    // partial sums of the per-channel reductions
-    size_t wgrad_scratch; // partial filter gradients (backward only) and partial tiles of channel-split convolutions
+    size_t wgrad_scratch; // partial filter gradients (backward only)
+    size_t conv_scratch;  // partial tiles of channel-split convolutions (kept apart: a filter gradient's
+                          // partial results stay alive across the following data-gradient convolution)
     size_t h[2];          // h_l = conv_l(a_l), fp32, input of layer l+1
     size_t g[2];          // gradient ping-pong buffers (backward only)
     // bf16 convolutions with large filters: the filters of the function at hand
@@ -96,7 +98,7 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     Plan p{};
     p.L = func_layers(d, p.layers);
     const size_t P = (size_t)g.pixels();
-    size_t off = 0, bn_s = 0, wg_s = 0, max_cin = 0, max_mid = 0;
+    size_t off = 0, bn_s = 0, wg_s = 0, cv_s = 0, max_cin = 0, max_mid = 0;
     for (int l = 0; l < p.L; ++l) {
         const Layer &ly = p.layers[l];
         p.stats[l] = off;
@@ -104,8 +106,8 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
         bn_s = std::max(bn_s, bn_scratch_floats(ly.cin, g));
         if (backward) wg_s = std::max(wg_s, wgrad_scratch_floats(ly.cin, ly.cout, ly.ks, g));
         if (d.conv_dtype == RVN_BF16) {
-            wg_s = std::max(wg_s, conv_bf16_scratch_floats(ly.cin, ly.cout, ly.ks, g));
-            if (backward) wg_s = std::max(wg_s, conv_bf16_scratch_floats(ly.cout, ly.cin, ly.ks, g));
+            cv_s = std::max(cv_s, conv_bf16_scratch_floats(ly.cin, ly.cout, ly.ks, g));
+            if (backward) cv_s = std::max(cv_s, conv_bf16_scratch_floats(ly.cout, ly.cin, ly.ks, g));
         }
         max_cin = std::max(max_cin, (size_t)ly.cin);
         if (l < p.L - 1) max_mid = std::max(max_mid, (size_t)ly.cout);
@@ -128,6 +130,8 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     off = align_up(off + bn_s * 4);
     p.wgrad_scratch = off;
     off = align_up(off + wg_s * 4);
+    p.conv_scratch = off;
+    off = align_up(off + cv_s * 4);
     if (backward) {
         // a_l = ReLU(BN(x_l)) is never stored: every convolution kernel forms it
         // from x_l (the function input or h_{l-1}) while staging its operands.
@@ -158,7 +162,7 @@ struct Bufs {
     float *h[2];
     float *g[2];
     float *bn_scratch;
-    float *wgrad_scratch;
+    float *wgrad_scratch, *conv_scratch;
     int *counters;
     uint16_t *wq_f[3], *wq_b[3];  // null where the layer does not use converted filters
 };
@@ -178,6 +182,7 @@ Bufs bind(const Plan &p, void *ws) {
     o.bn_scratch = reinterpret_cast<float *>(b + p.bn_scratch);
     o.counters = reinterpret_cast<int *>(b + p.counters);
     o.wgrad_scratch = reinterpret_cast<float *>(b + p.wgrad_scratch);
+    o.conv_scratch = reinterpret_cast<float *>(b + p.conv_scratch);
     return o;
 }
 
@@ -277,10 +282,10 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.wgrad_scratch);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.conv_scratch);
             cur = h;
         } else {
-            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.wgrad_scratch);
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.conv_scratch);
         }
     }
 }
@@ -296,19 +301,22 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
     for (int l = pl.L - 1; l >= 0; --l) {
         const Layer &ly = pl.layers[l];
         const View xl = l > 0 ? dense_view(b.h[l - 1], ly.cin, g) : x;
+        // The ordered sum of the filter gradient's partial results rides in the
+        // BN-backward apply launch below.
+        WgradReduce red;
         conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
-                   gr.d_conv_w[l], accumulate);
+                   gr.d_conv_w[l], accumulate, &red);
         float *da = b.g[cur];
-        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.wgrad_scratch);
+        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
             bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
-                        accumulate, nullptr, dx);
+                        accumulate, nullptr, dx, &red);
             dh = dx;
             cur ^= 1;
         } else {
             bn_relu_bwd(cx, x, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
-                        accumulate, &skip, out);
+                        accumulate, &skip, out, &red);
         }
     }
 }
