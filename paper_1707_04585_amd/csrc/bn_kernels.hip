@@ -10,6 +10,7 @@
 // reproducible -- the reconstruction of Section 3.2 relies on recomputing
 // exactly what the forward pass computed.
 #include "kernels.h"
+#include "prep_filter.h"
 #include "wgrad_reduce.h"
 
 namespace rvn {
@@ -95,10 +96,18 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
                                                        float *partial, int *counters, float eps,
                                                        const float *__restrict__ gamma,
                                                        const float *__restrict__ beta,
-                                                       float *__restrict__ stats) {
+                                                       float *__restrict__ stats, int S, int C,
+                                                       const PrepArgs carry) {
+    // The first carry.blocks workgroups convert the residual function's filters
+    // (independent work that would otherwise be a launch of its own).
+    if ((int)blockIdx.x < carry.blocks) {
+        prep_filter_body(carry, blockIdx.x);
+        return;
+    }
     __shared__ float lds[8];
     __shared__ int flag;
-    const int ch = blockIdx.y, s = blockIdx.x, S = gridDim.x, C = gridDim.y;
+    const int lin = blockIdx.x - carry.blocks;
+    const int ch = lin / S, s = lin - ch * S;
     const int n0 = s * ipw, n1 = min(N, n0 + ipw);
     const float *base = x + (int64_t)ch * sc;
     // Shift by a value from the data so that the sum of squares does not
@@ -354,16 +363,18 @@ void clear_counters(Ctx &cx, int *counters, int n) {
     cx.run(clear_counters_k, dim3((n + 255) / 256), dim3(256), 0, counters, n);
 }
 
-void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
-              float *scratch, int *counters, float *stats) {
+void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta, float *scratch,
+              int *counters, float *stats, const PrepArgs *carry, double carry_bytes) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
-    if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c)) return;
-    dim3 grid(S, c);
+    if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c + carry_bytes)) return;
+    PrepArgs pa{};
+    if (carry) pa = *carry;
+    const dim3 grid((unsigned)(S * c + pa.blocks));
     if (vec_ok(x, g.hw()))
-        cx.run(bn_stats_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw() / 4), scratch, counters, eps, gamma, beta, stats);
+        cx.run(bn_stats_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw() / 4), scratch, counters, eps, gamma, beta, stats, S, c, pa);
     else
-        cx.run(bn_stats_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw()), scratch, counters, eps, gamma, beta, stats);
+        cx.run(bn_stats_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, g.n, g.hw(), ipw, div_magic(ipw, g.hw()), scratch, counters, eps, gamma, beta, stats, S, c, pa);
 }
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,

@@ -29,6 +29,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "prep_filter.h"
 
 namespace rvn {
 
@@ -313,59 +314,7 @@ Bf16Plan plan_bf16(int ci, int co, int ks, const Geo &g) {
     return best;
 }
 
-// One launch converts every filter of a residual function.  A job is one
-// destination buffer:
-//   kind 0: q[ko][tap][c]  = w[ko][c][tap]           (forward, channel pitch KP)
-//   kind 1: q[c][tap][ko]  = w[ko][c][k*k-1-tap]     (data gradient: transposed and flipped, pitch KP)
-//   kind 2: q[mt][ks][lane][e] = w[row][col]         (1x1 forward, operand order of conv1x1_bf16:
-//   kind 3: q[mt][ks][lane][e] = w[col][row]          row = mt*32 + lane%32, col = ks*16 + (lane/32)*8 + e)
-// with zeros outside the filter.
-struct PrepJob {
-    const float *w;  // [CO][CI][KS2]
-    uint16_t *q;
-    int CO, CI, KS2, kind;
-    int KP;       // channel pitch (kinds 0, 1) or 16-channel steps per row tile (kinds 2, 3)
-    int block0;   // first workgroup of this job
-    int64_t n;    // elements to write
-};
-struct PrepArgs {
-    PrepJob job[6];
-    int jobs;
-};
-
-__global__ __launch_bounds__(kThreads) void prep_filter_k(const PrepArgs p) {
-    int j = 0;
-#pragma unroll
-    for (int i = 1; i < 6; ++i)
-        if (i < p.jobs && (int)blockIdx.x >= p.job[i].block0) j = i;
-    const PrepJob &jb = p.job[j];
-    const int64_t i = (int64_t)(blockIdx.x - jb.block0) * kThreads + threadIdx.x;
-    if (i >= jb.n) return;
-    const int CO = jb.CO, CI = jb.CI, KS2 = jb.KS2;
-    float v = 0.f;
-    if (jb.kind == 0) {
-        const int c = (int)(i % jb.KP);
-        const int64_t t = i / jb.KP;
-        const int tap = (int)(t % KS2), ko = (int)(t / KS2);
-        if (c < CI) v = jb.w[((int64_t)ko * CI + c) * KS2 + tap];
-    } else if (jb.kind == 1) {
-        const int ko = (int)(i % jb.KP);
-        const int64_t t = i / jb.KP;
-        const int tap = (int)(t % KS2), c = (int)(t / KS2);
-        if (ko < CO) v = jb.w[((int64_t)ko * CI + c) * KS2 + (KS2 - 1 - tap)];
-    } else {
-        const int e = (int)(i & 7), ln = (int)((i >> 3) & 63);
-        const int64_t blk = i >> 9;
-        const int ks = (int)(blk % jb.KP), mt = (int)(blk / jb.KP);
-        const int row = mt * 32 + (ln & 31), col = ks * 16 + (ln >> 5) * 8 + e;
-        if (jb.kind == 2) {
-            if (row < CO && col < CI) v = jb.w[(int64_t)row * CI + col];
-        } else {
-            if (row < CI && col < CO) v = jb.w[(int64_t)col * CI + row];
-        }
-    }
-    jb.q[i] = (uint16_t)(pack2(v, 0.f) & 0xffffu);
-}
+__global__ __launch_bounds__(kThreads) void prep_filter_k(const PrepArgs p) { prep_filter_body(p, blockIdx.x); }
 
 }  // namespace
 
@@ -378,7 +327,7 @@ size_t filter_bf16_elems(int rows, int cols_k, int ks) {
     return ks == 1 ? std::max(n, filter_1x1_elems(rows, cols_k)) : n;
 }
 
-void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g) {
+PrepArgs plan_filter_prep(const FilterPrep *f, int count, Geo g, double *bytes_out) {
     PrepArgs a{};
     int blocks = 0;
     double bytes = 0.0;
@@ -387,7 +336,7 @@ void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g) {
         jb.w = fp.w; jb.q = q; jb.CO = fp.cout; jb.CI = fp.cin; jb.KS2 = fp.ks * fp.ks; jb.kind = kind; jb.KP = kp;
         jb.block0 = blocks; jb.n = n;
         blocks += (int)((n + kThreads - 1) / kThreads);
-        bytes += 2.0 * n;
+        bytes += 2.0 * n * (kind <= 1 ? jb.KS2 : 1);
     };
     for (int i = 0; i < count && i < 3; ++i) {
         const FilterPrep &fp = f[i];
@@ -398,18 +347,24 @@ void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g) {
             if (fp.ks == 1 && conv1x1_direct_ok(fp.cin, g))
                 add(fp, fp.qf, 2, (fp.cin + 15) / 16, (int64_t)filter_1x1_elems(fp.cout, fp.cin));
             else
-                add(fp, fp.qf, 0, cip, (int64_t)fp.cout * ks2 * cip);
+                add(fp, fp.qf, 0, cip, (int64_t)fp.cout * cip);
         }
         if (fp.qb) {
             if (fp.ks == 1 && conv1x1_direct_ok(fp.cout, g))
                 add(fp, fp.qb, 3, (fp.cout + 15) / 16, (int64_t)filter_1x1_elems(fp.cin, fp.cout));
             else
-                add(fp, fp.qb, 1, cop, (int64_t)fp.cin * ks2 * cop);
+                add(fp, fp.qb, 1, cop, (int64_t)fp.cin * cop);
         }
     }
+    a.blocks = blocks;
+    if (bytes_out) *bytes_out = bytes;
+    return a;
+}
+
+void prep_filters_bf16(Ctx &cx, const PrepArgs &a, double bytes) {
     if (a.jobs == 0) return;
     if (!cx.launch(K_PREP_FILTER, bytes)) return;
-    cx.run(prep_filter_k, dim3((unsigned)blocks), dim3(kThreads), 0, a);
+    cx.run(prep_filter_k, dim3((unsigned)a.blocks), dim3(kThreads), 0, a);
 }
 
 bool conv_bf16(Ctx &cx, View in, const float *scale_shift, const float *w, const uint16_t *wq, bool transposed,

@@ -122,8 +122,10 @@ constexpr int kStatsArrays = 4;
 // so that the atomics of different channels do not serialise; left at zero
 // again).
 constexpr int kCounterStride = 32;
+// `carry`: a filter conversion (see PrepArgs below) whose workgroups ride in this launch.
+struct PrepArgs;
 void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta,
-              float *scratch, int *counters, float *stats);
+              float *scratch, int *counters, float *stats, const PrepArgs *carry = nullptr, double carry_bytes = 0.0);
 
 // Zero n ticket counters (once per library call; the workspace is caller
 // memory with unknown contents).
@@ -177,8 +179,23 @@ struct FilterPrep {
     int cin, cout, ks;
     uint16_t *qf, *qb;  // destinations (either may be null)
 };
-// Converts the filters of up to three layers in one launch.
-void prep_filters_bf16(Ctx &cx, const FilterPrep *f, int count, Geo g);
+// The conversion of the filters of up to three layers as one list of jobs
+// (see prep_filter.h); plan_filter_prep builds it, prep_filters_bf16 runs it in
+// a launch of its own, bn_stats can carry it instead.
+struct PrepJob {
+    const float *w;  // [CO][CI][KS2]
+    uint16_t *q;
+    int CO, CI, KS2, kind;
+    int KP;      // channel pitch (kinds 0, 1) or 16-channel steps per row tile (kinds 2, 3)
+    int block0;  // first workgroup of this job
+    int64_t n;   // threads: elements to write (kinds 2, 3) or (row, padded column) pairs (kinds 0, 1)
+};
+struct PrepArgs {
+    PrepJob job[6];
+    int jobs, blocks;
+};
+PrepArgs plan_filter_prep(const FilterPrep *f, int count, Geo g, double *bytes);
+void prep_filters_bf16(Ctx &cx, const PrepArgs &a, double bytes);
 
 // 1x1 convolution without LDS: activations go from HBM to the matrix
 // instruction's registers directly.  Needs the filter in operand order (wq from

@@ -275,10 +275,13 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
     FilterPrep prep[3];
     for (int l = 0; l < pl.L; ++l)
         prep[l] = FilterPrep{p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]};
-    prep_filters_bf16(cx, prep, pl.L, g);
+    // The conversion rides in the first statistics launch of the function.
+    double prep_bytes = 0.0;
+    const PrepArgs pa = plan_filter_prep(prep, pl.L, g, &prep_bytes);
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
-        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l]);
+        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l],
+                 l == 0 && pa.jobs > 0 ? &pa : nullptr, l == 0 ? prep_bytes : 0.0);
         const float *scale_shift = b.stats[l] + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
