@@ -43,6 +43,7 @@ enum KernelId {
     K_BN_BWD_REDUCE,
     K_BN_BWD_APPLY,
     K_PREP_FILTER,
+    K_CONV_DGRAD_WGRAD,
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -219,6 +220,12 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *
 void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh, int cin, int cout,
                 int ks, Geo g, float *scratch, float *dw, bool accumulate, WgradReduce *defer = nullptr);
 void wgrad_reduce(Ctx &cx, const WgradReduce &r);
+
+// conv_dgrad and conv_wgrad of one fp32 3x3 layer in a single launch (both need
+// only dh); the ordered sum of the filter gradient is left in *defer.  Returns
+// false (nothing launched, nothing accounted) for the shapes it does not take.
+bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, const float *w, int cin, int cout,
+                          int ks, Geo g, float *scratch, float *dw, bool accumulate, float *da, WgradReduce *defer);
 
 // The same with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
 // to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the

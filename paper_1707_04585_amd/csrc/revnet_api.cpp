@@ -307,10 +307,14 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         // The ordered sum of the filter gradient's partial results rides in the
         // BN-backward apply launch below.
         WgradReduce red;
-        conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
-                   gr.d_conv_w[l], accumulate, &red);
         float *da = b.g[cur];
-        conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
+        if (d.conv_dtype != RVN_F32 ||
+            !conv_dgrad_wgrad_f32(cx, xl, b.stats[l] + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
+                                  b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, &red)) {
+            conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
+                       gr.d_conv_w[l], accumulate, &red);
+            conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
+        }
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
             bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
