@@ -45,7 +45,7 @@ def bound_of(family: str, conv: str, flops: float, nbytes: float):
     algorithmic flops per algorithmic byte (summed over its launches in this
     workload) lie above the ridge of its matrix unit is matrix-bound, every
     other kernel is bound by HBM."""
-    if family in ("conv_fwd", "conv_dgrad", "conv_wgrad"):
+    if family in ("conv_fwd", "conv_dgrad", "conv_wgrad", "conv_dgrad_wgrad"):
         key = "mfma_bf16" if conv == "bf16" else "mfma_f32"
         ridge = PEAK[key][0] * 1e12 / (PEAK["hbm"][0] * 1e9)
         if nbytes > 0 and flops / nbytes >= ridge:
