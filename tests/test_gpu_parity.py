@@ -254,6 +254,53 @@ def test_accumulate_wgrads(oracle, torch_cuda):
     check_against_oracle(oracle, out, ref, x, "f32", scale_grads=2.0)
 
 
+def test_deep_stack_activation_memory_flat_and_drift_small(oracle, torch_cuda):
+    """Section 4, Table 1: the activation storage of a reversible stack does not
+    depend on its depth; Section 3.2 'Numerical error': the reconstruction error
+    grows with depth but stays small.  A 72-block stack against a 2-block one:
+    same workspace and same peak device memory around forward + backward (the
+    library allocates nothing).  The drift bar comes from the oracle alone: its
+    float32 run of Algorithm 1 on the same inputs, against its float64
+    stored-activation gradients; the GPU has to stay within 3x of that for the
+    reconstructed input, the input gradient and the parameter-gradient angle."""
+    import torch
+    from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
+    peaks, ws = {}, {}
+    for depth in (2, 72):
+        cfg = dict(kind="basic", n=8, c=32, h=16, w=16, depth=depth, width=None, conv="f32", affine="random")
+        x, params, dy = S.draw_stack(900 + depth, **cfg)
+        r = StackRunner(**cfg)
+        r.set_params(params)
+        X, DY = r.new_pair(x), r.new_pair(dy)
+        torch.cuda.synchronize()
+        torch.cuda.reset_peak_memory_stats()
+        before = torch.cuda.memory_allocated()
+        r.forward(X, X)
+        r.backward(X, DY, X, DY)
+        torch.cuda.synchronize()
+        peaks[depth] = torch.cuda.max_memory_allocated() - before
+        ws[depth] = (r.fwd_bytes, r.bwd_bytes, r.activation_bytes()["total"])
+        if depth == 72:
+            ref = oracle_reference(oracle, cfg, x, params, dy)
+            out = dict(x_rec=r.to_host(X[0]), dx=r.to_host(DY[0]), grads=download_grads(r.grads))
+            e_rec, e_dx = oracle.rel_l2(out["x_rec"], x), oracle.rel_l2(out["dx"], ref["dx"])
+            ang = oracle.angle_deg(oracle.flatten_grads(out["grads"]), oracle.flatten_grads(ref["grads"]))
+            c = cfg["c"] // 2
+            sp32 = lambda t: (np.ascontiguousarray(t[:, :c], dtype=np.float32),
+                              np.ascontiguousarray(t[:, c:], dtype=np.float32))
+            p32 = S.cast_params(params, np.float32)
+            y1, y2 = oracle.stack_fwd(*sp32(x), p32, eps=np.float32(1e-5))[:2]
+            (x1r, x2r), (d1, d2), g32, _ = oracle.stack_reverse(y1, y2, *sp32(dy), p32, eps=np.float32(1e-5))
+            o_rec = oracle.rel_l2(np.concatenate([x1r, x2r], 1), x)
+            o_dx = oracle.rel_l2(np.concatenate([d1, d2], 1), ref["dx"])
+            o_ang = oracle.angle_deg(oracle.flatten_grads(g32), oracle.flatten_grads(ref["grads"]))
+            print("depth 72: x_rec %.2e  dx %.2e  gradient angle %.3f deg  (oracle float32 Algorithm 1: %.2e %.2e %.3f)" %
+                  (e_rec, e_dx, ang, o_rec, o_dx, o_ang), flush=True)
+            assert e_rec < 3 * o_rec and e_dx < 3 * o_dx and ang < 3 * o_ang
+    assert ws[2] == ws[72], ws
+    assert peaks[2] == 0 and peaks[72] == 0, peaks
+
+
 def test_c2_full_size_with_drift_report(oracle, torch_cuda):
     """The 9-block stack at N=128, C=32, 32x32, fp32, every output against the
     float64 oracle, plus reconstruction error per depth (Section 3.2
