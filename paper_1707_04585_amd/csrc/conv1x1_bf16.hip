@@ -71,8 +71,8 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 
 // MTW: 32-channel output tiles per wavefront.  DEPTH: steps the loads run ahead
 // (1 or 2).  GEN: planes need not be 16-byte
-// aligned and H*W need not be a multiple of 4 (the last group of an image is
-// then loaded from H*W - 4 and shifted into place).
+// aligned and H*W need not be a multiple of 4 (the last group of an image then
+// starts at H*W - 4 and leaves the pixels it shares with its neighbour to it).
 template <int MTW, int DEPTH, bool GEN>
 __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     using F4 = typename std::conditional<GEN, f4u_t, f4a_t>::type;
@@ -96,13 +96,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     const bool live = g < p.groups;
     const int gg = live ? g : 0;
     const int n = fdiv(gg, p.m_gpi), q = gg - n * p.gpi;
-    const int pix = 4 * q;
-    const int valid = GEN ? min(4, HW - pix) : 4;
-    const int shift = 4 - valid;
+    // The last group of an image may have fewer than 4 pixels left (GEN): its
+    // window is moved back so that it ends with the plane, pix = H*W - 4.  Its first
+    // `dup` pixels then repeat the previous group's (computed again, not stored),
+    // so no data has to be shifted or masked on the way to the matrix instructions.
+    const int dup = GEN ? max(0, 4 * q + 4 - HW) : 0;
+    const int pix = 4 * q - dup;
     // Addresses are a wavefront-uniform 64-bit part (channel, step) plus a 32-bit
     // per-lane byte offset (image, pixel, channel octet half): the host keeps
     // every tensor slice handed to one launch below 4 GB.
-    const uint32_t in_off = (uint32_t)(((int64_t)n * p.isn + (pix - shift) + (int64_t)(kg * 8) * p.isc) * 4);
+    const uint32_t in_off = (uint32_t)(((int64_t)n * p.isn + pix + (int64_t)(kg * 8) * p.isc) * 4);
     const char *const in_base = reinterpret_cast<const char *>(p.in);
     const int64_t isc_b = p.isc * 4;
     const char *const w_base = reinterpret_cast<const char *>(p.wq) + (int64_t)mt0 * p.ksteps * 1024;
@@ -116,7 +119,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     const uint32_t r_off = (uint32_t)(((int64_t)n * p.rsn + pix + (int64_t)(4 * kg) * p.rsc) * 4);
     char *const o_base = reinterpret_cast<char *>(p.out);
     const char *const r_base = reinterpret_cast<const char *>(p.r);
-    const bool full = !GEN || valid == 4;
     // channel of register i of output tile m, without the lane's 4*kg
     auto chan = [&](int m, int i) { return (mt0 + m) * 32 + 8 * (i >> 2) + (i & 3); };
 
@@ -131,14 +133,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         for (int i = 0; i < 16; ++i) {
             F4 t = {0.f, 0.f, 0.f, 0.f};
             if (p.ep != EP_STORE && live && !idle && kw == 0 && chan(m, i) + 4 * kg < p.CO) {
-                const float *rp = reinterpret_cast<const float *>(r_base + (int64_t)chan(m, i) * p.rsc * 4 + r_off);
-                if (full) {
-                    t = *reinterpret_cast<const F4 *>(rp);
-                } else {
-                    t[0] = rp[0];
-                    if (valid > 1) t[1] = rp[1];
-                    if (valid > 2) t[2] = rp[2];
-                }
+                t = *reinterpret_cast<const F4 *>(r_base + (int64_t)chan(m, i) * p.rsc * 4 + r_off);
                 if (p.ep == EP_SUB) t = -t;
             }
 #pragma unroll
@@ -164,13 +159,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             float x0 = b.v[k][0], x1 = b.v[k][1], x2 = b.v[k][2], x3 = b.v[k][3];
-            if (GEN) {  // the last group of an image was loaded `shift` pixels early
-                const float y0 = shift == 0 ? x0 : shift == 1 ? x1 : shift == 2 ? x2 : x3;
-                const float y1 = shift == 0 ? x1 : shift == 1 ? x2 : shift == 2 ? x3 : 0.f;
-                const float y2 = shift == 0 ? x2 : shift == 1 ? x3 : 0.f;
-                const float y3 = shift == 0 ? x3 : 0.f;
-                x0 = y0; x1 = y1; x2 = y2; x3 = y3;
-            }
             if (bn) {
                 const int c = ks * 16 + k;  // wavefront-uniform: scalar loads
                 const float s_lo = p.scale_shift[c], s_hi = p.scale_shift[c + 8];
@@ -180,11 +168,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
                 x1 = fmaxf(fmaf(x1, sc, sh), 0.f);
                 x2 = fmaxf(fmaf(x2, sc, sh), 0.f);
                 x3 = fmaxf(fmaf(x3, sc, sh), 0.f);
-                if (GEN) {  // pixels past the end of the image stay zero
-                    x1 = valid > 1 ? x1 : 0.f;
-                    x2 = valid > 2 ? x2 : 0.f;
-                    x3 = valid > 3 ? x3 : 0.f;
-                }
             }
             v[k][0] = x0; v[k][1] = x1; v[k][2] = x2; v[k][3] = x3;
         }
@@ -268,12 +251,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
             F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
             if (p.ep == EP_SUB) t = -t;
             float *op = reinterpret_cast<float *>(o_base + (int64_t)chan(m, i) * p.osc * 4 + o_off);
-            if (full) {
+            if (!GEN || dup == 0) {
                 *reinterpret_cast<F4 *>(op) = t;
-            } else {
-                op[0] = t[0];
-                if (valid > 1) op[1] = t[1];
-                if (valid > 2) op[2] = t[2];
+            } else {  // the first dup pixels belong to the previous group
+                if (dup < 2) op[1] = t[1];
+                if (dup < 3) op[2] = t[2];
+                op[3] = t[3];
             }
         }
 }

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
     const int start_row = max(0, row0 - 1), end_row = min(H, row0 + p.TR + 1);
     const int range = (end_row - start_row) * W;  // contiguous pixels of the plane this block reads
     uint32_t it_off[kInItems];                    // byte offset of (image, pixel) in a plane (dead items: 0)
-    int it_rec[kInItems], it_info[kInItems];      // LDS record of pixel 0; col | nvalid << 16 | shift << 20 | oc << 24
+    int it_rec[kInItems], it_info[kInItems];      // LDS record of pixel 0; col | nvalid << 16 | oc << 24
 #pragma unroll
     for (int i = 0; i < kInItems; ++i) {
         const int e = tid + i * kThreads;
@@ -113,12 +113,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
         const int q = t % p.q_per_img, img = t / p.q_per_img;
         const int n = n0 + img, start = 4 * q;
         const bool live = e < p.in_items && n < N && start < range;
-        const int ld = min(start, range - 4), shift = start - ld;
-        const int lin = start_row * W + start, row = lin / W, col = lin - row * W;
+        // the last quad of the range is moved back to end with it: the pixels it shares
+        // with its neighbour are written twice, with the same values
+        const int ld = min(start, range - 4);
+        const int lin = start_row * W + ld, row = lin / W, col = lin - row * W;
         it_off[i] = live ? (uint32_t)(((int64_t)n * p.isn + start_row * W + ld) * 4) : 0u;
         it_rec[i] = (img * p.lrows + (row - (row0 - 1))) * p.lcols + 1 + col;
-        const int nvalid = live ? min(4, range - start) : 0;
-        it_info[i] = col | (nvalid << 16) | (shift << 20) | (oc << 24);
+        const int nvalid = live ? 4 : 0;
+        it_info[i] = col | (nvalid << 16) | (oc << 24);
     }
 
     // ---- this lane's pixel in each of its NTW pixel groups
@@ -170,17 +172,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
 #pragma unroll
         for (int i = 0; i < kInItems; ++i) {
             const int info = it_info[i];
-            const int col = info & 0xffff, nvalid = (info >> 16) & 15, shift = (info >> 20) & 15, oc = info >> 24;
+            const int col = info & 0xffff, nvalid = (info >> 16) & 15, oc = info >> 24;
             if (nvalid == 0) continue;
             const bool chan_ok = c0 + oc * 8 < CI;
             float v[8][4];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const f4u_t x = gin[i][k];
-                float x0 = shift == 0 ? x[0] : shift == 1 ? x[1] : shift == 2 ? x[2] : x[3];
-                float x1 = shift == 0 ? x[1] : shift == 1 ? x[2] : x[3];
-                float x2 = shift == 0 ? x[2] : x[3];
-                float x3 = x[3];
+                float x0 = x[0], x1 = x[1], x2 = x[2], x3 = x[3];
                 if (bn) {
                     const int ch = chan_ok ? c0 + oc * 8 + k : 0;
                     const float sc = ss_lds[ch], sh = ss_lds[CI + ch];
@@ -196,7 +195,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (j >= nvalid) break;
                 // pixels past the end of an image row continue in the next tile row, after 2 halo records
                 const int rec = it_rec[i] + j + (col + j >= W ? 2 : 0);
                 const uint4_t q = {pack2(v[0][j], v[1][j]), pack2(v[2][j], v[3][j]), pack2(v[4][j], v[5][j]),
