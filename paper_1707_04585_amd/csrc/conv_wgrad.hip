@@ -176,7 +176,8 @@ bool conv_wgrad_plan(View x, const float *scale_shift, bool bf16, View dh, int c
     red.part = scratch; red.dw = dw;
     red.part_stride = w.part_stride; red.S = w.S; red.KS2 = ks * ks; red.MT = w.MT; red.CT = w.CT;
     red.tiles_c = w.tiles_c; red.CO = cout; red.CI = cin; red.accumulate = accumulate ? 1 : 0;
-    red.tile = 16; red.blocks = (w.part_stride + 31) / 32;
+    red.tile = 16; red.wide = w.S <= 16 ? 1 : 0;
+    red.blocks = red.wide ? (w.part_stride + 255) / 256 : (w.part_stride + 31) / 32;
     return true;
 }
 

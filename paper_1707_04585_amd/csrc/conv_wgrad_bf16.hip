@@ -377,7 +377,8 @@ bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin
     red.part = scratch; red.dw = dw;
     red.part_stride = w.part_stride; red.S = w.S; red.KS2 = ks * ks; red.MT = w.MT; red.CT = w.CT;
     red.tiles_c = w.tiles_c; red.CO = cout; red.CI = cin; red.accumulate = accumulate ? 1 : 0;
-    red.tile = 32; red.blocks = (w.part_stride + 31) / 32;
+    red.tile = 32; red.wide = w.S <= 16 ? 1 : 0;
+    red.blocks = red.wide ? (w.part_stride + 255) / 256 : (w.part_stride + 31) / 32;
     if (defer) *defer = red;
     else wgrad_reduce(cx, red);
     return true;

@@ -98,6 +98,7 @@ struct WgradReduce {
     float *dw;          // [CO][CI][KS2]
     int part_stride, S, KS2, MT, CT, tiles_c, CO, CI, accumulate;
     int tile;    // 16 (fp32 instruction) or 32 (bf16 instruction): edge of a result tile
+    int wide;    // 1: one thread per slot sums all S slices (S small); 0: 8 threads share a slot
     int blocks;  // workgroups of 256 threads it needs
 };
 
