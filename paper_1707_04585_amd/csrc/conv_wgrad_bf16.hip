@@ -291,6 +291,9 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     WgPlan w{};
     w.ok = false;
     if (g.w < 4) return w;  // staging loads 4 pixels of a row at a time
+    // A 16 x 16 filter fills a quarter of a 32 x 32 result tile; the fp32-instruction
+    // kernel (16 x 16 tiles, operands rounded to bf16 on the way in) is faster there.
+    if (cin <= 16 && cout <= 16) return w;
     w.MT = cout <= 32 ? 1 : 2;
     w.CT = cin <= 32 ? 1 : 2;
     w.Wq = (g.w + 3) / 4;
