@@ -39,10 +39,17 @@ __device__ __forceinline__ void prep_filter_body(const PrepArgs &p, int block) {
         const bool in = jb.kind == 0 ? col < CI : col < CO;
         const float *src = jb.kind == 0 ? jb.w + ((int64_t)row * CI + col) * KS2   // row = ko, col = c
                                         : jb.w + ((int64_t)col * CI + row) * KS2;  // row = c, col = ko
-        for (int t = 0; t < KS2; ++t) {
-            const float v = in ? src[t] : 0.f;
+        // All taps are requested before the first is stored (q is not known to
+        // be distinct from w, so a store would otherwise wait for each load).
+        const float *safe = in ? src : jb.w;
+        float v[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) v[t] = safe[t < KS2 ? t : 0];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            if (t >= KS2) break;
             const int tq = jb.kind == 0 ? t : KS2 - 1 - t;
-            jb.q[((int64_t)row * KS2 + tq) * jb.KP + col] = to_bf16(v);
+            jb.q[((int64_t)row * KS2 + tq) * jb.KP + col] = to_bf16(in ? v[t] : 0.f);
         }
     } else {
         const int e = (int)(i & 7), ln = (int)((i >> 3) & 63);
