@@ -30,6 +30,18 @@ What it computes, and where the paper defines it:
                        "Numerical error", Section 5.2 "Impact of numerical
                        error").
 
+* ``down_fwd`` / ``down_bwd`` -- the non-reversible subsampling block between
+                       two stages (Section 3.1: a reversible block has stride
+                       1, so the network also needs ordinary layers whose
+                       inputs are stored; Section 3.2 end).  The paper does not
+                       give its form; the reading taken here is stated at the
+                       functions.
+* ``body_fwd`` / ``body_bwd_stored`` / ``body_reverse`` -- stages of reversible
+                       blocks joined by such blocks: ordinary backprop with
+                       everything stored, and the memory-saving way (Algorithm
+                       1 inside the stages, stored inputs at the subsampling
+                       blocks only).
+
 The layer operations (direct-loop convolution and its two adjoints, two-pass
 batch norm and its unfused chain-rule backward) are plain C in
 ``layer_ops_impl.h``; the precision is that of the arrays passed in
@@ -351,6 +363,118 @@ def stack_reverse(y1, y2, dy1, dy2, params, eps=1e-5):
         (y1, y2), (dy1, dy2), grads[k] = block_reverse(y1, y2, dy1, dy2, params[k], eps)
         recon[k] = (y1, y2)
     return (y1, y2), (dy1, dy2), grads, recon
+
+
+# ---------------------------------------------------------------------------
+# non-reversible subsampling block and multi-stage body (Section 3.1: "the
+# network must also contain non-reversible layers such as subsampling layers";
+# Section 3.2: their inputs are stored explicitly).
+#
+# Reading (the paper leaves the form open): an ordinary pre-activation residual
+# block on the concatenated tensor [N, C_in, H, W] -> [N, C_out, H/2, W/2],
+#     a0 = ReLU(BN_0(x));  y = Conv_1x1,stride2(a0; Ws) + R(x),
+# where R is the Basic / Bottleneck function of Section 2.2 with stride 2 on
+# its (first) 3x3 convolution and C_out outputs; the projection shortcut reads
+# the same pre-activation a0 as R's first convolution.  P = dict(R=layers with
+# a "stride" key, S=dict(w=[C_out, C_in, 1, 1])).
+# ---------------------------------------------------------------------------
+
+def down_fwd(x, P, eps=1e-5):
+    """Returns y and the stored state of every layer of R."""
+    R = P["R"]
+    stored = []
+    h = x
+    short = None
+    for l, L in enumerate(R):
+        a, st = bn_relu_fwd(h, L["gamma"], L["beta"], eps)
+        st["in_hw"] = h.shape[2:]
+        if l == 0:
+            short = conv_fwd(a, P["S"]["w"], 2)
+        h = conv_fwd(a, L["w"], L.get("stride", 1))
+        stored.append(st)
+    return short + h, stored
+
+
+def down_bwd(stored, P, dy, eps=1e-5):
+    """Ordinary backprop through the subsampling block from stored activations.
+    Returns (dx, dict(R=[per-layer grads], S=dict(w=)))."""
+    R = P["R"]
+    grads = [None] * len(R)
+    d = dy
+    for l in range(len(R) - 1, -1, -1):
+        L, st = R[l], stored[l]
+        ks = L["w"].shape[2]
+        s = L.get("stride", 1)
+        dw = conv_wgrad(st["a"], d, ks, s)
+        da = conv_dgrad(d, L["w"], st["in_hw"], s)
+        if l == 0:  # a0 has a second child: the shortcut convolution
+            dws = conv_wgrad(st["a"], dy, 1, 2)
+            da = da + conv_dgrad(dy, P["S"]["w"], st["in_hw"], 2)
+        d, dg, db = bn_relu_bwd(da, st, L["gamma"], eps)
+        grads[l] = dict(w=dw, gamma=dg, beta=db)
+    return d, dict(R=grads, S=dict(w=dws))
+
+
+def _halves(t):
+    c = t.shape[1] // 2
+    return np.ascontiguousarray(t[:, :c]), np.ascontiguousarray(t[:, c:])
+
+
+def body_fwd(x, stages, downs, eps=1e-5, keep=False):
+    """stages[s] = list of block parameters; downs[s] joins stage s and s+1.
+    Channels [0, C/2) of a stage's tensor are x1, the rest x2 (Section 3.1).
+    Returns the top activation of every stage (the last is the output); with
+    keep=True also everything ordinary backprop needs."""
+    tops, kept = [], []
+    for s, params in enumerate(stages):
+        x1, x2 = _halves(x)
+        if keep:
+            y1, y2, _, st = stack_fwd(x1, x2, params, eps, keep=True)
+        else:
+            y1, y2 = stack_fwd(x1, x2, params, eps)
+            st = None
+        y = np.concatenate([y1, y2], axis=1)
+        tops.append(y)
+        st_down = None
+        if s + 1 < len(stages):
+            x, st_down = down_fwd(y, downs[s], eps)
+        kept.append((st, st_down))
+    return (tops, kept) if keep else tops
+
+
+def body_bwd_stored(kept, stages, downs, dy, eps=1e-5):
+    """Ordinary backprop with every activation stored.  Returns (dx,
+    stage_grads[s][block], down_grads[s])."""
+    sg, dg = [None] * len(stages), [None] * (len(stages) - 1)
+    d = dy
+    for s in range(len(stages) - 1, -1, -1):
+        st, st_down = kept[s]
+        if st_down is not None:
+            d, dg[s] = down_bwd(st_down, downs[s], d, eps)
+        d1, d2 = _halves(d)
+        d1, d2, sg[s] = stack_bwd_stored(st, stages[s], d1, d2, eps)
+        d = np.concatenate([d1, d2], axis=1)
+    return d, sg, dg
+
+
+def body_reverse(tops, stages, downs, dy, eps=1e-5):
+    """The memory-saving backward pass: from the stored top activation of every
+    stage only.  A subsampling block recomputes its internals from its stored
+    input; a stage runs Algorithm 1.  Also returns each stage's reconstructed
+    input."""
+    sg, dg = [None] * len(stages), [None] * (len(stages) - 1)
+    recon = [None] * len(stages)
+    d = dy
+    for s in range(len(stages) - 1, -1, -1):
+        if s + 1 < len(stages):
+            _, st_down = down_fwd(tops[s], downs[s], eps)
+            d, dg[s] = down_bwd(st_down, downs[s], d, eps)
+        y1, y2 = _halves(tops[s])
+        d1, d2 = _halves(d)
+        (x1, x2), (d1, d2), sg[s], _ = stack_reverse(y1, y2, d1, d2, stages[s], eps)
+        recon[s] = np.concatenate([x1, x2], axis=1)
+        d = np.concatenate([d1, d2], axis=1)
+    return d, sg, dg, recon
 
 
 # ---------------------------------------------------------------------------

@@ -79,6 +79,61 @@ def draw_stack(seed, kind, n, c, h, w, depth, width=None, affine="random", **_un
     return x, params, dy
 
 
+def down_layers(kind: str, c_in: int, c_out: int):
+    """Layers (c_in, c_out, k, stride) of the residual branch of a subsampling
+    block; the bottleneck's inner width is c_out / 4."""
+    if kind == "basic":
+        return [(c_in, c_out, 3, 2), (c_out, c_out, 3, 1)]
+    if kind == "bottleneck":
+        w = c_out // 4
+        return [(c_in, w, 1, 1), (w, w, 3, 2), (w, c_out, 1, 1)]
+    raise ValueError(kind)
+
+
+def draw_down(rng, kind, c_in, c_out, affine):
+    layers = []
+    for (ci, co, k, s) in down_layers(kind, c_in, c_out):
+        w = rng.standard_normal((co, ci, k, k)) * np.sqrt(2.0 / (ci * k * k))
+        if affine == "unit":
+            gamma, beta = np.ones(ci), np.zeros(ci)
+        else:
+            gamma, beta = rng.uniform(0.5, 1.5, ci), rng.standard_normal(ci) * 0.1
+        layers.append(dict(w=w, gamma=gamma, beta=beta, stride=s))
+    ws = rng.standard_normal((c_out, c_in, 1, 1)) * np.sqrt(2.0 / c_in)
+    return dict(R=layers, S=dict(w=ws))
+
+
+# Multi-stage bodies: reversible stages joined by subsampling blocks.  The body
+# starts at the stem's output (the stem and pooling layers are not part of it).
+BODIES = {
+    # name: kind, N, H, W of the first stage, per-stage channels C / depth / bottleneck width, conv dtype
+    "c3_body": dict(kind="basic", n=128, h=32, w=32, channels=(32, 64, 112), depths=(9, 9, 9), widths=(None, None, None), conv="bf16"),
+    "c5_body": dict(kind="bottleneck", n=32, h=56, w=56, channels=(256, 512, 1024, 2048), depths=(3, 4, 6, 3), widths=(64, 128, 256, 512), conv="bf16"),
+}
+
+
+def draw_body(seed, kind, n, h, w, channels, depths, widths, affine="random", **_unused):
+    """Return (x, stages, downs, dy): x [N, channels[0], H, W]; stages[s] = list of
+    block parameters; downs[s] joins stage s and s+1; dy has the shape of the
+    last stage's output.  Draw order: x, then per stage its blocks followed by
+    the subsampling block above it, then dy."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((n, channels[0], h, w))
+    stages, downs = [], []
+    for s, (c, depth, width) in enumerate(zip(channels, depths, widths)):
+        blocks = []
+        for _ in range(depth):
+            F = draw_func(rng, kind, c // 2, width, affine)
+            G = draw_func(rng, kind, c // 2, width, affine)
+            blocks.append(dict(F=F, G=G))
+        stages.append(blocks)
+        if s + 1 < len(channels):
+            downs.append(draw_down(rng, kind, c, channels[s + 1], affine))
+    last = len(channels) - 1
+    dy = rng.standard_normal((n, channels[last], h >> last, w >> last))
+    return x, stages, downs, dy
+
+
 def draw_named(name, seed_offset=0, **override):
     cfg = dict(STACKS[name])
     cfg.update(override)

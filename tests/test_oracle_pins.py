@@ -460,3 +460,147 @@ def test_bf16_operands_make_gradients_sensitive_to_summation_order(oracle):
     y1, y2, _, stored = oracle.stack_fwd(*f32(x), p32, eps=np.float32(1e-5), keep=True)
     dx1, dx2, _ = oracle.stack_bwd_stored(stored, p32, *f32(dy), eps=np.float32(1e-5))
     assert oracle.rel_l2(np.concatenate([dx1, dx2], 1), ref_dx("exact")["dx"]) < 1e-3
+
+
+# --------------------------------------------------------------------------
+# non-reversible subsampling block and multi-stage body (Section 3.1 / 3.2:
+# ordinary layers between the reversible stages, inputs stored)
+# --------------------------------------------------------------------------
+
+def small_body(seed, kind, n=2, h=8, w=4):
+    if kind == "basic":
+        return S.draw_body(seed, kind, n, h, w, (4, 6, 8), (2, 1, 1), (None, None, None))
+    return S.draw_body(seed, kind, n, h, w, (4, 8, 8), (1, 2, 1), (3, 2, 3))
+
+
+def torch_body(torch, x, stages, downs, dy):
+    """The body built from a library's conv2d / batch_norm / relu (float64) and
+    differentiated by its autograd."""
+    F = torch.nn.functional
+    leaf = lambda v: torch.tensor(v, requires_grad=True)
+    tx = leaf(x)
+    tst = [[{fn: [{k: leaf(v) for k, v in L.items()} for L in P[fn]] for fn in ("F", "G")} for P in st] for st in stages]
+    tdn = [dict(R=[{k: (leaf(v) if k != "stride" else v) for k, v in L.items()} for L in D["R"]], S=dict(w=leaf(D["S"]["w"])))
+           for D in downs]
+
+    def act(h, L):
+        return torch.relu(F.batch_norm(h, None, None, L["gamma"], L["beta"], training=True, eps=1e-5))
+
+    def tfunc(h, layers):
+        for L in layers:
+            h = F.conv2d(act(h, L), L["w"], padding=(L["w"].shape[2] - 1) // 2)
+        return h
+
+    h = tx
+    tops = []
+    for s, st in enumerate(tst):
+        c = h.shape[1] // 2
+        a1, a2 = h[:, :c], h[:, c:]
+        for P in st:
+            b1 = a1 + tfunc(a2, P["F"])
+            b2 = a2 + tfunc(b1, P["G"])
+            a1, a2 = b1, b2
+        h = torch.cat([a1, a2], dim=1)
+        tops.append(h)
+        if s < len(tdn):
+            D = tdn[s]
+            a0 = act(h, D["R"][0])
+            r = a0
+            for l, L in enumerate(D["R"]):
+                if l:
+                    r = act(r, L)
+                r = F.conv2d(r, L["w"], stride=L["stride"], padding=(L["w"].shape[2] - 1) // 2)
+            h = F.conv2d(a0, D["S"]["w"], stride=2) + r
+    (h * torch.tensor(dy)).sum().backward()
+    return tx, tst, tdn, tops
+
+
+@pytest.mark.parametrize("kind", ["basic", "bottleneck"])
+def test_body_matches_autograd_library(oracle, kind):
+    """Stages of reversible blocks joined by subsampling blocks: outputs and
+    every gradient (inputs, stage parameters, subsampling-block parameters
+    including the projection shortcut) equal the library's, and the
+    memory-saving backward pass (Algorithm 1 in the stages, stored inputs at the
+    subsampling blocks) equals ordinary backprop (Section 3.2)."""
+    torch = pytest.importorskip("torch")
+    x, stages, downs, dy = small_body(31, kind)
+    tx, tst, tdn, ttops = torch_body(torch, x, stages, downs, dy)
+    tops, kept = oracle.body_fwd(x, stages, downs, keep=True)
+    for t, tt in zip(tops, ttops):
+        assert t.shape == tuple(tt.shape)
+        assert oracle.rel_l2(t, tt.detach().numpy()) < 1e-12
+    for which in ("stored", "reverse"):
+        if which == "stored":
+            dx, sg, dg = oracle.body_bwd_stored(kept, stages, downs, dy)
+        else:
+            dx, sg, dg, recon = oracle.body_reverse(tops, stages, downs, dy)
+            assert oracle.rel_l2(recon[0], x) < 1e-12
+        assert oracle.rel_l2(dx, tx.grad.numpy()) < 1e-9
+        for s in range(len(stages)):
+            for d in range(len(stages[s])):
+                for fn in ("F", "G"):
+                    for l in range(len(stages[s][d][fn])):
+                        for key in ("w", "gamma", "beta"):
+                            assert oracle.rel_l2(sg[s][d][fn][l][key], tst[s][d][fn][l][key].grad.numpy()) < 1e-8, (which, s, d, fn, l, key)
+        for s in range(len(downs)):
+            assert oracle.rel_l2(dg[s]["S"]["w"], tdn[s]["S"]["w"].grad.numpy()) < 1e-9
+            for l in range(len(downs[s]["R"])):
+                for key in ("w", "gamma", "beta"):
+                    assert oracle.rel_l2(dg[s]["R"][l][key], tdn[s]["R"][l][key].grad.numpy()) < 1e-8, (which, s, l, key)
+
+
+@pytest.mark.parametrize("kind", ["basic", "bottleneck"])
+def test_down_block_gradients_by_central_differences(oracle, kind):
+    """The subsampling block's derivatives are total derivatives of
+    C = <ybar, y> (Section 2.1): all inputs and samples of every parameter
+    tensor, central differences in float64."""
+    rng = np.random.default_rng(5)
+    c_in, c_out = (4, 6) if kind == "basic" else (4, 8)
+    x = rng.standard_normal((2, c_in, 4, 6))
+    P = S.draw_down(rng, kind, c_in, c_out, "random")
+    dy = rng.standard_normal((2, c_out, 2, 3))
+    y, stored = oracle.down_fwd(x, P)
+    assert y.shape == dy.shape
+    dx, grads = oracle.down_bwd(stored, P, dy)
+    step = 1e-6
+
+    def cost():
+        return float((oracle.down_fwd(x, P)[0] * dy).sum())
+
+    def fd(arr, idx):
+        old = arr[idx]
+        arr[idx] = old + step
+        fp = cost()
+        arr[idx] = old - step
+        fm = cost()
+        arr[idx] = old
+        return (fp - fm) / (2 * step)
+
+    num = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        num[idx] = fd(x, idx)
+    assert oracle.rel_l2(dx, num) < 1e-6
+    checks = [(P["S"]["w"], grads["S"]["w"])]
+    for l, L in enumerate(P["R"]):
+        checks += [(L[k], grads["R"][l][k]) for k in ("w", "gamma", "beta")]
+    for arr, g in checks:
+        for _ in range(5):
+            idx = tuple(rng.integers(0, s) for s in arr.shape)
+            n_ = fd(arr, idx)
+            assert abs(n_ - g[idx]) < 1e-5 * max(1.0, abs(n_)), (idx, n_, g[idx])
+
+
+def test_strided_convolution_is_a_subsampled_stride1_convolution(oracle):
+    """With even H, W and padding (k-1)/2, the stride-2 convolution takes every
+    second row and column of the stride-1 result, and its two adjoints are the
+    stride-1 adjoints of the gradient spread out with zeros between."""
+    rng = np.random.default_rng(6)
+    for ks in (1, 3):
+        a = rng.standard_normal((2, 3, 6, 4))
+        w = rng.standard_normal((5, 3, ks, ks))
+        assert np.allclose(oracle.conv_fwd(a, w, 2), oracle.conv_fwd(a, w, 1)[:, :, ::2, ::2], rtol=0, atol=1e-13)
+        d = rng.standard_normal((2, 5, 3, 2))
+        up = np.zeros((2, 5, 6, 4))
+        up[:, :, ::2, ::2] = d
+        assert np.allclose(oracle.conv_dgrad(d, w, (6, 4), 2), oracle.conv_dgrad(up, w, (6, 4), 1), rtol=0, atol=1e-13)
+        assert np.allclose(oracle.conv_wgrad(a, d, ks, 2), oracle.conv_wgrad(a, up, ks, 1), rtol=0, atol=1e-13)
