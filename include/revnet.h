@@ -208,6 +208,116 @@ int revnet_stack_bwd(const rvn_block_desc *desc, int32_t depth,
                      const rvn_block_grads *grads, int accumulate_wgrads,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Non-reversible subsampling block and multi-stage body.
+ *
+ * A reversible block has stride 1 (Section 3.1), so a network also holds
+ * ordinary layers that change the resolution; their inputs are stored
+ * (Section 3.2, last paragraph on storage).  The paper does not give their
+ * form.  The one built here is a pre-activation residual block on the whole
+ * tensor x [n, c_in, h, w] -> y [n, c_out, h/2, w/2] (h and w even):
+ *     a0 = ReLU(BN_0(x))
+ *     y  = Conv_1x1,stride 2(a0; shortcut_w) + R(x)
+ * with R the Basic function c3(c3(x)) or the Bottleneck function c1(c3(c1(x)))
+ * of Section 2.2, stride 2 on its (first) 3x3 convolution:
+ *     basic:      (c_in -> c_out, 3x3, stride 2), (c_out -> c_out, 3x3)
+ *     bottleneck: (c_in -> width, 1x1), (width -> width, 3x3, stride 2), (width -> c_out, 1x1)
+ * BN_0 is the BN of R's first unit: the shortcut reads the same pre-activation.
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    rvn_kind kind;
+    int32_t c_in, c_out;  /* channels of the whole input / output tensor */
+    int32_t width;        /* bottleneck inner width; ignored for RVN_BASIC */
+    float bn_eps;
+    rvn_dtype conv_dtype;
+} rvn_down_desc;
+
+typedef struct {
+    rvn_func_params R;       /* layers as listed above */
+    const float *shortcut_w; /* [c_out][c_in], device */
+} rvn_down_params;
+
+typedef struct {
+    rvn_func_grads R;
+    float *d_shortcut_w; /* [c_out][c_in], device */
+} rvn_down_grads;
+
+/* Workspace bytes for an input of n x c_in x h x w.  Either pointer may be NULL. */
+int revnet_down_workspace_bytes(const rvn_down_desc *desc, int64_t n, int64_t h, int64_t w,
+                                size_t *fwd_bytes, size_t *bwd_bytes);
+
+/*
+ * y = shortcut + R(x) as defined above.  x [n, c_in, h, w] is read and must be
+ * kept by the caller for revnet_down_bwd; y [n, c_out, h/2, w/2] is written.
+ * Tensors as in revnet_block_fwd (sw = 1, sh = w, sc >= h*w); x, y and the
+ * workspace must not overlap.  Errors as for the block entry points.
+ */
+int revnet_down_fwd(const rvn_down_desc *desc, const rvn_tensor *x, const rvn_down_params *params,
+                    const rvn_tensor *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Ordinary backprop (Section 2.1) through the subsampling block from its
+ * stored input: the internals are recomputed from x, then dx = (dy/dx)^T dy
+ * and the parameter gradients are formed.  x, dy: read.  dx [n, c_in, h, w]:
+ * written; it must not overlap x, dy or the workspace.  grads: every pointer
+ * of the layers in use and d_shortcut_w non-NULL; overwritten, or added to
+ * when accumulate_wgrads != 0.
+ */
+int revnet_down_bwd(const rvn_down_desc *desc, const rvn_tensor *x, const rvn_tensor *dy,
+                    const rvn_down_params *params, const rvn_tensor *dx, const rvn_down_grads *grads,
+                    int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Body: `stages` stacks of reversible blocks, stage s at half the resolution
+ * of stage s-1, joined by subsampling blocks (down[s] maps the output of stage
+ * s to the input of stage s+1).  Only the top activation of every stage is
+ * kept -- it is the stored input of the subsampling block above it -- so the
+ * activation memory does not depend on the stages' depths (Section 3.2).
+ * The body starts at the output of the network's first layers (stem, pooling),
+ * which are not part of it.
+ */
+#define RVN_MAX_STAGES 8
+typedef struct {
+    int32_t stages;
+    rvn_block_desc stage[RVN_MAX_STAGES]; /* c_half = half the stage's channels */
+    int32_t depth[RVN_MAX_STAGES];        /* reversible blocks per stage, >= 1 */
+    rvn_down_desc down[RVN_MAX_STAGES];   /* [stages - 1]; down[s].c_in = 2*stage[s].c_half,
+                                             down[s].c_out = 2*stage[s+1].c_half */
+} rvn_body_desc;
+
+/* Workspace bytes for a body whose first stage sees n x (2*stage[0].c_half) x h x w. */
+int revnet_body_workspace_bytes(const rvn_body_desc *desc, int64_t n, int64_t h, int64_t w,
+                                size_t *fwd_bytes, size_t *bwd_bytes);
+
+/*
+ * Body forward.  x [n, C_0, h, w]: read.  tops: host array [stages] of
+ * tensors, tops[s] = [n, C_s, h >> s, w >> s], dense (sc = h_s*w_s,
+ * sn = C_s*sc); all are written: tops[s] is the output of stage s and
+ * tops[stages-1] the body's output.  Channels [0, C_s/2) of a stage's tensor
+ * are x1, the others x2 (Section 3.1: the channels are partitioned).
+ * stage_params: host array [stages] of host arrays [depth[s]]; down_params:
+ * host array [stages-1].  x may be tops[0] itself (then stage 0 runs in
+ * place); no other overlap.
+ */
+int revnet_body_fwd(const rvn_body_desc *desc, const rvn_tensor *x,
+                    const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                    const rvn_tensor *tops, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Body backward from the stored tops alone.  tops: as left by revnet_body_fwd;
+ * every stage is reconstructed in place by Algorithm 1, so on return tops[s]
+ * holds the reconstructed input of stage s (tops[0]: the body's input).
+ * dtops: host array [stages] of tensors shaped like tops; dtops[stages-1]
+ * holds the derivative with respect to the body's output on entry; all are
+ * overwritten, and on return dtops[s] is the derivative with respect to the
+ * input of stage s (dtops[0]: with respect to the body's input).
+ * stage_grads / down_grads: shaped like the parameters.
+ */
+int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn_tensor *dtops,
+                    const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                    const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
+                    int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
+
 /*
  * What revnet_stack_fwd (fwd) and revnet_stack_bwd (bwd) would enqueue for
  * this descriptor, depth and half-tensor shape, without touching the device.

@@ -7,4 +7,6 @@ from .binding import (  # noqa: F401
     BASIC, BOTTLENECK, BF16, F32, BlockDesc, RevnetError, lib_path, load_library, pack_grads,
     pack_params, revnet_block_bwd_reconstruct, revnet_block_fwd, revnet_last_error, revnet_profile_begin, revnet_profile_end,
     revnet_stack_bwd, revnet_stack_cost, revnet_stack_fwd, revnet_version, revnet_workspace_bytes,
+    BodyDesc, DownDesc, pack_down, pack_stages, revnet_body_bwd, revnet_body_fwd, revnet_body_workspace_bytes,
+    revnet_down_bwd, revnet_down_fwd, revnet_down_workspace_bytes,
 )

@@ -22,7 +22,11 @@ EXPORTS = [
     "revnet_workspace_bytes", "revnet_block_fwd", "revnet_block_bwd_reconstruct", "revnet_stack_fwd",
     "revnet_stack_bwd", "revnet_stack_cost", "revnet_last_error", "revnet_version",
     "revnet_profile_begin", "revnet_profile_end",
+    "revnet_down_workspace_bytes", "revnet_down_fwd", "revnet_down_bwd",
+    "revnet_body_workspace_bytes", "revnet_body_fwd", "revnet_body_bwd",
 ]
+
+MAX_STAGES = 8
 
 
 class RevnetError(RuntimeError):
@@ -46,6 +50,20 @@ class rvn_func_ptrs(C.Structure):  # layout shared by rvn_func_params and rvn_fu
 
 class rvn_block_ptrs(C.Structure):  # rvn_block_params / rvn_block_grads
     _fields_ = [("F", rvn_func_ptrs), ("G", rvn_func_ptrs)]
+
+
+class rvn_down_desc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("c_in", C.c_int32), ("c_out", C.c_int32), ("width", C.c_int32),
+                ("bn_eps", C.c_float), ("conv_dtype", C.c_int)]
+
+
+class rvn_down_ptrs(C.Structure):  # rvn_down_params / rvn_down_grads
+    _fields_ = [("R", rvn_func_ptrs), ("shortcut_w", C.c_void_p)]
+
+
+class rvn_body_desc(C.Structure):
+    _fields_ = [("stages", C.c_int32), ("stage", rvn_block_desc * MAX_STAGES), ("depth", C.c_int32 * MAX_STAGES),
+                ("down", rvn_down_desc * MAX_STAGES)]
 
 
 class rvn_cost(C.Structure):
@@ -94,8 +112,39 @@ class BlockDesc:
         return 2 if self.kind == BASIC else 3
 
 
+class DownDesc:
+    """Subsampling block c_in -> c_out channels; the bottleneck's inner width defaults to c_out / 4."""
+
+    def __init__(self, kind, c_in, c_out, width=0, bn_eps=1e-5, conv_dtype=F32):
+        self.kind = {"basic": BASIC, "bottleneck": BOTTLENECK}.get(kind, kind)
+        self.conv_dtype = {"f32": F32, "bf16": BF16}.get(conv_dtype, conv_dtype)
+        self.c_in, self.c_out, self.bn_eps = int(c_in), int(c_out), float(bn_eps)
+        self.width = int(width or (c_out // 4 if self.kind == BOTTLENECK else 0))
+
+    def c(self):
+        return rvn_down_desc(self.kind, self.c_in, self.c_out, self.width, self.bn_eps, self.conv_dtype)
+
+
+class BodyDesc:
+    """Reversible stages (BlockDesc, depth) joined by subsampling blocks."""
+
+    def __init__(self, stages, depths, downs):
+        assert len(stages) == len(depths) == len(downs) + 1 <= MAX_STAGES
+        self.stages, self.depths, self.downs = list(stages), [int(d) for d in depths], list(downs)
+
+    def c(self):
+        out = rvn_body_desc()
+        out.stages = len(self.stages)
+        for s, st in enumerate(self.stages):
+            out.stage[s] = st.c()
+            out.depth[s] = self.depths[s]
+        for s, dn in enumerate(self.downs):
+            out.down[s] = dn.c()
+        return out
+
+
 def _desc(d):
-    return d.c() if isinstance(d, BlockDesc) else d
+    return d.c() if isinstance(d, (BlockDesc, DownDesc, BodyDesc)) else d
 
 
 def _tensor(t):
@@ -138,6 +187,40 @@ def pack_params(blocks):
 
 
 pack_grads = pack_params
+
+
+def _pack_down(P) -> rvn_down_ptrs:
+    out = rvn_down_ptrs()
+    for l, layer in enumerate(P["R"]):
+        out.R.conv_w[l] = _ptr(layer["w"])
+        out.R.bn_gamma[l] = _ptr(layer["gamma"])
+        out.R.bn_beta[l] = _ptr(layer["beta"])
+    out.shortcut_w = _ptr(P["S"]["w"])
+    return out
+
+
+def pack_down(downs):
+    """[{R: [layer, ...], S: {w: t}}, ...] -> C array of rvn_down_params / rvn_down_grads."""
+    if isinstance(downs, C.Array):
+        return downs
+    arr = (rvn_down_ptrs * max(len(downs), 1))()
+    for k, P in enumerate(downs):
+        arr[k] = _pack_down(P)
+    return arr
+
+
+def pack_stages(stages):
+    """[[block, ...], ...] -> (C array of pointers to per-stage arrays, the arrays kept alive)."""
+    arrays = [pack_params(st) for st in stages]
+    ptrs = (C.c_void_p * len(arrays))(*[C.cast(a, C.c_void_p).value for a in arrays])
+    return ptrs, arrays
+
+
+def _tensor_array(ts):
+    arr = (rvn_tensor * len(ts))()
+    for i, t in enumerate(ts):
+        arr[i] = _tensor(t)
+    return arr
 
 
 def _stream(stream):
@@ -227,6 +310,65 @@ def revnet_stack_cost(desc, depth, n, h, w):
     _check(load_library().revnet_stack_cost(C.byref(d), C.c_int32(depth), C.c_int64(n), C.c_int64(h),
                                             C.c_int64(w), C.byref(fwd), C.byref(bwd)))
     return fwd.as_dict(), bwd.as_dict()
+
+
+def revnet_down_workspace_bytes(desc, n, h, w):
+    fwd, bwd = C.c_size_t(0), C.c_size_t(0)
+    d = _desc(desc)
+    _check(load_library().revnet_down_workspace_bytes(C.byref(d), C.c_int64(n), C.c_int64(h), C.c_int64(w),
+                                                      C.byref(fwd), C.byref(bwd)))
+    return int(fwd.value), int(bwd.value)
+
+
+def revnet_down_fwd(desc, x, params, y, ws, stream=None):
+    d = _desc(desc)
+    p = pack_down([params])
+    wp, wb = _ws(ws)
+    tx, ty = _tensor(x), _tensor(y)
+    _check(load_library().revnet_down_fwd(C.byref(d), C.byref(tx), p, C.byref(ty), C.c_void_p(wp), C.c_size_t(wb),
+                                          C.c_void_p(_stream(stream))))
+
+
+def revnet_down_bwd(desc, x, dy, params, dx, grads, accumulate_wgrads, ws, stream=None):
+    d = _desc(desc)
+    p, g = pack_down([params]), pack_down([grads])
+    wp, wb = _ws(ws)
+    tx, tdy, tdx = _tensor(x), _tensor(dy), _tensor(dx)
+    _check(load_library().revnet_down_bwd(C.byref(d), C.byref(tx), C.byref(tdy), p, C.byref(tdx), g,
+                                          C.c_int(int(accumulate_wgrads)), C.c_void_p(wp), C.c_size_t(wb),
+                                          C.c_void_p(_stream(stream))))
+
+
+def revnet_body_workspace_bytes(desc, n, h, w):
+    fwd, bwd = C.c_size_t(0), C.c_size_t(0)
+    d = _desc(desc)
+    _check(load_library().revnet_body_workspace_bytes(C.byref(d), C.c_int64(n), C.c_int64(h), C.c_int64(w),
+                                                      C.byref(fwd), C.byref(bwd)))
+    return int(fwd.value), int(bwd.value)
+
+
+def revnet_body_fwd(desc, x, stage_params, down_params, tops, ws, stream=None):
+    d = _desc(desc)
+    sp, keep = pack_stages(stage_params)
+    dp = pack_down(down_params)
+    wp, wb = _ws(ws)
+    tx, tt = _tensor(x), _tensor_array(tops)
+    _check(load_library().revnet_body_fwd(C.byref(d), C.byref(tx), sp, dp, tt, C.c_void_p(wp), C.c_size_t(wb),
+                                          C.c_void_p(_stream(stream))))
+    del keep
+
+
+def revnet_body_bwd(desc, tops, dtops, stage_params, down_params, stage_grads, down_grads, accumulate_wgrads, ws,
+                    stream=None):
+    d = _desc(desc)
+    sp, keep_p = pack_stages(stage_params)
+    sg, keep_g = pack_stages(stage_grads)
+    dp, dg = pack_down(down_params), pack_down(down_grads)
+    wp, wb = _ws(ws)
+    tt, td = _tensor_array(tops), _tensor_array(dtops)
+    _check(load_library().revnet_body_bwd(C.byref(d), tt, td, sp, dp, sg, dg, C.c_int(int(accumulate_wgrads)),
+                                          C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
+    del keep_p, keep_g
 
 
 def revnet_profile_begin():

@@ -44,6 +44,7 @@ enum KernelId {
     K_BN_BWD_APPLY,
     K_PREP_FILTER,
     K_CONV_DGRAD_WGRAD,
+    K_RESAMPLE,
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -234,5 +235,14 @@ bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, co
 // plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.
 bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
                      float *scratch, float *dw, bool accumulate, double bytes, double flops, WgradReduce *defer);
+
+// ---- stride-2 resampling for the non-reversible subsampling block ----------
+// `full` is the geometry of the high-resolution side (h, w even).
+// out (dense [n][c][h/2][w/2]) = every second row and column of `in`.
+void subsample2(Ctx &cx, View in, int c, Geo full, float *out);
+// out (dense [n][c][h][w]) = `in` (dense, half resolution) at the even positions, zero elsewhere.
+void upsample2_zero(Ctx &cx, const float *in, int c, Geo full, float *out);
+// acc (dense [n][c][h][w]) += t (dense, half resolution) at the even positions.
+void upsample2_add(Ctx &cx, const float *t, int c, Geo full, float *acc);
 
 }  // namespace rvn

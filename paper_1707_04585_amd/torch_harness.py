@@ -89,3 +89,57 @@ class StackRunner:
         top-of-stack activations, their gradients, and the backward workspace."""
         s = self.n * self.c * self.h * self.w * 4
         return dict(stream=s, grads=s, workspace=self.bwd_bytes, total=2 * s + self.bwd_bytes)
+
+
+def upload_down(P, device="cuda:0"):
+    """{R: [{w,gamma,beta,stride}], S: {w}} of host arrays -> device tensors (the stride is part of the descriptor)."""
+    return dict(R=[{k: _dev(L[k], device) for k in ("w", "gamma", "beta")} for L in P["R"]],
+                S=dict(w=_dev(P["S"]["w"], device)))
+
+
+def zeros_like_down(D):
+    return dict(R=[{k: torch.zeros_like(v) for k, v in L.items()} for L in D["R"]], S=dict(w=torch.zeros_like(D["S"]["w"])))
+
+
+def download_down(D):
+    f = lambda v: v.detach().cpu().numpy().astype(np.float64)
+    return dict(R=[{k: f(v) for k, v in L.items()} for L in D["R"]], S=dict(w=f(D["S"]["w"])))
+
+
+class BodyRunner:
+    """Device buffers of a multi-stage body (reversible stages joined by
+    subsampling blocks) and the calls into the C ABI.  Keeps one activation
+    and one gradient tensor per stage, whatever the stages' depths."""
+
+    def __init__(self, kind, n, h, w, channels, depths, widths, conv="f32", eps=1e-5, device="cuda:0", **_unused):
+        self.n, self.h, self.w, self.channels, self.depths = n, h, w, tuple(channels), tuple(depths)
+        self.device = torch.device(device)
+        stages = [B.BlockDesc(kind, c // 2, wd or 0, eps, conv) for c, wd in zip(channels, widths)]
+        downs = [B.DownDesc(kind, channels[s], channels[s + 1], 0, eps, conv) for s in range(len(channels) - 1)]
+        self.down_descs = downs
+        self.desc = B.BodyDesc(stages, depths, downs)
+        self.fwd_bytes, self.bwd_bytes = B.revnet_body_workspace_bytes(self.desc, n, h, w)
+        self.ws = torch.empty(max(self.fwd_bytes, self.bwd_bytes), dtype=torch.uint8, device=self.device)
+        shape = lambda s: (n, channels[s], h >> s, w >> s)
+        self.tops = [torch.empty(shape(s), dtype=torch.float32, device=self.device) for s in range(len(channels))]
+        self.dtops = [torch.empty_like(t) for t in self.tops]
+
+    def set_params(self, stages, downs):
+        self.stage_params = [upload_params(st, self.device) for st in stages]
+        self.down_params = [upload_down(P, self.device) for P in downs]
+        self.stage_grads = [zeros_like_params(st) for st in self.stage_params]
+        self.down_grads = [zeros_like_down(D) for D in self.down_params]
+
+    def forward(self, x, stream=None):
+        """x: device tensor [n, channels[0], h, w]; it may be self.tops[0]."""
+        B.revnet_body_fwd(self.desc, x, self.stage_params, self.down_params, self.tops, self.ws, stream)
+
+    def backward(self, accumulate=False, stream=None):
+        """self.dtops[-1] holds the upstream derivative; see revnet_body_bwd for what is left where."""
+        B.revnet_body_bwd(self.desc, self.tops, self.dtops, self.stage_params, self.down_params, self.stage_grads,
+                          self.down_grads, int(accumulate), self.ws, stream)
+
+    def activation_bytes(self):
+        """Bytes alive between the end of forward and the end of backward."""
+        acts = sum(t.numel() * 4 for t in self.tops)
+        return dict(stream=acts, grads=acts, workspace=self.bwd_bytes, total=2 * acts + self.bwd_bytes)

@@ -143,3 +143,51 @@ def test_workspace_does_not_depend_on_depth_and_scales_with_batch():
     # one launch per call clears the reduction counters; the rest is per block
     assert c50[1]["kernel_launches"] - 1 == 50 * (c1[1]["kernel_launches"] - 1)
     assert abs(c50[1]["algorithmic_bytes"] - 50 * c1[1]["algorithmic_bytes"]) < 1e-6 * c50[1]["algorithmic_bytes"]
+
+
+def test_down_block_and_body_argument_validation():
+    """The subsampling block and the body check shapes, channel chains, even
+    sizes, overlaps and the workspace before anything is enqueued."""
+    d = rv.DownDesc("bottleneck", 8, 16)
+    assert d.width == 4
+    layer = dict(w=0x10, gamma=0x20, beta=0x30)
+    p = dict(R=[layer] * 3, S=dict(w=0x40))
+    x = fake(BASE, n=2, c=8, h=4, w=4, sn=8 * 16)
+    y = fake(BASE + 0x100000, n=2, c=16, h=2, w=2, sn=16 * 4)
+    dy = fake(BASE + 0x200000, n=2, c=16, h=2, w=2, sn=16 * 4)
+    dx = fake(BASE + 0x300000, n=2, c=8, h=4, w=4, sn=8 * 16)
+    fwd, bwd = rv.revnet_down_workspace_bytes(d, 2, 4, 4)
+    assert bwd > fwd > 0
+    ws = (BASE + 0x800000, bwd)
+    assert status_of(rv.revnet_down_workspace_bytes, d, 2, 5, 4)[0] == -2          # odd height
+    assert status_of(rv.revnet_down_fwd, d, x, p, fake(BASE + 0x100000, n=2, c=16, h=4, w=4), ws)[0] == -2
+    assert status_of(rv.revnet_down_fwd, d, x, p, y, (ws[0], fwd - 1))[0] == -5
+    assert status_of(rv.revnet_down_fwd, d, x, dict(R=[layer] * 3, S=dict(w=None)), y, ws)[0] == -1
+    assert status_of(rv.revnet_down_fwd, d, x, p, fake(BASE + 64, n=2, c=16, h=2, w=2, sn=16 * 4), ws)[0] == -6
+    assert status_of(rv.revnet_down_bwd, d, x, dy, p, x, p, 0, ws)[0] == -6          # dx must not be x
+    assert status_of(rv.revnet_down_bwd, d, x, dy, p, dx, dict(R=[layer] * 2 + [dict(w=None, gamma=1, beta=1)], S=dict(w=1)), 0, ws)[0] == -1
+    assert status_of(rv.revnet_down_bwd, d, x, dy, p, dx, p, 0, (BASE, bwd))[0] == -6  # workspace over x
+
+    stages = [rv.BlockDesc("basic", 4), rv.BlockDesc("basic", 8)]
+    body = rv.BodyDesc(stages, [2, 3], [rv.DownDesc("basic", 8, 16)])
+    f, b = rv.revnet_body_workspace_bytes(body, 2, 4, 4)
+    assert b > f > 0
+    # the workspace is the largest single need, not a sum over stages or depths
+    deeper = rv.BodyDesc(stages, [20, 30], [rv.DownDesc("basic", 8, 16)])
+    assert rv.revnet_body_workspace_bytes(deeper, 2, 4, 4) == (f, b)
+    wrong_chain = rv.BodyDesc(stages, [2, 3], [rv.DownDesc("basic", 8, 12)])
+    assert status_of(rv.revnet_body_workspace_bytes, wrong_chain, 2, 4, 4)[0] == -2
+    assert status_of(rv.revnet_body_workspace_bytes, body, 2, 6, 5)[0] == -2        # odd width at the block
+    bp = dict(F=[layer] * 2, G=[layer] * 2)
+    dp = dict(R=[layer] * 2, S=dict(w=0x40))
+    tops = [fake(BASE + 0x100000, n=2, c=8, h=4, w=4, sn=8 * 16), fake(BASE + 0x200000, n=2, c=16, h=2, w=2, sn=16 * 4)]
+    wsb = (BASE + 0x800000, b)
+    assert status_of(rv.revnet_body_fwd, body, x, [[bp] * 2, [bp] * 3], [dp], [tops[0], tops[0]], wsb)[0] == -2
+    assert status_of(rv.revnet_body_fwd, body, x, [[bp] * 2, [bp] * 3], [dp], tops, (wsb[0], f - 1))[0] == -5
+    overl = [tops[0], fake(BASE + 0x100000 + 64, n=2, c=16, h=2, w=2, sn=16 * 4)]
+    assert status_of(rv.revnet_body_fwd, body, x, [[bp] * 2, [bp] * 3], [dp], overl, wsb)[0] == -6
+    dtops = [fake(BASE + 0x300000, n=2, c=8, h=4, w=4, sn=8 * 16), fake(BASE + 0x400000, n=2, c=16, h=2, w=2, sn=16 * 4)]
+    assert status_of(rv.revnet_body_bwd, body, tops, [dtops[0], tops[1]], [[bp] * 2, [bp] * 3], [dp],
+                     [[bp] * 2, [bp] * 3], [dp], 0, wsb)[0] == -6
+    assert status_of(rv.revnet_body_bwd, body, tops, dtops, [[bp] * 2, [bp] * 3], [dp],
+                     [[bp] * 2, [bp] * 3], [dp], 0, (wsb[0], b - 1))[0] == -5

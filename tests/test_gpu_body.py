@@ -1,0 +1,195 @@
+"""GPU parity of the non-reversible subsampling block and of the multi-stage
+body (reversible stages joined by such blocks), called through the C ABI,
+against the CPU oracle on the same seeded inputs.
+
+Tolerances as for the stacks: fp32 forward 1e-5, gradients 1e-4; bf16
+convolution operands 2e-2 on gradients (1e-2 forward), or 3x the distance
+between the oracle's own float32 and float64 runs where that is larger (see
+test_gpu_parity.py for why bf16 operands make that the floor)."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": dict(fwd=1e-5, grad=1e-4), "bf16": dict(fwd=1e-2, grad=2e-2)}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return torch
+
+
+def grad_err(oracle, got, want):
+    floor = 1e-6 * max(1.0, float(np.abs(want).max()))
+    if np.linalg.norm(want) < floor:
+        return float(np.abs(got - want).max()) / (1e4 * floor)
+    return oracle.rel_l2(got, want)
+
+
+def down_errors(oracle, got, want, prefix=""):
+    err = {prefix + "S.w": grad_err(oracle, got["S"]["w"], want["S"]["w"])}
+    for l, (gl, wl) in enumerate(zip(got["R"], want["R"])):
+        for key in ("w", "gamma", "beta"):
+            err[f"{prefix}R.{l}.{key}"] = grad_err(oracle, gl[key], wl[key])
+    return err
+
+
+def cast_down(P, dt):
+    return dict(R=[{k: (np.ascontiguousarray(v, dtype=dt) if k != "stride" else v) for k, v in L.items()} for L in P["R"]],
+                S=dict(w=np.ascontiguousarray(P["S"]["w"], dtype=dt)))
+
+
+DOWN_CASES = [
+    # kind, n, c_in, c_out, h, w
+    ("basic", 3, 12, 20, 12, 8),
+    ("bottleneck", 2, 24, 32, 8, 12),
+    ("basic", 8, 32, 64, 32, 32),        # the first subsampling block of the three-stage basic body
+    ("bottleneck", 2, 64, 128, 28, 28),
+    ("bottleneck", 4, 48, 40, 10, 6),     # ragged: half resolution 5x3, inner width 10
+]
+
+
+@pytest.mark.parametrize("conv", ["f32", "bf16"])
+@pytest.mark.parametrize("kind,n,c_in,c_out,h,w", DOWN_CASES)
+def test_down_block_matches_oracle(oracle, torch_cuda, kind, n, c_in, c_out, h, w, conv):
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import upload_down, zeros_like_down, download_down, _dev
+    print(f"down block {kind} n={n} {c_in}->{c_out} {h}x{w} conv={conv}", flush=True)
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((n, c_in, h, w))
+    P = S.draw_down(rng, kind, c_in, c_out, "random")
+    dy = rng.standard_normal((n, c_out, h // 2, w // 2))
+    with oracle.conv_operands(conv):
+        y_ref, stored = oracle.down_fwd(x, P)
+        dx_ref, g_ref = oracle.down_bwd(stored, P, dy)
+    tol = dict(TOL[conv])
+    if conv == "bf16":
+        with oracle.conv_operands("bf16"):
+            P32 = cast_down(P, np.float32)
+            _, st32 = oracle.down_fwd(x.astype(np.float32), P32, np.float32(1e-5))
+            dx32, _ = oracle.down_bwd(st32, P32, dy.astype(np.float32), np.float32(1e-5))
+        floor = oracle.rel_l2(dx32, dx_ref)
+        tol["grad"] = max(tol["grad"], 3.0 * floor)
+        print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol["grad"]), flush=True)
+
+    desc = rv.DownDesc(kind, c_in, c_out, 0, 1e-5, conv)
+    fwd_b, bwd_b = rv.revnet_down_workspace_bytes(desc, n, h, w)
+    ws = torch.empty(max(fwd_b, bwd_b), dtype=torch.uint8, device="cuda:0")
+    dp = upload_down(P)
+    dg = zeros_like_down(dp)
+    X, DY = _dev(x, "cuda:0"), _dev(dy, "cuda:0")
+    Y = torch.empty((n, c_out, h // 2, w // 2), dtype=torch.float32, device="cuda:0")
+    DX = torch.empty_like(X)
+    rv.revnet_down_fwd(desc, X, dp, Y, ws)
+    rv.revnet_down_bwd(desc, X, DY, dp, DX, dg, 0, ws)
+    torch.cuda.synchronize()
+    e_y = oracle.rel_l2(Y.cpu().numpy(), y_ref)
+    e_dx = oracle.rel_l2(DX.cpu().numpy(), dx_ref)
+    errs = down_errors(oracle, download_down(dg), g_ref)
+    worst = max(errs, key=errs.get)
+    print("  rel. errors: y %.2e  dx %.2e  worst parameter gradient %s %.2e" % (e_y, e_dx, worst, errs[worst]), flush=True)
+    assert torch.equal(X.cpu(), torch.as_tensor(x.astype(np.float32))), "the stored input must not be modified"
+    assert e_y < tol["fwd"]
+    assert e_dx < tol["grad"]
+    assert errs[worst] < tol["grad"], (worst, errs[worst])
+
+    # accumulate_wgrads adds to what is there: a second backward doubles every gradient
+    rv.revnet_down_bwd(desc, X, DY, dp, DX, dg, 1, ws)
+    torch.cuda.synchronize()
+    twice = download_down(dg)
+    doubled = dict(R=[{k: 2.0 * v for k, v in L.items()} for L in g_ref["R"]], S=dict(w=2.0 * g_ref["S"]["w"]))
+    errs2 = down_errors(oracle, twice, doubled)
+    assert max(errs2.values()) < tol["grad"], errs2
+
+
+def small_body_cfg(kind, conv):
+    if kind == "basic":
+        return dict(kind=kind, n=4, h=16, w=16, channels=(8, 12, 16), depths=(2, 1, 2), widths=(None, None, None), conv=conv)
+    return dict(kind=kind, n=3, h=16, w=8, channels=(16, 32, 32), depths=(1, 2, 1), widths=(4, 8, 6), conv=conv)
+
+
+def run_body(cfg, x, stages, downs, dy):
+    import torch
+    from paper_1707_04585_amd.torch_harness import BodyRunner, download_grads, download_down, _dev
+    r = BodyRunner(**cfg)
+    r.set_params(stages, downs)
+    X = _dev(x, "cuda:0")
+    r.forward(X)
+    torch.cuda.synchronize()
+    tops = [t.cpu().numpy().astype(np.float64) for t in r.tops]
+    assert torch.equal(X.cpu(), torch.as_tensor(x.astype(np.float32))), "the body's input must not be modified"
+    r.dtops[-1].copy_(_dev(dy, "cuda:0"))
+    r.backward()
+    torch.cuda.synchronize()
+    return dict(runner=r, tops=tops, x_rec=r.tops[0].cpu().numpy().astype(np.float64),
+                dx=r.dtops[0].cpu().numpy().astype(np.float64),
+                stage_grads=[download_grads(g) for g in r.stage_grads],
+                down_grads=[download_down(g) for g in r.down_grads])
+
+
+def body_errors(oracle, out, tops_ref, dx_ref, sg_ref, dg_ref, x):
+    err = {f"top{s}": oracle.rel_l2(t, tr) for s, (t, tr) in enumerate(zip(out["tops"], tops_ref))}
+    fwd = max(err.values())
+    g = {}
+    for s, (gs, rs) in enumerate(zip(out["stage_grads"], sg_ref)):
+        for k, (gb, rb) in enumerate(zip(gs, rs)):
+            for fn in ("F", "G"):
+                for l, (gl, rl) in enumerate(zip(gb[fn], rb[fn])):
+                    for key in ("w", "gamma", "beta"):
+                        g[f"s{s}.{k}.{fn}.{l}.{key}"] = grad_err(oracle, gl[key], rl[key])
+    for s, (gd, rd) in enumerate(zip(out["down_grads"], dg_ref)):
+        g.update(down_errors(oracle, gd, rd, prefix=f"down{s}."))
+    return fwd, oracle.rel_l2(out["x_rec"], x), oracle.rel_l2(out["dx"], dx_ref), g
+
+
+@pytest.mark.parametrize("conv", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["basic", "bottleneck"])
+def test_body_matches_oracle(oracle, torch_cuda, kind, conv):
+    """Three stages joined by two subsampling blocks: every stage top, the
+    reconstructed input, the input gradient and every parameter gradient
+    against ordinary stored-activation backprop in float64."""
+    cfg = small_body_cfg(kind, conv)
+    print(f"body {cfg}", flush=True)
+    x, stages, downs, dy = S.draw_body(2025, **cfg)
+    with oracle.conv_operands(conv):
+        tops_ref, kept = oracle.body_fwd(x, stages, downs, keep=True)
+        dx_ref, sg_ref, dg_ref = oracle.body_bwd_stored(kept, stages, downs, dy)
+    tol = dict(TOL[conv])
+    if conv == "bf16":
+        f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+        with oracle.conv_operands("bf16"):
+            st32 = [S.cast_params(st, np.float32) for st in stages]
+            dn32 = [cast_down(P, np.float32) for P in downs]
+            t32, k32 = oracle.body_fwd(f32(x), st32, dn32, np.float32(1e-5), keep=True)
+            dx32, _, _ = oracle.body_bwd_stored(k32, st32, dn32, f32(dy), np.float32(1e-5))
+        floor = oracle.rel_l2(dx32, dx_ref)
+        # (capped: where two oracle runs are further apart than that, the case says nothing)
+        tol["grad"] = min(max(tol["grad"], 3.0 * floor), 1e-1)
+        tol["fwd"] = min(max(tol["fwd"], 3.0 * oracle.rel_l2(t32[-1], tops_ref[-1])), 1e-1)
+        print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol["grad"]), flush=True)
+    out = run_body(cfg, x, stages, downs, dy)
+    fwd, rec, dx, g = body_errors(oracle, out, tops_ref, dx_ref, sg_ref, dg_ref, x)
+    worst = max(g, key=g.get)
+    print("  rel. errors: tops %.2e  x_rec %.2e  dx %.2e  worst parameter gradient %s %.2e" % (fwd, rec, dx, worst, g[worst]), flush=True)
+    assert fwd < tol["fwd"]
+    assert rec < tol["fwd"]
+    assert dx < tol["grad"]
+    assert g[worst] < tol["grad"], (worst, g[worst])
+
+
+def test_body_activation_memory_does_not_depend_on_depth(torch_cuda):
+    """Section 3.2: only the stage tops (the stored inputs of the subsampling
+    blocks) and a workspace are alive between forward and backward, whatever the
+    stages' depths."""
+    from paper_1707_04585_amd.torch_harness import BodyRunner
+    base = dict(kind="basic", n=8, h=32, w=32, channels=(32, 64, 112), widths=(None, None, None), conv="bf16")
+    a = BodyRunner(depths=(1, 1, 1), **base).activation_bytes()
+    b = BodyRunner(depths=(9, 9, 9), **base).activation_bytes()
+    assert a == b
+    tops = 4 * 8 * (32 * 32 * 32 + 64 * 16 * 16 + 112 * 8 * 8)
+    assert a["stream"] == tops
