@@ -60,9 +60,21 @@ __device__ __forceinline__ float fetch(const float *p) {
 // holding the last of `expected` tickets returns true for all its threads and
 // has put the counter back to zero for the next use.  It must read the other
 // workgroups' results with fetch().
+//
+// The wait is explicit.  A workgroup-scope release fence only keeps the
+// compiler from moving the stores; it emits no s_waitcnt, and a store and an
+// atomic to different addresses travel to different L2 channels, so without
+// the wait the ticket can overtake the partial result and the last workgroup
+// can fetch what an earlier launch left there.  (An agent-scope fence would
+// wait as well, but it also writes back the whole L2.)
+__device__ __forceinline__ void wait_for_own_stores() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): every vector memory operation of this thread has completed
+}
+
 __device__ __forceinline__ bool arrive_last(int *counter, int expected, int *flag_lds) {
     if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt: stores done
+        wait_for_own_stores();
         const int prev = atomicAdd(counter, 1);
         const int last = prev == expected - 1;
         if (last) atomicExch(counter, 0);

@@ -244,6 +244,26 @@ def test_runs_are_bitwise_reproducible(oracle, torch_cuda):
     np.testing.assert_array_equal(oracle.flatten_grads(a["grads"]), oracle.flatten_grads(b["grads"]))
 
 
+def test_fresh_buffers_reproduce_bitwise_at_full_size(oracle, torch_cuda):
+    """A full-size bf16 stack run from freshly allocated buffers (new addresses,
+    stale workspace contents) gives the same bits every time.  The per-channel
+    reductions cross workgroups through published partial results and a
+    ticket; the ticket must not overtake the partial result it announces, or
+    the finishing workgroup reads what an earlier launch left in the scratch
+    area -- a plausible value, so only a comparison of bits shows it."""
+    cfg, x, params, dy = S.draw_named("c5_stage3")
+    ref = None
+    for rep in range(4):
+        out = gpu_run(cfg, x, params, dy)
+        got = (out["y"], out["x_rec"], out["dx"], oracle.flatten_grads(out["grads"]))
+        del out
+        if ref is None:
+            ref = got
+            continue
+        for name, a, b in zip(("y", "x_rec", "dx", "parameter gradients"), ref, got):
+            assert np.array_equal(a, b), f"run {rep}: {name} differ from the first run"
+
+
 def test_accumulate_wgrads(oracle, torch_cuda):
     """accumulate_wgrads adds to the gradient buffers (weight sharing, footnote
     to Algorithm 1): two backward passes give twice the gradient."""
