@@ -53,6 +53,117 @@ def bound_of(family: str, conv: str, flops: float, nbytes: float):
     return ("hbm", "hbm")
 
 
+def profiled_pass(rv, torch, step, steps, conv, workload):
+    """Per-kernel durations with HIP events on the launch stream, and the
+    roofline entry of the kernel family that takes the most time."""
+    rv.revnet_profile_begin()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    stats = rv.revnet_profile_end()
+    kern = {}
+    for name, st in stats.items():
+        avg_us = st["total_ms"] * 1e3 / st["launches"]
+        kern[name] = dict(launches_per_step=st["launches"] / steps, avg_us=round(avg_us, 3),
+                          ms_per_step=round(st["total_ms"] / steps, 4),
+                          GBps=round(st["algorithmic_bytes"] / st["total_ms"] / 1e6, 1) if st["total_ms"] else None,
+                          TFLOPs=round(st["flops"] / st["total_ms"] / 1e9, 2) if st["flops"] else None)
+    dom = max(stats, key=lambda k: stats[k]["total_ms"])
+    bound, peak_key = bound_of(dom, conv, stats[dom]["flops"], stats[dom]["algorithmic_bytes"])
+    peak, unit = PEAK[peak_key]
+    d = stats[dom]
+    per_launch_s = d["total_ms"] * 1e-3 / d["launches"]
+    quantity = (d["flops"] / 1e12 if bound != "hbm" else d["algorithmic_bytes"] / 1e9) / d["launches"]
+    achieved = quantity / per_launch_s
+    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 2), peak=peak, unit=unit,
+                    frac=round(achieved / peak, 4), avg_launch_us=round(per_launch_s * 1e6, 3),
+                    traffic=MEASURED_TRAFFIC.get((workload, dom)))
+    return kern, roofline
+
+
+def timed_steps(torch, step, steps, warmup, stream):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return max((t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps)
+
+
+def bench_body(args) -> int:
+    """A multi-stage body (reversible stages joined by subsampling blocks): one
+    step = body forward, then body backward from the stage tops alone."""
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import BodyRunner, _dev
+    cfg = dict(S.BODIES[args.workload])
+    seed = S.BASE_SEED + 100 + list(S.BODIES).index(args.workload)
+    x, stages, downs, dy = S.draw_body(seed, **cfg)
+    n, conv = cfg["n"], cfg["conv"]
+    torch.cuda.reset_peak_memory_stats()
+    r = BodyRunner(**cfg)
+    r.set_params(stages, downs)
+    base_alloc = torch.cuda.memory_allocated()
+    X, DY = _dev(x, r.device), _dev(dy, r.device)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        r.forward(X, stream)             # x -> top of every stage
+        r.dtops[-1].copy_(DY)            # the derivative arriving at the body's output
+        r.backward(stream=stream)        # tops reconstructed in place, dtops[0] = derivative at the input
+
+    ms_per_step = timed_steps(torch, step, args.steps, args.warmup, stream)
+    kern, roofline = profiled_pass(rv, torch, step, args.steps, conv, args.workload)
+    rec = float(np.linalg.norm(r.tops[0].cpu().numpy().astype(np.float64) - x) / np.linalg.norm(x))
+    act = r.activation_bytes()
+    shallow = BodyRunner(**dict(cfg, depths=tuple(1 for _ in cfg["depths"]))).activation_bytes()
+    out = {
+        "metric": "images/sec reversible fwd+bwd per stack on 1 MI355X; peak activation HBM bytes",
+        "value": round(n / (ms_per_step * 1e-3), 1), "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if conv == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "kind": cfg["kind"], "n": n, "h": cfg["h"], "w": cfg["w"],
+                   "channels": list(cfg["channels"]), "depths": list(cfg["depths"]), "widths": list(cfg["widths"]),
+                   "conv_operands": conv, "stem": "not part of the body: it starts at the stem's output"},
+        "roofline": roofline,
+        "kernels": kern,
+        "peak_activation_bytes": {"analytic": act, "same_body_one_block_per_stage": shallow,
+                                  "torch_max_allocated_over_params_and_inputs": int(torch.cuda.max_memory_allocated() - base_alloc)},
+        "body_input_reconstruction_rel_error": rec,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import revnet_oracle as O
+        O.build()
+
+        def oracle_pass(ns):
+            with O.conv_operands(conv):
+                t0 = time.perf_counter()
+                _, kept = O.body_fwd(x[:ns], stages, downs, keep=True)
+                O.body_bwd_stored(kept, stages, downs, dy[:ns])
+                return time.perf_counter() - t0
+
+        ns = min(args.cpu_sample_n, n) if args.cpu_sample_n else min(2, n)
+        secs, passes = 0.0, 0
+        while passes == 0 or (secs < 10.0 and passes < 8):
+            secs += oracle_pass(ns)
+            passes += 1
+        out["cpu_baseline"] = {"value": round(ns * passes / secs, 2), "unit": "images/s", "cores": O.num_threads(),
+                               "kind": "oracle", "seconds": round(secs, 2),
+                               "sample": f"first {ns} of {n} images, same stages, {passes} pass(es) of one forward + "
+                                         "stored-activation backward in float64"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -82,6 +193,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     rv.load_library()  # fails loudly if the HIP library is missing
+    if args.workload in S.BODIES:
+        return bench_body(args)
 
     cfg, x, params, dy = S.draw_named(args.workload)
     n, c, h, w, depth, conv = cfg["n"], cfg["c"], cfg["h"], cfg["w"], cfg["depth"], cfg["conv"]
@@ -97,44 +210,10 @@ def main() -> int:
         r.forward(X, Y, stream)               # x -> y, nothing else kept
         r.backward(Y, DY, Y, DX, stream=stream)   # y -> x in place; dy -> dx
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(args.steps):
-        step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall_ms = (t1 - t0) * 1e3 / args.steps
-    ms_per_step = max(wall_ms, ev0.elapsed_time(ev1) / args.steps)
+    ms_per_step = timed_steps(torch, step, args.steps, args.warmup, stream)
     peak_alloc = torch.cuda.max_memory_allocated() - base_alloc
 
-    # ---- profiled pass: per-kernel durations with HIP events on the launch stream
-    rv.revnet_profile_begin()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    stats = rv.revnet_profile_end()
-    kern = {}
-    for name, st in stats.items():
-        avg_us = st["total_ms"] * 1e3 / st["launches"]
-        kern[name] = dict(launches_per_step=st["launches"] / args.steps, avg_us=round(avg_us, 3),
-                          ms_per_step=round(st["total_ms"] / args.steps, 4),
-                          GBps=round(st["algorithmic_bytes"] / st["total_ms"] / 1e6, 1) if st["total_ms"] else None,
-                          TFLOPs=round(st["flops"] / st["total_ms"] / 1e9, 2) if st["flops"] else None)
-    dom = max(stats, key=lambda k: stats[k]["total_ms"])
-    bound, peak_key = bound_of(dom, conv, stats[dom]["flops"], stats[dom]["algorithmic_bytes"])
-    peak, unit = PEAK[peak_key]
-    d = stats[dom]
-    per_launch_s = d["total_ms"] * 1e-3 / d["launches"]
-    quantity = (d["flops"] / 1e12 if bound != "hbm" else d["algorithmic_bytes"] / 1e9) / d["launches"]
-    achieved = quantity / per_launch_s
-    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 2), peak=peak, unit=unit,
-                    frac=round(achieved / peak, 4), avg_launch_us=round(per_launch_s * 1e6, 3),
-                    traffic=MEASURED_TRAFFIC.get((args.workload, dom)))
+    kern, roofline = profiled_pass(rv, torch, step, args.steps, conv, args.workload)
 
     if args.copy_probe_mib:
         src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device=r.device).normal_()

@@ -210,7 +210,11 @@ def pack_down(downs):
 
 
 def pack_stages(stages):
-    """[[block, ...], ...] -> (C array of pointers to per-stage arrays, the arrays kept alive)."""
+    """[[block, ...], ...] -> (C array of pointers to per-stage arrays, the arrays kept alive).
+    A value this function returned earlier is passed through, so that a caller
+    can pack once and call many times."""
+    if isinstance(stages, tuple):
+        return stages
     arrays = [pack_params(st) for st in stages]
     ptrs = (C.c_void_p * len(arrays))(*[C.cast(a, C.c_void_p).value for a in arrays])
     return ptrs, arrays

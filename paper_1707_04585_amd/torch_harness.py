@@ -129,15 +129,18 @@ class BodyRunner:
         self.down_params = [upload_down(P, self.device) for P in downs]
         self.stage_grads = [zeros_like_params(st) for st in self.stage_params]
         self.down_grads = [zeros_like_down(D) for D in self.down_params]
+        # marshalled once: the per-call work is then independent of the depths
+        self._sp, self._sg = B.pack_stages(self.stage_params), B.pack_stages(self.stage_grads)
+        self._dp, self._dg = B.pack_down(self.down_params), B.pack_down(self.down_grads)
 
     def forward(self, x, stream=None):
         """x: device tensor [n, channels[0], h, w]; it may be self.tops[0]."""
-        B.revnet_body_fwd(self.desc, x, self.stage_params, self.down_params, self.tops, self.ws, stream)
+        B.revnet_body_fwd(self.desc, x, self._sp, self._dp, self.tops, self.ws, stream)
 
     def backward(self, accumulate=False, stream=None):
         """self.dtops[-1] holds the upstream derivative; see revnet_body_bwd for what is left where."""
-        B.revnet_body_bwd(self.desc, self.tops, self.dtops, self.stage_params, self.down_params, self.stage_grads,
-                          self.down_grads, int(accumulate), self.ws, stream)
+        B.revnet_body_bwd(self.desc, self.tops, self.dtops, self._sp, self._dp, self._sg, self._dg, int(accumulate),
+                          self.ws, stream)
 
     def activation_bytes(self):
         """Bytes alive between the end of forward and the end of backward."""
