@@ -274,6 +274,41 @@ def test_accumulate_wgrads(oracle, torch_cuda):
     check_against_oracle(oracle, out, ref, x, "f32", scale_grads=2.0)
 
 
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 6)])
+def test_weight_shared_stack(oracle, torch_cuda, kind, width):
+    """Footnote to Algorithm 1 (Section 3.2): when blocks share weights, their
+    contributions to the weight derivative are summed.  A 'recurrent' stack --
+    the same block applied five times -- through revnet_stack_bwd with every
+    block pointing at the same parameter and gradient buffers and
+    accumulate_wgrads set, against the sum over blocks of the oracle's
+    per-block stored-activation gradients."""
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import StackRunner, download_grads, zeros_like_params
+    depth = 5
+    cfg = dict(kind=kind, n=4, c=16, h=10, w=10, depth=1, width=width, conv="f32", affine="random")
+    x, one, dy = S.draw_stack(83, **cfg)
+    one[0]["F"] = [dict(L, w=0.5 * L["w"]) for L in one[0]["F"]]   # keep the five-fold composition tame
+    one[0]["G"] = [dict(L, w=0.5 * L["w"]) for L in one[0]["G"]]
+    params = one * depth
+    cfg["depth"] = depth
+    ref = oracle_reference(oracle, cfg, x, params, dy)
+    summed = {fn: [{k: sum(ref["grads"][d][fn][l][k] for d in range(depth)) for k in ("w", "gamma", "beta")}
+                   for l in range(len(one[0][fn]))] for fn in ("F", "G")}
+    r = StackRunner(**cfg)
+    r.set_params(one)                       # one block's parameters on the device ...
+    shared_p = rv.pack_params([r.params[0]] * depth)    # ... named by every block of the stack
+    shared_g = rv.pack_grads([r.grads[0]] * depth)      # gradients start at zero
+    X, DY = r.new_pair(x), r.new_pair(dy)
+    rv.revnet_stack_fwd(r.desc, depth, X[1], X[2], shared_p, X[1], X[2], r.ws)
+    torch.cuda.synchronize()
+    y = r.to_host(X[0])
+    rv.revnet_stack_bwd(r.desc, depth, X[1], X[2], DY[1], DY[2], shared_p, X[1], X[2], DY[1], DY[2], shared_g, 1, r.ws)
+    torch.cuda.synchronize()
+    out = dict(y=y, x_rec=r.to_host(X[0]), dx=r.to_host(DY[0]), grads=download_grads(r.grads))
+    check_against_oracle(oracle, out, dict(y=ref["y"], dx=ref["dx"], grads=[summed]), x, "f32")
+
+
 def test_deep_stack_activation_memory_flat_and_drift_small(oracle, torch_cuda):
     """Section 4, Table 1: the activation storage of a reversible stack does not
     depend on its depth; Section 3.2 'Numerical error': the reconstruction error
