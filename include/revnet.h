@@ -318,6 +318,48 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
                     const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
                     int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Fixed-point residual stream (Section 3.2, "Numerical error": with the x's
+ * and y's in fixed point and F, G in ordinary floating point the
+ * reconstruction is exact, at little extra cost).
+ *
+ * Stream tensors (x1, x2, y1, y2) hold int32 codes q standing for
+ * q * 2^-frac_bits, 1 <= frac_bits <= 30, in the same rvn_tensor layout
+ * (strides in 4-byte elements).  A function reads float(q) * 2^-frac_bits; its
+ * fp32 value f enters the stream as an integer sum,
+ *     y1 = x1 + rint(F(x2) * 2^frac_bits),   y2 = x2 + rint(G(y1) * 2^frac_bits),
+ * and the backward pass subtracts the same integers again, so x1, x2 come back
+ * bit for bit, at any depth, and the functions are back-propagated at exactly
+ * the activations of the forward pass.  Derivatives and parameters stay fp32.
+ * Codes wrap around on overflow (the caller chooses frac_bits so that the
+ * stream fits: |value| < 2^(31 - frac_bits)); the conversion of one function
+ * value saturates.  Everything else as for revnet_stack_fwd / revnet_stack_bwd,
+ * with the workspace size from revnet_fixed_workspace_bytes.
+ * ---------------------------------------------------------------------- */
+int revnet_fixed_workspace_bytes(const rvn_block_desc *desc, int64_t n, int64_t h, int64_t w,
+                                 size_t *fwd_bytes, size_t *bwd_bytes);
+
+/* dst (int32 codes) = rint(src * 2^frac_bits); src fp32.  dst may be src itself. */
+int revnet_fixed_from_float(const rvn_tensor *src, int32_t frac_bits, const rvn_tensor *dst, void *hip_stream);
+
+/* dst (fp32, dense: sc = h*w, sn = c*h*w) = src (int32 codes) * 2^-frac_bits.  No overlap. */
+int revnet_fixed_to_float(const rvn_tensor *src, int32_t frac_bits, const rvn_tensor *dst, void *hip_stream);
+
+int revnet_stack_fwd_fixed(const rvn_block_desc *desc, int32_t depth, int32_t frac_bits,
+                           const rvn_tensor *x1, const rvn_tensor *x2,
+                           const rvn_block_params *params,
+                           const rvn_tensor *y1, const rvn_tensor *y2,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
+int revnet_stack_bwd_fixed(const rvn_block_desc *desc, int32_t depth, int32_t frac_bits,
+                           const rvn_tensor *y1, const rvn_tensor *y2,
+                           const rvn_tensor *dy1, const rvn_tensor *dy2,
+                           const rvn_block_params *params,
+                           const rvn_tensor *x1, const rvn_tensor *x2,
+                           const rvn_tensor *dx1, const rvn_tensor *dx2,
+                           const rvn_block_grads *grads, int accumulate_wgrads,
+                           void *ws, size_t ws_bytes, void *hip_stream);
+
 /*
  * What revnet_stack_fwd (fwd) and revnet_stack_bwd (bwd) would enqueue for
  * this descriptor, depth and half-tensor shape, without touching the device.

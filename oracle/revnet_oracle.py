@@ -30,6 +30,10 @@ What it computes, and where the paper defines it:
                        "Numerical error", Section 5.2 "Impact of numerical
                        error").
 
+* ``fixed_encode`` / ``stack_fwd_fixed`` / ``stack_reverse_fixed`` -- the
+                       variant of Section 3.2 "Numerical error": the x's and
+                       y's in fixed point, F and G in floating point, so that
+                       the reconstruction is exact.
 * ``down_fwd`` / ``down_bwd`` -- the non-reversible subsampling block between
                        two stages (Section 3.1: a reversible block has stride
                        1, so the network also needs ordinary layers whose
@@ -363,6 +367,69 @@ def stack_reverse(y1, y2, dy1, dy2, params, eps=1e-5):
         (y1, y2), (dy1, dy2), grads[k] = block_reverse(y1, y2, dy1, dy2, params[k], eps)
         recon[k] = (y1, y2)
     return (y1, y2), (dy1, dy2), grads, recon
+
+
+# ---------------------------------------------------------------------------
+# fixed-point residual stream (Section 3.2, "Numerical error": fixed-point
+# arithmetic on the x's and y's, ordinary floating point for F and G, gives
+# exact reconstruction).  A stream value is an integer code q (int64 here)
+# standing for q * 2^-frac_bits; `dtype` is the floating-point type F and G
+# are computed in.  The paper does not say how a function value enters the
+# stream; the reading here is rounding to the nearest code (ties to even).
+# ---------------------------------------------------------------------------
+
+def fixed_encode(x, frac_bits):
+    return np.rint(np.asarray(x, dtype=np.float64) * 2.0 ** frac_bits).astype(np.int64)
+
+
+def fixed_decode(q, frac_bits, dtype=np.float64):
+    return q.astype(dtype) * dtype(2.0 ** -frac_bits)
+
+
+def _to_codes(f, frac_bits):
+    return np.rint(f * f.dtype.type(2.0 ** frac_bits)).astype(np.int64)
+
+
+def block_fwd_fixed(q1, q2, P, frac_bits, eps=1e-5, dtype=np.float64):
+    """y1 = x1 + F(x2), y2 = x2 + G(y1) with integer sums; returns the codes
+    and the stored state of both functions."""
+    f, st_f = func_fwd(fixed_decode(q2, frac_bits, dtype), P["F"], eps)
+    y1 = q1 + _to_codes(f, frac_bits)
+    g, st_g = func_fwd(fixed_decode(y1, frac_bits, dtype), P["G"], eps)
+    y2 = q2 + _to_codes(g, frac_bits)
+    return y1, y2, dict(F=st_f, G=st_g)
+
+
+def block_reverse_fixed(y1, y2, dy1, dy2, P, frac_bits, eps=1e-5, dtype=np.float64):
+    """Algorithm 1 with the stream in fixed point: the same steps, the two
+    reconstructions as integer differences."""
+    z1 = y1
+    g, st_g = func_fwd(fixed_decode(z1, frac_bits, dtype), P["G"], eps)
+    x2 = y2 - _to_codes(g, frac_bits)
+    f, st_f = func_fwd(fixed_decode(x2, frac_bits, dtype), P["F"], eps)
+    x1 = z1 - _to_codes(f, frac_bits)
+    vjp_g, grads_g = func_bwd(st_g, P["G"], dy2, eps)
+    dz1 = dy1 + vjp_g
+    vjp_f, grads_f = func_bwd(st_f, P["F"], dz1, eps)
+    dx2 = dy2 + vjp_f
+    dx1 = dz1
+    return (x1, x2), (dx1, dx2), dict(F=grads_f, G=grads_g)
+
+
+def stack_fwd_fixed(q1, q2, params, frac_bits, eps=1e-5, dtype=np.float64, keep=False):
+    stored = []
+    for P in params:
+        q1, q2, st = block_fwd_fixed(q1, q2, P, frac_bits, eps, dtype)
+        if keep:
+            stored.append(st)
+    return (q1, q2, stored) if keep else (q1, q2)
+
+
+def stack_reverse_fixed(y1, y2, dy1, dy2, params, frac_bits, eps=1e-5, dtype=np.float64):
+    grads = [None] * len(params)
+    for k in range(len(params) - 1, -1, -1):
+        (y1, y2), (dy1, dy2), grads[k] = block_reverse_fixed(y1, y2, dy1, dy2, params[k], frac_bits, eps, dtype)
+    return (y1, y2), (dy1, dy2), grads
 
 
 # ---------------------------------------------------------------------------

@@ -9,4 +9,6 @@ from .binding import (  # noqa: F401
     revnet_stack_bwd, revnet_stack_cost, revnet_stack_fwd, revnet_version, revnet_workspace_bytes,
     BodyDesc, DownDesc, pack_down, pack_stages, revnet_body_bwd, revnet_body_fwd, revnet_body_workspace_bytes,
     revnet_down_bwd, revnet_down_fwd, revnet_down_workspace_bytes,
+    revnet_fixed_from_float, revnet_fixed_to_float, revnet_fixed_workspace_bytes, revnet_stack_bwd_fixed,
+    revnet_stack_fwd_fixed,
 )

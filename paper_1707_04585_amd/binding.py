@@ -24,6 +24,8 @@ EXPORTS = [
     "revnet_profile_begin", "revnet_profile_end",
     "revnet_down_workspace_bytes", "revnet_down_fwd", "revnet_down_bwd",
     "revnet_body_workspace_bytes", "revnet_body_fwd", "revnet_body_bwd",
+    "revnet_fixed_workspace_bytes", "revnet_fixed_from_float", "revnet_fixed_to_float",
+    "revnet_stack_fwd_fixed", "revnet_stack_bwd_fixed",
 ]
 
 MAX_STAGES = 8
@@ -373,6 +375,49 @@ def revnet_body_bwd(desc, tops, dtops, stage_params, down_params, stage_grads, d
     _check(load_library().revnet_body_bwd(C.byref(d), tt, td, sp, dp, sg, dg, C.c_int(int(accumulate_wgrads)),
                                           C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
     del keep_p, keep_g
+
+
+def revnet_fixed_workspace_bytes(desc, n, h, w):
+    fwd, bwd = C.c_size_t(0), C.c_size_t(0)
+    d = _desc(desc)
+    _check(load_library().revnet_fixed_workspace_bytes(C.byref(d), C.c_int64(n), C.c_int64(h), C.c_int64(w),
+                                                       C.byref(fwd), C.byref(bwd)))
+    return int(fwd.value), int(bwd.value)
+
+
+def revnet_fixed_from_float(src, frac_bits, dst, stream=None):
+    ts, td = _tensor(src), _tensor(dst)
+    _check(load_library().revnet_fixed_from_float(C.byref(ts), C.c_int32(frac_bits), C.byref(td),
+                                                  C.c_void_p(_stream(stream))))
+
+
+def revnet_fixed_to_float(src, frac_bits, dst, stream=None):
+    ts, td = _tensor(src), _tensor(dst)
+    _check(load_library().revnet_fixed_to_float(C.byref(ts), C.c_int32(frac_bits), C.byref(td),
+                                                C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_fwd_fixed(desc, depth, frac_bits, x1, x2, params, y1, y2, ws, stream=None):
+    d = _desc(desc)
+    p = pack_params(params)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (x1, x2, y1, y2)]
+    _check(load_library().revnet_stack_fwd_fixed(C.byref(d), C.c_int32(depth), C.c_int32(frac_bits), C.byref(t[0]),
+                                                 C.byref(t[1]), p, C.byref(t[2]), C.byref(t[3]), C.c_void_p(wp),
+                                                 C.c_size_t(wb), C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_bwd_fixed(desc, depth, frac_bits, y1, y2, dy1, dy2, params, x1, x2, dx1, dx2, grads,
+                           accumulate_wgrads, ws, stream=None):
+    d = _desc(desc)
+    p = pack_params(params)
+    g = pack_grads(grads)
+    wp, wb = _ws(ws)
+    t = [_tensor(v) for v in (y1, y2, dy1, dy2, x1, x2, dx1, dx2)]
+    _check(load_library().revnet_stack_bwd_fixed(
+        C.byref(d), C.c_int32(depth), C.c_int32(frac_bits), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]),
+        C.byref(t[3]), p, C.byref(t[4]), C.byref(t[5]), C.byref(t[6]), C.byref(t[7]), g,
+        C.c_int(int(accumulate_wgrads)), C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
 
 
 def revnet_profile_begin():

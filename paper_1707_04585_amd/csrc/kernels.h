@@ -45,6 +45,7 @@ enum KernelId {
     K_PREP_FILTER,
     K_CONV_DGRAD_WGRAD,
     K_RESAMPLE,
+    K_FIXED_POINT,
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -235,6 +236,16 @@ bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, co
 // plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.
 bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g,
                      float *scratch, float *dw, bool accumulate, double bytes, double flops, WgradReduce *defer);
+
+// ---- fixed-point residual stream (Section 3.2, "Numerical error") ------------
+// A stream element is an int32 code q standing for q * 2^-frac_bits; the Views
+// of stream tensors carry int32 data behind their float pointer.
+// out (dense fp32 [n][c][h*w]) = float(x) * 2^-frac_bits.
+void fix_to_float(Ctx &cx, View x, int c, Geo g, int frac_bits, float *out);
+// out = r + sign * rint(f * 2^frac_bits) as an integer sum; f dense fp32, sign = +1 or -1; out may be r.
+void fix_axpy(Ctx &cx, View r, const float *f, int c, Geo g, int frac_bits, int sign, View out);
+// out (int32 codes) = rint(x * 2^frac_bits).
+void fix_from_float(Ctx &cx, View x, int c, Geo g, int frac_bits, View out);
 
 // ---- stride-2 resampling for the non-reversible subsampling block ----------
 // `full` is the geometry of the high-resolution side (h, w even).

@@ -83,6 +83,9 @@ struct Plan {
     // the data gradient; `prep[l]` says whether layer l uses them
     size_t wq_f[3], wq_b[3];
     bool prep[3];
+    // fixed-point residual stream only: the function's input as fp32 and the
+    // function's value before it is rounded into the stream
+    size_t xf, fout;
     size_t total;
 };
 
@@ -95,7 +98,7 @@ bool wants_prep(const rvn_block_desc &d, const Layer &ly, const Geo &g) {
     return (int64_t)ly.cin * ly.cout * ly.ks * ly.ks >= 16384;
 }
 
-Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
+Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed = false) {
     Plan p{};
     p.L = func_layers(d, p.layers);
     const size_t P = (size_t)g.pixels();
@@ -133,6 +136,12 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward) {
     off = align_up(off + wg_s * 4);
     p.conv_scratch = off;
     off = align_up(off + cv_s * 4);
+    if (fixed) {
+        p.xf = off;
+        off = align_up(off + P * d.c_half * 4);
+        p.fout = off;
+        off = align_up(off + P * d.c_half * 4);
+    }
     if (backward) {
         // a_l = ReLU(BN(x_l)) is never stored: every convolution kernel forms it
         // from x_l (the function input or h_{l-1}) while staging its operands.
@@ -166,6 +175,7 @@ struct Bufs {
     float *wgrad_scratch, *conv_scratch;
     int *counters;
     uint16_t *wq_f[3], *wq_b[3];  // null where the layer does not use converted filters
+    float *xf, *fout;
 };
 
 Bufs bind(const Plan &p, void *ws) {
@@ -184,6 +194,8 @@ Bufs bind(const Plan &p, void *ws) {
     o.counters = reinterpret_cast<int *>(b + p.counters);
     o.wgrad_scratch = reinterpret_cast<float *>(b + p.wgrad_scratch);
     o.conv_scratch = reinterpret_cast<float *>(b + p.conv_scratch);
+    o.xf = reinterpret_cast<float *>(b + p.xf);
+    o.fout = reinterpret_cast<float *>(b + p.fout);
     return o;
 }
 
@@ -270,9 +282,18 @@ int check_ws(const void *ws, size_t have, size_t need) {
 // ---- residual function drivers ----------------------------------------------
 
 // out = ep(r, Func(x)); leaves the layer inputs h_l and the BN statistics in `b`.
+// frac_bits > 0: x, r and out are fixed-point stream tensors (int32 codes of
+// 2^-frac_bits).  The function then runs on the fp32 copy b.xf of x -- which
+// func_backward reads as the function's input afterwards -- and its value is
+// rounded into the stream by an integer add / subtract (Section 3.2,
+// "Numerical error").
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
-                  const rvn_func_params &p, Epilogue ep, const View *r, View out) {
+                  const rvn_func_params &p, Epilogue ep, const View *r, View out, int frac_bits) {
     View cur = x;
+    if (frac_bits) {
+        fix_to_float(cx, x, pl.layers[0].cin, g, frac_bits, b.xf);
+        cur = dense_view(b.xf, pl.layers[0].cin, g);
+    }
     FilterPrep prep[3];
     for (int l = 0; l < pl.L; ++l)
         prep[l] = FilterPrep{p.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]};
@@ -288,6 +309,10 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
             View h = dense_view(b.h[l], ly.cout, g);
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.conv_scratch);
             cur = h;
+        } else if (frac_bits) {
+            conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr,
+                     dense_view(b.fout, ly.cout, g), b.conv_scratch);
+            fix_axpy(cx, *r, b.fout, ly.cout, g, frac_bits, ep == EP_SUB ? -1 : 1, out);
         } else {
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.conv_scratch);
         }
@@ -331,23 +356,26 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
 
 // Section 3.1: y1 = x1 + F(x2); y2 = x2 + G(y1).
 void block_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x1,
-                   View x2, const rvn_block_params &p, View y1, View y2) {
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1);
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2);
+                   View x2, const rvn_block_params &p, View y1, View y2, int frac_bits) {
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_ADD, &x1, y1, frac_bits);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_ADD, &x2, y2, frac_bits);
 }
 
-// Section 3.2, Algorithm 1, with G handled completely before F.
+// Section 3.2, Algorithm 1, with G handled completely before F.  With a
+// fixed-point stream (frac_bits > 0) the tensors y, x hold int32 codes and the
+// derivatives stay fp32.
 void block_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View y1,
                     View y2, View dy1, View dy2, const rvn_block_params &p, View x1, View x2, View dx1,
-                    View dx2, const rvn_block_grads &gr, bool accumulate) {
+                    View dx2, const rvn_block_grads &gr, bool accumulate, int frac_bits) {
+    const View shadow = dense_view(b.xf, d.c_half, g);  // fp32 copy of the function input at hand
     // z1 = y1;  x2 = y2 - G(z1)
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2);
+    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2, frac_bits);
     // dz1 = dy1 + (dG/dz1)^T dy2;  dwG          (dx1 = dz1)
-    func_backward(cx, d, pl, b, g, y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
+    func_backward(cx, d, pl, b, g, frac_bits ? shadow : y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
     // x1 = z1 - F(x2)
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1);
+    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1, frac_bits);
     // dx2 = dy2 + (dF/dx2)^T dz1;  dwF
-    func_backward(cx, d, pl, b, g, x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
+    func_backward(cx, d, pl, b, g, frac_bits ? shadow : x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
 }
 
 int finish(Ctx &cx) {
@@ -356,7 +384,8 @@ int finish(Ctx &cx) {
 }
 
 int check_fwd_args(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_tensor *x2,
-                   const rvn_tensor *y1, const rvn_tensor *y2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo) {
+                   const rvn_tensor *y1, const rvn_tensor *y2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo,
+                   bool fixed = false) {
     if (int rc = check_desc(desc)) return rc;
     if (int rc = check_tensor("x1", x1, *desc, nullptr)) return rc;
     if (int rc = check_tensor("x2", x2, *desc, x1)) return rc;
@@ -371,7 +400,7 @@ int check_fwd_args(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_t
             if (overlaps(t[i], t[j])) return fail(RVN_ERR_ALIAS, "%s and %s overlap", nm[i], nm[j]);
         }
     *geo = Geo{(int)x1->n, (int)x1->h, (int)x1->w};
-    *plan = make_plan(*desc, *geo, false);
+    *plan = make_plan(*desc, *geo, false, fixed);
     if (int rc = check_ws(ws, ws_bytes, plan->total)) return rc;
     for (int i = 0; i < 4; ++i)
         if (overlaps_range(t[i], ws, plan->total)) return fail(RVN_ERR_ALIAS, "%s overlaps the workspace", nm[i]);
@@ -380,7 +409,8 @@ int check_fwd_args(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_t
 
 int check_bwd_args(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_tensor *y2,
                    const rvn_tensor *dy1, const rvn_tensor *dy2, const rvn_tensor *x1, const rvn_tensor *x2,
-                   const rvn_tensor *dx1, const rvn_tensor *dx2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo) {
+                   const rvn_tensor *dx1, const rvn_tensor *dx2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo,
+                   bool fixed = false) {
     if (int rc = check_desc(desc)) return rc;
     const rvn_tensor *t[8] = {y1, y2, dy1, dy2, x1, x2, dx1, dx2};
     const char *nm[8] = {"y1", "y2", "dy1", "dy2", "x1", "x2", "dx1", "dx2"};
@@ -393,7 +423,7 @@ int check_bwd_args(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_t
             if (overlaps(t[i], t[j])) return fail(RVN_ERR_ALIAS, "%s and %s overlap", nm[i], nm[j]);
         }
     *geo = Geo{(int)y1->n, (int)y1->h, (int)y1->w};
-    *plan = make_plan(*desc, *geo, true);
+    *plan = make_plan(*desc, *geo, true, fixed);
     if (int rc = check_ws(ws, ws_bytes, plan->total)) return rc;
     for (int i = 0; i < 8; ++i)
         if (overlaps_range(t[i], ws, plan->total)) return fail(RVN_ERR_ALIAS, "%s overlaps the workspace", nm[i]);
@@ -401,21 +431,21 @@ int check_bwd_args(const rvn_block_desc *desc, const rvn_tensor *y1, const rvn_t
 }
 
 void stack_forward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
-                   View x1, View x2, const rvn_block_params *params, View y1, View y2) {
+                   View x1, View x2, const rvn_block_params *params, View y1, View y2, int frac_bits = 0) {
     clear_counters(cx, b.counters, pl.n_counters);
     for (int k = 0; k < depth; ++k) {
-        block_forward(cx, d, pl, b, g, k ? y1 : x1, k ? y2 : x2, params[k], y1, y2);
+        block_forward(cx, d, pl, b, g, k ? y1 : x1, k ? y2 : x2, params[k], y1, y2, frac_bits);
     }
 }
 
 void stack_backward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl, const Bufs &b, Geo g,
                     View y1, View y2, View dy1, View dy2, const rvn_block_params *params, View x1, View x2,
-                    View dx1, View dx2, const rvn_block_grads *grads, bool accumulate) {
+                    View dx1, View dx2, const rvn_block_grads *grads, bool accumulate, int frac_bits = 0) {
     clear_counters(cx, b.counters, pl.n_counters);
     for (int k = depth - 1; k >= 0; --k) {
         const bool top = k == depth - 1;
         block_backward(cx, d, pl, b, g, top ? y1 : x1, top ? y2 : x2, top ? dy1 : dx1, top ? dy2 : dx2,
-                       params[k], x1, x2, dx1, dx2, grads[k], accumulate);
+                       params[k], x1, x2, dx1, dx2, grads[k], accumulate, frac_bits);
     }
 }
 
@@ -1019,6 +1049,95 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
         stack_backward(cx, bd.stage[s], bd.depth[s], pl, bind(pl, ws), g, t1, t2, d1, d2, stage_params[s], t1, t2, d1, d2,
                        stage_grads[s], acc);
     }
+    return finish(cx);
+}
+
+// ---- fixed-point residual stream ---------------------------------------------
+
+namespace {
+
+int check_frac_bits(int32_t frac_bits) {
+    if (frac_bits < 1 || frac_bits > 30) return fail(RVN_ERR_SHAPE, "frac_bits = %d out of range [1, 30]", frac_bits);
+    return RVN_OK;
+}
+
+}  // namespace
+
+int revnet_fixed_workspace_bytes(const rvn_block_desc *desc, int64_t n, int64_t h, int64_t w, size_t *fwd_bytes,
+                                 size_t *bwd_bytes) {
+    if (int rc = check_desc(desc)) return rc;
+    if (int rc = check_geo(n, h, w)) return rc;
+    const Geo g{(int)n, (int)h, (int)w};
+    if (fwd_bytes) *fwd_bytes = make_plan(*desc, g, false, true).total;
+    if (bwd_bytes) *bwd_bytes = make_plan(*desc, g, true, true).total;
+    return RVN_OK;
+}
+
+int revnet_fixed_from_float(const rvn_tensor *src, int32_t frac_bits, const rvn_tensor *dst, void *hip_stream) {
+    if (int rc = check_frac_bits(frac_bits)) return rc;
+    if (!src) return fail(RVN_ERR_NULL, "tensor src is NULL");
+    if (int rc = check_any_tensor("src", src, src->c, src->n, src->h, src->w)) return rc;
+    if (int rc = check_any_tensor("dst", dst, src->c, src->n, src->h, src->w)) return rc;
+    if (!same_tensor(src, dst) && overlaps(src, dst)) return fail(RVN_ERR_ALIAS, "src and dst overlap");
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    fix_from_float(cx, view_of(src), (int)src->c, Geo{(int)src->n, (int)src->h, (int)src->w}, frac_bits, view_of(dst));
+    return finish(cx);
+}
+
+int revnet_fixed_to_float(const rvn_tensor *src, int32_t frac_bits, const rvn_tensor *dst, void *hip_stream) {
+    if (int rc = check_frac_bits(frac_bits)) return rc;
+    if (!src) return fail(RVN_ERR_NULL, "tensor src is NULL");
+    if (int rc = check_any_tensor("src", src, src->c, src->n, src->h, src->w)) return rc;
+    if (int rc = check_any_tensor("dst", dst, src->c, src->n, src->h, src->w)) return rc;
+    if (dst->sc != dst->h * dst->w || dst->sn != dst->c * dst->sc)
+        return fail(RVN_ERR_STRIDE, "tensor dst must be dense (sc = h*w, sn = c*h*w)");
+    if (overlaps(src, dst)) return fail(RVN_ERR_ALIAS, "src and dst overlap");
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    fix_to_float(cx, view_of(src), (int)src->c, Geo{(int)src->n, (int)src->h, (int)src->w}, frac_bits,
+                 static_cast<float *>(dst->ptr));
+    return finish(cx);
+}
+
+int revnet_stack_fwd_fixed(const rvn_block_desc *desc, int32_t depth, int32_t frac_bits, const rvn_tensor *x1,
+                           const rvn_tensor *x2, const rvn_block_params *params, const rvn_tensor *y1,
+                           const rvn_tensor *y2, void *ws, size_t ws_bytes, void *hip_stream) {
+    Plan pl;
+    Geo g;
+    if (depth <= 0) return fail(RVN_ERR_SHAPE, "depth = %d must be positive", depth);
+    if (int rc = check_frac_bits(frac_bits)) return rc;
+    if (int rc = check_fwd_args(desc, x1, x2, y1, y2, ws, ws_bytes, &pl, &g, true)) return rc;
+    if (!params) return fail(RVN_ERR_NULL, "params is NULL");
+    for (int k = 0; k < depth; ++k)
+        if (int rc = check_params(*desc, &params[k], "params")) return rc;
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    stack_forward(cx, *desc, depth, pl, bind(pl, ws), g, view_of(x1), view_of(x2), params, view_of(y1), view_of(y2),
+                  frac_bits);
+    return finish(cx);
+}
+
+int revnet_stack_bwd_fixed(const rvn_block_desc *desc, int32_t depth, int32_t frac_bits, const rvn_tensor *y1,
+                           const rvn_tensor *y2, const rvn_tensor *dy1, const rvn_tensor *dy2,
+                           const rvn_block_params *params, const rvn_tensor *x1, const rvn_tensor *x2,
+                           const rvn_tensor *dx1, const rvn_tensor *dx2, const rvn_block_grads *grads,
+                           int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream) {
+    Plan pl;
+    Geo g;
+    if (depth <= 0) return fail(RVN_ERR_SHAPE, "depth = %d must be positive", depth);
+    if (int rc = check_frac_bits(frac_bits)) return rc;
+    if (int rc = check_bwd_args(desc, y1, y2, dy1, dy2, x1, x2, dx1, dx2, ws, ws_bytes, &pl, &g, true)) return rc;
+    if (!params) return fail(RVN_ERR_NULL, "params is NULL");
+    if (!grads) return fail(RVN_ERR_NULL, "grads is NULL");
+    for (int k = 0; k < depth; ++k) {
+        if (int rc = check_params(*desc, &params[k], "params")) return rc;
+        if (int rc = check_grads(*desc, &grads[k], "grads")) return rc;
+    }
+    Ctx cx;
+    cx.stream = static_cast<hipStream_t>(hip_stream);
+    stack_backward(cx, *desc, depth, pl, bind(pl, ws), g, view_of(y1), view_of(y2), view_of(dy1), view_of(dy2), params,
+                   view_of(x1), view_of(x2), view_of(dx1), view_of(dx2), grads, accumulate_wgrads != 0, frac_bits);
     return finish(cx);
 }
 

@@ -38,12 +38,15 @@ class StackRunner:
     [N, C, H, W] buffer, i.e. strided views, unless split_buffers=True."""
 
     def __init__(self, kind, n, c, h, w, depth, width=None, conv="f32", eps=1e-5, device="cuda:0",
-                 split_buffers=False, **_unused):
+                 split_buffers=False, frac_bits=0, **_unused):
         self.desc = B.BlockDesc(kind, c // 2, width or 0, eps, conv)
         self.n, self.c, self.h, self.w, self.depth = n, c, h, w, depth
         self.device = torch.device(device)
         self.split_buffers = split_buffers
-        self.fwd_bytes, self.bwd_bytes = B.revnet_workspace_bytes(self.desc, n, h, w)
+        # frac_bits > 0: the residual stream is kept in fixed point (int32 codes of 2^-frac_bits)
+        self.frac_bits = int(frac_bits)
+        query = B.revnet_fixed_workspace_bytes if self.frac_bits else B.revnet_workspace_bytes
+        self.fwd_bytes, self.bwd_bytes = query(self.desc, n, h, w)
         self.ws = torch.empty(max(self.fwd_bytes, self.bwd_bytes), dtype=torch.uint8, device=self.device)
         self.params = self.grads = self._pp = self._pg = None
 
@@ -63,6 +66,28 @@ class StackRunner:
             full.copy_(_dev(src, self.device))
         return full, full[:, :ch], full[:, ch:]
 
+    def new_stream_pair(self, src=None):
+        """A pair of the residual stream's type: int32 codes when frac_bits > 0
+        (src, real values, is converted by the library), else as new_pair."""
+        if not self.frac_bits:
+            return self.new_pair(src)
+        assert not self.split_buffers
+        pair = self.new_pair(src)
+        full = pair[0]
+        if src is not None:
+            B.revnet_fixed_from_float(full, self.frac_bits, full)   # in place: same bytes, now int32 codes
+        q = full.view(torch.int32)
+        ch = self.c // 2
+        return q, q[:, :ch], q[:, ch:]
+
+    def stream_to_host(self, full):
+        """Real values of a stream tensor as float64."""
+        if not self.frac_bits:
+            return self.to_host(full)
+        out = torch.empty(full.shape, dtype=torch.float32, device=self.device)
+        B.revnet_fixed_to_float(full, self.frac_bits, out)
+        return out.cpu().numpy().astype(np.float64)
+
     def to_host(self, full):
         if self.split_buffers:
             return np.concatenate([full[0].cpu().numpy(), full[1].cpu().numpy()], axis=1).astype(np.float64)
@@ -76,13 +101,22 @@ class StackRunner:
 
     # -- calls ----------------------------------------------------------------
     def forward(self, xpair, ypair, stream=None):
-        B.revnet_stack_fwd(self.desc, self.depth, xpair[1], xpair[2], self._pp, ypair[1], ypair[2],
-                           self.ws, stream)
+        if self.frac_bits:
+            B.revnet_stack_fwd_fixed(self.desc, self.depth, self.frac_bits, xpair[1], xpair[2], self._pp, ypair[1],
+                                     ypair[2], self.ws, stream)
+        else:
+            B.revnet_stack_fwd(self.desc, self.depth, xpair[1], xpair[2], self._pp, ypair[1], ypair[2],
+                               self.ws, stream)
 
     def backward(self, ypair, dypair, xpair, dxpair, accumulate=False, stream=None):
-        B.revnet_stack_bwd(self.desc, self.depth, ypair[1], ypair[2], dypair[1], dypair[2], self._pp,
-                           xpair[1], xpair[2], dxpair[1], dxpair[2], self._pg, int(accumulate), self.ws,
-                           stream)
+        if self.frac_bits:
+            B.revnet_stack_bwd_fixed(self.desc, self.depth, self.frac_bits, ypair[1], ypair[2], dypair[1], dypair[2],
+                                     self._pp, xpair[1], xpair[2], dxpair[1], dxpair[2], self._pg, int(accumulate),
+                                     self.ws, stream)
+        else:
+            B.revnet_stack_bwd(self.desc, self.depth, ypair[1], ypair[2], dypair[1], dypair[2], self._pp,
+                               xpair[1], xpair[2], dxpair[1], dxpair[2], self._pg, int(accumulate), self.ws,
+                               stream)
 
     def activation_bytes(self):
         """Bytes alive between the end of forward and the end of backward:

@@ -191,3 +191,23 @@ def test_down_block_and_body_argument_validation():
                      [[bp] * 2, [bp] * 3], [dp], 0, wsb)[0] == -6
     assert status_of(rv.revnet_body_bwd, body, tops, dtops, [[bp] * 2, [bp] * 3], [dp],
                      [[bp] * 2, [bp] * 3], [dp], 0, (wsb[0], b - 1))[0] == -5
+
+
+def test_fixed_point_entry_points_validate_arguments():
+    d = rv.BlockDesc("basic", 4)
+    x1, x2 = halves(BASE)
+    y1, y2 = halves(BASE + 0x100000)
+    p = fake_params(d)
+    fwd, bwd = rv.revnet_fixed_workspace_bytes(d, 2, 4, 4)
+    plain_fwd, plain_bwd = rv.revnet_workspace_bytes(d, 2, 4, 4)
+    assert fwd > plain_fwd and bwd > plain_bwd
+    ws = (BASE + 0x800000, fwd)
+    assert status_of(rv.revnet_stack_fwd_fixed, d, 1, 0, x1, x2, [p], y1, y2, ws)[0] == -2     # frac_bits out of range
+    assert status_of(rv.revnet_stack_fwd_fixed, d, 1, 31, x1, x2, [p], y1, y2, ws)[0] == -2
+    assert status_of(rv.revnet_stack_fwd_fixed, d, 1, 16, x1, x2, [p], y1, y2, (ws[0], plain_fwd))[0] == -5
+    assert status_of(rv.revnet_stack_fwd_fixed, d, 1, 16, x1, x2, [p], x2, y2, ws)[0] == -6
+    full = fake(BASE, c=8, sn=8 * 16)
+    strided = fake(BASE + 0x100000, c=8, sc=32, sn=8 * 32)
+    assert status_of(rv.revnet_fixed_to_float, full, 16, strided)[0] == -3                     # destination must be dense
+    assert status_of(rv.revnet_fixed_from_float, full, 40, full)[0] == -2
+    assert status_of(rv.revnet_fixed_from_float, full, 16, fake(BASE + 64, c=8, sn=8 * 16))[0] == -6

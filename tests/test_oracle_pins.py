@@ -604,3 +604,61 @@ def test_strided_convolution_is_a_subsampled_stride1_convolution(oracle):
         up[:, :, ::2, ::2] = d
         assert np.allclose(oracle.conv_dgrad(d, w, (6, 4), 2), oracle.conv_dgrad(up, w, (6, 4), 1), rtol=0, atol=1e-13)
         assert np.allclose(oracle.conv_wgrad(a, d, ks, 2), oracle.conv_wgrad(a, up, ks, 1), rtol=0, atol=1e-13)
+
+
+# --------------------------------------------------------------------------
+# fixed-point residual stream (Section 3.2 "Numerical error")
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [np.float64, np.float32])
+@pytest.mark.parametrize("kind,width", [("basic", None), ("bottleneck", 3)])
+def test_fixed_point_stream_reconstructs_exactly(oracle, kind, width, dtype):
+    """With the stream in fixed point the inverse returns the input codes bit
+    for bit whatever precision F and G are computed in, at a depth where the
+    floating-point stream has visibly drifted; and because the functions are
+    then evaluated at exactly the forward activations, Algorithm 1 gives the
+    stored-activation gradients exactly, not just up to rounding."""
+    depth, fb = 12, 16
+    x, params, dy = small_stack(41, kind=kind, width=width, n=2, c=6, h=5, w=4, depth=depth)
+    params = S.cast_params(params, dtype)
+    q1, q2 = (oracle.fixed_encode(t, fb) for t in split(x))
+    d1, d2 = (t.astype(dtype) for t in split(dy))
+    y1, y2, stored = oracle.stack_fwd_fixed(q1, q2, params, fb, dtype(1e-5), dtype, keep=True)
+    assert y1.dtype == np.int64 and not np.array_equal(y1, q1)
+    (r1, r2), (dx1, dx2), grads = oracle.stack_reverse_fixed(y1, y2, d1, d2, params, fb, dtype(1e-5), dtype)
+    assert np.array_equal(r1, q1) and np.array_equal(r2, q2)
+    sx1, sx2, sgrads = oracle.stack_bwd_stored(stored, params, d1, d2, dtype(1e-5))
+    assert np.array_equal(dx1, sx1) and np.array_equal(dx2, sx2)
+    assert np.array_equal(oracle.flatten_grads(grads), oracle.flatten_grads(sgrads))
+    if dtype is np.float32:  # the same stack with a float32 stream does not come back exactly
+        f1, f2 = (t.astype(np.float32) for t in split(x))
+        z1, z2 = oracle.stack_fwd(f1, f2, params, np.float32(1e-5))
+        (b1, b2), _, _, _ = oracle.stack_reverse(z1, z2, d1, d2, params, np.float32(1e-5))
+        assert not np.array_equal(b1, f1)
+
+
+def test_fixed_point_stream_follows_the_real_valued_one(oracle):
+    """The codes stand for q * 2^-frac_bits and a function value enters by
+    rounding to the nearest code: one block moves every output by at most half
+    a code per function from the real-valued block applied to the decoded
+    input; the error of a whole stack shrinks by about 2^4 when frac_bits grows
+    by 4."""
+    x, params, dy = small_stack(42, kind="basic", n=2, c=6, h=5, w=4, depth=6)
+    x1, x2 = split(x)
+    errs = {}
+    for fb in (12, 16, 20):
+        q1, q2 = (oracle.fixed_encode(t, fb) for t in (x1, x2))
+        assert np.abs(oracle.fixed_decode(q1, fb) - x1).max() <= 2.0 ** -(fb + 1)
+        # one block, from the decoded input: at most half a code (y1), one code (y2: G sees a y1 that is off already,
+        # so allow the propagated part separately by evaluating G at the fixed-point y1)
+        a1, a2 = oracle.fixed_decode(q1, fb), oracle.fixed_decode(q2, fb)
+        y1, y2, _ = oracle.block_fwd_fixed(q1, q2, params[0], fb)
+        f, _ = oracle.func_fwd(a2, params[0]["F"])
+        assert np.abs(oracle.fixed_decode(y1, fb) - (a1 + f)).max() <= 2.0 ** -(fb + 1) * (1 + 1e-9)
+        g, _ = oracle.func_fwd(oracle.fixed_decode(y1, fb), params[0]["G"])
+        assert np.abs(oracle.fixed_decode(y2, fb) - (a2 + g)).max() <= 2.0 ** -(fb + 1) * (1 + 1e-9)
+        t1, t2 = oracle.stack_fwd_fixed(q1, q2, params, fb)
+        r1, r2 = oracle.stack_fwd(x1, x2, params)
+        errs[fb] = oracle.rel_l2(np.concatenate([oracle.fixed_decode(t1, fb), oracle.fixed_decode(t2, fb)], 1),
+                                 np.concatenate([r1, r2], 1))
+    assert errs[12] < 2e-3 and errs[16] < errs[12] / 6 and errs[20] < errs[16] / 6, errs
