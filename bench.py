@@ -170,6 +170,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2_stack9")
+    ap.add_argument("--frac-bits", type=int, default=0,
+                    help="keep the residual stream in fixed point with this many fraction bits (exact reconstruction); "
+                         "0 = floating-point stream, the benchmark configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-n", type=int, default=0,
                     help="batch of the oracle timing sample (0: the whole batch if one pass takes under ~30 s, "
@@ -198,12 +201,12 @@ def main() -> int:
 
     cfg, x, params, dy = S.draw_named(args.workload)
     n, c, h, w, depth, conv = cfg["n"], cfg["c"], cfg["h"], cfg["w"], cfg["depth"], cfg["conv"]
-    r = StackRunner(**cfg)
+    r = StackRunner(frac_bits=args.frac_bits, **cfg)
     r.set_params(params)
     torch.cuda.reset_peak_memory_stats()
     base_alloc = torch.cuda.memory_allocated()
-    X, DY = r.new_pair(x), r.new_pair(dy)     # inputs, read only in every step
-    Y, DX = r.new_pair(), r.new_pair()        # top activations (reconstructed in place), gradients
+    X, DY = r.new_stream_pair(x), r.new_pair(dy)     # inputs, read only in every step
+    Y, DX = r.new_stream_pair(), r.new_pair()        # top activations (reconstructed in place), gradients
     stream = torch.cuda.current_stream()
 
     def step():
@@ -230,7 +233,9 @@ def main() -> int:
 
     # ---- reconstruction error versus depth (input of block k, top block first)
     drift = None
-    if depth > 1:
+    if args.frac_bits:
+        drift = "exact" if torch.equal(X[0], Y[0]) else "NOT exact"   # integer codes of the input against the reconstruction
+    elif depth > 1:
         drift = []
         fwd_only = []
         cur = r.new_pair(x)
@@ -254,7 +259,8 @@ def main() -> int:
     esz = 2 if conv == "bf16" else 4
     per_block_stored = 2 * sum(n * h * w * cin * (4 + esz) for cin, _, _ in S.func_layers(cfg["kind"], c // 2, cfg["width"]))
     for dd in (1, 2, 4, 9, 18, 36):
-        assert rv.revnet_workspace_bytes(r.desc, n, h, w) == (r.fwd_bytes, r.bwd_bytes)
+        query = rv.revnet_fixed_workspace_bytes if args.frac_bits else rv.revnet_workspace_bytes
+        assert query(r.desc, n, h, w) == (r.fwd_bytes, r.bwd_bytes)
         act_vs_depth[str(dd)] = {"reversible": act["total"],
                                  "stored_activation_backprop": 2 * act["stream"] + dd * per_block_stored}
 
@@ -268,9 +274,11 @@ def main() -> int:
         "dtype": "f32" if conv == "f32" else "bf16",
         "data": "synthetic",
         "config": {"workload": args.workload, "kind": cfg["kind"], "n": n, "c": c, "h": h, "w": w,
-                   "depth": depth, "width": cfg["width"], "conv_operands": conv},
+                   "depth": depth, "width": cfg["width"], "conv_operands": conv,
+                   "residual_stream": f"fixed point, {args.frac_bits} fraction bits" if args.frac_bits else "fp32"},
         "roofline": roofline,
-        "step_totals": {"conv_TFLOP": round(step_flops / 1e12, 4), "algorithmic_GB": round(step_bytes / 1e9, 3),
+        "step_totals": {"note": "launch and byte totals are those of the fp32-stream path" if args.frac_bits else None,
+                        "conv_TFLOP": round(step_flops / 1e12, 4), "algorithmic_GB": round(step_bytes / 1e9, 3),
                         "kernel_launches": fwd_cost["kernel_launches"] + bwd_cost["kernel_launches"],
                         "achieved_TFLOPs": round(step_flops / 1e12 / (ms_per_step * 1e-3), 2),
                         "achieved_GBps": round(step_bytes / 1e9 / (ms_per_step * 1e-3), 1)},
