@@ -45,6 +45,8 @@ def run_fixed(cfg, x, params, dy, frac_bits=FB):
 @pytest.mark.parametrize("name,cfg", [
     ("basic_f32_24_blocks", dict(kind="basic", n=8, c=32, h=16, w=16, depth=24, width=None, conv="f32", affine="random")),
     ("basic_bf16_24_blocks", dict(kind="basic", n=8, c=32, h=16, w=16, depth=24, width=None, conv="bf16", affine="random")),
+    # 150 basic blocks = 600 convolution layers, the depth of the network the paper's appendix on memory savings mentions
+    ("basic_bf16_150_blocks", dict(kind="basic", n=4, c=16, h=8, w=8, depth=150, width=None, conv="bf16", affine="random")),
     ("bottleneck_bf16_12_blocks_ragged", dict(kind="bottleneck", n=3, c=96, h=9, w=7, depth=12, width=24, conv="bf16", affine="random")),
 ])
 def test_fixed_stream_reconstructs_bit_for_bit(oracle, torch_cuda, name, cfg):
