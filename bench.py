@@ -297,7 +297,11 @@ def main() -> int:
         def oracle_pass(ns):
             with O.conv_operands(conv):
                 t0 = time.perf_counter()
-                y1, y2, _, stored = O.stack_fwd(*sp(x[:ns]), params, keep=True)
+                if args.frac_bits:
+                    q1, q2 = (O.fixed_encode(t, args.frac_bits) for t in sp(x[:ns]))
+                    _, _, stored = O.stack_fwd_fixed(q1, q2, params, args.frac_bits, keep=True)
+                else:
+                    _, _, _, stored = O.stack_fwd(*sp(x[:ns]), params, keep=True)
                 O.stack_bwd_stored(stored, params, *sp(dy[:ns]))
                 return time.perf_counter() - t0
 
