@@ -106,6 +106,38 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
     constexpr int RB = 6;                          // rows a thread loads before it stores
     constexpr int WITER = (WCHUNK + kConvThreads - 1) / kConvThreads;
 
+    // ---- where this lane's results go: channels co0 + m*16 + 4*kq + j (j = 0..3) of
+    //      its pixel.  With few accumulators the skip operand is requested now, so
+    //      that it arrives under the staging and the matrix instructions (with many,
+    //      the registers are not there and it is requested after them); either way
+    //      it is added at the very end, with one rounding, as a separate pass would.
+    //      r may alias out element for element: every address is read before the
+    //      same lane writes it, and all reads come before the first write.
+    constexpr bool kEarlySkip = MT * NT <= 8;
+    int64_t e_off[NT];  // offset of (image, pixel) in out, -1: nothing to write
+    float rv[NT][MT][4];
+    auto locate_and_request = [&]() {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int tile = wave + kWaves * t;
+            const int img = tile / p.tiles_per_img, rem = tile - img * p.tiles_per_img;
+            const int tr = rem / p.ctl, tc = rem - tr * p.ctl;
+            const int n = n0 + img, row = row0 + tr * p.trows + dr, col = (tc << p.tcols_log2) + dc;
+            const bool ok = tile < p.n_tiles && n < p.N && row < p.H && row < row0 + p.TH && col < p.W;
+            const int pix = row * p.W + col;
+            e_off[t] = ok ? (int64_t)n * p.osn + pix : -1;
+            const int64_t roff = (int64_t)n * p.rsn + pix;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ko = co0 + m * 16 + kq * 4 + j;
+                    rv[t][m][j] = p.ep != EP_STORE && ok && ko < p.CO ? p.r[roff + (int64_t)ko * p.rsc] : 0.f;
+                }
+        }
+    };
+    if (kEarlySkip) locate_and_request();
+
     for (int c0 = 0; c0 < p.CI; c0 += KC) {
         __syncthreads();  // previous chunk fully consumed
         // ---- filter chunk: read global memory in its own order (runs of
@@ -232,33 +264,9 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
         }
     }
 
-    // ---- epilogue: lane holds channels co0 + m*16 + 4*kq + j (j = 0..3) of its pixel.
-    //      r may alias out (element for element), so the compiler cannot move a
-    //      skip load above an earlier store: all skip values are requested first.
-    int64_t e_off[NT];  // offset of (image, pixel) in out / r, -1: nothing to write
-    int64_t e_roff[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int tile = wave + kWaves * t;
-        const int img = tile / p.tiles_per_img, rem = tile - img * p.tiles_per_img;
-        const int tr = rem / p.ctl, tc = rem - tr * p.ctl;
-        const int n = n0 + img, row = row0 + tr * p.trows + dr, col = (tc << p.tcols_log2) + dc;
-        const bool ok = tile < p.n_tiles && n < p.N && row < p.H && row < row0 + p.TH && col < p.W;
-        const int pix = row * p.W + col;
-        e_off[t] = ok ? (int64_t)n * p.osn + pix : -1;
-        e_roff[t] = (int64_t)n * p.rsn + pix;
-    }
+    // ---- epilogue
+    if (!kEarlySkip) locate_and_request();
     if (p.ep != EP_STORE) {
-        float rv[NT][MT][4];
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int m = 0; m < MT; ++m)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int ko = co0 + m * 16 + kq * 4 + j;
-                    rv[t][m][j] = e_off[t] >= 0 && ko < p.CO ? p.r[e_roff[t] + (int64_t)ko * p.rsc] : 0.f;
-                }
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
