@@ -40,6 +40,9 @@ What it computes, and where the paper defines it:
                        inputs are stored; Section 3.2 end).  The paper does not
                        give its form; the reading taken here is stated at the
                        functions.
+* ``stem_fwd`` / ``stem_bwd`` -- the network's first, non-reversible layers
+                       (a convolution of the image, optionally followed by
+                       3x3 stride-2 max-pooling), whose inputs are stored.
 * ``body_fwd`` / ``body_bwd_stored`` / ``body_reverse`` -- stages of reversible
                        blocks joined by such blocks: ordinary backprop with
                        everything stored, and the memory-saving way (Algorithm
@@ -480,6 +483,65 @@ def down_bwd(stored, P, dy, eps=1e-5):
         d, dg, db = bn_relu_bwd(da, st, L["gamma"], eps)
         grads[l] = dict(w=dw, gamma=dg, beta=db)
     return d, dict(R=grads, S=dict(w=dws))
+
+
+# ---------------------------------------------------------------------------
+# stem: the first layers of the network, ahead of the reversible stages
+# (Section 3.2: non-reversible layers, inputs stored).  Reading (the paper only
+# cites the residual-network design it follows): a plain convolution of the
+# image, k x k with stride s and padding (k-1)/2, no bias, optionally followed
+# by max-pooling over 3x3 windows with stride 2 and padding 1 (positions
+# outside the image never win).  S = dict(w=[C0, C_img, k, k], stride=s,
+# pool=bool).  Where several elements of a window share the maximum, the first
+# in row-major order takes the whole derivative.
+# ---------------------------------------------------------------------------
+
+def maxpool3s2_fwd(x):
+    """Returns (y, arg): arg[n,c,p,q] = flat index (i*W + j) of the winning input element."""
+    n, c, h, w = x.shape
+    ho, wo = (h + 2 - 3) // 2 + 1, (w + 2 - 3) // 2 + 1
+    y = np.full((n, c, ho, wo), -np.inf, dtype=x.dtype)
+    arg = np.zeros((n, c, ho, wo), dtype=np.int64)
+    for r in range(3):
+        for s in range(3):
+            for p in range(ho):
+                i = 2 * p + r - 1
+                if i < 0 or i >= h:
+                    continue
+                for q in range(wo):
+                    j = 2 * q + s - 1
+                    if j < 0 or j >= w:
+                        continue
+                    v = x[:, :, i, j]
+                    better = v > y[:, :, p, q]          # strict: the first maximum in row-major order stays
+                    y[:, :, p, q] = np.where(better, v, y[:, :, p, q])
+                    arg[:, :, p, q] = np.where(better, i * w + j, arg[:, :, p, q])
+    return y, arg
+
+
+def maxpool3s2_bwd(dy, arg, in_hw):
+    n, c, ho, wo = dy.shape
+    h, w = in_hw
+    dx = np.zeros((n, c, h * w), dtype=dy.dtype)
+    flat_dy, flat_arg = dy.reshape(n, c, -1), arg.reshape(n, c, -1)
+    for k in range(ho * wo):   # windows overlap: accumulate one window position at a time
+        np.add.at(dx, (np.arange(n)[:, None], np.arange(c)[None, :], flat_arg[:, :, k]), flat_dy[:, :, k])
+    return dx.reshape(n, c, h, w)
+
+
+def stem_fwd(img, S):
+    """Returns the body's input and what backprop needs (the stored inputs of both layers)."""
+    h = conv_fwd(img, S["w"], S.get("stride", 1))
+    if S.get("pool", False):
+        y, arg = maxpool3s2_fwd(h)
+        return y, dict(img=img, h_hw=h.shape[2:], arg=arg)
+    return h, dict(img=img, h_hw=h.shape[2:], arg=None)
+
+
+def stem_bwd(stored, S, dy):
+    """Derivative with respect to the stem's filter (the image needs none)."""
+    dh = maxpool3s2_bwd(dy, stored["arg"], stored["h_hw"]) if stored["arg"] is not None else dy
+    return conv_wgrad(stored["img"], dh, S["w"].shape[2], S.get("stride", 1))
 
 
 def _halves(t):

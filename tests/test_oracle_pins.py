@@ -662,3 +662,52 @@ def test_fixed_point_stream_follows_the_real_valued_one(oracle):
         errs[fb] = oracle.rel_l2(np.concatenate([oracle.fixed_decode(t1, fb), oracle.fixed_decode(t2, fb)], 1),
                                  np.concatenate([r1, r2], 1))
     assert errs[12] < 2e-3 and errs[16] < errs[12] / 6 and errs[20] < errs[16] / 6, errs
+
+
+# --------------------------------------------------------------------------
+# stem: image convolution and max-pooling ahead of the reversible stages
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("ks,stride,pool,h,w", [(3, 1, False, 6, 5), (7, 2, True, 12, 10), (7, 2, True, 9, 11), (3, 1, True, 5, 7)])
+def test_stem_matches_autograd_library(oracle, ks, stride, pool, h, w):
+    """Convolution of the image (k x k, stride s, padding (k-1)/2) and 3x3
+    stride-2 max-pooling with padding 1: output and filter derivative equal the
+    library's conv2d / max_pool2d under autograd (float64; random inputs have no
+    ties)."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(61)
+    img = rng.standard_normal((2, 3, h, w))
+    wt = rng.standard_normal((5, 3, ks, ks))
+    S_ = dict(w=wt, stride=stride, pool=pool)
+    y, stored = oracle.stem_fwd(img, S_)
+    tw = torch.tensor(wt, requires_grad=True)
+    t = F.conv2d(torch.tensor(img), tw, stride=stride, padding=(ks - 1) // 2)
+    if pool:
+        t = F.max_pool2d(t, 3, 2, 1)
+    assert y.shape == tuple(t.shape)
+    assert oracle.rel_l2(y, t.detach().numpy()) < 1e-13
+    dy = rng.standard_normal(y.shape)
+    (t * torch.tensor(dy)).sum().backward()
+    assert oracle.rel_l2(oracle.stem_bwd(stored, S_, dy), tw.grad.numpy()) < 1e-12
+
+
+def test_maxpool_brute_force_and_tie_rule(oracle):
+    """Every output is the maximum over its (clipped) window; the derivative of
+    a window goes to one element only, the first maximal one in row-major
+    order, so the derivatives still sum to those of the output."""
+    rng = np.random.default_rng(62)
+    x = rng.integers(0, 3, size=(2, 2, 7, 6)).astype(np.float64)   # many ties
+    y, arg = oracle.maxpool3s2_fwd(x)
+    n, c, ho, wo = y.shape
+    assert (ho, wo) == (4, 3)
+    for i, k, p, q in itertools.product(range(n), range(c), range(ho), range(wo)):
+        r0, r1, c0, c1 = max(2 * p - 1, 0), min(2 * p + 2, 7), max(2 * q - 1, 0), min(2 * q + 2, 6)
+        win = x[i, k, r0:r1, c0:c1]
+        assert y[i, k, p, q] == win.max()
+        first = np.argwhere(win == win.max())[0]
+        assert arg[i, k, p, q] == (r0 + first[0]) * 6 + (c0 + first[1])
+    dy = rng.standard_normal(y.shape)
+    dx = oracle.maxpool3s2_bwd(dy, arg, (7, 6))
+    assert np.allclose(dx.sum(axis=(2, 3)), dy.sum(axis=(2, 3)), rtol=0, atol=1e-12)
+    assert ((dx != 0).sum(axis=(2, 3)) <= ho * wo).all()
