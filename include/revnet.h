@@ -319,6 +319,42 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
                     int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
 
 /* ------------------------------------------------------------------------
+ * Stem: the network's first layers, ahead of the body.  Non-reversible, so
+ * their inputs are stored (Section 3.2).  The paper follows the residual
+ * networks it cites for these layers; built here: a k x k convolution of the
+ * image (k odd, c_in * k * k <= 256, stride 1 or 2, zero padding (k-1)/2, no
+ * bias, fp32), optionally followed by max-pooling over 3x3 windows with stride
+ * 2 and padding 1.  img [n, c_in, h, w] -> conv_out [n, c_out, ho, wo],
+ * ho = (h-1)/stride + 1; with pool != 0: y [n, c_out, (ho-1)/2 + 1, (wo-1)/2 + 1].
+ * ---------------------------------------------------------------------- */
+typedef struct {
+    int32_t c_in, c_out, ks, stride;
+    int32_t pool; /* 0: the convolution's output is the stem's output */
+} rvn_stem_desc;
+
+/* Workspace bytes revnet_stem_bwd needs for an image batch of n x c_in x h x w. */
+int revnet_stem_workspace_bytes(const rvn_stem_desc *desc, int64_t n, int64_t h, int64_t w, size_t *bwd_bytes);
+
+/*
+ * img: read.  w: filter [c_out][c_in][ks][ks], device.  pool == 0: y receives
+ * the convolution and conv_out must be NULL.  pool != 0: conv_out receives the
+ * convolution (the caller keeps it for revnet_stem_bwd: it is the stored input
+ * of the pooling layer) and y the pooled result.  No overlaps.
+ */
+int revnet_stem_fwd(const rvn_stem_desc *desc, const rvn_tensor *img, const float *w,
+                    const rvn_tensor *conv_out, const rvn_tensor *y, void *hip_stream);
+
+/*
+ * d_w (+)= derivative with respect to the filter, from the stored img (and
+ * conv_out when pool != 0, else NULL) and dy, the derivative with respect to
+ * the stem's output.  A pooling window passes its derivative to its first
+ * maximal element in row-major order.  The image receives no derivative.
+ */
+int revnet_stem_bwd(const rvn_stem_desc *desc, const rvn_tensor *img, const rvn_tensor *conv_out,
+                    const rvn_tensor *dy, float *d_w, int accumulate_wgrads,
+                    void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ------------------------------------------------------------------------
  * Fixed-point residual stream (Section 3.2, "Numerical error": with the x's
  * and y's in fixed point and F, G in ordinary floating point the
  * reconstruction is exact, at little extra cost).

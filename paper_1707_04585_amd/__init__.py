@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     BodyDesc, DownDesc, pack_down, pack_stages, revnet_body_bwd, revnet_body_fwd, revnet_body_workspace_bytes,
     revnet_down_bwd, revnet_down_fwd, revnet_down_workspace_bytes,
     revnet_fixed_from_float, revnet_fixed_to_float, revnet_fixed_workspace_bytes, revnet_stack_bwd_fixed,
-    revnet_stack_fwd_fixed,
+    revnet_stack_fwd_fixed, revnet_stem_bwd, revnet_stem_fwd, revnet_stem_workspace_bytes, rvn_stem_desc,
 )

@@ -26,6 +26,7 @@ EXPORTS = [
     "revnet_body_workspace_bytes", "revnet_body_fwd", "revnet_body_bwd",
     "revnet_fixed_workspace_bytes", "revnet_fixed_from_float", "revnet_fixed_to_float",
     "revnet_stack_fwd_fixed", "revnet_stack_bwd_fixed",
+    "revnet_stem_workspace_bytes", "revnet_stem_fwd", "revnet_stem_bwd",
 ]
 
 MAX_STAGES = 8
@@ -66,6 +67,10 @@ class rvn_down_ptrs(C.Structure):  # rvn_down_params / rvn_down_grads
 class rvn_body_desc(C.Structure):
     _fields_ = [("stages", C.c_int32), ("stage", rvn_block_desc * MAX_STAGES), ("depth", C.c_int32 * MAX_STAGES),
                 ("down", rvn_down_desc * MAX_STAGES)]
+
+
+class rvn_stem_desc(C.Structure):
+    _fields_ = [("c_in", C.c_int32), ("c_out", C.c_int32), ("ks", C.c_int32), ("stride", C.c_int32), ("pool", C.c_int32)]
 
 
 class rvn_cost(C.Structure):
@@ -418,6 +423,30 @@ def revnet_stack_bwd_fixed(desc, depth, frac_bits, y1, y2, dy1, dy2, params, x1,
         C.byref(d), C.c_int32(depth), C.c_int32(frac_bits), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]),
         C.byref(t[3]), p, C.byref(t[4]), C.byref(t[5]), C.byref(t[6]), C.byref(t[7]), g,
         C.c_int(int(accumulate_wgrads)), C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
+
+
+def _opt_tensor(t):
+    return None if t is None else C.byref(_tensor(t))
+
+
+def revnet_stem_workspace_bytes(desc, n, h, w):
+    bwd = C.c_size_t(0)
+    _check(load_library().revnet_stem_workspace_bytes(C.byref(desc), C.c_int64(n), C.c_int64(h), C.c_int64(w), C.byref(bwd)))
+    return int(bwd.value)
+
+
+def revnet_stem_fwd(desc, img, w, conv_out, y, stream=None):
+    ti, ty = _tensor(img), _tensor(y)
+    _check(load_library().revnet_stem_fwd(C.byref(desc), C.byref(ti), C.c_void_p(_ptr(w)), _opt_tensor(conv_out),
+                                          C.byref(ty), C.c_void_p(_stream(stream))))
+
+
+def revnet_stem_bwd(desc, img, conv_out, dy, d_w, accumulate_wgrads, ws, stream=None):
+    ti, td = _tensor(img), _tensor(dy)
+    wp, wb = _ws(ws)
+    _check(load_library().revnet_stem_bwd(C.byref(desc), C.byref(ti), _opt_tensor(conv_out), C.byref(td),
+                                          C.c_void_p(_ptr(d_w)), C.c_int(int(accumulate_wgrads)), C.c_void_p(wp),
+                                          C.c_size_t(wb), C.c_void_p(_stream(stream))))
 
 
 def revnet_profile_begin():

@@ -46,6 +46,7 @@ enum KernelId {
     K_CONV_DGRAD_WGRAD,
     K_RESAMPLE,
     K_FIXED_POINT,
+    K_STEM,
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -246,6 +247,21 @@ void fix_to_float(Ctx &cx, View x, int c, Geo g, int frac_bits, float *out);
 void fix_axpy(Ctx &cx, View r, const float *f, int c, Geo g, int frac_bits, int sign, View out);
 // out (int32 codes) = rint(x * 2^frac_bits).
 void fix_from_float(Ctx &cx, View x, int c, Geo g, int frac_bits, View out);
+
+// ---- stem: image convolution and max-pooling ahead of the reversible stages ----
+// Direct fp32 kernels for a convolution whose input has a handful of channels
+// (c_in * k * k <= 256), stride 1 or 2, padding (k-1)/2; HO, WO are its output size.
+struct StemShape {
+    int N, CI, H, W, CO, KS, stride, HO, WO;
+};
+void stem_conv(Ctx &cx, View x, const float *w, const StemShape &g, View out);
+// dw[k][c][r][s] (+)= sum over output pixels of dh * x; scratch: stem_wgrad_scratch_floats(g) floats.
+size_t stem_wgrad_scratch_floats(const StemShape &g);
+void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, float *dw, bool accumulate);
+// 3x3 windows, stride 2, padding 1 (outside positions never win); output size ((h-1)/2+1, (w-1)/2+1).
+// The derivative of a window goes to its first maximal element in row-major order.
+void maxpool3s2_fwd(Ctx &cx, View x, int c, Geo in, View y);
+void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, float *dx);  // dx dense [n][c][h][w]
 
 // ---- stride-2 resampling for the non-reversible subsampling block ----------
 // `full` is the geometry of the high-resolution side (h, w even).

@@ -211,3 +211,22 @@ def test_fixed_point_entry_points_validate_arguments():
     assert status_of(rv.revnet_fixed_to_float, full, 16, strided)[0] == -3                     # destination must be dense
     assert status_of(rv.revnet_fixed_from_float, full, 40, full)[0] == -2
     assert status_of(rv.revnet_fixed_from_float, full, 16, fake(BASE + 64, c=8, sn=8 * 16))[0] == -6
+
+
+def test_stem_argument_validation():
+    d = rv.rvn_stem_desc(3, 8, 7, 2, 1)
+    img = fake(BASE, n=2, c=3, h=16, w=12, sn=3 * 192)
+    conv = fake(BASE + 0x100000, n=2, c=8, h=8, w=6, sn=8 * 48)
+    y = fake(BASE + 0x200000, n=2, c=8, h=4, w=3, sn=8 * 12)
+    bwd = rv.revnet_stem_workspace_bytes(d, 2, 16, 12)
+    assert bwd >= 2 * 8 * 48 * 4
+    assert status_of(rv.revnet_stem_workspace_bytes, rv.rvn_stem_desc(3, 8, 4, 2, 1), 2, 16, 12)[0] == -2    # even kernel
+    assert status_of(rv.revnet_stem_workspace_bytes, rv.rvn_stem_desc(8, 8, 7, 2, 1), 2, 16, 12)[0] == -2    # reduction too long
+    assert status_of(rv.revnet_stem_workspace_bytes, rv.rvn_stem_desc(3, 8, 7, 3, 1), 2, 16, 12)[0] == -2    # stride
+    assert status_of(rv.revnet_stem_fwd, d, img, 0x10, None, y)[0] == -1                                    # conv_out needed
+    assert status_of(rv.revnet_stem_fwd, d, img, 0x10, conv, fake(BASE + 0x200000, n=2, c=8, h=8, w=6, sn=8 * 48))[0] == -2
+    assert status_of(rv.revnet_stem_fwd, d, img, None, conv, y)[0] == -1
+    assert status_of(rv.revnet_stem_fwd, rv.rvn_stem_desc(3, 8, 7, 2, 0), img, 0x10, conv, conv)[0] == -2   # no pooling: no conv_out
+    assert status_of(rv.revnet_stem_bwd, d, img, conv, y, 0x10, 0, (BASE + 0x800000, bwd - 1))[0] == -5
+    assert status_of(rv.revnet_stem_bwd, d, img, conv, y, None, 0, (BASE + 0x800000, bwd))[0] == -1
+    assert status_of(rv.revnet_stem_bwd, d, img, conv, y, 0x10, 0, (BASE, bwd))[0] == -6
