@@ -103,27 +103,49 @@ def bench_body(args) -> int:
     import torch
     import synth_inputs as S
     import paper_1707_04585_amd as rv
-    from paper_1707_04585_amd.torch_harness import BodyRunner, _dev
-    cfg = dict(S.BODIES[args.workload])
-    seed = S.BASE_SEED + 100 + list(S.BODIES).index(args.workload)
-    x, stages, downs, dy = S.draw_body(seed, **cfg)
-    n, conv = cfg["n"], cfg["conv"]
+    from paper_1707_04585_amd.torch_harness import BodyRunner, NetRunner, _dev
+    is_net = args.workload in S.NETS
     torch.cuda.reset_peak_memory_stats()
-    r = BodyRunner(**cfg)
-    r.set_params(stages, downs)
+    if is_net:
+        seed = S.BASE_SEED + 200 + list(S.NETS).index(args.workload)
+        cfg, x, stem, stages, downs, dy = S.draw_net(seed, **S.NETS[args.workload])   # x: the image batch
+        net = NetRunner(cfg, stem)
+        r = net.body
+        net.set_params(stages, downs)
+    else:
+        cfg = dict(S.BODIES[args.workload])
+        seed = S.BASE_SEED + 100 + list(S.BODIES).index(args.workload)
+        x, stages, downs, dy = S.draw_body(seed, **cfg)
+        stem = None
+        r = BodyRunner(**cfg)
+        r.set_params(stages, downs)
+    n, conv = cfg["n"], cfg["conv"]
     base_alloc = torch.cuda.memory_allocated()
     X, DY = _dev(x, r.device), _dev(dy, r.device)
     stream = torch.cuda.current_stream()
 
     def step():
-        r.forward(X, stream)             # x -> top of every stage
-        r.dtops[-1].copy_(DY)            # the derivative arriving at the body's output
-        r.backward(stream=stream)        # tops reconstructed in place, dtops[0] = derivative at the input
+        if is_net:
+            net.forward(X, stream)       # image -> stem -> top of every stage
+        else:
+            r.forward(X, stream)         # x -> top of every stage
+        r.dtops[-1].copy_(DY)            # the derivative arriving at the last stage's top
+        if is_net:
+            net.backward(stream)         # ... down to the stem's filter gradient
+        else:
+            r.backward(stream=stream)    # tops reconstructed in place, dtops[0] = derivative at the input
 
     ms_per_step = timed_steps(torch, step, args.steps, args.warmup, stream)
     kern, roofline = profiled_pass(rv, torch, step, args.steps, conv, args.workload)
-    rec = float(np.linalg.norm(r.tops[0].cpu().numpy().astype(np.float64) - x) / np.linalg.norm(x))
-    act = r.activation_bytes()
+    if is_net:   # the body's input is the stem's output: compare the reconstruction with a fresh stem forward
+        ref0 = torch.empty_like(r.tops[0])
+        rv.revnet_stem_fwd(net.stem_desc, X, net.stem_w, net.conv_out, ref0, stream)
+        torch.cuda.synchronize()
+        x0 = ref0.cpu().numpy().astype(np.float64)
+    else:
+        x0 = x
+    rec = float(np.linalg.norm(r.tops[0].cpu().numpy().astype(np.float64) - x0) / np.linalg.norm(x0))
+    act = net.activation_bytes() if is_net else r.activation_bytes()
     shallow = BodyRunner(**dict(cfg, depths=tuple(1 for _ in cfg["depths"]))).activation_bytes()
     out = {
         "metric": "images/sec reversible fwd+bwd per stack on 1 MI355X; peak activation HBM bytes",
@@ -133,7 +155,10 @@ def bench_body(args) -> int:
         "dtype": "f32" if conv == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "kind": cfg["kind"], "n": n, "h": cfg["h"], "w": cfg["w"],
                    "channels": list(cfg["channels"]), "depths": list(cfg["depths"]), "widths": list(cfg["widths"]),
-                   "conv_operands": conv, "stem": "not part of the body: it starts at the stem's output"},
+                   "conv_operands": conv,
+                   "stem": (f"{stem['w'].shape[2]}x{stem['w'].shape[2]} stride {stem['stride']} convolution of a 3-channel "
+                            f"{x.shape[2]}x{x.shape[3]} image" + (", 3x3 stride-2 max-pooling" if stem["pool"] else "") + ", fp32")
+                   if is_net else "not part of the body: it starts at the stem's output"},
         "roofline": roofline,
         "kernels": kern,
         "peak_activation_bytes": {"analytic": act, "same_body_one_block_per_stage": shallow,
@@ -147,8 +172,13 @@ def bench_body(args) -> int:
         def oracle_pass(ns):
             with O.conv_operands(conv):
                 t0 = time.perf_counter()
-                _, kept = O.body_fwd(x[:ns], stages, downs, keep=True)
-                O.body_bwd_stored(kept, stages, downs, dy[:ns])
+                xin = x[:ns]
+                if is_net:
+                    xin, kept_stem = O.stem_fwd(xin, stem)
+                _, kept = O.body_fwd(xin, stages, downs, keep=True)
+                d0, _, _ = O.body_bwd_stored(kept, stages, downs, dy[:ns])
+                if is_net:
+                    O.stem_bwd(kept_stem, stem, d0)
                 return time.perf_counter() - t0
 
         ns = min(args.cpu_sample_n, n) if args.cpu_sample_n else min(2, n)
@@ -196,7 +226,7 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     rv.load_library()  # fails loudly if the HIP library is missing
-    if args.workload in S.BODIES:
+    if args.workload in S.BODIES or args.workload in S.NETS:
         return bench_body(args)
 
     cfg, x, params, dy = S.draw_named(args.workload)

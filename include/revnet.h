@@ -322,7 +322,7 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
  * Stem: the network's first layers, ahead of the body.  Non-reversible, so
  * their inputs are stored (Section 3.2).  The paper follows the residual
  * networks it cites for these layers; built here: a k x k convolution of the
- * image (k odd, c_in * k * k <= 256, stride 1 or 2, zero padding (k-1)/2, no
+ * image (k = 1, 3, 5 or 7, c_in * k * k <= 256, stride 1 or 2, zero padding (k-1)/2, no
  * bias, fp32), optionally followed by max-pooling over 3x3 windows with stride
  * 2 and padding 1.  img [n, c_in, h, w] -> conv_out [n, c_out, ho, wo],
  * ho = (h-1)/stride + 1; with pool != 0: y [n, c_out, (ho-1)/2 + 1, (wo-1)/2 + 1].

@@ -261,7 +261,9 @@ void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, fl
 // 3x3 windows, stride 2, padding 1 (outside positions never win); output size ((h-1)/2+1, (w-1)/2+1).
 // The derivative of a window goes to its first maximal element in row-major order.
 void maxpool3s2_fwd(Ctx &cx, View x, int c, Geo in, View y);
-void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, float *dx);  // dx dense [n][c][h][w]
+// dx dense [n][c][h][w]; scratch: maxpool3s2_scratch_bytes(c, in) bytes (the windows' winners).
+size_t maxpool3s2_scratch_bytes(int c, Geo in);
+void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, unsigned char *scratch, float *dx);
 
 // ---- stride-2 resampling for the non-reversible subsampling block ----------
 // `full` is the geometry of the high-resolution side (h, w even).

@@ -1148,8 +1148,8 @@ namespace {
 int check_stem(const rvn_stem_desc *d, int64_t n, int64_t h, int64_t w, StemShape *g) {
     if (!d) return fail(RVN_ERR_NULL, "descriptor is NULL");
     if (d->c_in <= 0 || d->c_out <= 0 || d->c_out > 65536) return fail(RVN_ERR_SHAPE, "c_in = %d, c_out = %d out of range", d->c_in, d->c_out);
-    if (d->ks < 1 || d->ks % 2 == 0 || (int64_t)d->c_in * d->ks * d->ks > 256)
-        return fail(RVN_ERR_SHAPE, "ks = %d must be odd with c_in * ks * ks <= 256 (c_in = %d)", d->ks, d->c_in);
+    if (d->ks < 1 || d->ks > 7 || d->ks % 2 == 0 || (int64_t)d->c_in * d->ks * d->ks > 256)
+        return fail(RVN_ERR_SHAPE, "ks = %d must be 1, 3, 5 or 7 with c_in * ks * ks <= 256 (c_in = %d)", d->ks, d->c_in);
     if (d->stride != 1 && d->stride != 2) return fail(RVN_ERR_SHAPE, "stride = %d must be 1 or 2", d->stride);
     if (int rc = check_geo(n, h, w)) return rc;
     *g = StemShape{(int)n, d->c_in, (int)h, (int)w, d->c_out, d->ks, d->stride, (int)((h - 1) / d->stride + 1),
@@ -1158,7 +1158,9 @@ int check_stem(const rvn_stem_desc *d, int64_t n, int64_t h, int64_t w, StemShap
 }
 
 struct StemPlan {
-    size_t dh, part, total;  // pooled derivative spread back to the convolution's output; filter-gradient partial sums
+    // pooled derivative spread back to the convolution's output; the pooling windows' winners;
+    // filter-gradient partial sums
+    size_t dh, arg, part, total;
 };
 
 StemPlan make_stem_plan(const rvn_stem_desc &d, const StemShape &g) {
@@ -1166,6 +1168,8 @@ StemPlan make_stem_plan(const rvn_stem_desc &d, const StemShape &g) {
     size_t off = 0;
     p.dh = off;
     if (d.pool) off = align_up(off + (size_t)g.N * g.CO * g.HO * g.WO * 4);
+    p.arg = off;
+    if (d.pool) off = align_up(off + maxpool3s2_scratch_bytes(g.CO, Geo{g.N, g.HO, g.WO}));
     p.part = off;
     off = align_up(off + stem_wgrad_scratch_floats(g) * 4);
     p.total = off;
@@ -1234,7 +1238,7 @@ int revnet_stem_bwd(const rvn_stem_desc *desc, const rvn_tensor *img, const rvn_
     if (overlaps_range(img, ws, pl.total) || overlaps_range(dy, ws, pl.total) || overlaps_range(conv_out, ws, pl.total))
         return fail(RVN_ERR_ALIAS, "a tensor overlaps the workspace");
     float *dh = reinterpret_cast<float *>(base + pl.dh);
-    maxpool3s2_bwd(cx, view_of(conv_out), view_of(dy), g.CO, mid, dh);
+    maxpool3s2_bwd(cx, view_of(conv_out), view_of(dy), g.CO, mid, reinterpret_cast<unsigned char *>(base + pl.arg), dh);
     stem_wgrad(cx, view_of(img), dense_view(dh, g.CO, mid), g, part, d_w, accumulate_wgrads != 0);
     return finish(cx);
 }

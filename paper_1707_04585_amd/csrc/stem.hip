@@ -8,9 +8,10 @@
 //   stem_conv_k    one thread per output pixel and 16 output channels; the
 //                  filters of those channels sit in LDS and are read as
 //                  broadcasts, the image through the vector cache.
-//   stem_wgrad_k   one thread per filter tap (c, r, s) and 8 output channels,
-//                  one workgroup per chunk of output pixels; partial sums per
-//                  chunk, added in a fixed order by stem_wgrad_reduce_k.
+//   stem_wgrad_k   one workgroup per filter row (c, r), 8 output channels and
+//                  chunk of output pixels, threads striding over the pixels;
+//                  partial sums per chunk, added in a fixed order by
+//                  stem_wgrad_reduce_k.
 //   maxpool_fwd_k  one thread per output element.
 //   maxpool_bwd_k  one thread per input element: it looks at the (at most four)
 //                  windows that contain it and takes the derivative of those
@@ -69,45 +70,66 @@ __global__ __launch_bounds__(kThreads) void stem_conv_k(const float *__restrict_
 }
 
 // part[chunk][k][tap] over the chunk's output pixels [chunk*per, (chunk+1)*per).
+// A workgroup owns 8 output channels and one filter row (c, r); its threads
+// stride over the chunk's pixels, so the loads of dh (8 planes) and of the
+// image row (KS neighbouring values) are coalesced across the lanes, and each
+// thread keeps 8 x KS sums in registers.  At the end the sums are added over
+// the workgroup: butterfly within a wavefront, then one thread per sum adds the
+// four wavefronts' values in order.
+template <int KS>
 __global__ __launch_bounds__(kThreads) void stem_wgrad_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
                                                          const float *__restrict__ dh, int64_t dsn, int64_t dsc,
                                                          float *__restrict__ part, StemShape g, int64_t pixels,
                                                          int64_t per) {
-    const int taps = g.CI * g.KS * g.KS, pad = (g.KS - 1) / 2;
-    const int t = threadIdx.x;
-    if (t >= taps) return;
-    const int c = t / (g.KS * g.KS), rs = t - c * (g.KS * g.KS), r = rs / g.KS, s = rs - r * g.KS;
+    __shared__ float red[kThreads / 64][kWgradKG * KS];
+    const int pad = (KS - 1) / 2, taps = g.CI * KS * KS;
     const int k0 = blockIdx.y * kWgradKG;
-    float acc[kWgradKG];
-#pragma unroll
-    for (int kk = 0; kk < kWgradKG; ++kk) acc[kk] = 0.f;
-    const int64_t i0 = (int64_t)blockIdx.x * per, i1 = min(pixels, i0 + per);
-    int q = (int)(i0 % g.WO);
-    int64_t t1 = i0 / g.WO;
-    int p = (int)(t1 % g.HO);
-    int64_t n = t1 / g.HO;
-    for (int64_t i = i0; i < i1; ++i) {
-        const int ih = p * g.stride + r - pad, iw = q * g.stride + s - pad;
-        const bool in = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
-        const float v = in ? x[n * xsn + (int64_t)c * xsc + ih * g.W + iw] : 0.f;
-        const float *d = dh + n * dsn + p * g.WO + q;  // the same address in every lane: one request
-#pragma unroll
-        for (int kk = 0; kk < kWgradKG; ++kk) {
-            const int k = min(k0 + kk, g.CO - 1);
-            acc[kk] = fmaf(d[(int64_t)k * dsc], v, acc[kk]);
-        }
-        if (++q == g.WO) {
-            q = 0;
-            if (++p == g.HO) {
-                p = 0;
-                ++n;
-            }
-        }
-    }
-    float *o = part + ((int64_t)blockIdx.x * g.CO) * taps;
+    const int c = blockIdx.z / KS, r = blockIdx.z - c * KS;
+    const int HWO = g.HO * g.WO;
+    float acc[kWgradKG][KS];
 #pragma unroll
     for (int kk = 0; kk < kWgradKG; ++kk)
-        if (k0 + kk < g.CO) o[(int64_t)(k0 + kk) * taps + t] = acc[kk];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) acc[kk][s] = 0.f;
+    const int64_t i0 = (int64_t)blockIdx.x * per, i1 = min(pixels, i0 + per);
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += kThreads) {
+        const int64_t n = i / HWO;
+        const int pq = (int)(i - n * HWO);
+        const int p = pq / g.WO, q = pq - p * g.WO;
+        const int ih = p * g.stride + r - pad;
+        if (ih < 0 || ih >= g.H) continue;
+        const float *xrow = x + n * xsn + (int64_t)c * xsc + ih * g.W;
+        float v[KS], d[kWgradKG];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int iw = q * g.stride + s - pad;
+            v[s] = iw >= 0 && iw < g.W ? xrow[iw] : 0.f;
+        }
+        const float *dp = dh + n * dsn + pq;
+#pragma unroll
+        for (int kk = 0; kk < kWgradKG; ++kk) d[kk] = dp[(int64_t)min(k0 + kk, g.CO - 1) * dsc];
+#pragma unroll
+        for (int kk = 0; kk < kWgradKG; ++kk)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) acc[kk][s] = fmaf(d[kk], v[s], acc[kk][s]);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int kk = 0; kk < kWgradKG; ++kk)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            float a = acc[kk][s];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
+            if (lane == 0) red[wave][kk * KS + s] = a;
+        }
+    __syncthreads();
+    if (threadIdx.x < kWgradKG * KS) {
+        const int kk = threadIdx.x / KS, s = threadIdx.x - kk * KS;
+        const float sum = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+        if (k0 + kk < g.CO)
+            part[((int64_t)blockIdx.x * g.CO + (k0 + kk)) * taps + (c * KS + r) * KS + s] = sum;
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void stem_wgrad_reduce_k(const float *__restrict__ part, float *__restrict__ dw,
@@ -160,7 +182,26 @@ __global__ __launch_bounds__(kThreads) void maxpool_fwd_k(const float *__restric
     y[n * ysn + (int64_t)c * ysc + p * WO + q] = best;
 }
 
-__global__ __launch_bounds__(kThreads) void maxpool_bwd_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
+// arg[n][c][p][q] = 3*r + s of the window's winner (dense bytes).
+__global__ __launch_bounds__(kThreads) void maxpool_arg_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
+                                                          unsigned char *__restrict__ arg, int C, int H, int W, int HO,
+                                                          int WO, int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (e >= total) return;
+    const int q = (int)(e % WO);
+    int64_t t = e / WO;
+    const int p = (int)(t % HO);
+    t /= HO;
+    const int c = (int)(t % C);
+    const int64_t n = t / C;
+    float best;
+    int bi, bj;
+    window_winner(x + n * xsn + (int64_t)c * xsc, H, W, p, q, &best, &bi, &bj);
+    arg[e] = (unsigned char)((bi - (2 * p - 1)) * 3 + (bj - (2 * q - 1)));
+}
+
+// dx[n][c][i][j] (dense) = sum of dy over the windows that (i, j) wins, in a fixed order.
+__global__ __launch_bounds__(kThreads) void maxpool_bwd_k(const unsigned char *__restrict__ arg,
                                                           const float *__restrict__ dy, int64_t dsn, int64_t dsc,
                                                           float *__restrict__ dx, int C, int H, int W, int HO, int WO,
                                                           int64_t total) {
@@ -172,20 +213,18 @@ __global__ __launch_bounds__(kThreads) void maxpool_bwd_k(const float *__restric
     t /= H;
     const int c = (int)(t % C);
     const int64_t n = t / C;
-    const float *plane = x + n * xsn + (int64_t)c * xsc;
+    const unsigned char *a = arg + (n * C + c) * (int64_t)(HO * WO);
     const float *g = dy + n * dsn + (int64_t)c * dsc;
     // windows p with 2p-1 <= i <= 2p+1
-    const int p_lo = max(0, i / 2), p_hi = min(HO - 1, (i + 1) / 2);
-    const int q_lo = max(0, j / 2), q_hi = min(WO - 1, (j + 1) / 2);
+    const int p_lo = i / 2, p_hi = min(HO - 1, (i + 1) / 2);
+    const int q_lo = j / 2, q_hi = min(WO - 1, (j + 1) / 2);
     float sum = 0.f;
     for (int p = p_lo; p <= p_hi; ++p)
         for (int q = q_lo; q <= q_hi; ++q) {
-            float best;
-            int bi, bj;
-            window_winner(plane, H, W, p, q, &best, &bi, &bj);
-            if (bi == i && bj == j) sum += g[p * WO + q];
+            const int mine = (i - (2 * p - 1)) * 3 + (j - (2 * q - 1));
+            if (a[p * WO + q] == mine) sum += g[p * WO + q];
         }
-    dx[e] = sum;  // dense [n][c][h][w]
+    dx[e] = sum;
 }
 
 unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
@@ -194,9 +233,9 @@ unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads
 
 int stem_wgrad_chunks(const StemShape &g) {
     const int64_t pixels = (int64_t)g.N * g.HO * g.WO;
-    const int groups = (g.CO + kWgradKG - 1) / kWgradKG;
-    int64_t chunks = std::max<int64_t>(1, 2048 / groups);
-    chunks = std::min<int64_t>(chunks, (pixels + 255) / 256);  // at least 256 pixels each
+    const int64_t tiles = (int64_t)((g.CO + kWgradKG - 1) / kWgradKG) * g.CI * g.KS;  // workgroups per chunk
+    int64_t chunks = (1024 + tiles - 1) / tiles;                 // about 1024 workgroups in all
+    chunks = std::min<int64_t>(chunks, (pixels + 1023) / 1024);  // at least 1024 pixels each
     return (int)std::max<int64_t>(chunks, 1);
 }
 
@@ -225,9 +264,15 @@ void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, fl
     const int chunks = stem_wgrad_chunks(g);
     const int64_t per = (pixels + chunks - 1) / chunks;
     if (cx.launch(K_STEM, 4.0 * ((double)g.N * g.CI * g.H * g.W + (double)pixels * g.CO), flops)) {
-        const dim3 grid((unsigned)chunks, (unsigned)((g.CO + kWgradKG - 1) / kWgradKG));
-        cx.run(stem_wgrad_k, grid, dim3(kThreads), 0, (const float *)x.p, x.sn, x.sc, (const float *)dh.p, dh.sn, dh.sc,
-               scratch, g, pixels, per);
+        const dim3 grid((unsigned)chunks, (unsigned)((g.CO + kWgradKG - 1) / kWgradKG), (unsigned)(g.CI * g.KS));
+        const float *xp = x.p, *dp = dh.p;
+        switch (g.KS) {
+            case 1: cx.run(stem_wgrad_k<1>, grid, dim3(kThreads), 0, xp, x.sn, x.sc, dp, dh.sn, dh.sc, scratch, g, pixels, per); break;
+            case 3: cx.run(stem_wgrad_k<3>, grid, dim3(kThreads), 0, xp, x.sn, x.sc, dp, dh.sn, dh.sc, scratch, g, pixels, per); break;
+            case 5: cx.run(stem_wgrad_k<5>, grid, dim3(kThreads), 0, xp, x.sn, x.sc, dp, dh.sn, dh.sc, scratch, g, pixels, per); break;
+            case 7: cx.run(stem_wgrad_k<7>, grid, dim3(kThreads), 0, xp, x.sn, x.sc, dp, dh.sn, dh.sc, scratch, g, pixels, per); break;
+            default: cx.fail(hipErrorInvalidValue);  // larger kernels are refused by the caller
+        }
     }
     if (cx.launch(K_STEM, 4.0 * (double)chunks * g.CO * taps))
         cx.run(stem_wgrad_reduce_k, dim3(blocks_for((int64_t)g.CO * taps)), dim3(kThreads), 0, (const float *)scratch, dw,
@@ -242,12 +287,21 @@ void maxpool3s2_fwd(Ctx &cx, View x, int c, Geo in, View y) {
            in.w, ho, wo, total);
 }
 
-void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, float *dx) {
+size_t maxpool3s2_scratch_bytes(int c, Geo in) {
+    return (size_t)in.n * c * ((in.h - 1) / 2 + 1) * ((in.w - 1) / 2 + 1);
+}
+
+void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, unsigned char *scratch, float *dx) {
     const int ho = (in.h - 1) / 2 + 1, wo = (in.w - 1) / 2 + 1;
-    const int64_t total = in.pixels() * c;
-    if (!cx.launch(K_STEM, 4.0 * (2.0 * (double)total + (double)in.n * c * ho * wo))) return;
-    cx.run(maxpool_bwd_k, dim3(blocks_for(total)), dim3(kThreads), 0, (const float *)x.p, x.sn, x.sc, (const float *)dy.p,
-           dy.sn, dy.sc, dx, c, in.h, in.w, ho, wo, total);
+    const int64_t total = in.pixels() * c, outs = (int64_t)in.n * c * ho * wo;
+    // the winners are found again from the stored input (one byte per window), then every input
+    // element collects from the windows it won
+    if (cx.launch(K_STEM, 4.0 * (double)total + (double)outs))
+        cx.run(maxpool_arg_k, dim3(blocks_for(outs)), dim3(kThreads), 0, (const float *)x.p, x.sn, x.sc, scratch, c, in.h, in.w,
+               ho, wo, outs);
+    if (cx.launch(K_STEM, 4.0 * (double)total + 5.0 * (double)outs))
+        cx.run(maxpool_bwd_k, dim3(blocks_for(total)), dim3(kThreads), 0, (const unsigned char *)scratch, (const float *)dy.p,
+               dy.sn, dy.sc, dx, c, in.h, in.w, ho, wo, total);
 }
 
 }  // namespace rvn

@@ -180,3 +180,52 @@ class BodyRunner:
         """Bytes alive between the end of forward and the end of backward."""
         acts = sum(t.numel() * 4 for t in self.tops)
         return dict(stream=acts, grads=acts, workspace=self.bwd_bytes, total=2 * acts + self.bwd_bytes)
+
+
+class NetRunner:
+    """Stem (image convolution, optional pooling) followed by a body: the whole
+    network up to the last stage's top.  Stored between forward and backward:
+    the image, the convolution's output when it is pooled, and one activation
+    per stage."""
+
+    def __init__(self, cfg, stem, device="cuda:0"):
+        self.body = BodyRunner(device=device, **cfg)
+        self.device = self.body.device
+        c0 = cfg["channels"][0]
+        ks = int(stem["w"].shape[2])
+        self.stem_desc = B.rvn_stem_desc(3, c0, ks, int(stem["stride"]), 1 if stem["pool"] else 0)
+        self.stem_w = _dev(stem["w"], self.device)
+        self.stem_dw = torch.zeros_like(self.stem_w)
+        self.pool = bool(stem["pool"])
+        self.stride = int(stem["stride"])
+        self.conv_out = None
+        self.ws = None
+
+    def set_params(self, stages, downs):
+        self.body.set_params(stages, downs)
+
+    def forward(self, img, stream=None):
+        n, _, h, w = img.shape
+        if self.pool and self.conv_out is None:
+            ho, wo = (h - 1) // self.stride + 1, (w - 1) // self.stride + 1
+            self.conv_out = torch.empty((n, self.stem_w.shape[0], ho, wo), dtype=torch.float32, device=self.device)
+        if self.ws is None:
+            self.ws = torch.empty(max(B.revnet_stem_workspace_bytes(self.stem_desc, n, h, w), 256), dtype=torch.uint8,
+                                  device=self.device)
+        self.img = img
+        # the stem writes the body's input into tops[0]; stage 0 then runs in place
+        B.revnet_stem_fwd(self.stem_desc, img, self.stem_w, self.conv_out, self.body.tops[0], stream)
+        self.body.forward(self.body.tops[0], stream)
+
+    def backward(self, stream=None):
+        """body.dtops[-1] holds the upstream derivative."""
+        self.body.backward(stream=stream)
+        B.revnet_stem_bwd(self.stem_desc, self.img, self.conv_out, self.body.dtops[0], self.stem_dw, 0, self.ws, stream)
+
+    def activation_bytes(self):
+        act = self.body.activation_bytes()
+        stem = self.img.numel() * 4 + (self.conv_out.numel() * 4 if self.conv_out is not None else 0)
+        act["stem_stored"] = stem
+        act["stem_workspace"] = self.ws.numel()
+        act["total"] += stem + self.ws.numel()
+        return act

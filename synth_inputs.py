@@ -134,6 +134,34 @@ def draw_body(seed, kind, n, h, w, channels, depths, widths, affine="random", **
     return x, stages, downs, dy
 
 
+# Whole networks up to the last stage's top: stem (image convolution, optional 3x3 stride-2 max-pooling)
+# followed by a body.  The image is N x 3 x H x W; the stem's output is the body's input.
+NETS = {
+    # name: body, image size, stem kernel / stride / pooling
+    "c3_net": dict(body="c3_body", img_h=32, img_w=32, stem_ks=3, stem_stride=1, stem_pool=False),
+    "c5_net": dict(body="c5_body", img_h=224, img_w=224, stem_ks=7, stem_stride=2, stem_pool=True),
+}
+
+
+def draw_net(seed, body, img_h, img_w, stem_ks, stem_stride, stem_pool, n=None, **body_override):
+    """Return (img, stem, x_shape, stages, downs, dy): img [N, 3, H, W] ~ N(0,1); stem = dict(w=He-normal
+    [C0, 3, k, k], stride=, pool=); the body's parameters and dy as draw_body draws them (its own x is not used)."""
+    cfg = dict(BODIES[body])
+    cfg.update(body_override)
+    if n is not None:
+        cfg["n"] = n
+    rng = np.random.default_rng(seed)
+    img = rng.standard_normal((cfg["n"], 3, img_h, img_w))
+    c0 = cfg["channels"][0]
+    w = rng.standard_normal((c0, 3, stem_ks, stem_ks)) * np.sqrt(2.0 / (3 * stem_ks * stem_ks))
+    ho, wo = (img_h - 1) // stem_stride + 1, (img_w - 1) // stem_stride + 1
+    if stem_pool:
+        ho, wo = (ho - 1) // 2 + 1, (wo - 1) // 2 + 1
+    assert (ho, wo) == (cfg["h"], cfg["w"]), "the stem's output must have the body's input size"
+    _, stages, downs, dy = draw_body(seed + 1, **cfg)
+    return cfg, img, dict(w=w, stride=stem_stride, pool=stem_pool), stages, downs, dy
+
+
 def draw_named(name, seed_offset=0, **override):
     cfg = dict(STACKS[name])
     cfg.update(override)

@@ -81,3 +81,60 @@ def test_stem_pooling_tie_rule_and_accumulate(oracle, torch_cuda):
     assert ties > 0, "the case is meant to contain tied windows"
     assert np.array_equal(y, y_ref)
     assert np.array_equal(dw, 2.0 * oracle.stem_bwd(stored, S_, dy))
+
+
+@pytest.mark.parametrize("name,n", [("c3_net", 4), ("c5_net", 1)])
+def test_whole_network_matches_oracle_fp32(oracle, torch_cuda, name, n):
+    """Stem, stages and subsampling blocks end to end at the real channel counts
+    and image sizes, one reversible block per stage, fp32 operands, small
+    batch: last stage's top and every parameter derivative (stem filter
+    included) against ordinary stored-activation backprop in float64.  The bar
+    allows for the few 0/1 ReLU decisions that fp32 sums take differently (see
+    test_body_real_shapes_reduced_batch): 3x the oracle's own float32-to-float64
+    distance where that exceeds 1e-4."""
+    import torch
+    import synth_inputs as S
+    from paper_1707_04585_amd.torch_harness import NetRunner, download_grads, download_down, _dev
+    from test_gpu_body import body_errors, cast_down
+    net = dict(S.NETS[name])
+    depths = tuple(1 for _ in S.BODIES[net["body"]]["depths"])
+    cfg, img, stem, stages, downs, dy = S.draw_net(95, n=n, depths=depths, conv="f32", **net)
+    img = img.astype(np.float32).astype(np.float64)
+
+    def oracle_run(dt):
+        c = lambda a: np.ascontiguousarray(a, dtype=dt)
+        st = [S.cast_params(s_, dt) for s_ in stages]
+        dn = [cast_down(P, dt) for P in downs]
+        sm = dict(stem, w=c(stem["w"]))
+        x0, kept_stem = oracle.stem_fwd(c(img), sm)
+        tops, kept = oracle.body_fwd(x0, st, dn, dt(1e-5), keep=True)
+        dx0, sg, dg = oracle.body_bwd_stored(kept, st, dn, c(dy), dt(1e-5))
+        return x0, tops, dx0, sg, dg, oracle.stem_bwd(kept_stem, sm, dx0)
+
+    x0, tops_ref, dx_ref, sg_ref, dg_ref, dws_ref = oracle_run(np.float64)
+    _, t32, dx32, sg32, dg32, dws32 = oracle_run(np.float32)
+    o32 = dict(tops=t32, x_rec=x0, dx=dx32, stage_grads=sg32, down_grads=dg32)
+    f_fwd, _, f_dx, f_g = body_errors(oracle, o32, tops_ref, dx_ref, sg_ref, dg_ref, x0)
+    floor = max(f_dx, max(f_g.values()), oracle.rel_l2(dws32, dws_ref))
+    tol = max(1e-4, 3.0 * floor)
+    print(f"{name}: floor (oracle float32 vs float64) {floor:.2e} -> gradient tolerance {tol:.2e}", flush=True)
+
+    r = NetRunner(cfg, stem)
+    r.set_params(stages, downs)
+    r.forward(_dev(img, "cuda:0"))
+    torch.cuda.synchronize()
+    tops = [t.cpu().numpy().astype(np.float64) for t in r.body.tops]
+    r.body.dtops[-1].copy_(_dev(dy, "cuda:0"))
+    r.backward()
+    torch.cuda.synchronize()
+    out = dict(tops=tops, x_rec=r.body.tops[0].cpu().numpy().astype(np.float64),
+               dx=r.body.dtops[0].cpu().numpy().astype(np.float64),
+               stage_grads=[download_grads(g) for g in r.body.stage_grads],
+               down_grads=[download_down(g) for g in r.body.down_grads])
+    fwd, rec, dx, g = body_errors(oracle, out, tops_ref, dx_ref, sg_ref, dg_ref, x0)
+    e_stem = oracle.rel_l2(r.stem_dw.cpu().numpy(), dws_ref)
+    worst = max(g, key=g.get)
+    print("  rel. errors: tops %.2e  stem output reconstructed %.2e  dx %.2e  stem filter gradient %.2e  worst other %s %.2e" %
+          (fwd, rec, dx, e_stem, worst, g[worst]), flush=True)
+    assert fwd < max(1e-5, 3.0 * f_fwd) and rec < 1e-5
+    assert dx < tol and e_stem < tol and g[worst] < tol
