@@ -153,12 +153,15 @@ def test_stack_matches_oracle(oracle, torch_cuda, name, conv):
     check_against_oracle(oracle, out, ref, x, conv, tol=tol)
 
 
-@pytest.mark.parametrize("kind,c,width,h,w", [
-    ("basic", 32, None, 16, 16), ("bottleneck", 64, 16, 14, 14),
+@pytest.mark.parametrize("kind,c,width,h,w,n", [
+    ("basic", 32, None, 16, 16, 8), ("bottleneck", 64, 16, 14, 14, 8),
     # ragged shapes for the bf16 kernels: H*W and W not multiples of 4 (unaligned 16-byte loads,
     # quads that run over row ends), channel counts that fill matrix-instruction tiles only partly
-    ("bottleneck", 96, 24, 9, 7), ("basic", 48, None, 10, 6), ("bottleneck", 64, 32, 5, 5)])
-def test_bf16_every_block_of_a_stack_from_oracle_inputs(oracle, torch_cuda, kind, c, width, h, w):
+    ("bottleneck", 96, 24, 9, 7, 5), ("basic", 48, None, 10, 6, 5), ("bottleneck", 64, 32, 5, 5, 5),
+    # the three stages of the 32x32 bf16 workload at their full batch, i.e. in the launch
+    # configuration the benchmark times
+    ("basic", 32, None, 32, 32, 128), ("basic", 64, None, 16, 16, 128), ("basic", 112, None, 8, 8, 128)])
+def test_bf16_every_block_of_a_stack_from_oracle_inputs(oracle, torch_cuda, kind, c, width, h, w, n):
     """bf16 operands, 2e-2 bar, block by block: block k of a 4-block stack gets
     the oracle's (x, y, ybar) of that block, so every block is checked at its
     real statistics without the divergence between two precisions compounding
@@ -166,8 +169,7 @@ def test_bf16_every_block_of_a_stack_from_oracle_inputs(oracle, torch_cuda, kind
     import torch
     import paper_1707_04585_amd as rv
     from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
-    cfg = dict(kind=kind, n=8 if h * w >= 100 else 5, c=c, h=h, w=w, depth=4, width=width, conv="bf16",
-               affine="random")
+    cfg = dict(kind=kind, n=n, c=c, h=h, w=w, depth=4, width=width, conv="bf16", affine="random")
     x, params, dy = S.draw_stack(4321, **cfg)
     with oracle.conv_operands("bf16"):
         x1, x2 = split(x)
