@@ -5,7 +5,10 @@
  * Backpropagation Without Storing Activations" (Gomez, Ren, Urtasun, Grosse,
  * 2017): the forward pass of a reversible block and the backward pass that
  * reconstructs the block's inputs from its outputs instead of reading stored
- * activations, for single blocks and for stacks of blocks.
+ * activations, for single blocks and for stacks of blocks.  Further entry
+ * points build whole networks around such stacks: the non-reversible
+ * subsampling block between stages, the multi-stage body, the stem, and a
+ * variant that keeps the residual stream in fixed point (exact reconstruction).
  *
  * Conventions common to every entry point
  * ---------------------------------------
