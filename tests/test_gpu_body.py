@@ -269,3 +269,43 @@ def test_body_full_size_properties(oracle, torch_cuda, name):
         assert np.array_equal(a["tops"][s], b["tops"][s])
     act = a["runner"].activation_bytes()
     print(f"{name}: activation bytes alive between forward and backward: {act}", flush=True)
+
+
+def test_down_block_with_gapped_planes(oracle, torch_cuda):
+    """Channel and image strides are free (sc >= h*w): every tensor of the call
+    is a view with a gap after each plane, fp32 and bf16."""
+    import torch
+    import paper_1707_04585_amd as rv
+    from paper_1707_04585_amd.torch_harness import upload_down, zeros_like_down, download_down, _dev
+    kind, n, c_in, c_out, h, w = "bottleneck", 3, 24, 40, 12, 8
+    rng = np.random.default_rng(78)
+    x = rng.standard_normal((n, c_in, h, w))
+    P = S.draw_down(rng, kind, c_in, c_out, "random")
+    dy = rng.standard_normal((n, c_out, h // 2, w // 2))
+
+    def gapped(shape, src=None):
+        nn, cc, hh, ww = shape
+        buf = torch.full((nn, cc, hh + 3, ww), float("nan"), dtype=torch.float32, device="cuda:0")
+        view = buf[:, :, :hh, :]
+        if src is not None:
+            view.copy_(_dev(src, "cuda:0"))
+        return buf, view
+
+    for conv in ("f32", "bf16"):
+        with oracle.conv_operands(conv):
+            y_ref, stored = oracle.down_fwd(x, P)
+            dx_ref, g_ref = oracle.down_bwd(stored, P, dy)
+        desc = rv.DownDesc(kind, c_in, c_out, 0, 1e-5, conv)
+        ws = torch.empty(max(rv.revnet_down_workspace_bytes(desc, n, h, w)), dtype=torch.uint8, device="cuda:0")
+        dp = upload_down(P)
+        dg = zeros_like_down(dp)
+        (_, X), (_, DY) = gapped(x.shape, x), gapped(dy.shape, dy)
+        (ybuf, Y), (dxbuf, DX) = gapped(dy.shape), gapped(x.shape)
+        rv.revnet_down_fwd(desc, X, dp, Y, ws)
+        rv.revnet_down_bwd(desc, X, DY, dp, DX, dg, 0, ws)
+        torch.cuda.synchronize()
+        assert torch.isnan(ybuf[:, :, h // 2:, :]).all() and torch.isnan(dxbuf[:, :, h:, :]).all(), "wrote into the gaps"
+        tol = TOL[conv]
+        assert oracle.rel_l2(Y.cpu().numpy(), y_ref) < tol["fwd"]
+        assert oracle.rel_l2(DX.cpu().numpy(), dx_ref) < tol["grad"]
+        assert max(down_errors(oracle, download_down(dg), g_ref).values()) < tol["grad"]
