@@ -246,6 +246,23 @@ def main() -> int:
     ms_per_step = timed_steps(torch, step, args.steps, args.warmup, stream)
     peak_alloc = torch.cuda.max_memory_allocated() - base_alloc
 
+    # ---- the two halves of a step on their own (Section 3.2 "Computational overhead": forward N,
+    #      reversible backward 3N, i.e. 4N against the 3N of backprop from stored activations)
+    ms_forward = timed_steps(torch, lambda: r.forward(X, Y, stream), args.steps, 1, stream)
+    r.forward(X, Y, stream)
+
+    def bwd_only():      # Y is reconstructed in place to x, so run forward untimed to restore it
+        r.backward(Y, DY, Y, DX, stream=stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ms_backward = 0.0
+    for _ in range(args.steps):
+        ev[0].record(stream)
+        bwd_only()
+        ev[1].record(stream)
+        r.forward(X, Y, stream)
+        torch.cuda.synchronize()
+        ms_backward += ev[0].elapsed_time(ev[1]) / args.steps
+
     kern, roofline = profiled_pass(rv, torch, step, args.steps, conv, args.workload)
 
     if args.copy_probe_mib:
@@ -300,6 +317,7 @@ def main() -> int:
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_forward": round(ms_forward, 4), "ms_backward": round(ms_backward, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if conv == "f32" else "bf16",
         "data": "synthetic",
