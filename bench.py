@@ -109,6 +109,7 @@ def bench_body(args) -> int:
     if is_net:
         seed = S.BASE_SEED + 200 + list(S.NETS).index(args.workload)
         cfg, x, stem, stages, downs, dy = S.draw_net(seed, **S.NETS[args.workload])   # x: the image batch
+        cfg["frac_bits"] = args.frac_bits
         net = NetRunner(cfg, stem)
         r = net.body
         net.set_params(stages, downs)
@@ -117,6 +118,7 @@ def bench_body(args) -> int:
         seed = S.BASE_SEED + 100 + list(S.BODIES).index(args.workload)
         x, stages, downs, dy = S.draw_body(seed, **cfg)
         stem = None
+        cfg["frac_bits"] = args.frac_bits
         r = BodyRunner(**cfg)
         r.set_params(stages, downs)
     n, conv = cfg["n"], cfg["conv"]
@@ -144,9 +146,16 @@ def bench_body(args) -> int:
         x0 = ref0.cpu().numpy().astype(np.float64)
     else:
         x0 = x
-    rec = float(np.linalg.norm(r.tops[0].cpu().numpy().astype(np.float64) - x0) / np.linalg.norm(x0))
+    if args.frac_bits:   # codes of the reconstructed stage-0 input against the encoded input
+        enc = torch.empty_like(r.tops[0])
+        rv.revnet_fixed_from_float(_dev(x0, r.device), args.frac_bits, enc, stream)
+        torch.cuda.synchronize()
+        rec = "exact" if torch.equal(enc.view(torch.int32), r.tops[0].view(torch.int32)) else "NOT exact"
+    else:
+        rec = float(np.linalg.norm(r.tops[0].cpu().numpy().astype(np.float64) - x0) / np.linalg.norm(x0))
     act = net.activation_bytes() if is_net else r.activation_bytes()
     shallow = BodyRunner(**dict(cfg, depths=tuple(1 for _ in cfg["depths"]))).activation_bytes()
+    cfg.pop("frac_bits")
     out = {
         "metric": "images/sec reversible fwd+bwd per stack on 1 MI355X; peak activation HBM bytes",
         "value": round(n / (ms_per_step * 1e-3), 1), "unit": "images/s",
@@ -156,6 +165,7 @@ def bench_body(args) -> int:
         "config": {"workload": args.workload, "kind": cfg["kind"], "n": n, "h": cfg["h"], "w": cfg["w"],
                    "channels": list(cfg["channels"]), "depths": list(cfg["depths"]), "widths": list(cfg["widths"]),
                    "conv_operands": conv,
+                   "residual_stream": f"fixed point, {args.frac_bits} fraction bits" if args.frac_bits else "fp32",
                    "stem": (f"{stem['w'].shape[2]}x{stem['w'].shape[2]} stride {stem['stride']} convolution of a 3-channel "
                             f"{x.shape[2]}x{x.shape[3]} image" + (", 3x3 stride-2 max-pooling" if stem["pool"] else "") + ", fp32")
                    if is_net else "not part of the body: it starts at the stem's output"},

@@ -321,6 +321,26 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
                     const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
                     int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * The body with a fixed-point residual stream (see revnet_stack_fwd_fixed
+ * further down for the format): tops hold int32 codes of 2^-frac_bits, x and
+ * dtops stay fp32.  x is encoded into tops[0]; a subsampling block reads its
+ * stored input decoded to fp32, and its fp32 output is encoded (rounded to the
+ * nearest code) into the next stage's tensor.  Every stage then reconstructs
+ * bit for bit in revnet_body_bwd_fixed, so the whole backward pass runs at
+ * exactly the forward activations.  x may be tops[0] itself (encoded in place).
+ */
+int revnet_body_fixed_workspace_bytes(const rvn_body_desc *desc, int64_t n, int64_t h, int64_t w,
+                                      size_t *fwd_bytes, size_t *bwd_bytes);
+int revnet_body_fwd_fixed(const rvn_body_desc *desc, int32_t frac_bits, const rvn_tensor *x,
+                          const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                          const rvn_tensor *tops, void *ws, size_t ws_bytes, void *hip_stream);
+int revnet_body_bwd_fixed(const rvn_body_desc *desc, int32_t frac_bits, const rvn_tensor *tops,
+                          const rvn_tensor *dtops,
+                          const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                          const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
+                          int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* ------------------------------------------------------------------------
  * Stem: the network's first layers, ahead of the body.  Non-reversible, so
  * their inputs are stored (Section 3.2).  The paper follows the residual

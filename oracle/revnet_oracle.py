@@ -606,6 +606,44 @@ def body_reverse(tops, stages, downs, dy, eps=1e-5):
     return d, sg, dg, recon
 
 
+def body_fwd_fixed(x, stages, downs, frac_bits, eps=1e-5, dtype=np.float64):
+    """body_fwd with the stage tensors in fixed point: x is encoded, every stage
+    runs on codes, a subsampling block reads the decoded top and its output is
+    encoded for the next stage.  Returns the tops (codes) and what stored
+    backprop needs."""
+    tops, kept = [], []
+    q = fixed_encode(x, frac_bits)
+    for s, params in enumerate(stages):
+        c = q.shape[1] // 2
+        y1, y2, st = stack_fwd_fixed(q[:, :c], q[:, c:], params, frac_bits, eps, dtype, keep=True)
+        top = np.concatenate([y1, y2], axis=1)
+        tops.append(top)
+        st_down = None
+        if s + 1 < len(stages):
+            y, st_down = down_fwd(fixed_decode(top, frac_bits, dtype), downs[s], eps)
+            q = fixed_encode(y, frac_bits)
+        kept.append((st, st_down))
+    return tops, kept
+
+
+def body_reverse_fixed(tops, stages, downs, dy, frac_bits, eps=1e-5, dtype=np.float64):
+    """The memory-saving backward pass of the fixed-point body; also returns each
+    stage's reconstructed input codes."""
+    sg, dg = [None] * len(stages), [None] * (len(stages) - 1)
+    recon = [None] * len(stages)
+    d = dy
+    for s in range(len(stages) - 1, -1, -1):
+        if s + 1 < len(stages):
+            _, st_down = down_fwd(fixed_decode(tops[s], frac_bits, dtype), downs[s], eps)
+            d, dg[s] = down_bwd(st_down, downs[s], d, eps)
+        c = tops[s].shape[1] // 2
+        d1, d2 = _halves(d)
+        (x1, x2), (d1, d2), sg[s] = stack_reverse_fixed(tops[s][:, :c], tops[s][:, c:], d1, d2, stages[s], frac_bits, eps, dtype)
+        recon[s] = np.concatenate([x1, x2], axis=1)
+        d = np.concatenate([d1, d2], axis=1)
+    return d, sg, dg, recon
+
+
 # ---------------------------------------------------------------------------
 # error measures used by tests and reports
 # ---------------------------------------------------------------------------

@@ -27,6 +27,7 @@ EXPORTS = [
     "revnet_fixed_workspace_bytes", "revnet_fixed_from_float", "revnet_fixed_to_float",
     "revnet_stack_fwd_fixed", "revnet_stack_bwd_fixed",
     "revnet_stem_workspace_bytes", "revnet_stem_fwd", "revnet_stem_bwd",
+    "revnet_body_fixed_workspace_bytes", "revnet_body_fwd_fixed", "revnet_body_bwd_fixed",
 ]
 
 MAX_STAGES = 8
@@ -423,6 +424,39 @@ def revnet_stack_bwd_fixed(desc, depth, frac_bits, y1, y2, dy1, dy2, params, x1,
         C.byref(d), C.c_int32(depth), C.c_int32(frac_bits), C.byref(t[0]), C.byref(t[1]), C.byref(t[2]),
         C.byref(t[3]), p, C.byref(t[4]), C.byref(t[5]), C.byref(t[6]), C.byref(t[7]), g,
         C.c_int(int(accumulate_wgrads)), C.c_void_p(wp), C.c_size_t(wb), C.c_void_p(_stream(stream))))
+
+
+def revnet_body_fixed_workspace_bytes(desc, n, h, w):
+    fwd, bwd = C.c_size_t(0), C.c_size_t(0)
+    d = _desc(desc)
+    _check(load_library().revnet_body_fixed_workspace_bytes(C.byref(d), C.c_int64(n), C.c_int64(h), C.c_int64(w),
+                                                            C.byref(fwd), C.byref(bwd)))
+    return int(fwd.value), int(bwd.value)
+
+
+def revnet_body_fwd_fixed(desc, frac_bits, x, stage_params, down_params, tops, ws, stream=None):
+    d = _desc(desc)
+    sp, keep = pack_stages(stage_params)
+    dp = pack_down(down_params)
+    wp, wb = _ws(ws)
+    tx, tt = _tensor(x), _tensor_array(tops)
+    _check(load_library().revnet_body_fwd_fixed(C.byref(d), C.c_int32(frac_bits), C.byref(tx), sp, dp, tt, C.c_void_p(wp),
+                                                C.c_size_t(wb), C.c_void_p(_stream(stream))))
+    del keep
+
+
+def revnet_body_bwd_fixed(desc, frac_bits, tops, dtops, stage_params, down_params, stage_grads, down_grads,
+                          accumulate_wgrads, ws, stream=None):
+    d = _desc(desc)
+    sp, keep_p = pack_stages(stage_params)
+    sg, keep_g = pack_stages(stage_grads)
+    dp, dg = pack_down(down_params), pack_down(down_grads)
+    wp, wb = _ws(ws)
+    tt, td = _tensor_array(tops), _tensor_array(dtops)
+    _check(load_library().revnet_body_bwd_fixed(C.byref(d), C.c_int32(frac_bits), tt, td, sp, dp, sg, dg,
+                                                C.c_int(int(accumulate_wgrads)), C.c_void_p(wp), C.c_size_t(wb),
+                                                C.c_void_p(_stream(stream))))
+    del keep_p, keep_g
 
 
 def _opt_tensor(t):

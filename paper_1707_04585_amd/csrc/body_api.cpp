@@ -305,14 +305,35 @@ int check_body_desc(const rvn_body_desc *bd, int64_t n, int64_t h, int64_t w) {
     return RVN_OK;
 }
 
-size_t body_ws_bytes(const rvn_body_desc &bd, const Geo &g0, bool backward) {
-    size_t need = 0;
+// Workspace of a body call: the largest need of any stage or subsampling block.
+// With a fixed-point stream two fp32 tensors follow it: the input of the
+// subsampling block at hand (the stored top, decoded) and its output (before
+// it is encoded into the next stage's tensor).
+struct BodyWs {
+    size_t plan, xin, yout, total;
+};
+
+BodyWs body_ws(const rvn_body_desc &bd, const Geo &g0, bool backward, bool fixed) {
+    BodyWs w{};
+    size_t in_max = 0, out_max = 0;
     for (int s = 0; s < bd.stages; ++s) {
         const Geo g{g0.n, g0.h >> s, g0.w >> s};
-        need = std::max(need, make_plan(bd.stage[s], g, backward).total);
-        if (s + 1 < bd.stages) need = std::max(need, make_down_plan(bd.down[s], g, backward).total);
+        w.plan = std::max(w.plan, make_plan(bd.stage[s], g, backward, fixed).total);
+        if (s + 1 < bd.stages) {
+            w.plan = std::max(w.plan, make_down_plan(bd.down[s], g, backward).total);
+            in_max = std::max(in_max, (size_t)g.pixels() * bd.down[s].c_in * 4);
+            out_max = std::max(out_max, (size_t)(g.pixels() / 4) * bd.down[s].c_out * 4);
+        }
     }
-    return need;
+    w.plan = align_up(w.plan);
+    w.xin = w.plan;
+    w.yout = w.xin + (fixed ? align_up(in_max) : 0);
+    w.total = w.yout + (fixed ? align_up(out_max) : 0);
+    return w;
+}
+
+size_t body_ws_bytes(const rvn_body_desc &bd, const Geo &g0, bool backward, bool fixed = false) {
+    return body_ws(bd, g0, backward, fixed).total;
 }
 
 View half_view(const rvn_tensor *t, int which) {
@@ -403,9 +424,14 @@ int check_body_tensors(const rvn_body_desc &bd, const char *name, const rvn_tens
 
 }  // namespace
 
-int revnet_body_fwd(const rvn_body_desc *desc, const rvn_tensor *x, const rvn_block_params *const *stage_params,
-                    const rvn_down_params *down_params, const rvn_tensor *tops, void *ws, size_t ws_bytes,
-                    void *hip_stream) {
+namespace {
+
+// frac_bits > 0: the tops hold fixed-point codes (x is fp32 and is encoded into
+// tops[0]; every subsampling block reads the decoded top and its fp32 output is
+// encoded into the next stage's tensor).
+int body_fwd_impl(const rvn_body_desc *desc, const rvn_tensor *x, const rvn_block_params *const *stage_params,
+                  const rvn_down_params *down_params, const rvn_tensor *tops, void *ws, size_t ws_bytes,
+                  void *hip_stream, int frac_bits) {
     if (!x) return fail(RVN_ERR_NULL, "tensor x is NULL");
     if (int rc = check_body_desc(desc, x->n, x->h, x->w)) return rc;
     const rvn_body_desc &bd = *desc;
@@ -423,7 +449,8 @@ int revnet_body_fwd(const rvn_body_desc *desc, const rvn_tensor *x, const rvn_bl
         if (!same && overlaps(x, &tops[s])) return fail(RVN_ERR_ALIAS, "x and tops[%d] overlap", s);
     }
     const Geo g0{(int)x->n, (int)x->h, (int)x->w};
-    const size_t need = body_ws_bytes(bd, g0, false);
+    const BodyWs bw = body_ws(bd, g0, false, frac_bits != 0);
+    const size_t need = bw.total;
     if (int rc = check_ws(ws, ws_bytes, need)) return rc;
     if (overlaps_range(x, ws, need)) return fail(RVN_ERR_ALIAS, "x overlaps the workspace");
     for (int s = 0; s < bd.stages; ++s)
@@ -432,23 +459,57 @@ int revnet_body_fwd(const rvn_body_desc *desc, const rvn_tensor *x, const rvn_bl
     cx.stream = static_cast<hipStream_t>(hip_stream);
     for (int s = 0; s < bd.stages; ++s) {
         const Geo g{g0.n, g0.h >> s, g0.w >> s};
-        const Plan pl = make_plan(bd.stage[s], g, false);
+        const Plan pl = make_plan(bd.stage[s], g, false, frac_bits != 0);
         const rvn_tensor *in = s == 0 ? x : &tops[s];  // later stages run in place on the subsampling block's output
+        if (frac_bits && s == 0) {
+            fix_from_float(cx, view_of(x), (int)x->c, g, frac_bits, view_of(&tops[0]));
+            in = &tops[0];
+        }
         stack_forward(cx, bd.stage[s], bd.depth[s], pl, bind(pl, ws), g, half_view(in, 0), half_view(in, 1),
-                      stage_params[s], half_view(&tops[s], 0), half_view(&tops[s], 1));
+                      stage_params[s], half_view(&tops[s], 0), half_view(&tops[s], 1), frac_bits);
         if (s + 1 < bd.stages) {
             const DownPlan dp = make_down_plan(bd.down[s], g, false);
-            down_forward(cx, bd.down[s], dp, bind(dp, ws, false), view_of(&tops[s]), down_params[s], view_of(&tops[s + 1]),
-                         false);
+            if (frac_bits) {
+                char *base = static_cast<char *>(ws);
+                float *xin = reinterpret_cast<float *>(base + bw.xin), *yout = reinterpret_cast<float *>(base + bw.yout);
+                const Geo low{g.n, g.h / 2, g.w / 2};
+                fix_to_float(cx, view_of(&tops[s]), bd.down[s].c_in, g, frac_bits, xin);
+                const View yv = dense_view(yout, bd.down[s].c_out, low);
+                down_forward(cx, bd.down[s], dp, bind(dp, ws, false), dense_view(xin, bd.down[s].c_in, g), down_params[s], yv,
+                             false);
+                fix_from_float(cx, yv, bd.down[s].c_out, low, frac_bits, view_of(&tops[s + 1]));
+            } else {
+                down_forward(cx, bd.down[s], dp, bind(dp, ws, false), view_of(&tops[s]), down_params[s],
+                             view_of(&tops[s + 1]), false);
+            }
         }
     }
     return finish(cx);
 }
 
-int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn_tensor *dtops,
-                    const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
-                    const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
-                    int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream) {
+}  // namespace
+
+int revnet_body_fwd(const rvn_body_desc *desc, const rvn_tensor *x, const rvn_block_params *const *stage_params,
+                    const rvn_down_params *down_params, const rvn_tensor *tops, void *ws, size_t ws_bytes,
+                    void *hip_stream) {
+    return body_fwd_impl(desc, x, stage_params, down_params, tops, ws, ws_bytes, hip_stream, 0);
+}
+
+int revnet_body_fwd_fixed(const rvn_body_desc *desc, int32_t frac_bits, const rvn_tensor *x,
+                          const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                          const rvn_tensor *tops, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (frac_bits < 1 || frac_bits > 30) return fail(RVN_ERR_SHAPE, "frac_bits = %d out of range [1, 30]", frac_bits);
+    return body_fwd_impl(desc, x, stage_params, down_params, tops, ws, ws_bytes, hip_stream, frac_bits);
+}
+
+
+
+namespace {
+
+int body_bwd_impl(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn_tensor *dtops,
+                  const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                  const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
+                  int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream, int frac_bits) {
     if (!tops) return fail(RVN_ERR_NULL, "tops is NULL");
     if (int rc = check_body_desc(desc, tops[0].n, tops[0].h, tops[0].w)) return rc;
     const rvn_body_desc &bd = *desc;
@@ -471,7 +532,8 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
             if (overlaps(&tops[s], &dtops[r])) return fail(RVN_ERR_ALIAS, "tops[%d] and dtops[%d] overlap", s, r);
     }
     const Geo g0{(int)n, (int)h, (int)w};
-    const size_t need = body_ws_bytes(bd, g0, true);
+    const BodyWs bw = body_ws(bd, g0, true, frac_bits != 0);
+    const size_t need = bw.total;
     if (int rc = check_ws(ws, ws_bytes, need)) return rc;
     for (int s = 0; s < bd.stages; ++s)
         if (overlaps_range(&tops[s], ws, need) || overlaps_range(&dtops[s], ws, need))
@@ -484,16 +546,52 @@ int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn
         if (s + 1 < bd.stages) {
             // dtops[s+1] now holds the derivative with respect to this block's output
             const DownPlan dp = make_down_plan(bd.down[s], g, true);
-            down_backward(cx, bd.down[s], dp, bind(dp, ws, true), view_of(&tops[s]), view_of(&dtops[s + 1]), down_params[s],
+            View xin = view_of(&tops[s]);
+            if (frac_bits) {  // the stored input, decoded
+                float *xf = reinterpret_cast<float *>(static_cast<char *>(ws) + bw.xin);
+                fix_to_float(cx, xin, bd.down[s].c_in, g, frac_bits, xf);
+                xin = dense_view(xf, bd.down[s].c_in, g);
+            }
+            down_backward(cx, bd.down[s], dp, bind(dp, ws, true), xin, view_of(&dtops[s + 1]), down_params[s],
                           view_of(&dtops[s]), down_grads[s], acc);
         }
-        const Plan pl = make_plan(bd.stage[s], g, true);
+        const Plan pl = make_plan(bd.stage[s], g, true, frac_bits != 0);
         const View t1 = half_view(&tops[s], 0), t2 = half_view(&tops[s], 1);
         const View d1 = half_view(&dtops[s], 0), d2 = half_view(&dtops[s], 1);
         stack_backward(cx, bd.stage[s], bd.depth[s], pl, bind(pl, ws), g, t1, t2, d1, d2, stage_params[s], t1, t2, d1, d2,
-                       stage_grads[s], acc);
+                       stage_grads[s], acc, frac_bits);
     }
     return finish(cx);
 }
+
+}  // namespace
+
+int revnet_body_bwd(const rvn_body_desc *desc, const rvn_tensor *tops, const rvn_tensor *dtops,
+                    const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                    const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
+                    int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream) {
+    return body_bwd_impl(desc, tops, dtops, stage_params, down_params, stage_grads, down_grads, accumulate_wgrads, ws,
+                         ws_bytes, hip_stream, 0);
+}
+
+int revnet_body_bwd_fixed(const rvn_body_desc *desc, int32_t frac_bits, const rvn_tensor *tops, const rvn_tensor *dtops,
+                          const rvn_block_params *const *stage_params, const rvn_down_params *down_params,
+                          const rvn_block_grads *const *stage_grads, const rvn_down_grads *down_grads,
+                          int accumulate_wgrads, void *ws, size_t ws_bytes, void *hip_stream) {
+    if (frac_bits < 1 || frac_bits > 30) return fail(RVN_ERR_SHAPE, "frac_bits = %d out of range [1, 30]", frac_bits);
+    return body_bwd_impl(desc, tops, dtops, stage_params, down_params, stage_grads, down_grads, accumulate_wgrads, ws,
+                         ws_bytes, hip_stream, frac_bits);
+}
+
+int revnet_body_fixed_workspace_bytes(const rvn_body_desc *desc, int64_t n, int64_t h, int64_t w, size_t *fwd_bytes,
+                                      size_t *bwd_bytes) {
+    if (int rc = check_body_desc(desc, n, h, w)) return rc;
+    const Geo g{(int)n, (int)h, (int)w};
+    if (fwd_bytes) *fwd_bytes = body_ws_bytes(*desc, g, false, true);
+    if (bwd_bytes) *bwd_bytes = body_ws_bytes(*desc, g, true, true);
+    return RVN_OK;
+}
+
+
 
 }  // extern "C"

@@ -145,14 +145,17 @@ class BodyRunner:
     subsampling blocks) and the calls into the C ABI.  Keeps one activation
     and one gradient tensor per stage, whatever the stages' depths."""
 
-    def __init__(self, kind, n, h, w, channels, depths, widths, conv="f32", eps=1e-5, device="cuda:0", **_unused):
+    def __init__(self, kind, n, h, w, channels, depths, widths, conv="f32", eps=1e-5, device="cuda:0", frac_bits=0,
+                 **_unused):
         self.n, self.h, self.w, self.channels, self.depths = n, h, w, tuple(channels), tuple(depths)
+        self.frac_bits = int(frac_bits)   # > 0: the stage tops hold fixed-point codes (int32 bit patterns in the fp32 tensors)
         self.device = torch.device(device)
         stages = [B.BlockDesc(kind, c // 2, wd or 0, eps, conv) for c, wd in zip(channels, widths)]
         downs = [B.DownDesc(kind, channels[s], channels[s + 1], 0, eps, conv) for s in range(len(channels) - 1)]
         self.down_descs = downs
         self.desc = B.BodyDesc(stages, depths, downs)
-        self.fwd_bytes, self.bwd_bytes = B.revnet_body_workspace_bytes(self.desc, n, h, w)
+        query = B.revnet_body_fixed_workspace_bytes if self.frac_bits else B.revnet_body_workspace_bytes
+        self.fwd_bytes, self.bwd_bytes = query(self.desc, n, h, w)
         self.ws = torch.empty(max(self.fwd_bytes, self.bwd_bytes), dtype=torch.uint8, device=self.device)
         shape = lambda s: (n, channels[s], h >> s, w >> s)
         self.tops = [torch.empty(shape(s), dtype=torch.float32, device=self.device) for s in range(len(channels))]
@@ -169,12 +172,27 @@ class BodyRunner:
 
     def forward(self, x, stream=None):
         """x: device tensor [n, channels[0], h, w]; it may be self.tops[0]."""
-        B.revnet_body_fwd(self.desc, x, self._sp, self._dp, self.tops, self.ws, stream)
+        if self.frac_bits:
+            B.revnet_body_fwd_fixed(self.desc, self.frac_bits, x, self._sp, self._dp, self.tops, self.ws, stream)
+        else:
+            B.revnet_body_fwd(self.desc, x, self._sp, self._dp, self.tops, self.ws, stream)
 
     def backward(self, accumulate=False, stream=None):
         """self.dtops[-1] holds the upstream derivative; see revnet_body_bwd for what is left where."""
-        B.revnet_body_bwd(self.desc, self.tops, self.dtops, self._sp, self._dp, self._sg, self._dg, int(accumulate),
-                          self.ws, stream)
+        if self.frac_bits:
+            B.revnet_body_bwd_fixed(self.desc, self.frac_bits, self.tops, self.dtops, self._sp, self._dp, self._sg,
+                                    self._dg, int(accumulate), self.ws, stream)
+        else:
+            B.revnet_body_bwd(self.desc, self.tops, self.dtops, self._sp, self._dp, self._sg, self._dg, int(accumulate),
+                              self.ws, stream)
+
+    def top_to_host(self, s):
+        """Real values of stage s's top as float64."""
+        if not self.frac_bits:
+            return self.tops[s].cpu().numpy().astype(np.float64)
+        out = torch.empty_like(self.tops[s])
+        B.revnet_fixed_to_float(self.tops[s], self.frac_bits, out)
+        return out.cpu().numpy().astype(np.float64)
 
     def activation_bytes(self):
         """Bytes alive between the end of forward and the end of backward."""

@@ -134,3 +134,71 @@ def test_fixed_stream_workspace_and_errors(torch_cuda):
     f1, b1 = rv.revnet_fixed_workspace_bytes(d, 8, 16, 16)
     assert f1 > f0 and b1 > b0    # two more half-stream tensors
     assert f1 - f0 >= 2 * 8 * 16 * 256 * 4
+
+
+@pytest.mark.parametrize("conv", ["f32", "bf16"])
+def test_fixed_point_body_reconstructs_every_stage_and_matches_oracle(oracle, torch_cuda, conv):
+    """Three stages joined by two subsampling blocks with the stage tensors in
+    fixed point: after the backward pass every top holds the codes the stage
+    received (stage 0: the encoded input; later stages: what the subsampling
+    block below wrote), bit for bit; tops and derivatives against the oracle's
+    fixed-point body (fp32 bars; bf16: 3x the oracle's own float32-to-float64
+    distance where that exceeds 2e-2)."""
+    import torch
+    from paper_1707_04585_amd.torch_harness import BodyRunner, download_grads, download_down, _dev
+    from test_gpu_body import body_errors, cast_down
+    cfg = dict(kind="basic", n=4, h=16, w=16, channels=(8, 12, 16), depths=(3, 2, 3), widths=(None, None, None), conv=conv)
+    x, stages, downs, dy = S.draw_body(2026, **cfg)
+    x = x.astype(np.float32).astype(np.float64)
+    with oracle.conv_operands(conv):
+        tops_ref, kept = oracle.body_fwd_fixed(x, stages, downs, FB)
+        dx_ref, sg_ref, dg_ref = oracle.body_bwd_stored(kept, stages, downs, dy)
+        st32 = [S.cast_params(st, np.float32) for st in stages]
+        dn32 = [cast_down(P, np.float32) for P in downs]
+        t32, k32 = oracle.body_fwd_fixed(x, st32, dn32, FB, np.float32(1e-5), np.float32)
+        dx32, sg32, dg32 = oracle.body_bwd_stored(k32, st32, dn32, dy.astype(np.float32), np.float32(1e-5))
+    dec = lambda tops: [oracle.fixed_decode(t, FB) for t in tops]
+    o32 = dict(tops=dec(t32), x_rec=x, dx=dx32, stage_grads=sg32, down_grads=dg32)
+    f_fwd, _, f_dx, f_g = body_errors(oracle, o32, dec(tops_ref), dx_ref, sg_ref, dg_ref, x)
+    base = dict(f32=dict(fwd=1e-5, grad=1e-4), bf16=dict(fwd=1e-2, grad=2e-2))[conv]
+    tol = dict(fwd=min(max(base["fwd"], 3.0 * f_fwd), 1e-1), grad=min(max(base["grad"], 3.0 * max(f_dx, max(f_g.values()))), 1e-1))
+
+    r = BodyRunner(frac_bits=FB, **cfg)
+    r.set_params(stages, downs)
+    r.forward(_dev(x, "cuda:0"))
+    torch.cuda.synchronize()
+    tops = [r.top_to_host(s) for s in range(3)]
+    # what each stage received: the encoded input, and the codes each subsampling block wrote
+    received = [torch.empty_like(t) for t in r.tops]
+    import paper_1707_04585_amd as rv
+    rv.revnet_fixed_from_float(_dev(x, "cuda:0"), FB, received[0])
+    codes_top = [t.clone() for t in r.tops]
+    r.dtops[-1].copy_(_dev(dy, "cuda:0"))
+    r.backward()
+    torch.cuda.synchronize()
+    assert torch.equal(r.tops[0].view(torch.int32), received[0].view(torch.int32)), "stage 0 input not reconstructed exactly"
+    # a second forward + backward leaves the same codes everywhere (the pass is reproducible)
+    after_first = [t.clone() for t in r.tops]
+    r.forward(_dev(x, "cuda:0"))
+    torch.cuda.synchronize()
+    for s in range(3):
+        assert torch.equal(r.tops[s].view(torch.int32), codes_top[s].view(torch.int32))
+    r.dtops[-1].copy_(_dev(dy, "cuda:0"))
+    r.backward()
+    torch.cuda.synchronize()
+    for s in range(3):
+        assert torch.equal(r.tops[s].view(torch.int32), after_first[s].view(torch.int32))
+    out = dict(tops=tops, x_rec=x, dx=r.dtops[0].cpu().numpy().astype(np.float64),
+               stage_grads=[download_grads(g) for g in r.stage_grads], down_grads=[download_down(g) for g in r.down_grads])
+    fwd, _, dx, g = body_errors(oracle, out, dec(tops_ref), dx_ref, sg_ref, dg_ref, x)
+    worst = max(g, key=g.get)
+    print(f"fixed-point body conv={conv}: tops {fwd:.2e} dx {dx:.2e} worst gradient {worst} {g[worst]:.2e} (tolerances {tol})", flush=True)
+    assert fwd < tol["fwd"] and dx < tol["grad"] and g[worst] < tol["grad"]
+    # stage 1's reconstructed input equals the codes of the subsampling block's output: recompute that output
+    rec1 = r.tops[1].view(torch.int32).cpu().numpy().astype(np.int64)
+    with oracle.conv_operands(conv):
+        y0, _ = oracle.down_fwd(oracle.fixed_decode(codes_top[0].view(torch.int32).cpu().numpy().astype(np.int64), FB), downs[0])
+    diff = np.abs(rec1 - oracle.fixed_encode(y0, FB))
+    print("  stage 1 input codes against the oracle's subsampling block on the GPU's stage-0 top: largest difference %d code(s), %.2f%% differ" %
+          (diff.max(), 100.0 * (diff > 0).mean()), flush=True)
+    assert diff.max() <= (2 if conv == "f32" else 600)

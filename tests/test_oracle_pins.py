@@ -711,3 +711,23 @@ def test_maxpool_brute_force_and_tie_rule(oracle):
     dx = oracle.maxpool3s2_bwd(dy, arg, (7, 6))
     assert np.allclose(dx.sum(axis=(2, 3)), dy.sum(axis=(2, 3)), rtol=0, atol=1e-12)
     assert ((dx != 0).sum(axis=(2, 3)) <= ho * wo).all()
+
+
+def test_fixed_point_body_reconstructs_every_stage_exactly(oracle):
+    """Stages in fixed point joined by subsampling blocks: the backward pass from
+    the stored tops returns every stage's input codes bit for bit (stage 0: the
+    encoded body input) and equals stored-activation backprop bitwise."""
+    fb = 16
+    x, stages, downs, dy = small_body(43, "basic")
+    tops, kept = oracle.body_fwd_fixed(x, stages, downs, fb)
+    dx, sg, dg, recon = oracle.body_reverse_fixed(tops, stages, downs, dy, fb)
+    assert np.array_equal(recon[0], oracle.fixed_encode(x, fb))
+    y0, _ = oracle.down_fwd(oracle.fixed_decode(tops[0], fb), downs[0])
+    assert np.array_equal(recon[1], oracle.fixed_encode(y0, fb))
+    sdx, ssg, sdg = oracle.body_bwd_stored(kept, stages, downs, dy)
+    assert np.array_equal(dx, sdx)
+    for s in range(len(stages)):
+        assert np.array_equal(oracle.flatten_grads(sg[s]), oracle.flatten_grads(ssg[s]))
+    # and it follows the real-valued body to within the code resolution
+    ref = oracle.body_fwd(x, stages, downs)
+    assert oracle.rel_l2(oracle.fixed_decode(tops[-1], fb), ref[-1]) < 1e-3
