@@ -18,6 +18,17 @@ const char *last_error();
 // cx.err as a status of the ABI.
 int finish(Ctx &cx);
 
+// The integer a caller put into an enum field.  Read as bytes: a value outside
+// the enumerators' range must be reported, and loading it through the enum
+// type would be undefined behaviour in C++.
+template <typename E>
+inline int enum_bits(const E &field) {
+    static_assert(sizeof(E) == sizeof(int), "enum fields of the ABI are int-sized");
+    int v;
+    __builtin_memcpy(&v, &field, sizeof v);
+    return v;
+}
+
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 

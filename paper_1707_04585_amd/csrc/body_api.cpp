@@ -41,13 +41,12 @@ int down_layers(const rvn_down_desc &d, DownLayer out[3]) {
 
 int check_down_desc(const rvn_down_desc *d) {
     if (!d) return fail(RVN_ERR_NULL, "descriptor is NULL");
-    if (d->kind != RVN_BASIC && d->kind != RVN_BOTTLENECK)
-        return fail(RVN_ERR_DTYPE, "unknown block kind %d", (int)d->kind);
-    if (d->conv_dtype != RVN_F32 && d->conv_dtype != RVN_BF16)
-        return fail(RVN_ERR_DTYPE, "unknown conv_dtype %d", (int)d->conv_dtype);
+    const int kind = enum_bits(d->kind), conv_dtype = enum_bits(d->conv_dtype);
+    if (kind != RVN_BASIC && kind != RVN_BOTTLENECK) return fail(RVN_ERR_DTYPE, "unknown block kind %d", kind);
+    if (conv_dtype != RVN_F32 && conv_dtype != RVN_BF16) return fail(RVN_ERR_DTYPE, "unknown conv_dtype %d", conv_dtype);
     if (d->c_in <= 0 || d->c_in > 131072 || d->c_out <= 0 || d->c_out > 131072)
         return fail(RVN_ERR_SHAPE, "c_in = %d, c_out = %d out of range [1, 131072]", d->c_in, d->c_out);
-    if (d->kind == RVN_BOTTLENECK && (d->width <= 0 || d->width > 65536))
+    if (kind == RVN_BOTTLENECK && (d->width <= 0 || d->width > 65536))
         return fail(RVN_ERR_SHAPE, "bottleneck width = %d out of range [1, 65536]", d->width);
     if (!(d->bn_eps > 0.f)) return fail(RVN_ERR_SHAPE, "bn_eps must be > 0");
     return RVN_OK;

@@ -44,13 +44,12 @@ int func_layers(const rvn_block_desc &d, Layer out[3]) {
 
 int check_desc(const rvn_block_desc *d) {
     if (!d) return fail(RVN_ERR_NULL, "descriptor is NULL");
-    if (d->kind != RVN_BASIC && d->kind != RVN_BOTTLENECK)
-        return fail(RVN_ERR_DTYPE, "unknown block kind %d", (int)d->kind);
-    if (d->conv_dtype != RVN_F32 && d->conv_dtype != RVN_BF16)
-        return fail(RVN_ERR_DTYPE, "unknown conv_dtype %d", (int)d->conv_dtype);
+    const int kind = enum_bits(d->kind), conv_dtype = enum_bits(d->conv_dtype);
+    if (kind != RVN_BASIC && kind != RVN_BOTTLENECK) return fail(RVN_ERR_DTYPE, "unknown block kind %d", kind);
+    if (conv_dtype != RVN_F32 && conv_dtype != RVN_BF16) return fail(RVN_ERR_DTYPE, "unknown conv_dtype %d", conv_dtype);
     if (d->c_half <= 0 || d->c_half > 65536)
         return fail(RVN_ERR_SHAPE, "c_half = %d out of range [1, 65536]", d->c_half);
-    if (d->kind == RVN_BOTTLENECK && (d->width <= 0 || d->width > 65536))
+    if (kind == RVN_BOTTLENECK && (d->width <= 0 || d->width > 65536))
         return fail(RVN_ERR_SHAPE, "bottleneck width = %d out of range [1, 65536]", d->width);
     if (!(d->bn_eps > 0.f)) return fail(RVN_ERR_SHAPE, "bn_eps must be > 0");
     return RVN_OK;
@@ -519,19 +518,21 @@ int revnet_stack_cost(const rvn_block_desc *desc, int32_t depth, int64_t n, int6
     std::vector<rvn_block_grads> grads((size_t)depth);
     std::memset(params.data(), 0, params.size() * sizeof(rvn_block_params));
     std::memset(grads.data(), 0, grads.size() * sizeof(rvn_block_grads));
-    const View v = dense_view(nullptr, desc->c_half, g);
+    // (non-null: the drivers form addresses from these bases, and offsetting a null pointer is undefined)
+    void *const placeholder_ws = reinterpret_cast<void *>(uintptr_t{1} << 40);
+    const View v = dense_view(reinterpret_cast<float *>(uintptr_t{1} << 41), desc->c_half, g);
     if (fwd) {
         const Plan pl = make_plan(*desc, g, false);
         Ctx cx;
         cx.dry = true;
-        stack_forward(cx, *desc, depth, pl, bind(pl, nullptr), g, v, v, params.data(), v, v);
+        stack_forward(cx, *desc, depth, pl, bind(pl, placeholder_ws), g, v, v, params.data(), v, v);
         *fwd = cx.cost;
     }
     if (bwd) {
         const Plan pl = make_plan(*desc, g, true);
         Ctx cx;
         cx.dry = true;
-        stack_backward(cx, *desc, depth, pl, bind(pl, nullptr), g, v, v, v, v, params.data(), v, v, v, v,
+        stack_backward(cx, *desc, depth, pl, bind(pl, placeholder_ws), g, v, v, v, v, params.data(), v, v, v, v,
                        grads.data(), false);
         *bwd = cx.cost;
     }
