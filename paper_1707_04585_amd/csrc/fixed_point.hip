@@ -89,7 +89,7 @@ void fix_to_float(Ctx &cx, View x, int c, Geo g, int frac_bits, float *out) {
     if (!cx.launch(K_FIXED_POINT, 8.0 * (double)elems)) return;
     const float unit = ldexpf(1.0f, -frac_bits);
     const int *xp = reinterpret_cast<const int *>(x.p);
-    if (aligned16(x, g.hw()))
+    if (aligned16(x, g.hw()) && (reinterpret_cast<uintptr_t>(out) & 15) == 0)
         cx.run(fix_to_float_k<true>, dim3(blocks_for(elems / 4)), dim3(kThreads), 0, xp, x.sn, x.sc, out, c, g.hw() / 4, unit, elems / 4);
     else
         cx.run(fix_to_float_k<false>, dim3(blocks_for(elems)), dim3(kThreads), 0, xp, x.sn, x.sc, out, c, g.hw(), unit, elems);
@@ -101,7 +101,7 @@ void fix_axpy(Ctx &cx, View r, const float *f, int c, Geo g, int frac_bits, int 
     const float scale = ldexpf(1.0f, frac_bits);
     const int *rp = reinterpret_cast<const int *>(r.p);
     int *op = reinterpret_cast<int *>(out.p);
-    if (aligned16(r, g.hw()) && aligned16(out, g.hw()))
+    if (aligned16(r, g.hw()) && aligned16(out, g.hw()) && (reinterpret_cast<uintptr_t>(f) & 15) == 0)
         cx.run(fix_axpy_k<true>, dim3(blocks_for(elems / 4)), dim3(kThreads), 0, rp, r.sn, r.sc, f, op, out.sn, out.sc, c,
                g.hw() / 4, scale, sign, elems / 4);
     else
