@@ -255,6 +255,13 @@ struct StemShape {
     int N, CI, H, W, CO, KS, stride, HO, WO;
 };
 void stem_conv(Ctx &cx, View x, const float *w, const StemShape &g, View out);
+// The same on the matrix cores (stem_mfma.hip) for the shapes it takes; stem_conv dispatches.
+bool stem_conv_mfma_takes(const StemShape &g);
+void stem_conv_mfma(Ctx &cx, View x, const float *w, const StemShape &g, View out);
+// Filter gradient on the matrix cores: partial results part[chunk][k][tap] for stem_wgrad's reduce pass;
+// stem_wgrad_mfma_chunks is 0 for shapes it does not take.
+int stem_wgrad_mfma_chunks(const StemShape &g);
+void stem_wgrad_mfma(Ctx &cx, View x, View dh, const StemShape &g, float *part);
 // dw[k][c][r][s] (+)= sum over output pixels of dh * x; scratch: stem_wgrad_scratch_floats(g) floats.
 size_t stem_wgrad_scratch_floats(const StemShape &g);
 void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, float *dw, bool accumulate);

@@ -13,10 +13,12 @@
 //                  partial sums per chunk, added in a fixed order by
 //                  stem_wgrad_reduce_k.
 //   maxpool_fwd_k  one thread per output element.
-//   maxpool_bwd_k  one thread per input element: it looks at the (at most four)
-//                  windows that contain it and takes the derivative of those
-//                  it wins.  A window's winner is its first maximal element in
-//                  row-major order.  No atomics: results are reproducible.
+//   maxpool_bwd_k  one thread per input element or per four of a row: it looks
+//                  at the windows that contain them (winner codes written by
+//                  maxpool_arg_k from the stored input) and takes the
+//                  derivative of those they win.  A window's winner is its
+//                  first maximal element in row-major order.  No atomics:
+//                  results are reproducible.
 #include <algorithm>
 
 #include "kernels.h"
@@ -141,28 +143,36 @@ __global__ __launch_bounds__(kThreads) void stem_wgrad_reduce_k(const float *__r
     dw[i] = accumulate ? dw[i] + sum : sum;
 }
 
-// The first maximal element of window (p, q) in row-major order; returns its value and position.
-__device__ __forceinline__ void window_winner(const float *plane, int H, int W, int p, int q, float *best, int *bi, int *bj) {
+// The first maximal element of window (p, q) in row-major order: its value and
+// its position in the window, 3 * r + s.  All nine elements are requested
+// before the first comparison (positions outside the plane re-read a valid one
+// and are skipped), so the loads are in flight together.
+__device__ __forceinline__ void window_winner(const float *plane, int H, int W, int p, int q, float *best, int *code) {
+    float v[9];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const int i = min(max(2 * p + r - 1, 0), H - 1);
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int j = min(max(2 * q + s - 1, 0), W - 1);
+            v[3 * r + s] = plane[i * W + j];
+        }
+    }
     float b = -INFINITY;
-    int wi = -1, wj = -1;
+    int w = 4;  // the centre is always inside the plane
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
         const int i = 2 * p + r - 1;
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int j = 2 * q + s - 1;
-            if (i < 0 || i >= H || j < 0 || j >= W) continue;
-            const float v = plane[i * W + j];
-            if (v > b) {
-                b = v;
-                wi = i;
-                wj = j;
-            }
+            const bool take = i >= 0 && i < H && j >= 0 && j < W && v[3 * r + s] > b;
+            b = take ? v[3 * r + s] : b;
+            w = take ? 3 * r + s : w;
         }
     }
     *best = b;
-    *bi = wi;
-    *bj = wj;
+    *code = w;
 }
 
 __global__ __launch_bounds__(kThreads) void maxpool_fwd_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
@@ -177,8 +187,8 @@ __global__ __launch_bounds__(kThreads) void maxpool_fwd_k(const float *__restric
     const int c = (int)(t % C);
     const int64_t n = t / C;
     float best;
-    int bi, bj;
-    window_winner(x + n * xsn + (int64_t)c * xsc, H, W, p, q, &best, &bi, &bj);
+    int code;
+    window_winner(x + n * xsn + (int64_t)c * xsc, H, W, p, q, &best, &code);
     y[n * ysn + (int64_t)c * ysc + p * WO + q] = best;
 }
 
@@ -195,36 +205,71 @@ __global__ __launch_bounds__(kThreads) void maxpool_arg_k(const float *__restric
     const int c = (int)(t % C);
     const int64_t n = t / C;
     float best;
-    int bi, bj;
-    window_winner(x + n * xsn + (int64_t)c * xsc, H, W, p, q, &best, &bi, &bj);
-    arg[e] = (unsigned char)((bi - (2 * p - 1)) * 3 + (bj - (2 * q - 1)));
+    int code;
+    window_winner(x + n * xsn + (int64_t)c * xsc, H, W, p, q, &best, &code);
+    arg[e] = (unsigned char)code;
 }
 
-// dx[n][c][i][j] (dense) = sum of dy over the windows that (i, j) wins, in a fixed order.
+// dx[n][c][i][j] (dense) = sum of dy over the windows that (i, j) wins, in a
+// fixed order (window rows, then window columns).  A thread owns VEC
+// consecutive j of one row (VEC = 4 needs W % 4 == 0; then the quad starts at
+// an even j and lies in the windows q = j/2, j/2 + 1, j/2 + 2).  The winner
+// codes and derivatives of those windows are requested up front, clamped to
+// valid windows, and the ones that do not apply are masked.
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void maxpool_bwd_k(const unsigned char *__restrict__ arg,
                                                           const float *__restrict__ dy, int64_t dsn, int64_t dsc,
                                                           float *__restrict__ dx, int C, int H, int W, int HO, int WO,
                                                           int64_t total) {
-    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    constexpr int NQ = VEC == 4 ? 3 : 2;  // window columns a thread looks at
+    const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;  // index of the thread's first element / VEC
     if (e >= total) return;
-    const int j = (int)(e % W);
-    int64_t t = e / W;
+    const int wv = W / VEC;
+    const int j0 = (int)(e % wv) * VEC;
+    int64_t t = e / wv;
     const int i = (int)(t % H);
     t /= H;
     const int c = (int)(t % C);
     const int64_t n = t / C;
     const unsigned char *a = arg + (n * C + c) * (int64_t)(HO * WO);
     const float *g = dy + n * dsn + (int64_t)c * dsc;
-    // windows p with 2p-1 <= i <= 2p+1
-    const int p_lo = i / 2, p_hi = min(HO - 1, (i + 1) / 2);
-    const int q_lo = j / 2, q_hi = min(WO - 1, (j + 1) / 2);
-    float sum = 0.f;
-    for (int p = p_lo; p <= p_hi; ++p)
-        for (int q = q_lo; q <= q_hi; ++q) {
-            const int mine = (i - (2 * p - 1)) * 3 + (j - (2 * q - 1));
-            if (a[p * WO + q] == mine) sum += g[p * WO + q];
+    // window rows p with 2p-1 <= i <= 2p+1: i/2 and, for odd i, (i+1)/2
+    const int p0 = i / 2, q0 = j0 / 2;
+    int code[2][NQ];
+    float d[2][NQ];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = min(p0 + u, HO - 1);
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) {
+            const int q = min(q0 + k, WO - 1);
+            code[u][k] = a[p * WO + q];
+            d[u][k] = g[p * WO + q];
         }
-    dx[e] = sum;
+    }
+    float out[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) out[k] = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = p0 + u;
+        const bool row_ok = p < HO && (u == 0 || (i & 1));
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) {
+            const int q = q0 + k;
+            // the winner's position in the plane
+            const int wi = 2 * p - 1 + code[u][k] / 3, wj = 2 * q - 1 + code[u][k] % 3;
+            const bool ok = row_ok && q < WO && wi == i;
+#pragma unroll
+            for (int m = 0; m < VEC; ++m) out[m] += ok && wj == j0 + m ? d[u][k] : 0.f;
+        }
+    }
+    float *o = dx + ((n * C + c) * (int64_t)H + i) * W + j0;
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4 *>(o) = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+        o[0] = out[0];
+    }
 }
 
 unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads); }
@@ -232,6 +277,7 @@ unsigned blocks_for(int64_t n) { return (unsigned)((n + kThreads - 1) / kThreads
 }  // namespace
 
 int stem_wgrad_chunks(const StemShape &g) {
+    if (const int m = stem_wgrad_mfma_chunks(g)) return m;
     const int64_t pixels = (int64_t)g.N * g.HO * g.WO;
     const int64_t tiles = (int64_t)((g.CO + kWgradKG - 1) / kWgradKG) * g.CI * g.KS;  // workgroups per chunk
     int64_t chunks = (1024 + tiles - 1) / tiles;                 // about 1024 workgroups in all
@@ -250,6 +296,10 @@ void stem_conv(Ctx &cx, View x, const float *w, const StemShape &g, View out) {
     cx.cost.conv_fwd_calls += 1;
     cx.cost.conv_flops += flops;
     if (!cx.launch(K_STEM, 4.0 * ((double)g.N * g.CI * g.H * g.W + (double)pixels * g.CO), flops)) return;
+    if (stem_conv_mfma_takes(g)) {
+        stem_conv_mfma(cx, x, w, g, out);
+        return;
+    }
     const dim3 grid(blocks_for(pixels), (unsigned)((g.CO + kConvKG - 1) / kConvKG));
     cx.run(stem_conv_k, grid, dim3(kThreads), (size_t)taps * kConvKG * 4, (const float *)x.p, x.sn, x.sc, w, out.p, out.sn,
            out.sc, g, pixels);
@@ -263,7 +313,10 @@ void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, fl
     cx.cost.conv_flops += flops;
     const int chunks = stem_wgrad_chunks(g);
     const int64_t per = (pixels + chunks - 1) / chunks;
-    if (cx.launch(K_STEM, 4.0 * ((double)g.N * g.CI * g.H * g.W + (double)pixels * g.CO), flops)) {
+    if (stem_wgrad_mfma_chunks(g)) {
+        if (cx.launch(K_STEM, 4.0 * ((double)g.N * g.CI * g.H * g.W + (double)pixels * g.CO), flops))
+            stem_wgrad_mfma(cx, x, dh, g, scratch);
+    } else if (cx.launch(K_STEM, 4.0 * ((double)g.N * g.CI * g.H * g.W + (double)pixels * g.CO), flops)) {
         const dim3 grid((unsigned)chunks, (unsigned)((g.CO + kWgradKG - 1) / kWgradKG), (unsigned)(g.CI * g.KS));
         const float *xp = x.p, *dp = dh.p;
         switch (g.KS) {
@@ -299,9 +352,15 @@ void maxpool3s2_bwd(Ctx &cx, View x, View dy, int c, Geo in, unsigned char *scra
     if (cx.launch(K_STEM, 4.0 * (double)total + (double)outs))
         cx.run(maxpool_arg_k, dim3(blocks_for(outs)), dim3(kThreads), 0, (const float *)x.p, x.sn, x.sc, scratch, c, in.h, in.w,
                ho, wo, outs);
-    if (cx.launch(K_STEM, 4.0 * (double)total + 5.0 * (double)outs))
-        cx.run(maxpool_bwd_k, dim3(blocks_for(total)), dim3(kThreads), 0, (const unsigned char *)scratch, (const float *)dy.p,
-               dy.sn, dy.sc, dx, c, in.h, in.w, ho, wo, total);
+    if (cx.launch(K_STEM, 4.0 * (double)total + 5.0 * (double)outs)) {
+        // dx is dense; quads need rows of whole quads and a 16-byte aligned base
+        if (in.w % 4 == 0 && (reinterpret_cast<uintptr_t>(dx) & 15) == 0)
+            cx.run(maxpool_bwd_k<4>, dim3(blocks_for(total / 4)), dim3(kThreads), 0, (const unsigned char *)scratch,
+                   (const float *)dy.p, dy.sn, dy.sc, dx, c, in.h, in.w, ho, wo, total / 4);
+        else
+            cx.run(maxpool_bwd_k<1>, dim3(blocks_for(total)), dim3(kThreads), 0, (const unsigned char *)scratch,
+                   (const float *)dy.p, dy.sn, dy.sc, dx, c, in.h, in.w, ho, wo, total);
+    }
 }
 
 }  // namespace rvn

@@ -1,0 +1,417 @@
+// The image convolution of the stem (Section 3.2: a non-reversible layer ahead
+// of the reversible stages) on the matrix cores, fp32 operands.
+//
+// GEMM view, forward:  D[ko][pixel] = sum_k W[ko][k] * X[k][pixel], where k runs
+// over the filter's taps (c, r, s) in the order they lie in memory.  One
+// v_mfma_f32_16x16x4_f32 multiplies 16 output channels x 4 taps by 4 taps x 16
+// output pixels.  With 3 input channels the reduction is only c_in * k * k = 27
+// or 147 long, so all of it is taken tap by tap from one LDS copy of the image
+// band: a lane's operand address is (offset of its tap) + (offset of its
+// pixel's window), the first from a small table in LDS, the second held in a
+// register per pixel tile.
+//
+// A workgroup (4 wavefronts) owns R output rows of one image and up to 64
+// output channels.  It stages the band of input rows those windows touch, with
+// the zero padding written out, and the filters of its channels in the order
+// the A operand consumes them (one 16-byte read per lane and step for four
+// channel tiles).  Wavefront w takes pixel tiles w*NT .. w*NT+NT-1, then
+// 4*NT further on, each tile 16 consecutive pixels of the band in row-major
+// order.  Results go to NCHW memory in 64-byte runs.
+//
+// Shapes whose band does not fit the LDS budget, and 1x1 filters, are left to
+// the direct kernels.
+#include <algorithm>
+
+#include "kernels.h"
+
+namespace rvn {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kNT = 4;                       // pixel tiles a wavefront multiplies per filter read
+constexpr size_t kLdsBudget = 96 * 1024;     // two workgroups per compute unit
+constexpr size_t kBandBudget = 48 * 1024;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct StemTiling {
+    int R;      // output rows per workgroup
+    int rows;   // input rows of its band
+    int LW;     // floats per band row (image row + padding on both sides)
+    int bands;  // workgroups per image
+    int steps;  // groups of 4 taps
+    size_t lds_bytes;
+};
+
+inline size_t band_bytes(const StemShape &g, int R) {
+    const int rows = (R - 1) * g.stride + g.KS;
+    const int LW = ((g.WO - 1) * g.stride + g.KS + 3) & ~3;
+    return (size_t)g.CI * rows * LW * 4;
+}
+
+// false: the shape is not taken
+inline bool stem_tiling(const StemShape &g, int MT, StemTiling *t) {
+    if (g.KS < 3) return false;
+    int R = std::max(1, std::min(g.HO, (512 + g.WO - 1) / g.WO));
+    while (R > 1 && band_bytes(g, R) > kBandBudget) --R;
+    t->R = R;
+    t->rows = (R - 1) * g.stride + g.KS;
+    t->LW = ((g.WO - 1) * g.stride + g.KS + 3) & ~3;
+    t->bands = (g.HO + R - 1) / R;
+    t->steps = (g.CI * g.KS * g.KS + 3) / 4;
+    t->lds_bytes = band_bytes(g, R) + (size_t)t->steps * 64 * MT * 4 + (size_t)t->steps * 4 * 4;
+    return t->lds_bytes <= kLdsBudget;
+}
+
+template <int MT>
+__global__ __launch_bounds__(kThreads) void stem_conv_mfma_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
+                                                             const float *__restrict__ w, float *__restrict__ out,
+                                                             int64_t osn, int64_t osc, StemShape g, StemTiling tl) {
+    extern __shared__ __align__(16) float lds[];
+    const int taps = g.CI * g.KS * g.KS, pad = (g.KS - 1) / 2;
+    const int band_floats = g.CI * tl.rows * tl.LW;  // a multiple of 4
+    float *xs = lds;                                 // [CI][rows][LW]
+    float *wl = xs + band_floats;                    // [steps][64 lanes][MT]
+    int *toff = reinterpret_cast<int *>(wl + tl.steps * 64 * MT);  // [steps * 4]
+    const int n = blockIdx.x / tl.bands, band = blockIdx.x - n * tl.bands;
+    const int p0 = band * tl.R;
+    const int k0 = blockIdx.y * (16 * MT);
+    const int tid = threadIdx.x;
+
+    // ---- the band: image rows p0*stride - pad .. of every input channel, zero outside the image.
+    // Four loads per thread are requested before the first is stored; positions
+    // outside the image re-read a valid element and are replaced by zero.
+    {
+        const float *xn = x + (int64_t)n * xsn;
+        const int ih0 = p0 * g.stride - pad;
+        for (int e0 = tid; e0 < band_floats; e0 += 4 * kThreads) {
+            float v[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = min(e0 + u * kThreads, band_floats - 1);
+                const int line = e / tl.LW, cc = e - line * tl.LW;
+                const int c = line / tl.rows, rr = line - c * tl.rows;
+                const int ih = ih0 + rr, iw = cc - pad;
+                ok[u] = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+                const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.W - 1);
+                v[u] = xn[(int64_t)c * xsc + ihc * g.W + iwc];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int e = e0 + u * kThreads;
+                if (e < band_floats) xs[e] = ok[u] ? v[u] : 0.f;
+            }
+        }
+    }
+    // ---- the filters: wl[(step * 64 + lane) * MT + mt] = w[k0 + 16 mt + lane % 16][4 step + lane / 16]
+    for (int e = tid; e < tl.steps * 64 * MT; e += kThreads) {
+        const int mt = e % MT, ln = (e / MT) & 63, step = e / (MT * 64);
+        const int row = k0 + 16 * mt + (ln & 15), tap = 4 * step + (ln >> 4);
+        const bool ok = row < g.CO && tap < taps;
+        const float v = w[ok ? (int64_t)row * taps + tap : 0];
+        wl[e] = ok ? v : 0.f;
+    }
+    // ---- where tap t = (c, r, s) lies relative to a window's first element
+    for (int t = tid; t < tl.steps * 4; t += kThreads) {
+        const int c = t / (g.KS * g.KS), rs = t - c * g.KS * g.KS;
+        const int r = rs / g.KS, s = rs - r * g.KS;
+        toff[t] = t < taps ? (c * tl.rows + r) * tl.LW + s : 0;
+    }
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int rows_here = min(tl.R, g.HO - p0);
+    const int npix = rows_here * g.WO, tiles = (npix + 15) / 16;
+    for (int t0 = wave * kNT; t0 < tiles; t0 += 4 * kNT) {
+        int pixbase[kNT];
+#pragma unroll
+        for (int i = 0; i < kNT; ++i) {
+            const int pix = min((t0 + i) * 16 + l16, npix - 1);  // slots past the end repeat the last pixel
+            const int pr = pix / g.WO, q = pix - pr * g.WO;
+            pixbase[i] = pr * g.stride * tl.LW + q * g.stride;
+        }
+        f32x4 acc[MT][kNT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int i = 0; i < kNT; ++i) acc[m][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int step = 0; step < tl.steps; ++step) {
+            float a[MT];
+            const float *ap = wl + (step * 64 + lane) * MT;  // MT * 4 bytes, aligned to that
+            if constexpr (MT == 4) {
+                const f32x4 av = *reinterpret_cast<const f32x4 *>(ap);
+                a[0] = av[0], a[1] = av[1], a[2] = av[2], a[3] = av[3];
+            } else {
+                const float2 av = *reinterpret_cast<const float2 *>(ap);
+                a[0] = av.x, a[1] = av.y;
+            }
+            const int to = toff[step * 4 + kq];
+            const bool live = step * 4 + kq < taps;  // the filter is zero there; keep the product finite
+            float b[kNT];
+#pragma unroll
+            for (int i = 0; i < kNT; ++i) b[i] = xs[to + pixbase[i]];
+#pragma unroll
+            for (int i = 0; i < kNT; ++i) b[i] = live ? b[i] : 0.f;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int i = 0; i < kNT; ++i)
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m], b[i], acc[m][i], 0, 0, 0);
+        }
+        // lane's results: channels k0 + 16 m + 4 kq + j (j = 0..3) of pixel l16 of each tile
+#pragma unroll
+        for (int i = 0; i < kNT; ++i) {
+            const int pix = (t0 + i) * 16 + l16;
+            if (pix >= npix) continue;
+            const int pr = pix / g.WO, q = pix - pr * g.WO;
+            float *o = out + (int64_t)n * osn + (int64_t)(p0 + pr) * g.WO + q;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ch = k0 + 16 * m + 4 * kq + j;
+                    if (ch < g.CO) o[(int64_t)ch * osc] = acc[m][i][j];
+                }
+        }
+    }
+}
+
+template <int MT>
+bool launch_fwd(Ctx &cx, View x, const float *w, const StemShape &g, View out) {
+    StemTiling tl;
+    if (!stem_tiling(g, MT, &tl)) return false;
+    static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once
+    if (!raised) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stem_conv_mfma_k<MT>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e != hipSuccess) {
+            cx.fail(e);
+            return true;
+        }
+        raised = true;
+    }
+    const dim3 grid((unsigned)(g.N * tl.bands), (unsigned)((g.CO + 16 * MT - 1) / (16 * MT)));
+    cx.run(stem_conv_mfma_k<MT>, grid, dim3(kThreads), tl.lds_bytes, (const float *)x.p, x.sn, x.sc, w, out.p, out.sn,
+           out.sc, g, tl);
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// Filter gradient:  dW[ko][k] = sum over output pixels of dh[ko][pixel] * X[k][pixel],
+// pixels on the reduction side.  One instruction multiplies 16 output channels
+// x 4 pixels (A, from an LDS copy of dh) by 4 pixels x 16 taps (B, from the LDS
+// band, address = tap offset held in a register per tap tile + window offset of
+// the pixel).  A workgroup owns 64 output channels (wavefront w its w-th 16)
+// and a run of bands of one image; the sums of all NTT tap tiles stay in
+// registers over the whole run and are written once, as partial result
+// part[chunk][ko][tap]; stem_wgrad_reduce_k adds the chunks in order.
+// ---------------------------------------------------------------------------
+struct StemWgradTiling {
+    int R, rows, LW, bands;
+    int cpi;  // chunks (workgroups) per image
+    int bpc;  // bands per chunk
+    int PP;   // pixel pitch of the dh copy: = 4 mod 64, so 16 channels x 4 pixels fall into 64 banks
+    int ntt;  // tap tiles of 16
+    size_t lds_bytes;
+};
+
+constexpr int kNttSizes[] = {2, 4, 5, 7, 10, 13, 16};  // instantiated tap-tile counts
+
+inline bool stem_wgrad_tiling(const StemShape &g, StemWgradTiling *t) {
+    if (g.KS < 3) return false;
+    const int taps = g.CI * g.KS * g.KS;
+    if (taps > 256) return false;
+    const int R = std::max(1, std::min(g.HO, 128 / g.WO));
+    t->R = R;
+    t->rows = (R - 1) * g.stride + g.KS;
+    t->LW = ((g.WO - 1) * g.stride + g.KS + 3) & ~3;
+    t->bands = (g.HO + R - 1) / R;
+    const int groups = (g.CO + 63) / 64;
+    int cpi = (768 + groups * g.N - 1) / (groups * g.N);  // about three workgroups per compute unit
+    cpi = std::max(1, std::min(cpi, t->bands));
+    t->bpc = (t->bands + cpi - 1) / cpi;
+    t->cpi = (t->bands + t->bpc - 1) / t->bpc;  // no empty chunk
+    const int npad = (R * g.WO + 3) & ~3;
+    t->PP = ((npad - 4 + 63) / 64) * 64 + 4;
+    const int need = (taps + 15) / 16;
+    t->ntt = 16;
+    for (int v : kNttSizes)
+        if (v >= need) {
+            t->ntt = v;
+            break;
+        }
+    t->lds_bytes = band_bytes(g, R) + (size_t)64 * t->PP * 4;
+    return t->lds_bytes <= kLdsBudget;
+}
+
+template <int NTT>
+__global__ __launch_bounds__(kThreads) void stem_wgrad_mfma_k(const float *__restrict__ x, int64_t xsn, int64_t xsc,
+                                                              const float *__restrict__ dh, int64_t dsn, int64_t dsc,
+                                                              float *__restrict__ part, StemShape g, StemWgradTiling tl) {
+    extern __shared__ __align__(16) float lds[];
+    const int taps = g.CI * g.KS * g.KS, pad = (g.KS - 1) / 2;
+    const int band_floats = g.CI * tl.rows * tl.LW;
+    float *xs = lds;                // [CI][rows][LW]
+    float *dl = xs + band_floats;   // [64][PP]
+    const int n = blockIdx.x / tl.cpi, chunk = blockIdx.x - n * tl.cpi;
+    const int k0 = blockIdx.y * 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const bool active = k0 + 16 * wave < g.CO;  // wavefronts past the last channel only help staging
+
+    int to[NTT];  // where this lane's tap of each tap tile lies relative to a window's first element
+#pragma unroll
+    for (int nt = 0; nt < NTT; ++nt) {
+        const int t = 16 * nt + l16;
+        const int c = t / (g.KS * g.KS), rs = t - c * g.KS * g.KS;
+        const int r = rs / g.KS, s = rs - r * g.KS;
+        to[nt] = t < taps ? (c * tl.rows + r) * tl.LW + s : 0;  // columns past the last tap are never stored
+    }
+    f32x4 acc[NTT];
+#pragma unroll
+    for (int nt = 0; nt < NTT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const float *xn = x + (int64_t)n * xsn;
+    const float *dn = dh + (int64_t)n * dsn;
+    const int b0 = chunk * tl.bpc, b1 = min(tl.bands, b0 + tl.bpc);
+    for (int band = b0; band < b1; ++band) {
+        const int p0 = band * tl.R;
+        const int rows_here = min(tl.R, g.HO - p0);
+        const int npix = rows_here * g.WO, npad = (npix + 3) & ~3;
+        __syncthreads();  // the previous band has been read
+        {
+            const int ih0 = p0 * g.stride - pad;
+            for (int e0 = tid; e0 < band_floats; e0 += 4 * kThreads) {
+                float v[4];
+                bool ok[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = min(e0 + u * kThreads, band_floats - 1);
+                    const int line = e / tl.LW, cc = e - line * tl.LW;
+                    const int c = line / tl.rows, rr = line - c * tl.rows;
+                    const int ih = ih0 + rr, iw = cc - pad;
+                    ok[u] = ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+                    const int ihc = min(max(ih, 0), g.H - 1), iwc = min(max(iw, 0), g.W - 1);
+                    v[u] = xn[(int64_t)c * xsc + ihc * g.W + iwc];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * kThreads;
+                    if (e < band_floats) xs[e] = ok[u] ? v[u] : 0.f;
+                }
+            }
+            // dh of the band's pixels, 64 channels; zero past the last channel and the last pixel
+            const int total = 64 * npad;
+            for (int e0 = tid; e0 < total; e0 += 4 * kThreads) {
+                float v[4];
+                bool ok[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = min(e0 + u * kThreads, total - 1);
+                    const int ch = e / npad, pix = e - ch * npad;
+                    ok[u] = k0 + ch < g.CO && pix < npix;
+                    v[u] = dn[(int64_t)min(k0 + ch, g.CO - 1) * dsc + (int64_t)p0 * g.WO + min(pix, npix - 1)];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int e = e0 + u * kThreads;
+                    if (e < total) {
+                        const int ch = e / npad, pix = e - ch * npad;
+                        dl[ch * tl.PP + pix] = ok[u] ? v[u] : 0.f;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (active) {
+            const float *ap = dl + (16 * wave + l16) * tl.PP + kq;
+            for (int step = 0; step < npad / 4; ++step) {
+                const int pixel = 4 * step + kq;
+                const int pc = min(pixel, npix - 1);
+                const int pr = pc / g.WO, q = pc - pr * g.WO;
+                const int pb = pr * g.stride * tl.LW + q * g.stride;
+                const float a = ap[4 * step];
+                const bool live = pixel < npix;  // dh is zero there; keep the product finite
+                float b[NTT];
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) b[nt] = xs[to[nt] + pb];
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt) b[nt] = live ? b[nt] : 0.f;
+#pragma unroll
+                for (int nt = 0; nt < NTT; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[nt], acc[nt], 0, 0, 0);
+            }
+        }
+    }
+    // lane's sums: channels k0 + 16 wave + 4 kq + j, tap 16 nt + l16
+    if (active) {
+        float *o = part + (int64_t)blockIdx.x * g.CO * taps;
+#pragma unroll
+        for (int nt = 0; nt < NTT; ++nt) {
+            const int t = 16 * nt + l16;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ko = k0 + 16 * wave + 4 * kq + j;
+                if (ko < g.CO && t < taps) o[(int64_t)ko * taps + t] = acc[nt][j];
+            }
+        }
+    }
+}
+
+template <int NTT>
+void launch_wgrad(Ctx &cx, View x, View dh, const StemShape &g, const StemWgradTiling &tl, float *part) {
+    static bool raised = false;
+    if (!raised) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stem_wgrad_mfma_k<NTT>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
+        if (e != hipSuccess) {
+            cx.fail(e);
+            return;
+        }
+        raised = true;
+    }
+    const dim3 grid((unsigned)(g.N * tl.cpi), (unsigned)((g.CO + 63) / 64));
+    cx.run(stem_wgrad_mfma_k<NTT>, grid, dim3(kThreads), tl.lds_bytes, (const float *)x.p, x.sn, x.sc,
+           (const float *)dh.p, dh.sn, dh.sc, part, g, tl);
+}
+
+}  // namespace
+
+bool stem_conv_mfma_takes(const StemShape &g) {
+    StemTiling tl;
+    return stem_tiling(g, g.CO <= 32 ? 2 : 4, &tl);
+}
+
+void stem_conv_mfma(Ctx &cx, View x, const float *w, const StemShape &g, View out) {
+    if (g.CO <= 32)
+        launch_fwd<2>(cx, x, w, g, out);
+    else
+        launch_fwd<4>(cx, x, w, g, out);
+}
+
+int stem_wgrad_mfma_chunks(const StemShape &g) {
+    StemWgradTiling tl;
+    return stem_wgrad_tiling(g, &tl) ? g.N * tl.cpi : 0;
+}
+
+void stem_wgrad_mfma(Ctx &cx, View x, View dh, const StemShape &g, float *part) {
+    StemWgradTiling tl;
+    if (!stem_wgrad_tiling(g, &tl)) {
+        cx.fail(hipErrorInvalidValue);  // the caller asks stem_wgrad_mfma_chunks first
+        return;
+    }
+    switch (tl.ntt) {
+        case 2: launch_wgrad<2>(cx, x, dh, g, tl, part); break;
+        case 4: launch_wgrad<4>(cx, x, dh, g, tl, part); break;
+        case 5: launch_wgrad<5>(cx, x, dh, g, tl, part); break;
+        case 7: launch_wgrad<7>(cx, x, dh, g, tl, part); break;
+        case 10: launch_wgrad<10>(cx, x, dh, g, tl, part); break;
+        case 13: launch_wgrad<13>(cx, x, dh, g, tl, part); break;
+        default: launch_wgrad<16>(cx, x, dh, g, tl, part); break;
+    }
+}
+
+}  // namespace rvn
