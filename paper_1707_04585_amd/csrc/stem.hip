@@ -136,11 +136,26 @@ __global__ __launch_bounds__(kThreads) void stem_wgrad_k(const float *__restrict
 
 __global__ __launch_bounds__(kThreads) void stem_wgrad_reduce_k(const float *__restrict__ part, float *__restrict__ dw,
                                                                 int chunks, int slots, int accumulate) {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= slots) return;
+    // 64 sums per workgroup; wavefront s adds the s-th quarter of the chunks in order (four loads in
+    // flight), then the four quarters are added in a fixed order.
+    __shared__ float red[kThreads / 64][64];
+    const int lane = threadIdx.x & 63, share = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + lane, ic = min(i, slots - 1);
+    const int per = (chunks + 3) / 4, c0 = share * per, c1 = min(chunks, c0 + per);
     float sum = 0.f;
-    for (int s = 0; s < chunks; ++s) sum += part[(int64_t)s * slots + i];
-    dw[i] = accumulate ? dw[i] + sum : sum;
+    for (int c = c0; c < c1; c += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = part[(int64_t)min(c + u, c1 - 1) * slots + ic];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sum += c + u < c1 ? v[u] : 0.f;
+    }
+    red[share][lane] = sum;
+    __syncthreads();
+    if (share == 0 && i < slots) {
+        const float total = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+        dw[i] = accumulate ? dw[i] + total : total;
+    }
 }
 
 // The first maximal element of window (p, q) in row-major order: its value and
@@ -328,7 +343,7 @@ void stem_wgrad(Ctx &cx, View x, View dh, const StemShape &g, float *scratch, fl
         }
     }
     if (cx.launch(K_STEM, 4.0 * (double)chunks * g.CO * taps))
-        cx.run(stem_wgrad_reduce_k, dim3(blocks_for((int64_t)g.CO * taps)), dim3(kThreads), 0, (const float *)scratch, dw,
+        cx.run(stem_wgrad_reduce_k, dim3((unsigned)((g.CO * taps + 63) / 64)), dim3(kThreads), 0, (const float *)scratch, dw,
                chunks, g.CO * taps, accumulate ? 1 : 0);
 }
 

@@ -43,7 +43,11 @@ STEM_CASES = [
     (3, 256, 7, 2, True, 1, 64, 48),     # its real channel count on a smaller image
     (3, 20, 7, 2, True, 3, 37, 29),      # ragged: odd sizes, channel count not a multiple of the per-thread groups
     (4, 9, 5, 1, True, 2, 11, 6),
-    (1, 5, 1, 2, False, 2, 7, 9),
+    (1, 5, 1, 2, False, 2, 7, 9),           # 1x1: the direct kernels
+    (2, 70, 5, 2, True, 2, 21, 19),         # two channel groups, the second ragged
+    (16, 48, 3, 2, False, 2, 12, 20),       # many input channels: 144 taps, three tap tiles per wavefront
+    (3, 8, 3, 1, False, 48, 40, 100),       # filter gradient: several bands per workgroup, the last run shorter
+    (3, 8, 7, 1, False, 1, 6, 1500),        # too wide for the matrix-core kernels' LDS band: the direct kernels
 ]
 
 
