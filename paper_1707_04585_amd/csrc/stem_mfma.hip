@@ -104,7 +104,7 @@ inline bool stem_tiling(const StemShape &g, int MT, StemTiling *t) {
     t->bands = (g.HO + R - 1) / R;
     t->steps = (g.CI * g.KS * g.KS + 3) / 4;
     t->m_rows = div_magic(t->rows), t->m_LW = div_magic(t->LW), t->m_WO = div_magic(g.WO);
-    t->lds_bytes = band_bytes(g, R) + (size_t)t->steps * 64 * MT * 4 + (size_t)t->steps * 4 * 4;
+    t->lds_bytes = band_bytes(g, R) + (size_t)t->steps * 64 * MT * 4 + (size_t)(t->steps + 2) * 4 * 4;
     // fast_div: indices stay below the LDS size in floats, divisors below 2^15
     return t->lds_bytes <= kLdsBudget && t->LW < (1 << 15) && t->rows < (1 << 15) && g.WO < (1 << 15);
 }
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void stem_conv_mfma_k(const float *__rest
     const int band_floats = g.CI * tl.rows * tl.LW;  // a multiple of 4
     float *xs = lds;                                 // [CI][rows][LW]
     float *wl = xs + band_floats;                    // [steps][64 lanes][MT]
-    int *toff = reinterpret_cast<int *>(wl + tl.steps * 64 * MT);  // [steps * 4]
+    int *toff = reinterpret_cast<int *>(wl + tl.steps * 64 * MT);  // [(steps + 2) * 4]
     const int n = blockIdx.x / tl.bands, band = blockIdx.x - n * tl.bands;
     const int p0 = band * tl.R;
     const int k0 = blockIdx.y * (16 * MT);
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void stem_conv_mfma_k(const float *__rest
         return w + (ok ? (int64_t)row * taps + tap : 0);
     });
     // ---- where tap t = (c, r, s) lies relative to a window's first element
-    for (int t = tid; t < tl.steps * 4; t += kThreads) {
+    for (int t = tid; t < (tl.steps + 2) * 4; t += kThreads) {
         const int c = t / (g.KS * g.KS), rs = t - c * g.KS * g.KS;
         const int r = rs / g.KS, s = rs - r * g.KS;
         toff[t] = t < taps ? (c * tl.rows + r) * tl.LW + s : 0;
@@ -161,8 +161,9 @@ __global__ __launch_bounds__(kThreads) void stem_conv_mfma_k(const float *__rest
         for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int i = 0; i < NT; ++i) acc[m][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int step = 0; step < tl.steps; ++step) {
-            float a[MT];
+        // The operands of step + 1 (and the tap offset of step + 2) are requested before the
+        // instructions of step are issued, so the LDS latency runs behind the matrix pipe.
+        auto load_a = [&](int step, float(&a)[MT]) {
             const float *ap = wl + (step * 64 + lane) * MT;  // MT * 4 bytes, aligned to that
             if constexpr (MT == 4) {
                 const f32x4 av = *reinterpret_cast<const f32x4 *>(ap);
@@ -171,18 +172,33 @@ __global__ __launch_bounds__(kThreads) void stem_conv_mfma_k(const float *__rest
                 const float2 av = *reinterpret_cast<const float2 *>(ap);
                 a[0] = av.x, a[1] = av.y;
             }
-            const int to = toff[step * 4 + kq];
+        };
+        float a_cur[MT], b_cur[NT];
+        int to_nxt = toff[4 + kq];  // the table has two steps of zeros behind the last
+        {
+            const int to = toff[kq];
+            load_a(0, a_cur);
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b_cur[i] = xs[to + pixbase[i]];
+        }
+        for (int step = 0; step < tl.steps; ++step) {
+            float a_nxt[MT], b_nxt[NT];
+            load_a(min(step + 1, tl.steps - 1), a_nxt);
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b_nxt[i] = xs[to_nxt + pixbase[i]];
+            to_nxt = toff[(step + 2) * 4 + kq];
             const bool live = step * 4 + kq < taps;  // the filter is zero there; keep the product finite
-            float b[NT];
 #pragma unroll
-            for (int i = 0; i < NT; ++i) b[i] = xs[to + pixbase[i]];
-#pragma unroll
-            for (int i = 0; i < NT; ++i) b[i] = live ? b[i] : 0.f;
+            for (int i = 0; i < NT; ++i) b_cur[i] = live ? b_cur[i] : 0.f;
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int i = 0; i < NT; ++i)
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m], b[i], acc[m][i], 0, 0, 0);
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[m], b_cur[i], acc[m][i], 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m) a_cur[m] = a_nxt[m];
+#pragma unroll
+            for (int i = 0; i < NT; ++i) b_cur[i] = b_nxt[i];
         }
         // lane's results: channels k0 + 16 m + 4 kq + j (j = 0..3) of pixel l16 of each tile
 #pragma unroll
@@ -328,25 +344,36 @@ __global__ __launch_bounds__(kThreads) void stem_wgrad_mfma_k(const float *__res
             });
         }
         __syncthreads();
+        // operands of one step: dh of 4 pixels x 16 channels per channel tile, the image at the
+        // wavefront's taps of those pixels' windows; step + 1 is requested before step is multiplied
         const float *ap = dl + l16 * tl.PP + kq;
-        for (int step = 0; step < npad / 4; ++step) {
-            const int pixel = 4 * step + kq;
-            const int pc = min(pixel, npix - 1);
+        auto operands = [&](int step, float(&a)[4], float(&b)[NTW]) {
+            const int pc = min(4 * step + kq, npix - 1);
             const int pr = fast_div(pc, tl.m_WO), q = pc - pr * g.WO;
             const int pb = pr * g.stride * tl.LW + q * g.stride;
-            float a[4], b[NTW];
 #pragma unroll
             for (int m = 0; m < 4; ++m) a[m] = ap[m * 16 * tl.PP + 4 * step];
 #pragma unroll
             for (int i = 0; i < NTW; ++i) b[i] = xs[to[i] + pb];
-            const bool live = pixel < npix;  // dh is zero there; keep the product finite
+        };
+        const int nsteps = npad / 4;
+        float a_cur[4], b_cur[NTW];
+        operands(0, a_cur, b_cur);
+        for (int step = 0; step < nsteps; ++step) {
+            float a_nxt[4], b_nxt[NTW];
+            operands(min(step + 1, nsteps - 1), a_nxt, b_nxt);
+            const bool live = 4 * step + kq < npix;  // dh is zero there; keep the product finite
 #pragma unroll
-            for (int i = 0; i < NTW; ++i) b[i] = live ? b[i] : 0.f;
+            for (int i = 0; i < NTW; ++i) b_cur[i] = live ? b_cur[i] : 0.f;
 #pragma unroll
             for (int m = 0; m < 4; ++m)
 #pragma unroll
                 for (int i = 0; i < NTW; ++i)
-                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m], b[i], acc[m][i], 0, 0, 0);
+                    acc[m][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[m], b_cur[i], acc[m][i], 0, 0, 0);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) a_cur[m] = a_nxt[m];
+#pragma unroll
+            for (int i = 0; i < NTW; ++i) b_cur[i] = b_nxt[i];
         }
     }
     // lane's sums: channels k0 + 16 m + 4 kq + j, tap 16 (wave + 4 i) + l16
