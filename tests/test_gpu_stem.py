@@ -67,6 +67,32 @@ def test_stem_matches_oracle(oracle, torch_cuda, c_in, c_out, ks, stride, pool, 
     assert e_y < 1e-5 and e_dw < 1e-4
 
 
+def test_stem_full_size_one_image_against_oracle(oracle, torch_cuda):
+    """The large-image stem at the size and launch shapes the benchmark times (32 images of 3x224x224,
+    256 channels): the outputs of three images against the oracle run on those images alone, and the
+    filter derivative with an upstream derivative that is zero outside those images (the derivative is
+    a sum over images, so it then equals the oracle's on them alone)."""
+    print("stem 3->256 7x7 s2 pool n=32 224x224, images 0, 13, 31 checked", flush=True)
+    rng = np.random.default_rng(72)
+    n, picks = 32, [0, 13, 31]
+    img = rng.standard_normal((n, 3, 224, 224)).astype(np.float32).astype(np.float64)
+    wt = (rng.standard_normal((256, 3, 7, 7)) * np.sqrt(2.0 / 147)).astype(np.float32).astype(np.float64)
+
+    def dy(shape):
+        d = np.zeros(shape)
+        d[picks] = rng.standard_normal((len(picks),) + tuple(shape[1:]))
+        return d
+
+    y, dw, dy_used = run_stem(3, 256, 7, 2, True, img, wt, dy)
+    S_ = dict(w=wt, stride=2, pool=True)
+    y_ref, stored = oracle.stem_fwd(img[picks], S_)
+    dw_ref = oracle.stem_bwd(stored, S_, dy_used[picks])
+    e_y, e_dw = oracle.rel_l2(y[picks], y_ref), oracle.rel_l2(dw, dw_ref)
+    print("  rel. errors: y %.2e  dw %.2e" % (e_y, e_dw), flush=True)
+    assert e_y < 1e-5 and e_dw < 1e-4
+    assert np.isfinite(y).all()
+
+
 def test_stem_pooling_tie_rule_and_accumulate(oracle, torch_cuda):
     """Integer-valued images and filters make exact ties in the pooling windows
     (and exact arithmetic on both sides): the derivative must go to the same
