@@ -70,6 +70,8 @@ struct Plan {
     // fixed-point residual stream only: the function's input as fp32 and the
     // function's value before it is rounded into the stream
     size_t xf, fout;
+    // per-tile statistics that a 1x1 bf16 convolution leaves for the BN layer reading its output
+    size_t emit, emit_floats;
     size_t total;
 };
 struct Bufs {
@@ -81,6 +83,7 @@ struct Bufs {
     int *counters;
     uint16_t *wq_f[3], *wq_b[3];  // null where the layer does not use converted filters
     float *xf, *fout;
+    float *emit;  // null when the plan has none
 };
 Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed = false);
 Bufs bind(const Plan &p, void *ws);

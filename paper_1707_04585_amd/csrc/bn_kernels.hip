@@ -202,6 +202,61 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------
+// statistics from partial results: (mean, M2) of every 128-pixel tile of a
+// channel, written by the convolution that produced the tensor, merged (Chan
+// et al., double precision, fixed order) into the same four per-channel arrays.
+// One workgroup per channel: thread t takes tiles t, t + 256, ..., then a
+// shuffle tree per wavefront and the four wavefronts in order.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void chan_merge(double &n, double &mean, double &m2, double nb, double mb, double m2b) {
+    const double tot = n + nb;
+    if (tot > 0.0) {
+        const double delta = mb - mean, fb = nb / tot;
+        mean += delta * fb;
+        m2 += m2b + delta * delta * n * fb;
+    }
+    n = tot;
+}
+
+__global__ __launch_bounds__(kThreads) void bn_stats_merge_k(const float *__restrict__ partials, int tiles, float count,
+                                                             float eps, const float *__restrict__ gamma,
+                                                             const float *__restrict__ beta, float *__restrict__ stats,
+                                                             int C, const PrepArgs carry) {
+    if ((int)blockIdx.x < carry.blocks) {
+        prep_filter_body(carry, blockIdx.x);
+        return;
+    }
+    __shared__ double red[kThreads / 64][3];
+    const int ch = blockIdx.x - carry.blocks;
+    const float2 *q = reinterpret_cast<const float2 *>(partials) + (int64_t)ch * tiles;
+    double n = 0.0, mean = 0.0, m2 = 0.0;
+    for (int t0 = threadIdx.x; t0 < tiles; t0 += 8 * kThreads) {
+        float2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = q[min(t0 + u * kThreads, tiles - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (t0 + u * kThreads < tiles) chan_merge(n, mean, m2, (double)count, (double)v[u].x, (double)v[u].y);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        chan_merge(n, mean, m2, shfl_down_f64(n, off), shfl_down_f64(mean, off), shfl_down_f64(m2, off));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) red[wave][0] = n, red[wave][1] = mean, red[wave][2] = m2;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int wv = 1; wv < kThreads / 64; ++wv) chan_merge(n, mean, m2, red[wv][0], red[wv][1], red[wv][2]);
+        const float mean_f = (float)mean;
+        const float rstd_f = (float)(1.0 / sqrt(m2 / n + (double)eps));
+        const float scale = gamma[ch] * rstd_f;
+        stats[ch] = mean_f;
+        stats[C + ch] = rstd_f;
+        stats[2 * C + ch] = scale;
+        stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // backward, reduce pass: per-channel sums of dy and dy*xhat, dy = da * [u > 0];
 // the last workgroup of a channel writes dbeta = sum dy, dgamma = sum dy*xhat
 // and the two per-channel means the apply pass needs (kept apart from
@@ -377,6 +432,18 @@ void clear_counters(Ctx &cx, int *counters, int n) {
 
 void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, const float *beta, float *scratch,
               int *counters, float *stats, const PrepArgs *carry, double carry_bytes) {
+    // The convolution that wrote x may have left per-tile statistics of exactly this tensor.
+    const EmittedStats e = cx.emitted;
+    cx.emitted = EmittedStats{};
+    if (e.p && cx.emit_buf && e.p == x.p && e.sn == x.sn && e.sc == x.sc && e.c == c && e.n == g.n && e.h == g.h &&
+        e.w == g.w) {
+        if (!cx.launch(K_BN_STATS, 8.0 * (double)c * e.tiles + carry_bytes)) return;
+        PrepArgs pa{};
+        if (carry) pa = *carry;
+        cx.run(bn_stats_merge_k, dim3((unsigned)(c + pa.blocks)), dim3(kThreads), 0, (const float *)cx.emit_buf, e.tiles,
+               128.f, eps, gamma, beta, stats, c, pa);
+        return;
+    }
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     if (!cx.launch(K_BN_STATS, 4.0 * (double)g.pixels() * c + carry_bytes)) return;

@@ -187,6 +187,8 @@ void prep_one(Ctx &cx, const float *w, int cin, int cout, int ks, const Geo &g, 
 void down_forward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const DownBufs &b, View x,
                   const rvn_down_params &p, View y, bool recompute_only) {
     clear_counters(cx, b.counters, pl.n_counters);
+    cx.emit_buf = nullptr;  // the statistics of this block's tensors are always read from the tensors
+    cx.emit_floats = 0;
     for (int l = 0; l < pl.L; ++l)
         prep_one(cx, p.R.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, pl.gin[l], b.wq_f[l], b.wq_b[l]);
     prep_one(cx, p.shortcut_w, d.c_in, d.c_out, 1, pl.low, b.wq_f[kShortcut], b.wq_b[kShortcut]);

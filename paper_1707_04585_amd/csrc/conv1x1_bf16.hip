@@ -55,6 +55,8 @@ struct C1Args {
     int gpi, groups;  // 4-pixel groups per image and in total
     int ksteps;       // CI / 16
     int mtiles;       // ceil(CO / 32)
+    float *emit;      // per (channel, 128-pixel tile) mean and M2 of the output (EMIT variants; needs whole tiles)
+    int ptiles;       // pixel tiles in all
     int PW, CW, KW;   // wavefronts of a workgroup: pixel tiles x output-channel tiles x shares of the channels
     int npt, ncg;     // workgroup grid: pixel tiles / PW, output-channel tiles / CW
     uint32_t m_gpi;   // fast-division multiplier (see fdiv)
@@ -69,11 +71,28 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     return *reinterpret_cast<const uint32_t *>(&b);
 }
 
+// One step of the 16-channel fold of the statistics epilogue: a lane holding CNT
+// channels keeps the lower or upper half (by bit CNT of its index) and adds
+// the same half of the lane CNT away; the pivot of a kept channel moves along.
+template <int CNT>
+__device__ __forceinline__ void fold_step(float (&ea)[16], float (&eb)[16], float (&piv)[16], int l32) {
+    constexpr int H = CNT / 2;
+    const bool up = (l32 & CNT) != 0;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+        const float keep_a = up ? ea[k + H] : ea[k], send_a = up ? ea[k] : ea[k + H];
+        const float keep_b = up ? eb[k + H] : eb[k], send_b = up ? eb[k] : eb[k + H];
+        ea[k] = keep_a + __shfl_xor(send_a, CNT, 64);
+        eb[k] = keep_b + __shfl_xor(send_b, CNT, 64);
+        piv[k] = up ? piv[k + H] : piv[k];
+    }
+}
+
 // MTW: 32-channel output tiles per wavefront.  DEPTH: steps the loads run ahead
 // (1 or 2).  GEN: planes need not be 16-byte
 // aligned and H*W need not be a multiple of 4 (the last group of an image then
 // starts at H*W - 4 and leaves the pixels it shares with its neighbour to it).
-template <int MTW, int DEPTH, bool GEN>
+template <int MTW, int DEPTH, bool GEN, bool EMIT = false>
 __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     using F4 = typename std::conditional<GEN, f4u_t, f4a_t>::type;
     const int lane = threadIdx.x & 63;
@@ -243,10 +262,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
     }
     if (!live || idle) return;
+    // Statistics of the stored values for the BN layer that reads them next
+    // (host: aligned variant, every tile whole): a channel's 128 pixels
+    // of this tile sit in the 32 lanes of one half, 4 per lane.  Sums of
+    // (v - pivot) and (v - pivot)^2, pivot = the half's first value, are folded
+    // over the lanes 16 channels at a time: each step halves the channels a lane
+    // holds and adds its partner's, so 16 + 16 shuffles do all of them and every
+    // sum has a fixed order.
+    constexpr bool emit = EMIT && !GEN;
 #pragma unroll
-    for (int m = 0; m < MTW; ++m)
+    for (int m = 0; m < MTW; ++m) {
+        float ea[16], eb[16], piv[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
+            ea[i] = eb[i] = piv[i] = 0.f;
             if (chan(m, i) + 4 * kg >= p.CO) continue;
             F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
             if (p.ep == EP_SUB) t = -t;
@@ -258,7 +287,34 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
                 if (dup < 3) op[2] = t[2];
                 op[3] = t[3];
             }
+            if constexpr (emit) {
+                const int t0 = __float_as_int(t[0]);
+                const float lo = __int_as_float(__builtin_amdgcn_readlane(t0, 0));
+                const float hi = __int_as_float(__builtin_amdgcn_readlane(t0, 32));
+                piv[i] = kg ? hi : lo;
+                const float d0 = t[0] - piv[i], d1 = t[1] - piv[i], d2 = t[2] - piv[i], d3 = t[3] - piv[i];
+                ea[i] = (d0 + d1) + (d2 + d3);
+                eb[i] = (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+            }
         }
+        if constexpr (emit) {
+            fold_step<16>(ea, eb, piv, l32);
+            fold_step<8>(ea, eb, piv, l32);
+            fold_step<4>(ea, eb, piv, l32);
+            fold_step<2>(ea, eb, piv, l32);
+            ea[0] += __shfl_xor(ea[0], 1, 64);
+            eb[0] += __shfl_xor(eb[0], 1, 64);
+            // the lane now holds register i = l32 / 2 of this tile
+            const int i = l32 >> 1;
+            const int c = (mt0 + m) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);
+            if ((l32 & 1) == 0 && c < p.CO) {
+                const float mean = piv[0] + ea[0] * (1.f / 128.f);
+                const float m2 = fmaxf(eb[0] - ea[0] * ea[0] * (1.f / 128.f), 0.f);
+                float2 *dst = reinterpret_cast<float2 *>(p.emit) + (int64_t)c * p.ptiles + (pt * p.PW + pw);
+                *dst = make_float2(mean, m2);
+            }
+        }
+    }
 }
 
 uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
@@ -304,6 +360,7 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         a.mtiles = (co + 31) / 32;
         a.m_gpi = fdiv_magic(a.gpi);
         const int ptiles = (a.groups + 31) / 32;
+        a.ptiles = ptiles;
         // With few tiles, the wavefronts of a workgroup split the input channels
         // (shorter dependent chains, more loads in flight).  Otherwise two output
         // tiles per wavefront halve the passes over the input, as long as that
@@ -323,10 +380,20 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
                          (out.sc & 3) != 0 || (reinterpret_cast<uintptr_t>(in.p) & 15) != 0 ||
                          (reinterpret_cast<uintptr_t>(out.p) & 15) != 0 ||
                          (r && ((r->sn & 3) != 0 || (r->sc & 3) != 0 || (reinterpret_cast<uintptr_t>(r->p) & 15) != 0));
+        // Statistics of the output for the BN layer that reads it next: whole 128-pixel tiles, aligned
+        // variant, one launch for all images (with channel shares the wavefront holding the final sums emits).
+        const bool emits = cx.want_emit && cx.emit_buf && !gen && a.groups % 32 == 0 && ns == g.n &&
+                           (size_t)co * ptiles * 2 <= cx.emit_floats;
+        a.emit = emits ? cx.emit_buf : nullptr;
+        if (emits) cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, ptiles};
         const dim3 grid((unsigned)wgs);
         const size_t lds = a.KW > 1 ? (size_t)(a.KW - 1) * (a.PW * a.CW) * mtw * 64 * 64 * 4 : 0;
         const int depth = mtw == 1 ? 2 : 1;
-        if (mtw == 2) {
+        if (emits) {  // (never the general variant)
+            if (mtw == 2) cx.run(conv1x1_bf16_k<2, 1, false, true>, grid, dim3(kThreads), lds, a);
+            else if (depth == 2) cx.run(conv1x1_bf16_k<1, 2, false, true>, grid, dim3(kThreads), lds, a);
+            else cx.run(conv1x1_bf16_k<1, 1, false, true>, grid, dim3(kThreads), lds, a);
+        } else if (mtw == 2) {
             if (gen) cx.run(conv1x1_bf16_k<2, 1, true>, grid, dim3(kThreads), lds, a);
             else cx.run(conv1x1_bf16_k<2, 1, false>, grid, dim3(kThreads), lds, a);
         } else if (depth == 2) {

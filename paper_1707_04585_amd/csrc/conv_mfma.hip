@@ -174,7 +174,11 @@ void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const flo
     cx.cost.conv_fwd_calls += 1;
     cx.cost.conv_flops += flops;
     if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
-    if (dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch)) return;
+    cx.emitted = EmittedStats{};
+    cx.want_emit = true;  // forward convolutions feed a BN layer next: let the kernel describe its output if it can
+    const bool done = dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch);
+    cx.want_emit = false;
+    if (done) return;
     conv_mfma(cx, x, scale_shift, w, false, cin, cout, ks, g, dt == RVN_BF16, ep, r, out);
 }
 

@@ -57,8 +57,26 @@ const char *kernel_name(int id);
 void profile_new_mark(int id, double bytes, double flops, hipEvent_t *start, hipEvent_t *stop);
 bool profile_enabled();
 
+// Per-channel (mean, M2) of every 128-pixel tile of a tensor, written by the
+// convolution that produced it; the next statistics pass of exactly that tensor
+// merges them instead of reading the tensor again.
+struct EmittedStats {
+    const float *p = nullptr;  // the tensor: base, strides, channels, geometry
+    int64_t sn = 0, sc = 0;
+    int c = 0, n = 0, h = 0, w = 0;
+    int tiles = 0;  // partial results per channel: partials[(channel * tiles + tile) * 2 + {0, 1}]
+};
+
 // One call's launch context.  With dry == true the wrappers only count.
 struct Ctx {
+    // Statistics from the producing epilogue: the driver lends a buffer
+    // (emit_buf, emit_floats floats; null = off), conv_fwd sets want_emit for the
+    // kernels it dispatches, a kernel that emits records what it described in
+    // `emitted`, and the next bn_stats call consumes that record (match or not).
+    float *emit_buf = nullptr;
+    size_t emit_floats = 0;
+    bool want_emit = false;
+    EmittedStats emitted;
     hipStream_t stream = nullptr;
     bool dry = false;
     rvn_cost cost = {};

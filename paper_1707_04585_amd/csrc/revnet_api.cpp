@@ -111,6 +111,14 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed)
     off = align_up(off + wg_s * 4);
     p.conv_scratch = off;
     off = align_up(off + cv_s * 4);
+    if (d.conv_dtype == RVN_BF16) {
+        // (mean, M2) per channel and 128-pixel tile of a 1x1 convolution's output
+        const size_t tiles = ((size_t)g.n * (((size_t)g.h * g.w + 3) / 4) + 31) / 32;
+        for (int l = 0; l < p.L; ++l)
+            if (p.layers[l].ks == 1) p.emit_floats = std::max(p.emit_floats, (size_t)p.layers[l].cout * tiles * 2);
+        p.emit = off;
+        off = align_up(off + p.emit_floats * 4);
+    }
     if (fixed) {
         p.xf = off;
         off = align_up(off + P * d.c_half * 4);
@@ -161,6 +169,7 @@ Bufs bind(const Plan &p, void *ws) {
     o.conv_scratch = reinterpret_cast<float *>(b + p.conv_scratch);
     o.xf = reinterpret_cast<float *>(b + p.xf);
     o.fout = reinterpret_cast<float *>(b + p.fout);
+    o.emit = p.emit_floats ? reinterpret_cast<float *>(b + p.emit) : nullptr;
     return o;
 }
 
@@ -255,6 +264,8 @@ int check_ws(const void *ws, size_t have, size_t need) {
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
                   const rvn_func_params &p, Epilogue ep, const View *r, View out, int frac_bits) {
     View cur = x;
+    cx.emit_buf = b.emit;  // 1x1 bf16 convolutions leave statistics of their output for the next BN layer
+    cx.emit_floats = pl.emit_floats;
     if (frac_bits) {
         fix_to_float(cx, x, pl.layers[0].cin, g, frac_bits, b.xf);
         cur = dense_view(b.xf, pl.layers[0].cin, g);

@@ -48,6 +48,10 @@ def run_fixed(cfg, x, params, dy, frac_bits=FB):
     # 150 basic blocks = 600 convolution layers, the depth of the network the paper's appendix on memory savings mentions
     ("basic_bf16_150_blocks", dict(kind="basic", n=4, c=16, h=8, w=8, depth=150, width=None, conv="bf16", affine="random")),
     ("bottleneck_bf16_12_blocks_ragged", dict(kind="bottleneck", n=3, c=96, h=9, w=7, depth=12, width=24, conv="bf16", affine="random")),
+    # whole 128-pixel tiles: inside F and G the 1x1 convolutions hand their outputs' statistics to the next BN
+    # layer, in the forward pass and in the recomputation alike
+    ("bottleneck_bf16_12_blocks_tiles", dict(kind="bottleneck", n=8, c=64, h=16, w=16, depth=12, width=16, conv="bf16", affine="random")),
+    ("bottleneck_bf16_6_blocks_shares", dict(kind="bottleneck", n=16, c=512, h=8, w=8, depth=6, width=128, conv="bf16", affine="random")),
 ])
 def test_fixed_stream_reconstructs_bit_for_bit(oracle, torch_cuda, name, cfg):
     """The reconstructed input codes equal the input codes exactly, at depths
