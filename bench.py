@@ -33,10 +33,10 @@ MEASURED_TRAFFIC = {
     ("c2_stack9", "conv_fwd"): 22915504,
     # c4_bneck12: conv1x1_bf16_k (128->64), conv3x3_bf16_k, conv1x1_bf16_k (64->128), same averaging
     # (profiles/c4_bneck12_hbm_traffic.txt)
-    ("c4_bneck12", "conv_fwd"): 170808685,
+    ("c4_bneck12", "conv_fwd"): 183077628,
     # c5_stage3: the two conv1x1_bf16_k shapes and conv3x3_bf16_k + its splitk_reduce_k
     # (profiles/c5_stage3_hbm_traffic.txt)
-    ("c5_stage3", "conv_fwd"): 52186495,
+    ("c5_stage3", "conv_fwd"): 52837304,
 }
 
 
