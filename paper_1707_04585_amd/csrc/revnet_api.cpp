@@ -286,8 +286,12 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.conv_scratch);
             cur = h;
         } else if (frac_bits) {
+            // (no statistics from this epilogue: the next BN layer reads the stream's fp32 copy, not fout)
+            float *const lent = cx.emit_buf;
+            cx.emit_buf = nullptr;
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr,
                      dense_view(b.fout, ly.cout, g), b.conv_scratch);
+            cx.emit_buf = lent;
             fix_axpy(cx, *r, b.fout, ly.cout, g, frac_bits, ep == EP_SUB ? -1 : 1, out);
         } else {
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.conv_scratch);
