@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void bn_stats_k(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------
-// statistics from partial results: (mean, M2) of every 128-pixel tile of a
+// statistics from partial results: (mean, M2) of every pixel tile of a
 // channel, written by the convolution that produced the tensor, merged (Chan
 // et al., double precision, fixed order) into the same four per-channel arrays.
 // One workgroup per channel: thread t takes tiles t, t + 256, ..., then a
@@ -441,7 +441,7 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
         PrepArgs pa{};
         if (carry) pa = *carry;
         cx.run(bn_stats_merge_k, dim3((unsigned)(c + pa.blocks)), dim3(kThreads), 0, (const float *)cx.emit_buf, e.tiles,
-               128.f, eps, gamma, beta, stats, c, pa);
+               (float)e.count, eps, gamma, beta, stats, c, pa);
         return;
     }
     const int S = reduce_splits(c, g);

@@ -385,7 +385,7 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         const bool emits = cx.want_emit && cx.emit_buf && !gen && a.groups % 32 == 0 && ns == g.n &&
                            (size_t)co * ptiles * 2 <= cx.emit_floats;
         a.emit = emits ? cx.emit_buf : nullptr;
-        if (emits) cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, ptiles};
+        if (emits) cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, ptiles, 128};
         const dim3 grid((unsigned)wgs);
         const size_t lds = a.KW > 1 ? (size_t)(a.KW - 1) * (a.PW * a.CW) * mtw * 64 * 64 * 4 : 0;
         const int depth = mtw == 1 ? 2 : 1;

@@ -34,10 +34,10 @@ namespace {
 
 constexpr int kThreads = kConvThreads;
 
-template <int KS, int MT, int NT, int KC>
+template <int KS, int MT, int NT, int KC, bool EMIT = false>
 __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
     extern __shared__ __align__(16) float smem[];
-    conv_mfma_f32_body<KS, MT, NT, KC>(p, blockIdx.x, blockIdx.y, smem);
+    conv_mfma_f32_body<KS, MT, NT, KC, EMIT>(p, blockIdx.x, blockIdx.y, smem);
 }
 
 int ilog2(int v) {
@@ -129,6 +129,20 @@ void conv_mfma(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
     tl.NT = L.nt;
     tl.lds_bytes = L.lds_bytes;
     ConvArgs a = L.a;
+    // Statistics of the output for the BN layer that reads it next (fp32 operands, 3x3, up to 32 output
+    // channels, 4 tiles per wavefront): every tile slot of every workgroup must be a whole, valid tile.
+    const int tiles = (int)L.grid.x * kWaves;
+    const bool whole = a.n_tiles == kWaves * L.nt && g.h % a.TH == 0 && a.TH % a.trows == 0 &&
+                       g.w % (1 << a.tcols_log2) == 0 && g.n % a.IMGS == 0;
+    if (cx.want_emit && cx.emit_buf && !bf16 && !transposed && ks == 3 && L.kc == 16 && L.nt == 4 && L.mt <= 2 &&
+        whole && (size_t)co * tiles * 2 <= cx.emit_floats) {
+        a.emit = cx.emit_buf;
+        a.emit_tiles = tiles;
+        cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, tiles, 16 * L.nt};
+        if (L.mt == 1) cx.run(conv_mfma_f32_k<3, 1, 4, 16, true>, L.grid, dim3(kThreads), tl.lds_bytes, a);
+        else cx.run(conv_mfma_f32_k<3, 2, 4, 16, true>, L.grid, dim3(kThreads), tl.lds_bytes, a);
+        return;
+    }
     if (ks == 3) {
         if (L.kc == 8) launch_conv<3, 8>(cx, a, tl, L.mt, L.grid);
         else launch_conv<3, 16>(cx, a, tl, L.mt, L.grid);
@@ -176,10 +190,9 @@ void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const flo
     if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
     cx.emitted = EmittedStats{};
     cx.want_emit = true;  // forward convolutions feed a BN layer next: let the kernel describe its output if it can
-    const bool done = dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch);
+    if (!(dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch)))
+        conv_mfma(cx, x, scale_shift, w, false, cin, cout, ks, g, dt == RVN_BF16, ep, r, out);
     cx.want_emit = false;
-    if (done) return;
-    conv_mfma(cx, x, scale_shift, w, false, cin, cout, ks, g, dt == RVN_BF16, ep, r, out);
 }
 
 void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *wq, int cin, int cout, int ks,

@@ -24,6 +24,11 @@ struct ConvArgs {
     int lrows, pitch, plane, img_stride;  // LDS geometry (floats)
     int tpr_log2;                 // threads per staged row
     float inv_lrows;
+    // EMIT instances (every tile slot of every workgroup a whole, valid tile): per channel and
+    // wavefront the mean and centred sum of squares of the 16 * NT pixels it stores, at
+    // emit[(channel * emit_tiles + workgroup * 4 + wavefront) * 2]
+    float *emit;
+    int emit_tiles;
 };
 
 // What a launch of the convolution needs besides its arguments.
@@ -54,7 +59,7 @@ __device__ __forceinline__ float bf16_round_dev(float f) {
 }
 
 // Workgroup (bx, by) of the convolution; `smem` is the workgroup's dynamic LDS.
-template <int KS, int MT, int NT, int KC>
+template <int KS, int MT, int NT, int KC, bool EMIT = false>
 __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, int by, float *smem) {
     constexpr int KS2 = KS * KS, PAD = KS / 2, LP = KS == 3 ? 4 : 0;
     constexpr int WCHUNK = (KC / 4) * KS2 * MT * 64;  // filter floats per chunk
@@ -284,6 +289,58 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
             for (int j = 0; j < 4; ++j) {
                 const int ko = co0 + m * 16 + kq * 4 + j;
                 if (ko < p.CO) p.out[e_off[t] + (int64_t)ko * p.osc] = acc[m][t][j];
+            }
+        }
+    }
+    // Statistics of what was stored, for the BN layer that reads it next: a channel's pixels of this
+    // wavefront are NT registers in each of the 16 lanes of one quarter.  Sums of (v - pivot) and
+    // (v - pivot)^2, pivot = the quarter's first value, are folded over the lanes four channels at a
+    // time (two steps halve the channels a lane holds and add its partner's, two plain steps follow).
+    if constexpr (EMIT) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            float ea[4], eb[4], piv[4];  // the pivots are uniform over the quarter
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                piv[j] = __shfl(acc[m][0][j], kq * 16, 64);
+                float a = 0.f, b = 0.f;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const float d = acc[m][t][j] - piv[j];
+                    a += d;
+                    b += d * d;
+                }
+                ea[j] = a;
+                eb[j] = b;
+            }
+            const bool up8 = (l16 & 8) != 0, up4 = (l16 & 4) != 0;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const float keep_a = up8 ? ea[k + 2] : ea[k], send_a = up8 ? ea[k] : ea[k + 2];
+                const float keep_b = up8 ? eb[k + 2] : eb[k], send_b = up8 ? eb[k] : eb[k + 2];
+                ea[k] = keep_a + __shfl_xor(send_a, 8, 64);
+                eb[k] = keep_b + __shfl_xor(send_b, 8, 64);
+            }
+            {
+                const float keep_a = up4 ? ea[1] : ea[0], send_a = up4 ? ea[0] : ea[1];
+                const float keep_b = up4 ? eb[1] : eb[0], send_b = up4 ? eb[0] : eb[1];
+                ea[0] = keep_a + __shfl_xor(send_a, 4, 64);
+                eb[0] = keep_b + __shfl_xor(send_b, 4, 64);
+            }
+            ea[0] += __shfl_xor(ea[0], 2, 64);
+            eb[0] += __shfl_xor(eb[0], 2, 64);
+            ea[0] += __shfl_xor(ea[0], 1, 64);
+            eb[0] += __shfl_xor(eb[0], 1, 64);
+            // the lane now holds channel j = l16 / 4 of its quarter
+            const int j = l16 >> 2;
+            const float pivot = j == 0 ? piv[0] : j == 1 ? piv[1] : j == 2 ? piv[2] : piv[3];
+            const int ko = co0 + m * 16 + kq * 4 + j;
+            if ((l16 & 3) == 0 && ko < p.CO) {
+                constexpr float inv = 1.f / (16 * NT);
+                const float mean = pivot + ea[0] * inv;
+                const float m2 = fmaxf(eb[0] - ea[0] * ea[0] * inv, 0.f);
+                float2 *dst = reinterpret_cast<float2 *>(p.emit) + (int64_t)ko * p.emit_tiles + (bx * kWaves + wave);
+                *dst = make_float2(mean, m2);
             }
         }
     }

@@ -57,7 +57,7 @@ const char *kernel_name(int id);
 void profile_new_mark(int id, double bytes, double flops, hipEvent_t *start, hipEvent_t *stop);
 bool profile_enabled();
 
-// Per-channel (mean, M2) of every 128-pixel tile of a tensor, written by the
+// Per-channel (mean, M2) of every pixel tile (128 or 64 pixels) of a tensor, written by the
 // convolution that produced it; the next statistics pass of exactly that tensor
 // merges them instead of reading the tensor again.
 struct EmittedStats {
@@ -65,6 +65,7 @@ struct EmittedStats {
     int64_t sn = 0, sc = 0;
     int c = 0, n = 0, h = 0, w = 0;
     int tiles = 0;  // partial results per channel: partials[(channel * tiles + tile) * 2 + {0, 1}]
+    int count = 0;  // pixels behind every partial result
 };
 
 // One call's launch context.  With dry == true the wrappers only count.

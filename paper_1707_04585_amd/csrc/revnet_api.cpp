@@ -111,11 +111,16 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed)
     off = align_up(off + wg_s * 4);
     p.conv_scratch = off;
     off = align_up(off + cv_s * 4);
-    if (d.conv_dtype == RVN_BF16) {
-        // (mean, M2) per channel and 128-pixel tile of a 1x1 convolution's output
-        const size_t tiles = ((size_t)g.n * (((size_t)g.h * g.w + 3) / 4) + 31) / 32;
-        for (int l = 0; l < p.L; ++l)
-            if (p.layers[l].ks == 1) p.emit_floats = std::max(p.emit_floats, (size_t)p.layers[l].cout * tiles * 2);
+    {
+        // (mean, M2) per channel and pixel tile of a convolution's output: 128-pixel tiles of the bf16
+        // 1x1 kernel, 64-pixel wavefront shares of the fp32 3x3 kernel
+        const size_t tiles128 = ((size_t)g.n * (((size_t)g.h * g.w + 3) / 4) + 31) / 32, tiles64 = P / 64 + kAlign;
+        for (int l = 0; l < p.L; ++l) {
+            const Layer &ly = p.layers[l];
+            if (d.conv_dtype == RVN_BF16 && ly.ks == 1) p.emit_floats = std::max(p.emit_floats, (size_t)ly.cout * tiles128 * 2);
+            if (d.conv_dtype != RVN_BF16 && ly.ks == 3 && ly.cout <= 32)
+                p.emit_floats = std::max(p.emit_floats, (size_t)ly.cout * tiles64 * 2);
+        }
         p.emit = off;
         off = align_up(off + p.emit_floats * 4);
     }
