@@ -28,9 +28,9 @@ PEAK = {"hbm": (8000.0, "GB/s"), "mfma_f32": (157.3, "TFLOP/s"), "mfma_bf16": (2
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs (profiles/), keyed by (workload, kernel family); None = not measured.
 MEASURED_TRAFFIC = {
-    # conv_mfma_f32_k at c2_stack9: (FETCH_SIZE 7094.0 KiB x 2.0 + WRITE_SIZE 8192.0 KiB x 1.0) per dispatch,
+    # conv_mfma_f32_k at c2_stack9: (FETCH_SIZE 7108.5 KiB x 2.0 + WRITE_SIZE 8448.0 KiB x 1.0) per dispatch,
     # averaged over forward and recompute launches (profiles/c2_stack9_hbm_traffic.txt)
-    ("c2_stack9", "conv_fwd"): 22915504,
+    ("c2_stack9", "conv_fwd"): 23207351,
     # c4_bneck12: conv1x1_bf16_k (128->64), conv3x3_bf16_k, conv1x1_bf16_k (64->128), same averaging
     # (profiles/c4_bneck12_hbm_traffic.txt)
     ("c4_bneck12", "conv_fwd"): 183077628,
