@@ -26,6 +26,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "stats_fold.h"
 
 namespace rvn {
 
@@ -69,23 +70,6 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     const float2_t v = {lo, hi};
     const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
     return *reinterpret_cast<const uint32_t *>(&b);
-}
-
-// One step of the 16-channel fold of the statistics epilogue: a lane holding CNT
-// channels keeps the lower or upper half (by bit CNT of its index) and adds
-// the same half of the lane CNT away; the pivot of a kept channel moves along.
-template <int CNT>
-__device__ __forceinline__ void fold_step(float (&ea)[16], float (&eb)[16], float (&piv)[16], int l32) {
-    constexpr int H = CNT / 2;
-    const bool up = (l32 & CNT) != 0;
-#pragma unroll
-    for (int k = 0; k < H; ++k) {
-        const float keep_a = up ? ea[k + H] : ea[k], send_a = up ? ea[k] : ea[k + H];
-        const float keep_b = up ? eb[k + H] : eb[k], send_b = up ? eb[k] : eb[k + H];
-        ea[k] = keep_a + __shfl_xor(send_a, CNT, 64);
-        eb[k] = keep_b + __shfl_xor(send_b, CNT, 64);
-        piv[k] = up ? piv[k + H] : piv[k];
-    }
 }
 
 // MTW: 32-channel output tiles per wavefront.  DEPTH: steps the loads run ahead
@@ -298,12 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
             }
         }
         if constexpr (emit) {
-            fold_step<16>(ea, eb, piv, l32);
-            fold_step<8>(ea, eb, piv, l32);
-            fold_step<4>(ea, eb, piv, l32);
-            fold_step<2>(ea, eb, piv, l32);
-            ea[0] += __shfl_xor(ea[0], 1, 64);
-            eb[0] += __shfl_xor(eb[0], 1, 64);
+            fold_16_channels(ea, eb, piv, l32);
             // the lane now holds register i = l32 / 2 of this tile
             const int i = l32 >> 1;
             const int c = (mt0 + m) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3);

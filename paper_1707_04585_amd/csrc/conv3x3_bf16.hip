@@ -25,6 +25,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "stats_fold.h"
 
 namespace rvn {
 
@@ -61,6 +62,11 @@ struct C3Args {
     int chunks, cps;      // channel chunks in total and per split
     float *part;          // partial tiles [split][n][ko][h*w] when gridDim.z > 1
     int64_t part_stride;
+    // EMIT instances (no split, every pixel slot of every workgroup a valid pixel): per channel and
+    // wavefront the mean and centred sum of squares of the 32 * NTW pixels it stores, at
+    // emit[(channel * emit_tiles + blockIdx.x * WN + wn) * 2]
+    float *emit;
+    int emit_tiles;
 };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -71,7 +77,7 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 
 // WM x WN wavefronts (WM * WN = 4), each MTW x NTW tiles of 32 output channels
 // x 32 pixels; KC input channels per chunk.
-template <int WM, int MTW, int NTW, int KC>
+template <int WM, int MTW, int NTW, int KC, bool EMIT = false>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
     constexpr int WN = 4 / WM;
     constexpr int REC = KC + kPadK, OCTS = KC / 8;
@@ -282,6 +288,41 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
             }
         }
     }
+    // Statistics of what was stored, for the BN layer that reads it next (host: no split, every
+    // slot a valid pixel): a channel's 32 * NTW pixels of this wavefront sit in the 32 lanes of one
+    // half, NTW per lane; sums about the half's first value, folded 16 channels at a time.
+    if constexpr (EMIT) {
+#pragma unroll
+        for (int m = 0; m < MTW; ++m) {
+            float ea[16], eb[16], piv[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int v0 = __float_as_int(acc[m][0][i]);
+                const float lo = __int_as_float(__builtin_amdgcn_readlane(v0, 0));
+                const float hi = __int_as_float(__builtin_amdgcn_readlane(v0, 32));
+                piv[i] = kg ? hi : lo;
+                float a = 0.f, b = 0.f;
+#pragma unroll
+                for (int t = 0; t < NTW; ++t) {
+                    const float d = acc[m][t][i] - piv[i];
+                    a += d;
+                    b += d * d;
+                }
+                ea[i] = a;
+                eb[i] = b;
+            }
+            fold_16_channels(ea, eb, piv, l32);
+            const int i = l32 >> 1;  // the register this lane now holds
+            const int ko = co0 + (wm * MTW + m) * 32 + 4 * kg + 8 * (i >> 2) + (i & 3);
+            if ((l32 & 1) == 0 && ko < CO) {
+                constexpr float inv = 1.f / (32 * NTW);
+                const float mean = piv[0] + ea[0] * inv;
+                const float m2 = fmaxf(eb[0] - ea[0] * ea[0] * inv, 0.f);
+                float2 *dst = reinterpret_cast<float2 *>(p.emit) + (int64_t)ko * p.emit_tiles + ((int)blockIdx.x * WN + wn);
+                *dst = make_float2(mean, m2);
+            }
+        }
+    }
 }
 
 // out = ep(r, sum_s part[s]) over dense partial tiles [S][n][c][hw], summed in
@@ -358,11 +399,11 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
     return pl;
 }
 
-template <int WM, int MTW, int NTW, int KC>
-void launch_c3(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
+template <int WM, int MTW, int NTW, int KC, bool EMIT>
+void launch_c3_variant(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once
     if (!raised) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (e != hipSuccess) {
             cx.fail(e);
@@ -370,7 +411,13 @@ void launch_c3(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
         }
         raised = true;
     }
-    cx.run(conv3x3_bf16_k<WM, MTW, NTW, KC>, grid, dim3(kThreads), pl.lds_bytes, a);
+    cx.run(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT>, grid, dim3(kThreads), pl.lds_bytes, a);
+}
+
+template <int WM, int MTW, int NTW, int KC>
+void launch_c3(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
+    if (a.emit) launch_c3_variant<WM, MTW, NTW, KC, true>(cx, pl, a, grid);
+    else launch_c3_variant<WM, MTW, NTW, KC, false>(cx, pl, a, grid);
 }
 
 }  // namespace
@@ -403,6 +450,15 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     a.part = scratch; a.part_stride = (int64_t)g.n * co * g.h * g.w;
     const int ch = pl.WM * pl.MTW * 32;
     const dim3 grid((unsigned)(pl.bands * ((g.n + pl.IMGS - 1) / pl.IMGS)), (unsigned)((co + ch - 1) / ch), (unsigned)pl.S);
+    // Statistics of the output for the BN layer that reads it next: no split, and every pixel slot
+    // of every workgroup a valid pixel (whole blocks of rows or images).
+    const int wn_count = 4 / pl.WM, slots = wn_count * 2 * 32, tiles = (int)grid.x * wn_count;
+    const bool whole = a.n_pix == slots && g.n % pl.IMGS == 0 && g.h % pl.TR == 0;
+    if (cx.want_emit && cx.emit_buf && pl.S == 1 && whole && (size_t)co * tiles * 2 <= cx.emit_floats) {
+        a.emit = cx.emit_buf;
+        a.emit_tiles = tiles;
+        cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, tiles, 64};
+    }
     bool launched = true;
     if (pl.WM == 1 && pl.MTW == 1 && pl.KC == 16) launch_c3<1, 1, 2, 16>(cx, pl, a, grid);
     else if (pl.WM == 1 && pl.MTW == 1 && pl.KC == 32) launch_c3<1, 1, 2, 32>(cx, pl, a, grid);
@@ -410,7 +466,10 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     else if (pl.WM == 1 && pl.MTW == 2 && pl.KC == 32) launch_c3<1, 2, 2, 32>(cx, pl, a, grid);
     else if (pl.WM == 2 && pl.MTW == 2 && pl.KC == 16) launch_c3<2, 2, 2, 16>(cx, pl, a, grid);
     else launched = false;
-    if (!launched) return false;
+    if (!launched) {
+        cx.emitted = EmittedStats{};
+        return false;
+    }
     if (pl.S > 1) {
         const int64_t total = a.part_stride;
         cx.run(splitk_reduce_k, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, scratch,

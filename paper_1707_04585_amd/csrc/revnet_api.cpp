@@ -113,12 +113,12 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed)
     off = align_up(off + cv_s * 4);
     {
         // (mean, M2) per channel and pixel tile of a convolution's output: 128-pixel tiles of the bf16
-        // 1x1 kernel, 64-pixel wavefront shares of the fp32 3x3 kernel
+        // 1x1 kernel, 64-pixel wavefront shares of the 3x3 kernels
         const size_t tiles128 = ((size_t)g.n * (((size_t)g.h * g.w + 3) / 4) + 31) / 32, tiles64 = P / 64 + kAlign;
         for (int l = 0; l < p.L; ++l) {
             const Layer &ly = p.layers[l];
             if (d.conv_dtype == RVN_BF16 && ly.ks == 1) p.emit_floats = std::max(p.emit_floats, (size_t)ly.cout * tiles128 * 2);
-            if (d.conv_dtype != RVN_BF16 && ly.ks == 3 && ly.cout <= 32)
+            if (ly.ks == 3 && (d.conv_dtype == RVN_BF16 || ly.cout <= 32))
                 p.emit_floats = std::max(p.emit_floats, (size_t)ly.cout * tiles64 * 2);
         }
         p.emit = off;
