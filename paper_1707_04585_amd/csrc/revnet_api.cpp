@@ -269,7 +269,10 @@ int check_ws(const void *ws, size_t have, size_t need) {
 void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
                   const rvn_func_params &p, Epilogue ep, const View *r, View out, int frac_bits) {
     View cur = x;
-    cx.emit_buf = b.emit;  // 1x1 bf16 convolutions leave statistics of their output for the next BN layer
+    // Convolutions leave statistics of their output for the next BN layer.  With the fixed-point
+    // stream only the inner tensors of a function can use them; that pays for the three-layer
+    // function (-1 % at the bottleneck workload) and not for the two-layer one (+0.5 %).
+    cx.emit_buf = frac_bits && pl.L < 3 ? nullptr : b.emit;
     cx.emit_floats = pl.emit_floats;
     if (frac_bits) {
         fix_to_float(cx, x, pl.layers[0].cin, g, frac_bits, b.xf);
