@@ -72,6 +72,9 @@ struct Plan {
     size_t xf, fout;
     // per-tile statistics that a 1x1 bf16 convolution leaves for the BN layer reading its output
     size_t emit, emit_floats;
+    // two spare layer-0 statistics arrays: a function's input statistics that a launch of the
+    // backward pass computed ahead (merge of the producing convolution's partial results)
+    size_t stats_in[2];
     size_t total;
 };
 struct Bufs {
@@ -84,6 +87,7 @@ struct Bufs {
     uint16_t *wq_f[3], *wq_b[3];  // null where the layer does not use converted filters
     float *xf, *fout;
     float *emit;  // null when the plan has none
+    float *stats_in[2];
 };
 Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed = false);
 Bufs bind(const Plan &p, void *ws);

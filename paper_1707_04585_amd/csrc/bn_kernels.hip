@@ -218,16 +218,11 @@ __device__ __forceinline__ void chan_merge(double &n, double &mean, double &m2, 
     n = tot;
 }
 
-__global__ __launch_bounds__(kThreads) void bn_stats_merge_k(const float *__restrict__ partials, int tiles, float count,
-                                                             float eps, const float *__restrict__ gamma,
-                                                             const float *__restrict__ beta, float *__restrict__ stats,
-                                                             int C, const PrepArgs carry) {
-    if ((int)blockIdx.x < carry.blocks) {
-        prep_filter_body(carry, blockIdx.x);
-        return;
-    }
+// Channel `ch` of the merge, by one workgroup of kThreads threads.
+__device__ __forceinline__ void bn_stats_merge_body(const float *__restrict__ partials, int tiles, float count, float eps,
+                                                    const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                    float *__restrict__ stats, int C, int ch) {
     __shared__ double red[kThreads / 64][3];
-    const int ch = blockIdx.x - carry.blocks;
     const float2 *q = reinterpret_cast<const float2 *>(partials) + (int64_t)ch * tiles;
     double n = 0.0, mean = 0.0, m2 = 0.0;
     for (int t0 = threadIdx.x; t0 < tiles; t0 += 8 * kThreads) {
@@ -254,6 +249,17 @@ __global__ __launch_bounds__(kThreads) void bn_stats_merge_k(const float *__rest
         stats[2 * C + ch] = scale;
         stats[3 * C + ch] = fmaf(-mean_f, scale, beta[ch]);
     }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_stats_merge_k(const float *__restrict__ partials, int tiles, float count,
+                                                             float eps, const float *__restrict__ gamma,
+                                                             const float *__restrict__ beta, float *__restrict__ stats,
+                                                             int C, const PrepArgs carry) {
+    if ((int)blockIdx.x < carry.blocks) {
+        prep_filter_body(carry, blockIdx.x);
+        return;
+    }
+    bn_stats_merge_body(partials, tiles, count, eps, gamma, beta, stats, C, (int)blockIdx.x - carry.blocks);
 }
 
 // ---------------------------------------------------------------------------
@@ -344,17 +350,24 @@ template <bool VEC, bool SKIP>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
-    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry) {
-    // The first carry.blocks workgroups sum a filter gradient's partial results
-    // (independent work that would otherwise be a launch of its own; first, so
-    // that its dependent loads run under the streaming of the others).
-    if ((int)blockIdx.x < carry.blocks) {
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge) {
+    // The first workgroups do independent work that would otherwise be launches of their own (first,
+    // so that their dependent loads run under the streaming of the others): merge.blocks of them merge
+    // the partial statistics of a tensor that a later BN layer reads, carry.blocks sum a filter
+    // gradient's partial results.
+    if ((int)blockIdx.x < merge.blocks) {
+        bn_stats_merge_body(merge.partials, merge.tiles, merge.count, merge.eps, merge.gamma, merge.beta, merge.stats,
+                            merge.C, (int)blockIdx.x);
+        return;
+    }
+    const int bx = (int)blockIdx.x - merge.blocks;
+    if (bx < carry.blocks) {
         __shared__ float lds[kThreads];
-        wgrad_reduce_body(carry, blockIdx.x, lds);
+        wgrad_reduce_body(carry, bx, lds);
         return;
     }
     constexpr int E = VEC ? 4 : 1;
-    const int64_t v = (int64_t)(blockIdx.x - carry.blocks) * kThreads + threadIdx.x;
+    const int64_t v = (int64_t)(bx - carry.blocks) * kThreads + threadIdx.x;
     if (v >= total) return;
     const int per_plane = HW / E;
     const int64_t plane = v / per_plane;
@@ -481,9 +494,11 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         WgradReduce red{};
         if (carry) red = *carry;
         if (red.blocks < 0) red.blocks = 0;
-        const unsigned extra = (unsigned)red.blocks;
+        const StatsMerge merge = cx.merge_carry;  // a waiting merge rides along
+        cx.merge_carry = StatsMerge{};
+        const unsigned extra = (unsigned)red.blocks + (unsigned)merge.blocks;
 #define RVN_LAUNCH(V, K) \
-    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red)
+    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);

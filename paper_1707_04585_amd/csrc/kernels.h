@@ -68,8 +68,28 @@ struct EmittedStats {
     int count = 0;  // pixels behind every partial result
 };
 
+// A merge of such partial results into the four per-channel statistics arrays
+// (what bn_stats_merge_k does), as work that another launch can carry:
+// `blocks` workgroups of 256 threads, one per channel; 0 = nothing.
+struct StatsMerge {
+    const float *partials = nullptr;
+    int tiles = 0;
+    float count = 0.f;
+    const float *gamma = nullptr, *beta = nullptr;
+    float *stats = nullptr;
+    int C = 0;
+    float eps = 0.f;
+    int blocks = 0;
+};
+
 // One call's launch context.  With dry == true the wrappers only count.
 struct Ctx {
+    // A merge waiting for a launch to carry it (the next BN-backward apply launch takes it), and the
+    // record of a tensor whose statistics such a carried merge has put into `premerged_stats`.
+    StatsMerge merge_carry;
+    EmittedStats premerged;
+    const float *premerged_stats = nullptr;
+    int premerge_slot = 0;
     // Statistics from the producing epilogue: the driver lends a buffer
     // (emit_buf, emit_floats floats; null = off), conv_fwd sets want_emit for the
     // kernels it dispatches, a kernel that emits records what it described in

@@ -124,6 +124,10 @@ Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed)
         p.emit = off;
         off = align_up(off + p.emit_floats * 4);
     }
+    for (int i = 0; i < 2; ++i) {
+        p.stats_in[i] = off;
+        off = align_up(off + kStatsArrays * (size_t)p.layers[0].cin * 4);
+    }
     if (fixed) {
         p.xf = off;
         off = align_up(off + P * d.c_half * 4);
@@ -175,6 +179,7 @@ Bufs bind(const Plan &p, void *ws) {
     o.xf = reinterpret_cast<float *>(b + p.xf);
     o.fout = reinterpret_cast<float *>(b + p.fout);
     o.emit = p.emit_floats ? reinterpret_cast<float *>(b + p.emit) : nullptr;
+    for (int i = 0; i < 2; ++i) o.stats_in[i] = reinterpret_cast<float *>(b + p.stats_in[i]);
     return o;
 }
 
@@ -266,8 +271,18 @@ int check_ws(const void *ws, size_t have, size_t need) {
 // func_backward reads as the function's input afterwards -- and its value is
 // rounded into the stream by an integer add / subtract (Section 3.2,
 // "Numerical error").
-void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
-                  const rvn_func_params &p, Epilogue ep, const View *r, View out, int frac_bits) {
+// Returns where the statistics of layer 0 are: b.stats[0], or the spare array that a carried merge
+// filled ahead (see arm_merge); func_backward of the same function must be given that pointer.
+const float *func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
+                          const rvn_func_params &p, Epilogue ep, const View *r, View out, int frac_bits) {
+    // the input's statistics may be there already
+    const EmittedStats pm = cx.premerged;
+    const float *const pm_stats = cx.premerged_stats;
+    cx.premerged = EmittedStats{};
+    cx.premerged_stats = nullptr;
+    const bool ahead = !frac_bits && pm.p && pm_stats && pm.p == x.p && pm.sn == x.sn && pm.sc == x.sc &&
+                       pm.c == pl.layers[0].cin && pm.n == g.n && pm.h == g.h && pm.w == g.w;
+    const float *const stats0 = ahead ? pm_stats : b.stats[0];
     View cur = x;
     // Convolutions leave statistics of their output for the next BN layer.  With the fixed-point
     // stream only the inner tensors of a function can use them; that pays for the three-layer
@@ -286,9 +301,13 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
     const PrepArgs pa = plan_filter_prep(prep, pl.L, g, &prep_bytes);
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
-        bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l],
-                 l == 0 && pa.jobs > 0 ? &pa : nullptr, l == 0 ? prep_bytes : 0.0);
-        const float *scale_shift = b.stats[l] + 2 * ly.cin;
+        if (l == 0 && ahead) {
+            cx.emitted = EmittedStats{};  // (arm_merge only runs without a filter conversion to carry)
+        } else {
+            bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l],
+                     l == 0 && pa.jobs > 0 ? &pa : nullptr, l == 0 ? prep_bytes : 0.0);
+        }
+        const float *scale_shift = (l == 0 ? stats0 : b.stats[l]) + 2 * ly.cin;
         if (l < pl.L - 1) {
             View h = dense_view(b.h[l], ly.cout, g);
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE, nullptr, h, b.conv_scratch);
@@ -305,6 +324,36 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, ep, r, out, b.conv_scratch);
         }
     }
+    return stats0;
+}
+
+// If the convolution that has just run left partial statistics of `t` (the input of a function that
+// runs only after the backward pass of another), let the next BN-backward apply launch merge them
+// into a spare statistics array with that function's layer-0 parameters; func_forward finds them
+// there.  Only without a filter conversion to carry in the statistics launch this replaces (fp32
+// operands), and only with the floating-point stream.
+void arm_merge(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View t,
+               const rvn_func_params &consumer, int frac_bits) {
+    const EmittedStats e = cx.emitted;
+    const int c = pl.layers[0].cin;
+    if (cx.dry || frac_bits || d.conv_dtype != RVN_F32 || !cx.emit_buf || !e.p || e.count <= 0) return;
+    if (e.p != t.p || e.sn != t.sn || e.sc != t.sc || e.c != c || e.n != g.n || e.h != g.h || e.w != g.w) return;
+    float *const slot = b.stats_in[cx.premerge_slot];
+    cx.premerge_slot ^= 1;
+    StatsMerge m;
+    m.partials = cx.emit_buf;
+    m.tiles = e.tiles;
+    m.count = (float)e.count;
+    m.gamma = consumer.bn_gamma[0];
+    m.beta = consumer.bn_beta[0];
+    m.stats = slot;
+    m.C = c;
+    m.eps = d.bn_eps;
+    m.blocks = c;
+    cx.merge_carry = m;
+    cx.premerged = e;
+    cx.premerged_stats = slot;
+    cx.emitted = EmittedStats{};
 }
 
 // Ordinary backprop through Func at the activations func_forward left in `b`
@@ -312,31 +361,32 @@ void func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &
 // the parameter gradients.
 void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View x,
                    const rvn_func_params &p, View upstream, const rvn_func_grads &gr, bool accumulate,
-                   View skip, View out) {
+                   View skip, View out, const float *stats0) {
     View dh = upstream;
     int cur = 0;
     for (int l = pl.L - 1; l >= 0; --l) {
         const Layer &ly = pl.layers[l];
+        const float *const st = l == 0 ? stats0 : b.stats[l];
         const View xl = l > 0 ? dense_view(b.h[l - 1], ly.cin, g) : x;
         // The ordered sum of the filter gradient's partial results rides in the
         // BN-backward apply launch below.
         WgradReduce red;
         float *da = b.g[cur];
         if (d.conv_dtype != RVN_F32 ||
-            !conv_dgrad_wgrad_f32(cx, xl, b.stats[l] + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
+            !conv_dgrad_wgrad_f32(cx, xl, st + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
                                   b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, &red)) {
-            conv_wgrad(cx, xl, b.stats[l] + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
+            conv_wgrad(cx, xl, st + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                        gr.d_conv_w[l], accumulate, &red);
             conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
         }
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
-            bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+            bn_relu_bwd(cx, xl, da, ly.cin, g, st, b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, nullptr, dx, &red);
             dh = dx;
             cur ^= 1;
         } else {
-            bn_relu_bwd(cx, x, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
+            bn_relu_bwd(cx, x, da, ly.cin, g, st, b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, &skip, out, &red);
         }
     }
@@ -354,16 +404,21 @@ void block_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
 // derivatives stay fp32.
 void block_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View y1,
                     View y2, View dy1, View dy2, const rvn_block_params &p, View x1, View x2, View dx1,
-                    View dx2, const rvn_block_grads &gr, bool accumulate, int frac_bits) {
+                    View dx2, const rvn_block_grads &gr, bool accumulate, int frac_bits,
+                    const rvn_func_params *below_G) {
     const View shadow = dense_view(b.xf, d.c_half, g);  // fp32 copy of the function input at hand
     // z1 = y1;  x2 = y2 - G(z1)
-    func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2, frac_bits);
+    const float *const sg = func_forward(cx, d, pl, b, g, y1, p.G, EP_SUB, &y2, x2, frac_bits);
+    // (x2 is read next by F, after G's backward pass: its statistics can be merged in between)
+    arm_merge(cx, d, pl, b, g, x2, p.F, frac_bits);
     // dz1 = dy1 + (dG/dz1)^T dy2;  dwG          (dx1 = dz1)
-    func_backward(cx, d, pl, b, g, frac_bits ? shadow : y1, p.G, dy2, gr.G, accumulate, dy1, dx1);
+    func_backward(cx, d, pl, b, g, frac_bits ? shadow : y1, p.G, dy2, gr.G, accumulate, dy1, dx1, sg);
     // x1 = z1 - F(x2)
-    func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1, frac_bits);
+    const float *const sf = func_forward(cx, d, pl, b, g, x2, p.F, EP_SUB, &y1, x1, frac_bits);
+    // (x1 is the y1 of the block below: its G reads it after F's backward pass)
+    if (below_G) arm_merge(cx, d, pl, b, g, x1, *below_G, frac_bits);
     // dx2 = dy2 + (dF/dx2)^T dz1;  dwF
-    func_backward(cx, d, pl, b, g, frac_bits ? shadow : x2, p.F, dx1, gr.F, accumulate, dy2, dx2);
+    func_backward(cx, d, pl, b, g, frac_bits ? shadow : x2, p.F, dx1, gr.F, accumulate, dy2, dx2, sf);
 }
 
 int finish(Ctx &cx) {
@@ -433,7 +488,7 @@ void stack_backward(Ctx &cx, const rvn_block_desc &d, int depth, const Plan &pl,
     for (int k = depth - 1; k >= 0; --k) {
         const bool top = k == depth - 1;
         block_backward(cx, d, pl, b, g, top ? y1 : x1, top ? y2 : x2, top ? dy1 : dx1, top ? dy2 : dx2,
-                       params[k], x1, x2, dx1, dx2, grads[k], accumulate, frac_bits);
+                       params[k], x1, x2, dx1, dx2, grads[k], accumulate, frac_bits, k > 0 ? &params[k - 1].G : nullptr);
     }
 }
 
