@@ -350,7 +350,8 @@ template <bool VEC, bool SKIP>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
-    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge) {
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge,
+    const PrepArgs prep) {
     // The first workgroups do independent work that would otherwise be launches of their own (first,
     // so that their dependent loads run under the streaming of the others): merge.blocks of them merge
     // the partial statistics of a tensor that a later BN layer reads, carry.blocks sum a filter
@@ -360,7 +361,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
                             merge.C, (int)blockIdx.x);
         return;
     }
-    const int bx = (int)blockIdx.x - merge.blocks;
+    // (and prep.blocks convert the filters of the function that will read those statistics)
+    if ((int)blockIdx.x < merge.blocks + prep.blocks) {
+        prep_filter_body(prep, (int)blockIdx.x - merge.blocks);
+        return;
+    }
+    const int bx = (int)blockIdx.x - merge.blocks - prep.blocks;
     if (bx < carry.blocks) {
         __shared__ float lds[kThreads];
         wgrad_reduce_body(carry, bx, lds);
@@ -494,11 +500,18 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         WgradReduce red{};
         if (carry) red = *carry;
         if (red.blocks < 0) red.blocks = 0;
-        const StatsMerge merge = cx.merge_carry;  // a waiting merge rides along
-        cx.merge_carry = StatsMerge{};
-        const unsigned extra = (unsigned)red.blocks + (unsigned)merge.blocks;
+        // a waiting merge and filter conversion ride along when the caller says this is the launch
+        StatsMerge merge{};
+        PrepArgs prep{};
+        if (cx.carry_now) {
+            merge = cx.merge_carry;
+            prep = cx.prep_carry;
+            cx.merge_carry = StatsMerge{};
+            cx.prep_carry = PrepArgs{};
+        }
+        const unsigned extra = (unsigned)red.blocks + (unsigned)merge.blocks + (unsigned)prep.blocks;
 #define RVN_LAUNCH(V, K) \
-    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge)
+    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);

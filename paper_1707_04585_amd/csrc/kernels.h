@@ -68,6 +68,36 @@ struct EmittedStats {
     int count = 0;  // pixels behind every partial result
 };
 
+// The filter w [cout][cin][ks][ks] in bf16 and in the order the bf16 kernel
+// consumes it: qf [cout][ks*ks][cin padded to 8] for the forward convolution and
+// (if qb != nullptr) qb [cin][ks*ks][cout padded to 8], transposed and flipped,
+// for the data gradient.  filter_bf16_elems(rows, k_channels, ks) = elements of
+// such a buffer.
+//
+// 1x1 filters whose reduction length (cin forward, cout for the data gradient)
+// passes conv1x1_direct_ok are stored instead in the operand order of
+// conv1x1_bf16: [rows / 32][k_channels / 16][64 lanes][8], zero padded.
+size_t filter_bf16_elems(int rows, int k_channels, int ks);
+struct FilterPrep {
+    const float *w;  // [cout][cin][ks][ks]
+    int cin, cout, ks;
+    uint16_t *qf, *qb;  // destinations (either may be null)
+};
+// The conversion of the filters of up to three layers as one list of jobs
+// (see prep_filter.h); plan_filter_prep builds it, prep_filters_bf16 runs it in
+// a launch of its own, bn_stats can carry it instead.
+struct PrepJob {
+    const float *w;  // [CO][CI][KS2]
+    uint16_t *q;
+    int CO, CI, KS2, kind;
+    int KP;      // channel pitch (kinds 0, 1) or 16-channel steps per row tile (kinds 2, 3)
+    int block0;  // first workgroup of this job
+    int64_t n;   // threads: elements to write (kinds 2, 3) or (row, padded column) pairs (kinds 0, 1)
+};
+struct PrepArgs {
+    PrepJob job[6];
+    int jobs, blocks;
+};
 // A merge of such partial results into the four per-channel statistics arrays
 // (what bn_stats_merge_k does), as work that another launch can carry:
 // `blocks` workgroups of 256 threads, one per channel; 0 = nothing.
@@ -84,9 +114,11 @@ struct StatsMerge {
 
 // One call's launch context.  With dry == true the wrappers only count.
 struct Ctx {
-    // A merge waiting for a launch to carry it (the next BN-backward apply launch takes it), and the
+    // A merge waiting for a launch to carry it (the apply launch of a BN-backward call made with carry_now), and the
     // record of a tensor whose statistics such a carried merge has put into `premerged_stats`.
     StatsMerge merge_carry;
+    PrepArgs prep_carry = {};  // the filter conversion of the function that will read those statistics
+    bool carry_now = false;    // set around the one BN-backward call whose apply launch takes both
     EmittedStats premerged;
     const float *premerged_stats = nullptr;
     int premerge_slot = 0;
@@ -208,36 +240,6 @@ size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g);
 bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
                   Epilogue ep, const View *r, View out, float *scratch);
 
-// The filter w [cout][cin][ks][ks] in bf16 and in the order the bf16 kernel
-// consumes it: qf [cout][ks*ks][cin padded to 8] for the forward convolution and
-// (if qb != nullptr) qb [cin][ks*ks][cout padded to 8], transposed and flipped,
-// for the data gradient.  filter_bf16_elems(rows, k_channels, ks) = elements of
-// such a buffer.
-//
-// 1x1 filters whose reduction length (cin forward, cout for the data gradient)
-// passes conv1x1_direct_ok are stored instead in the operand order of
-// conv1x1_bf16: [rows / 32][k_channels / 16][64 lanes][8], zero padded.
-size_t filter_bf16_elems(int rows, int k_channels, int ks);
-struct FilterPrep {
-    const float *w;  // [cout][cin][ks][ks]
-    int cin, cout, ks;
-    uint16_t *qf, *qb;  // destinations (either may be null)
-};
-// The conversion of the filters of up to three layers as one list of jobs
-// (see prep_filter.h); plan_filter_prep builds it, prep_filters_bf16 runs it in
-// a launch of its own, bn_stats can carry it instead.
-struct PrepJob {
-    const float *w;  // [CO][CI][KS2]
-    uint16_t *q;
-    int CO, CI, KS2, kind;
-    int KP;      // channel pitch (kinds 0, 1) or 16-channel steps per row tile (kinds 2, 3)
-    int block0;  // first workgroup of this job
-    int64_t n;   // threads: elements to write (kinds 2, 3) or (row, padded column) pairs (kinds 0, 1)
-};
-struct PrepArgs {
-    PrepJob job[6];
-    int jobs, blocks;
-};
 PrepArgs plan_filter_prep(const FilterPrep *f, int count, Geo g, double *bytes);
 void prep_filters_bf16(Ctx &cx, const PrepArgs &a, double bytes);
 

@@ -302,7 +302,7 @@ const float *func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, cons
     for (int l = 0; l < pl.L; ++l) {
         const Layer &ly = pl.layers[l];
         if (l == 0 && ahead) {
-            cx.emitted = EmittedStats{};  // (arm_merge only runs without a filter conversion to carry)
+            cx.emitted = EmittedStats{};  // (the filters were converted in the launch that merged the statistics)
         } else {
             bn_stats(cx, cur, ly.cin, g, d.bn_eps, p.bn_gamma[l], p.bn_beta[l], b.bn_scratch, b.counters, b.stats[l],
                      l == 0 && pa.jobs > 0 ? &pa : nullptr, l == 0 ? prep_bytes : 0.0);
@@ -328,15 +328,15 @@ const float *func_forward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, cons
 }
 
 // If the convolution that has just run left partial statistics of `t` (the input of a function that
-// runs only after the backward pass of another), let the next BN-backward apply launch merge them
+// runs only after the backward pass of another), let the last launch of that backward pass merge them
 // into a spare statistics array with that function's layer-0 parameters; func_forward finds them
-// there.  Only without a filter conversion to carry in the statistics launch this replaces (fp32
-// operands), and only with the floating-point stream.
+// there.  The conversion of that function's filters to bf16, which the replaced statistics launch
+// would have carried, rides in the same launch.  Only with the floating-point stream.
 void arm_merge(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, Geo g, View t,
                const rvn_func_params &consumer, int frac_bits) {
     const EmittedStats e = cx.emitted;
     const int c = pl.layers[0].cin;
-    if (cx.dry || frac_bits || d.conv_dtype != RVN_F32 || !cx.emit_buf || !e.p || e.count <= 0) return;
+    if (cx.dry || frac_bits || !cx.emit_buf || !e.p || e.count <= 0) return;
     if (e.p != t.p || e.sn != t.sn || e.sc != t.sc || e.c != c || e.n != g.n || e.h != g.h || e.w != g.w) return;
     float *const slot = b.stats_in[cx.premerge_slot];
     cx.premerge_slot ^= 1;
@@ -351,6 +351,12 @@ void arm_merge(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, 
     m.eps = d.bn_eps;
     m.blocks = c;
     cx.merge_carry = m;
+    // the statistics launch this replaces would have carried the conversion of the consumer's filters
+    FilterPrep prep[3];
+    for (int l = 0; l < pl.L; ++l)
+        prep[l] = FilterPrep{consumer.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]};
+    double prep_bytes = 0.0;
+    cx.prep_carry = plan_filter_prep(prep, pl.L, g, &prep_bytes);
     cx.premerged = e;
     cx.premerged_stats = slot;
     cx.emitted = EmittedStats{};
@@ -386,8 +392,12 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
             dh = dx;
             cur ^= 1;
         } else {
+            // the last launch of this function's backward pass: every use of its converted filters is
+            // behind it, so what arm_merge prepared for the next function can ride here
+            cx.carry_now = true;
             bn_relu_bwd(cx, x, da, ly.cin, g, st, b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
                         accumulate, &skip, out, &red);
+            cx.carry_now = false;
         }
     }
 }
