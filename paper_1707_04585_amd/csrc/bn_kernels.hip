@@ -346,12 +346,12 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_reduce_k(
 }
 
 // dx = gamma*rstd*(dy - mean(dy) - xhat*mean(dy*xhat)); out = [skip +] dx
-template <bool VEC, bool SKIP>
-__global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
+template <bool VEC, bool SKIP, bool PREP>
+__device__ __forceinline__ void bn_bwd_apply_body(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
-    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge,
-    const PrepArgs prep) {
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce &carry, const StatsMerge &merge,
+    const PrepArgs &prep) {
     // The first workgroups do independent work that would otherwise be launches of their own (first,
     // so that their dependent loads run under the streaming of the others): merge.blocks of them merge
     // the partial statistics of a tensor that a later BN layer reads, carry.blocks sum a filter
@@ -361,12 +361,13 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
                             merge.C, (int)blockIdx.x);
         return;
     }
-    // (and prep.blocks convert the filters of the function that will read those statistics)
-    if ((int)blockIdx.x < merge.blocks + prep.blocks) {
+    // (and, in the PREP variant, prep.blocks convert the filters of the function that will read those statistics)
+    const int prep_blocks = PREP ? prep.blocks : 0;
+    if (PREP && (int)blockIdx.x < merge.blocks + prep_blocks) {
         prep_filter_body(prep, (int)blockIdx.x - merge.blocks);
         return;
     }
-    const int bx = (int)blockIdx.x - merge.blocks - prep.blocks;
+    const int bx = (int)blockIdx.x - merge.blocks - prep_blocks;
     if (bx < carry.blocks) {
         __shared__ float lds[kThreads];
         wgrad_reduce_body(carry, bx, lds);
@@ -410,6 +411,27 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
         const float dx = scale * ((dy - c1) - xh * c2);
         *po = SKIP ? *pk + dx : dx;
     }
+}
+
+template <bool VEC, bool SKIP>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
+    int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge) {
+    bn_bwd_apply_body<VEC, SKIP, false>(x, sn, sc, da, C, HW, total, stats, coef, skip, ksn, ksc, out, osn, osc, carry,
+                                        merge, PrepArgs{});
+}
+
+// The same with a filter conversion among the carried work (a large argument block: kept out of the
+// ordinary launches).
+template <bool VEC, bool SKIP>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_prep_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
+    int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge,
+    const PrepArgs prep) {
+    bn_bwd_apply_body<VEC, SKIP, true>(x, sn, sc, da, C, HW, total, stats, coef, skip, ksn, ksc, out, osn, osc, carry,
+                                       merge, prep);
 }
 
 __global__ void clear_counters_k(int *p, int n) {
@@ -510,8 +532,15 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
             cx.prep_carry = PrepArgs{};
         }
         const unsigned extra = (unsigned)red.blocks + (unsigned)merge.blocks + (unsigned)prep.blocks;
-#define RVN_LAUNCH(V, K) \
-    cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep)
+#define RVN_LAUNCH(V, K)                                                                                              \
+    do {                                                                                                              \
+        if (prep.blocks > 0)                                                                                          \
+            cx.run(bn_bwd_apply_prep_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(), \
+                   total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep);                         \
+        else                                                                                                          \
+            cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(),      \
+                   total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge);                               \
+    } while (0)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);
         else if (skip) RVN_LAUNCH(false, true);
