@@ -326,11 +326,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
 }
 
 // out = ep(r, sum_s part[s]) over dense partial tiles [S][n][c][hw], summed in
-// the order s = 0, 1, ...
+// the order s = 0, 1, ...  EMIT (host: h*w a multiple of 64, total a multiple of
+// the workgroup size, so a wavefront holds 64 consecutive pixels of one plane):
+// the wavefront also leaves the mean and centred sum of squares of what it
+// stores at emit[(c * emit_tiles + n * (h*w / 64) + pixel / 64) * 2], for the
+// BN layer that reads the tensor next.
+template <bool EMIT>
 __global__ __launch_bounds__(kThreads) void splitk_reduce_k(const float *__restrict__ part, int64_t part_stride, int S,
                                                             int C, int HW, int64_t total, const float *r,
                                                             int64_t rsn, int64_t rsc, float *out, int64_t osn,
-                                                            int64_t osc, int ep) {
+                                                            int64_t osc, int ep, float *emit, int emit_tiles) {
     const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (i >= total) return;
     float v = part[i];
@@ -344,6 +349,21 @@ __global__ __launch_bounds__(kThreads) void splitk_reduce_k(const float *__restr
         v = ep == EP_ADD ? rv + v : rv - v;
     }
     out[n * osn + (int64_t)c * osc + pix] = v;
+    if constexpr (EMIT) {
+        const float pivot = __shfl(v, 0, 64);
+        float a = v - pivot, b = a * a;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            a += __shfl_xor(a, off, 64);
+            b += __shfl_xor(b, off, 64);
+        }
+        if ((threadIdx.x & 63) == 0) {
+            const float mean = pivot + a * (1.f / 64.f);
+            const float m2 = fmaxf(b - a * a * (1.f / 64.f), 0.f);
+            const int tile = (int)n * (HW >> 6) + (pix >> 6);
+            reinterpret_cast<float2 *>(emit)[(int64_t)c * emit_tiles + tile] = make_float2(mean, m2);
+        }
+    }
 }
 
 struct C3Plan {
@@ -450,8 +470,8 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     a.part = scratch; a.part_stride = (int64_t)g.n * co * g.h * g.w;
     const int ch = pl.WM * pl.MTW * 32;
     const dim3 grid((unsigned)(pl.bands * ((g.n + pl.IMGS - 1) / pl.IMGS)), (unsigned)((co + ch - 1) / ch), (unsigned)pl.S);
-    // Statistics of the output for the BN layer that reads it next: no split, and every pixel slot
-    // of every workgroup a valid pixel (whole blocks of rows or images).
+    // Statistics of the output for the BN layer that reads it next: no split (for split launches see
+    // below), and every pixel slot of every workgroup a valid pixel (whole blocks of rows or images).
     const int wn_count = 4 / pl.WM, slots = wn_count * 2 * 32, tiles = (int)grid.x * wn_count;
     const bool whole = a.n_pix == slots && g.n % pl.IMGS == 0 && g.h % pl.TR == 0;
     if (cx.want_emit && cx.emit_buf && pl.S == 1 && whole && (size_t)co * tiles * 2 <= cx.emit_floats) {
@@ -472,8 +492,19 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     }
     if (pl.S > 1) {
         const int64_t total = a.part_stride;
-        cx.run(splitk_reduce_k, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, scratch,
-               a.part_stride, pl.S, co, g.h * g.w, total, a.r, a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep);
+        // the values are final only here: this kernel leaves the statistics when its wavefronts are whole
+        // runs of 64 pixels of one plane
+        const int hw = g.h * g.w, rtiles = g.n * (hw / 64);
+        const dim3 rgrid((unsigned)((total + kThreads - 1) / kThreads));
+        if (cx.want_emit && cx.emit_buf && hw % 64 == 0 && total % kThreads == 0 &&
+            (size_t)co * rtiles * 2 <= cx.emit_floats) {
+            cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, rtiles, 64};
+            cx.run(splitk_reduce_k<true>, rgrid, dim3(kThreads), 0, scratch, a.part_stride, pl.S, co, hw, total, a.r,
+                   a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep, cx.emit_buf, rtiles);
+        } else {
+            cx.run(splitk_reduce_k<false>, rgrid, dim3(kThreads), 0, scratch, a.part_stride, pl.S, co, hw, total, a.r,
+                   a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep, (float *)nullptr, 0);
+        }
     }
     return true;
 }
