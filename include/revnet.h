@@ -50,9 +50,16 @@
  *           and the upstream gradient where it enters a convolution); sums,
  *           BN, the residual stream and all gradients are fp32.
  *           Every kernel is deterministic (no floating-point atomics): the
- *           recomputation of G(y1) in the backward pass is bit-identical to
- *           the forward one, so the only reconstruction error is the rounding
- *           of (x + g) - g (Section 3.2, "Numerical error").
+ *           same call on the same inputs gives the same bits.  With the
+ *           floating-point stream the backward pass may form the batch
+ *           statistics of a stream tensor in another summation order than the
+ *           forward pass did (a full pass over the tensor against partial
+ *           sums left by the convolution that produced it), so a recomputed
+ *           G(y1) agrees with the forward one to fp32 rounding, not bit for
+ *           bit; the reconstruction error is that plus the rounding of
+ *           (x + g) - g (Section 3.2, "Numerical error").  The fixed-point
+ *           entry points further down take every statistic of a stream tensor
+ *           from one algorithm in both passes and reconstruct bit for bit.
  */
 #ifndef REVNET_H
 #define REVNET_H
@@ -148,21 +155,16 @@ int revnet_block_fwd(const rvn_block_desc *desc,
 
 /*
  * Reversible block, backward without stored activations (Section 3.2,
- * Algorithm 1).  Given the block's outputs (y1, y2) and their total
- * derivatives (dy1, dy2) it computes
- *     z1  = y1
- *     x2  = y2 - G(z1)                      (reconstruction)
- *     x1  = z1 - F(x2)                      (reconstruction)
- *     dz1 = dy1 + (dG/dz1)^T dy2
- *     dx2 = dy2 + (dF/dx2)^T dz1
- *     dx1 = dz1
- *     dwF = (dF/dwF)^T dz1,   dwG = (dG/dwG)^T dy2
- * where F and G are evaluated once each and the activations of those
- * evaluations are the ones back-propagated through (Section 5.1: reusing the
- * reconstruction activations gives the 4N total cost of Section 3.2).  The
- * steps are interleaved as G: recompute, reconstruct x2, backprop; then F:
- * recompute, reconstruct x1, backprop -- the same data flow, with only one
- * function's internals alive at a time.
+ * Algorithm 1).  From the block's outputs (y1, y2) and their total
+ * derivatives (dy1, dy2) alone it returns the block's inputs, their total
+ * derivatives and the parameter derivatives.  Data flow: G is evaluated once
+ * at y1, which gives x2 = y2 - G(y1) and, by ordinary backprop through the
+ * activations of that evaluation, dwG and the derivative reaching y1's node,
+ * dx1 = dy1 + (dG/dy1)^T dy2; F is then evaluated once at the recovered x2,
+ * which gives x1 = y1 - F(x2), dwF and dx2 = dy2 + (dF/dx2)^T dx1.
+ * (Section 5.1: back-propagating through the activations of the two
+ * reconstruction evaluations gives the 4N total cost of Section 3.2.)  Only
+ * one function's internals are alive at a time.
  * y1, y2, dy1, dy2: read.  x1, x2, dx1, dx2: written.  x_i may be the same
  * tensor as y_i and dx_i the same as dy_i (in place); any other overlap is
  * RVN_ERR_ALIAS.  grads: every pointer of the layers the descriptor uses must

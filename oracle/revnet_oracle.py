@@ -23,8 +23,9 @@ What it computes, and where the paper defines it:
                        must reproduce (Section 3.2: the algorithm combines the
                        reconstruction formulas with the backprop rule, so in
                        exact arithmetic its result is the ordinary gradient).
-* ``block_reverse`` / ``stack_reverse`` -- Algorithm 1 (Section 3.2) in its own
-                       steps and notation, from ``(y, ybar)`` only; used to pin
+* ``block_reverse`` / ``stack_reverse`` -- Algorithm 1 (Section 3.2) as its data
+                       flow (undo G and backprop it, then F), from ``(y, ybar)``
+                       only; used to pin
                        Algorithm 1 == stored backprop and to report
                        reconstruction drift versus depth (Section 3.2
                        "Numerical error", Section 5.2 "Impact of numerical
@@ -311,25 +312,28 @@ def block_bwd_stored(stored, P, dy1, dy2, eps=1e-5):
     return dx1, dx2, dict(F=grads_f, G=grads_g)
 
 
+def _undo_and_backprop(layers, at, minuend, upstream, eps):
+    """One half of the reversible backward pass: evaluate a residual function
+    once at `at`, undo its addition (`minuend` - value) and push `upstream`
+    back through the activations of that same evaluation (Section 5.1: reusing
+    them is what gives the 4N cost of Section 3.2)."""
+    value, st = func_fwd(at, layers, eps)
+    vjp, grads = func_bwd(st, layers, upstream, eps)
+    return minuend - value, vjp, grads
+
+
 def block_reverse(y1, y2, dy1, dy2, P, eps=1e-5):
     """Algorithm 1 (Section 3.2): from (y, ybar) alone return the inputs,
     their total derivatives and the parameter derivatives.
 
-    The Jacobian-transpose products are 'ordinary backprop' through F and G
-    evaluated at the *reconstructed* inputs; the activations of the two
-    reconstruction evaluations are the ones reused for it (Section 5.1, last
-    sentence: this gives the 4N cost)."""
-    z1 = y1
-    g, st_g = func_fwd(z1, P["G"], eps)
-    x2 = y2 - g
-    f, st_f = func_fwd(x2, P["F"], eps)
-    x1 = z1 - f
-    vjp_g, grads_g = func_bwd(st_g, P["G"], dy2, eps)
-    dz1 = dy1 + vjp_g
-    vjp_f, grads_f = func_bwd(st_f, P["F"], dz1, eps)
-    dx2 = dy2 + vjp_f
-    dx1 = dz1
-    return (x1, x2), (dx1, dx2), dict(F=grads_f, G=grads_g)
+    Data flow: G is evaluated at y1, which both recovers x2 and carries ybar2
+    back to y1's node; F is then evaluated at the recovered x2, which recovers
+    x1 and carries the total derivative of y1's node back to x2.  x1 feeds only
+    that node, so it inherits its derivative; x2 also feeds y2 directly."""
+    x2, into_y1, grads_g = _undo_and_backprop(P["G"], y1, y2, dy2, eps)
+    d_node1 = dy1 + into_y1
+    x1, into_x2, grads_f = _undo_and_backprop(P["F"], x2, y1, d_node1, eps)
+    return (x1, x2), (d_node1, dy2 + into_x2), dict(F=grads_f, G=grads_g)
 
 
 # ---------------------------------------------------------------------------
@@ -404,19 +408,17 @@ def block_fwd_fixed(q1, q2, P, frac_bits, eps=1e-5, dtype=np.float64):
 
 
 def block_reverse_fixed(y1, y2, dy1, dy2, P, frac_bits, eps=1e-5, dtype=np.float64):
-    """Algorithm 1 with the stream in fixed point: the same steps, the two
-    reconstructions as integer differences."""
-    z1 = y1
-    g, st_g = func_fwd(fixed_decode(z1, frac_bits, dtype), P["G"], eps)
-    x2 = y2 - _to_codes(g, frac_bits)
-    f, st_f = func_fwd(fixed_decode(x2, frac_bits, dtype), P["F"], eps)
-    x1 = z1 - _to_codes(f, frac_bits)
-    vjp_g, grads_g = func_bwd(st_g, P["G"], dy2, eps)
-    dz1 = dy1 + vjp_g
-    vjp_f, grads_f = func_bwd(st_f, P["F"], dz1, eps)
-    dx2 = dy2 + vjp_f
-    dx1 = dz1
-    return (x1, x2), (dx1, dx2), dict(F=grads_f, G=grads_g)
+    """block_reverse with the stream in fixed point: the functions read decoded
+    values and the two additions are undone as integer differences."""
+    def half(layers, at_codes, minuend_codes, upstream):
+        value, st = func_fwd(fixed_decode(at_codes, frac_bits, dtype), layers, eps)
+        vjp, grads = func_bwd(st, layers, upstream, eps)
+        return minuend_codes - _to_codes(value, frac_bits), vjp, grads
+
+    x2, into_y1, grads_g = half(P["G"], y1, y2, dy2)
+    d_node1 = dy1 + into_y1
+    x1, into_x2, grads_f = half(P["F"], x2, y1, d_node1)
+    return (x1, x2), (d_node1, dy2 + into_x2), dict(F=grads_f, G=grads_g)
 
 
 def stack_fwd_fixed(q1, q2, params, frac_bits, eps=1e-5, dtype=np.float64, keep=False):

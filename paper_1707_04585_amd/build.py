@@ -1,17 +1,25 @@
-"""Compile the HIP library in-tree for gfx950 (``python -m paper_1707_04585_amd.build``)."""
+"""Compile the HIP library in-tree for gfx950 (``python -m paper_1707_04585_amd.build``).
+
+Every source is compiled to an object of its own (in parallel) and the objects
+are linked into ``librevnet_hip.so``.  ``build()`` compiles everything each time
+it is called; ``build(incremental=True)`` (``--incremental`` on the command
+line) skips objects that are newer than their source and every header.
+"""
 from __future__ import annotations
 
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "librevnet_hip.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # hipcc must not form packed-fp32 instructions on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
@@ -22,21 +30,41 @@ def sources():
     return sorted(glob.glob(os.path.join(csrc, "*.cpp")) + glob.glob(os.path.join(csrc, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
-           *sources(), "-o", LIB_PATH]
+def _headers():
+    return glob.glob(os.path.join(HERE, "csrc", "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+
+
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = False, incremental: bool = False, jobs: int | None = None) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
+    newest_header = max(os.path.getmtime(h) for h in _headers())
+    todo, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        objs.append(obj)
+        fresh = (incremental and os.path.exists(obj)
+                 and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header))
+        if not fresh:
+            todo.append([hipcc, *HIPCC_FLAGS, *inc, "-c", src, "-o", obj])
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(lambda c: _run(c, verbose), todo))
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH], verbose)
     return LIB_PATH
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, incremental="--incremental" in sys.argv[1:]))
     sys.exit(0)

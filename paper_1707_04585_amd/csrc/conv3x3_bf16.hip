@@ -422,7 +422,7 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
 template <int WM, int MTW, int NTW, int KC, bool EMIT>
 void launch_c3_variant(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once
-    if (!raised) {
+    if (!raised && !cx.dry) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (e != hipSuccess) {
@@ -496,12 +496,15 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         // runs of 64 pixels of one plane
         const int hw = g.h * g.w, rtiles = g.n * (hw / 64);
         const dim3 rgrid((unsigned)((total + kThreads - 1) / kThreads));
+        // (a launch of its own in the accounts; the convolution's algorithmic bytes were counted with the first)
+        const bool go = cx.launch(K_SPLITK_REDUCE, 0.0);
         if (cx.want_emit && cx.emit_buf && hw % 64 == 0 && total % kThreads == 0 &&
             (size_t)co * rtiles * 2 <= cx.emit_floats) {
             cx.emitted = EmittedStats{out.p, out.sn, out.sc, co, g.n, g.h, g.w, rtiles, 64};
-            cx.run(splitk_reduce_k<true>, rgrid, dim3(kThreads), 0, scratch, a.part_stride, pl.S, co, hw, total, a.r,
-                   a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep, cx.emit_buf, rtiles);
-        } else {
+            if (go)
+                cx.run(splitk_reduce_k<true>, rgrid, dim3(kThreads), 0, scratch, a.part_stride, pl.S, co, hw, total, a.r,
+                       a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep, cx.emit_buf, rtiles);
+        } else if (go) {
             cx.run(splitk_reduce_k<false>, rgrid, dim3(kThreads), 0, scratch, a.part_stride, pl.S, co, hw, total, a.r,
                    a.rsn, a.rsc, a.out, a.osn, a.osc, a.ep, (float *)nullptr, 0);
         }

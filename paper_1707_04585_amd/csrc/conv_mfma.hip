@@ -187,7 +187,9 @@ void conv_fwd(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, const flo
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_fwd_calls += 1;
     cx.cost.conv_flops += flops;
-    if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops)) return;
+    // (counting mode walks through the dispatch as well: which kernel takes the layer decides whether the
+    // next statistics call is a merge of epilogue partials or a pass over the tensor)
+    if (!cx.launch(K_CONV_FWD, P * cin * 4.0 + P * cout * 4.0 * (ep == EP_STORE ? 1.0 : 2.0), flops) && !cx.dry) return;
     cx.emitted = EmittedStats{};
     cx.want_emit = true;  // forward convolutions feed a BN layer next: let the kernel describe its output if it can
     if (!(dt == RVN_BF16 && conv_bf16(cx, x, scale_shift, w, wq, false, cin, cout, ks, g, ep, r, out, scratch)))

@@ -36,6 +36,13 @@ __global__ __launch_bounds__(kThreads) void fix_to_float_k(const int *__restrict
     }
 }
 
+// q + sign * rint(v) on codes.  The documented behaviour on overflow is wrap-around, so the sum is
+// formed in unsigned arithmetic (signed overflow would be undefined); the conversion of v saturates.
+__device__ __forceinline__ int code_axpy(int q, int sign, float v) {
+    const uint32_t t = (uint32_t)__float2int_rn(v);
+    return (int)(sign > 0 ? (uint32_t)q + t : (uint32_t)q - t);
+}
+
 // out = r + sign * rint(f * scale); f dense, r and out strided; out may be r.
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void fix_axpy_k(const int *r, int64_t rsn, int64_t rsc, const float *__restrict__ f,
@@ -53,13 +60,13 @@ __global__ __launch_bounds__(kThreads) void fix_axpy_k(const int *r, int64_t rsn
         const int4 q = reinterpret_cast<const int4 *>(rp)[e];
         const float4 v = reinterpret_cast<const float4 *>(f)[i];
         int4 o;
-        o.x = q.x + sign * __float2int_rn(v.x * scale);
-        o.y = q.y + sign * __float2int_rn(v.y * scale);
-        o.z = q.z + sign * __float2int_rn(v.z * scale);
-        o.w = q.w + sign * __float2int_rn(v.w * scale);
+        o.x = code_axpy(q.x, sign, v.x * scale);
+        o.y = code_axpy(q.y, sign, v.y * scale);
+        o.z = code_axpy(q.z, sign, v.z * scale);
+        o.w = code_axpy(q.w, sign, v.w * scale);
         reinterpret_cast<int4 *>(op)[e] = o;
     } else {
-        op[e] = rp[e] + sign * __float2int_rn(f[i] * scale);
+        op[e] = code_axpy(rp[e], sign, f[i] * scale);
     }
 }
 

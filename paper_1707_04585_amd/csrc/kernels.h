@@ -47,6 +47,7 @@ enum KernelId {
     K_RESAMPLE,
     K_FIXED_POINT,
     K_STEM,
+    K_SPLITK_REDUCE,  // second launch of a convolution whose input channels were split over workgroups
     K_COUNT
 };
 const char *kernel_name(int id);
@@ -146,9 +147,12 @@ struct Ctx {
         if (go && profile_enabled()) profile_new_mark(id, bytes, flops, &ev_start, &ev_stop);
         return go;
     }
-    // Enqueue `kernel` on the stream and record the launch status.
+    // Enqueue `kernel` on the stream and record the launch status.  Counting mode enqueues nothing, so
+    // that a wrapper whose later bookkeeping depends on what its dispatch decides (which kernel, what
+    // it leaves for the next call) can walk through that dispatch when only counting.
     template <typename... KArgs, typename... Args>
     void run(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, Args... args) {
+        if (dry) return;
         if (ev_start) {
             hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, ev_start, ev_stop, 0,
                                   static_cast<KArgs>(args)...);

@@ -39,7 +39,7 @@ hipEvent_t take_event() {
 const char *const kNames[K_COUNT] = {
     "bn_stats_k", "clear_counters_k", "conv_fwd", "conv_dgrad",
     "conv_wgrad", "wgrad_reduce_k", "bn_bwd_reduce_k", "bn_bwd_apply_k", "prep_filter_k", "conv_dgrad_wgrad",
-    "resample2_k", "fixed_point_k", "stem_k",
+    "resample2_k", "fixed_point_k", "stem_k", "splitk_reduce_k",
 };
 
 }  // namespace

@@ -336,7 +336,7 @@ void arm_merge(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs &b, 
                const rvn_func_params &consumer, int frac_bits) {
     const EmittedStats e = cx.emitted;
     const int c = pl.layers[0].cin;
-    if (cx.dry || frac_bits || !cx.emit_buf || !e.p || e.count <= 0) return;
+    if (frac_bits || !cx.emit_buf || !e.p || e.count <= 0) return;
     if (e.p != t.p || e.sn != t.sn || e.sc != t.sc || e.c != c || e.n != g.n || e.h != g.h || e.w != g.w) return;
     float *const slot = b.stats_in[cx.premerge_slot];
     cx.premerge_slot ^= 1;
