@@ -203,7 +203,8 @@ void conv_dgrad(Ctx &cx, View dh, rvn_dtype dt, const float *w, const uint16_t *
     const double flops = 2.0 * P * cin * cout * ks * ks;
     cx.cost.conv_dgrad_calls += 1;
     cx.cost.conv_flops += flops;
-    if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops)) return;
+    // (counting mode walks through the dispatch: a channel-split launch is followed by a reduce launch)
+    if (!cx.launch(K_CONV_DGRAD, P * cout * 4.0 + P * cin * 4.0, flops) && !cx.dry) return;
     // A stride-1 "same" convolution of dh (cout channels) with the transposed,
     // flipped filter, producing cin channels.
     if (dt == RVN_BF16 && conv_bf16(cx, dh, nullptr, w, wq, true, cout, cin, ks, g, EP_STORE, nullptr, dense_view(da, cin, g), scratch))
