@@ -213,6 +213,33 @@ int revnet_stack_bwd(const rvn_block_desc *desc, int32_t depth,
                      const rvn_block_grads *grads, int accumulate_wgrads,
                      void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * revnet_stack_fwd for callers that cannot allocate device memory and hold no
+ * workspace of their own: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * revnet_stack_fwd, without `ws` / `ws_bytes`: the workspace is a fixed array
+ * of RVN_STATIC_WS_BYTES inside the library's device image (one copy per GPU
+ * that uses the library, held until the process ends).  The call allocates
+ * and frees nothing, on the device or through any library.
+ * Limit: shapes whose forward workspace (revnet_workspace_bytes: fwd_bytes)
+ * exceeds RVN_STATIC_WS_BYTES are rejected with RVN_ERR_WORKSPACE before
+ * anything is enqueued.
+ * Sharing: every call on one GPU uses that GPU's one array, on whatever
+ * stream.  Calls on the same stream are ordered and safe; calls whose work
+ * can overlap on one GPU (different streams, different host threads without
+ * stream ordering) race on the array and give undefined results.  The array
+ * keeps the previous call's contents; the call itself clears what it needs
+ * zeroed (with a kernel, so it can be captured).
+ * The first call on a device looks up the array's address
+ * (hipGetSymbolAddress); make that call outside stream capture.
+ */
+#define RVN_STATIC_WS_BYTES ((size_t)32 << 20)
+int revnet_stack_fwd_static(const rvn_block_desc *desc, int32_t depth,
+                            const rvn_tensor *x1, const rvn_tensor *x2,
+                            const rvn_block_params *params,
+                            const rvn_tensor *y1, const rvn_tensor *y2,
+                            void *hip_stream);
+
 /* ------------------------------------------------------------------------
  * Non-reversible subsampling block and multi-stage body.
  *

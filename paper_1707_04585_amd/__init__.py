@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     revnet_fixed_from_float, revnet_fixed_to_float, revnet_fixed_workspace_bytes, revnet_stack_bwd_fixed,
     revnet_stack_fwd_fixed, revnet_stem_bwd, revnet_stem_fwd, revnet_stem_workspace_bytes, rvn_stem_desc,
     revnet_body_bwd_fixed, revnet_body_fixed_workspace_bytes, revnet_body_fwd_fixed,
+    revnet_stack_fwd_static, STATIC_WS_BYTES,
 )

@@ -28,7 +28,9 @@ EXPORTS = [
     "revnet_stack_fwd_fixed", "revnet_stack_bwd_fixed",
     "revnet_stem_workspace_bytes", "revnet_stem_fwd", "revnet_stem_bwd",
     "revnet_body_fixed_workspace_bytes", "revnet_body_fwd_fixed", "revnet_body_bwd_fixed",
+    "revnet_stack_fwd_static",
 ]
+STATIC_WS_BYTES = 32 << 20   # RVN_STATIC_WS_BYTES
 
 MAX_STAGES = 8
 
@@ -301,6 +303,14 @@ def revnet_stack_fwd(desc, depth, x1, x2, params, y1, y2, ws, stream=None):
     _check(load_library().revnet_stack_fwd(C.byref(d), C.c_int32(depth), C.byref(t[0]), C.byref(t[1]), p,
                                            C.byref(t[2]), C.byref(t[3]), C.c_void_p(wp), C.c_size_t(wb),
                                            C.c_void_p(_stream(stream))))
+
+
+def revnet_stack_fwd_static(desc, depth, x1, x2, params, y1, y2, stream=None):
+    d = _desc(desc)
+    p = pack_params(params)
+    t = [_tensor(v) for v in (x1, x2, y1, y2)]
+    _check(load_library().revnet_stack_fwd_static(C.byref(d), C.c_int32(depth), C.byref(t[0]), C.byref(t[1]), p,
+                                                  C.byref(t[2]), C.byref(t[3]), C.c_void_p(_stream(stream))))
 
 
 def revnet_stack_bwd(desc, depth, y1, y2, dy1, dy2, params, x1, x2, dx1, dx2, grads, accumulate_wgrads,

@@ -91,6 +91,10 @@ struct Bufs {
 };
 Plan make_plan(const rvn_block_desc &d, const Geo &g, bool backward, bool fixed = false);
 Bufs bind(const Plan &p, void *ws);
+// All argument checks of a forward call (descriptor, the four tensors, aliasing, workspace size,
+// alignment and overlap); on success *plan and *geo describe the call.
+int check_fwd_args(const rvn_block_desc *desc, const rvn_tensor *x1, const rvn_tensor *x2, const rvn_tensor *y1,
+                   const rvn_tensor *y2, void *ws, size_t ws_bytes, Plan *plan, Geo *geo, bool fixed);
 
 // Section 3.2: blocks params[0 .. depth-1] in order, only the top pair kept; and
 // Algorithm 1 applied from the top block down.  frac_bits > 0: the stream

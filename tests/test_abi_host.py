@@ -237,3 +237,19 @@ def test_stem_argument_validation():
     assert status_of(rv.revnet_stem_bwd, d, img, conv, y, None, 0, (BASE + 0x800000, bwd))[0] == -1
     assert status_of(rv.revnet_stem_bwd, d, img, conv, y, 0x10, 0, (BASE, bwd))[0] == -6
 
+
+def test_static_workspace_entry_point_validates_and_rejects_oversize_on_the_host():
+    """revnet_stack_fwd_static: argument checks and the size limit of its
+    built-in workspace come before the first device call."""
+    d = rv.BlockDesc("bottleneck", 128, 64, conv_dtype="bf16")
+    n, c, h, w = 64, 128, 56, 56
+    fwd, _ = rv.revnet_workspace_bytes(d, n, h, w)
+    assert fwd > rv.STATIC_WS_BYTES
+    big = lambda base: fake(base, n=n, c=c, h=h, w=w, sn=c * h * w)
+    step = 4 * n * c * h * w
+    x1, x2 = big(BASE), big(BASE + step)
+    st, msg = status_of(rv.revnet_stack_fwd_static, d, 1, x1, x2, [fake_params(d)], x1, x2)
+    assert st == -5 and "built-in workspace" in msg and str(fwd) in msg
+    assert status_of(rv.revnet_stack_fwd_static, d, 0, x1, x2, [fake_params(d)], x1, x2)[0] == -2
+    assert status_of(rv.revnet_stack_fwd_static, d, 1, x1, x1, [fake_params(d)], x1, x2)[0] == -6
+    assert status_of(rv.revnet_stack_fwd_static, d, 1, big(0), x2, [fake_params(d)], x1, x2)[0] == -1
