@@ -3,13 +3,16 @@ body (reversible stages joined by such blocks), called through the C ABI,
 against the CPU oracle on the same seeded inputs.
 
 Tolerances as for the stacks: fp32 forward 1e-5, gradients 1e-4; bf16
-convolution operands 2e-2 on gradients (1e-2 forward), or 3x the distance
-between the oracle's own float32 and float64 runs where that is larger (see
-test_gpu_parity.py for why bf16 operands make that the floor)."""
+convolution operands 2e-2 on gradients (1e-2 forward).  A tensor that misses
+its bar passes only within 1.5x its own floor -- the distance between the
+oracle's float32 and float64 runs for that tensor (see test_gpu_parity.py for
+why bf16 operands make that the floor) -- and then the GPU must be as close to
+the float32 oracle as well."""
 import numpy as np
 import pytest
 
 import synth_inputs as S
+from parity_checks import check_with_floors, record, assert_structure
 
 pytestmark = pytest.mark.gpu
 
@@ -73,14 +76,13 @@ def test_down_block_matches_oracle(oracle, torch_cuda, kind, n, c_in, c_out, h, 
         y_ref, stored = oracle.down_fwd(x, P)
         dx_ref, g_ref = oracle.down_bwd(stored, P, dy)
     tol = dict(TOL[conv])
-    if conv == "bf16":
+    floors = {}
+    if conv == "bf16":   # the same block in float32: its distance from float64, per tensor
         with oracle.conv_operands("bf16"):
             P32 = cast_down(P, np.float32)
             _, st32 = oracle.down_fwd(x.astype(np.float32), P32, np.float32(1e-5))
-            dx32, _ = oracle.down_bwd(st32, P32, dy.astype(np.float32), np.float32(1e-5))
-        floor = oracle.rel_l2(dx32, dx_ref)
-        tol["grad"] = max(tol["grad"], 3.0 * floor)
-        print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol["grad"]), flush=True)
+            dx32, g32 = oracle.down_bwd(st32, P32, dy.astype(np.float32), np.float32(1e-5))
+        floors = dict(down_errors(oracle, g32, g_ref), dx=oracle.rel_l2(dx32, dx_ref))
 
     desc = rv.DownDesc(kind, c_in, c_out, 0, 1e-5, conv)
     fwd_b, bwd_b = rv.revnet_down_workspace_bytes(desc, n, h, w)
@@ -100,16 +102,24 @@ def test_down_block_matches_oracle(oracle, torch_cuda, kind, n, c_in, c_out, h, 
     print("  rel. errors: y %.2e  dx %.2e  worst parameter gradient %s %.2e" % (e_y, e_dx, worst, errs[worst]), flush=True)
     assert torch.equal(X.cpu(), torch.as_tensor(x.astype(np.float32))), "the stored input must not be modified"
     assert e_y < tol["fwd"]
-    assert e_dx < tol["grad"]
-    assert errs[worst] < tol["grad"], (worst, errs[worst])
+    vs32 = dict(down_errors(oracle, download_down(dg), g32), dx=oracle.rel_l2(DX.cpu().numpy(), dx32)) if floors else {}
+    used = check_with_floors(dict(errs, dx=e_dx), floors, vs32, tol["grad"])
+    st_y = assert_structure("y", Y.cpu().numpy(), y_ref, tol["fwd"], smooth=True)
+    st = assert_structure("dx", DX.cpu().numpy(), dx_ref, max(tol["grad"], 1.5 * floors.get("dx", 0.0)), smooth=False)
+    record(f"down_block/{kind}_{c_in}to{c_out}_{h}x{w}_n{n}/{conv}", conv=conv, y=e_y, dx=e_dx, worst_param=errs[worst],
+           worst_param_name=worst, bar=tol["grad"], dx_floor=floors.get("dx"), worst_param_floor=floors.get(worst),
+           dx_vs_f32_oracle=vs32.get("dx"), worst_fraction_of_allowance=used, dx_per_image=st["per_image"],
+           dx_per_channel=st["per_channel"], dx_border=st["border"], y_max_abs_over_rms=st_y["max_abs_over_rms"],
+           dx_outliers=st["outliers"])
 
-    # accumulate_wgrads adds to what is there: a second backward doubles every gradient
+    # accumulate_wgrads adds to what is there: a second backward doubles every gradient (the kernels are
+    # deterministic, so up to the rounding of the one addition)
+    first = download_down(dg)
     rv.revnet_down_bwd(desc, X, DY, dp, DX, dg, 1, ws)
     torch.cuda.synchronize()
-    twice = download_down(dg)
-    doubled = dict(R=[{k: 2.0 * v for k, v in L.items()} for L in g_ref["R"]], S=dict(w=2.0 * g_ref["S"]["w"]))
-    errs2 = down_errors(oracle, twice, doubled)
-    assert max(errs2.values()) < tol["grad"], errs2
+    doubled = dict(R=[{k: 2.0 * v for k, v in L.items()} for L in first["R"]], S=dict(w=2.0 * first["S"]["w"]))
+    errs2 = down_errors(oracle, download_down(dg), doubled)
+    assert max(errs2.values()) < 1e-6, errs2
 
 
 def small_body_cfg(kind, conv):
@@ -165,26 +175,35 @@ def test_body_matches_oracle(oracle, torch_cuda, kind, conv):
         tops_ref, kept = oracle.body_fwd(x, stages, downs, keep=True)
         dx_ref, sg_ref, dg_ref = oracle.body_bwd_stored(kept, stages, downs, dy)
     tol = dict(TOL[conv])
-    if conv == "bf16":
-        f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
-        with oracle.conv_operands("bf16"):
-            st32 = [S.cast_params(st, np.float32) for st in stages]
-            dn32 = [cast_down(P, np.float32) for P in downs]
-            t32, k32 = oracle.body_fwd(f32(x), st32, dn32, np.float32(1e-5), keep=True)
-            dx32, _, _ = oracle.body_bwd_stored(k32, st32, dn32, f32(dy), np.float32(1e-5))
-        floor = oracle.rel_l2(dx32, dx_ref)
-        # (capped: where two oracle runs are further apart than that, the case says nothing)
-        tol["grad"] = min(max(tol["grad"], 3.0 * floor), 1e-1)
-        tol["fwd"] = min(max(tol["fwd"], 3.0 * oracle.rel_l2(t32[-1], tops_ref[-1])), 1e-1)
-        print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol["grad"]), flush=True)
     out = run_body(cfg, x, stages, downs, dy)
     fwd, rec, dx, g = body_errors(oracle, out, tops_ref, dx_ref, sg_ref, dg_ref, x)
     worst = max(g, key=g.get)
     print("  rel. errors: tops %.2e  x_rec %.2e  dx %.2e  worst parameter gradient %s %.2e" % (fwd, rec, dx, worst, g[worst]), flush=True)
-    assert fwd < tol["fwd"]
-    assert rec < tol["fwd"]
-    assert dx < tol["grad"]
-    assert g[worst] < tol["grad"], (worst, g[worst])
+    floors, vs32, f_fwd = body_floors(oracle, out, x, stages, downs, dy, tops_ref, dx_ref, sg_ref, dg_ref) if conv == "bf16" else ({}, {}, 0.0)
+    assert fwd < max(tol["fwd"], 1.5 * f_fwd)
+    assert rec < max(tol["fwd"], 1.5 * f_fwd)
+    used = check_with_floors(dict(g, dx=dx), floors, vs32, tol["grad"])
+    record(f"body_small/{kind}/{conv}", conv=conv, y=fwd, x_rec=rec, dx=dx, worst_param=g[worst], worst_param_name=worst,
+           bar=tol["grad"], dx_floor=floors.get("dx"), worst_param_floor=floors.get(worst), dx_vs_f32_oracle=vs32.get("dx"),
+           worst_fraction_of_allowance=used)
+
+
+def body_floors(oracle, out, x, stages, downs, dy, tops_ref, dx_ref, sg_ref, dg_ref):
+    """Per tensor: the distance of the oracle's memory-saving backward pass in
+    float32 (Algorithm 1 inside the stages, bf16 operands) from the float64
+    stored-activation reference, and of the GPU from that float32 run.  Also
+    the float32 oracle's largest forward (stage top) distance."""
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    with oracle.conv_operands("bf16"):
+        st32 = [S.cast_params(st, np.float32) for st in stages]
+        dn32 = [cast_down(P, np.float32) for P in downs]
+        t32 = oracle.body_fwd(f32(x), st32, dn32, np.float32(1e-5))
+        dx32, sg32, dg32, _ = oracle.body_reverse(t32, st32, dn32, f32(dy), np.float32(1e-5))
+    o32 = dict(tops=t32, x_rec=x, dx=dx32, stage_grads=sg32, down_grads=dg32)
+    f_fwd, _, f_dx, f_g = body_errors(oracle, o32, tops_ref, dx_ref, sg_ref, dg_ref, x)
+    _, _, v_dx, v_g = body_errors(oracle, out, t32, dx32, sg32, dg32, x)
+    print("  floor (oracle float32 vs float64): tops %.2e, dx %.2e, worst gradient %.2e" % (f_fwd, f_dx, max(f_g.values())), flush=True)
+    return dict(f_g, dx=f_dx), dict(v_g, dx=v_dx), f_fwd
 
 
 def test_body_activation_memory_does_not_depend_on_depth(torch_cuda):
@@ -208,8 +227,10 @@ def test_body_real_shapes_reduced_batch(oracle, torch_cuda, name, n, conv):
     down to 7x7), one reversible block per stage and a batch the oracle
     finishes in seconds.
 
-    Bars: the fp32 / bf16 ones, or 3x the distance between the oracle's own
-    float32 and float64 runs where that is larger.  That distance is what the
+    Bars: the fp32 / bf16 ones; a tensor above its bar must be within 1.5x its
+    own floor, the distance between the oracle's float32 run of the memory-saving
+    backward pass and its float64 stored-activation run (and as close to the
+    float32 run).  That distance is what the
     0/1 ReLU decisions leave: a pre-activation summed in float32 differs from
     the float64 one by ~1e-6 of its scale, so a few of the ~5e6 decisions of
     the larger body differ whatever the kernel, each an O(1) change of its
@@ -226,25 +247,31 @@ def test_body_real_shapes_reduced_batch(oracle, torch_cuda, name, n, conv):
     with oracle.conv_operands(conv):
         tops_ref, kept = oracle.body_fwd(x, stages, downs, keep=True)
         dx_ref, sg_ref, dg_ref = oracle.body_bwd_stored(kept, stages, downs, dy)
-        f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
-        st32 = [S.cast_params(st, np.float32) for st in stages]
-        dn32 = [cast_down(P, np.float32) for P in downs]
-        t32, k32 = oracle.body_fwd(f32(x), st32, dn32, np.float32(1e-5), keep=True)
-        dx32, sg32, dg32 = oracle.body_bwd_stored(k32, st32, dn32, f32(dy), np.float32(1e-5))
-        o32 = dict(tops=t32, x_rec=x, dx=dx32, stage_grads=sg32, down_grads=dg32)
-        f_fwd, _, f_dx, f_g = body_errors(oracle, o32, tops_ref, dx_ref, sg_ref, dg_ref, x)
-        floor = max(f_dx, max(f_g.values()))
-        tol = dict(fwd=max(tol["fwd"], 3.0 * f_fwd), grad=max(tol["grad"], 3.0 * floor))
-        print("  floor (oracle float32 vs float64): tops %.2e, dx %.2e, worst gradient %.2e -> gradient tolerance %.2e" %
-              (f_fwd, f_dx, max(f_g.values()), tol["grad"]), flush=True)
+    del kept
     out = run_body(cfg, x, stages, downs, dy)
     fwd, rec, dx, g = body_errors(oracle, out, tops_ref, dx_ref, sg_ref, dg_ref, x)
     worst = max(g, key=g.get)
     print("  rel. errors: tops %.2e  x_rec %.2e  dx %.2e  worst parameter gradient %s %.2e" % (fwd, rec, dx, worst, g[worst]), flush=True)
-    assert fwd < tol["fwd"]
-    assert rec < TOL[conv]["fwd"]
-    assert dx < tol["grad"]
-    assert g[worst] < tol["grad"], (worst, g[worst])
+    if conv == "bf16":
+        floors, vs32, f_fwd = body_floors(oracle, out, x, stages, downs, dy, tops_ref, dx_ref, sg_ref, dg_ref)
+    else:   # fp32 operands: the same construction with exact operands (a few ReLU decisions differ between float32 and float64)
+        with oracle.conv_operands("exact"):
+            f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+            st32 = [S.cast_params(st, np.float32) for st in stages]
+            dn32 = [cast_down(P, np.float32) for P in downs]
+            t32 = oracle.body_fwd(f32(x), st32, dn32, np.float32(1e-5))
+            dx32, sg32, dg32, _ = oracle.body_reverse(t32, st32, dn32, f32(dy), np.float32(1e-5))
+        o32 = dict(tops=t32, x_rec=x, dx=dx32, stage_grads=sg32, down_grads=dg32)
+        f_fwd, _, f_dx, f_g = body_errors(oracle, o32, tops_ref, dx_ref, sg_ref, dg_ref, x)
+        _, _, v_dx, v_g = body_errors(oracle, out, t32, dx32, sg32, dg32, x)
+        floors, vs32 = dict(f_g, dx=f_dx), dict(v_g, dx=v_dx)
+        print("  floor (oracle float32 vs float64): tops %.2e, dx %.2e, worst gradient %.2e" % (f_fwd, f_dx, max(f_g.values())), flush=True)
+    assert fwd < max(tol["fwd"], 1.5 * f_fwd)
+    assert rec < max(TOL[conv]["fwd"], 1.5 * f_fwd)
+    used = check_with_floors(dict(g, dx=dx), floors, vs32, tol["grad"], pooled=conv == "f32")
+    record(f"body_real_shapes/{name}_n{n}/{conv}", conv=conv, y=fwd, x_rec=rec, dx=dx, worst_param=g[worst], worst_param_name=worst,
+           bar=tol["grad"], dx_floor=floors.get("dx"), worst_param_floor=floors.get(worst), dx_vs_f32_oracle=vs32.get("dx"),
+           worst_fraction_of_allowance=used)
 
 
 @pytest.mark.parametrize("name", ["c3_body", "c5_body"])

@@ -146,8 +146,8 @@ def test_fixed_point_body_reconstructs_every_stage_and_matches_oracle(oracle, to
     fixed point: after the backward pass every top holds the codes the stage
     received (stage 0: the encoded input; later stages: what the subsampling
     block below wrote), bit for bit; tops and derivatives against the oracle's
-    fixed-point body (fp32 bars; bf16: 3x the oracle's own float32-to-float64
-    distance where that exceeds 2e-2)."""
+    fixed-point body (fp32 / bf16 bars; a tensor above its bar must be within
+    1.5x its own float32-to-float64 oracle distance, of both oracle runs)."""
     import torch
     from paper_1707_04585_amd.torch_harness import BodyRunner, download_grads, download_down, _dev
     from test_gpu_body import body_errors, cast_down
@@ -165,7 +165,7 @@ def test_fixed_point_body_reconstructs_every_stage_and_matches_oracle(oracle, to
     o32 = dict(tops=dec(t32), x_rec=x, dx=dx32, stage_grads=sg32, down_grads=dg32)
     f_fwd, _, f_dx, f_g = body_errors(oracle, o32, dec(tops_ref), dx_ref, sg_ref, dg_ref, x)
     base = dict(f32=dict(fwd=1e-5, grad=1e-4), bf16=dict(fwd=1e-2, grad=2e-2))[conv]
-    tol = dict(fwd=min(max(base["fwd"], 3.0 * f_fwd), 1e-1), grad=min(max(base["grad"], 3.0 * max(f_dx, max(f_g.values()))), 1e-1))
+    tol = dict(fwd=max(base["fwd"], 1.5 * f_fwd), grad=base["grad"])
 
     r = BodyRunner(frac_bits=FB, **cfg)
     r.set_params(stages, downs)
@@ -197,7 +197,12 @@ def test_fixed_point_body_reconstructs_every_stage_and_matches_oracle(oracle, to
     fwd, _, dx, g = body_errors(oracle, out, dec(tops_ref), dx_ref, sg_ref, dg_ref, x)
     worst = max(g, key=g.get)
     print(f"fixed-point body conv={conv}: tops {fwd:.2e} dx {dx:.2e} worst gradient {worst} {g[worst]:.2e} (tolerances {tol})", flush=True)
-    assert fwd < tol["fwd"] and dx < tol["grad"] and g[worst] < tol["grad"]
+    assert fwd < tol["fwd"]
+    _, _, v_dx, v_g = body_errors(oracle, out, dec(t32), dx32, sg32, dg32, x)
+    from parity_checks import check_with_floors, record
+    used = check_with_floors(dict(g, dx=dx), dict(f_g, dx=f_dx), dict(v_g, dx=v_dx), tol["grad"], pooled=conv == "f32")
+    record(f"fixed_point_body/{conv}", conv=conv, y=fwd, dx=dx, worst_param=g[worst], worst_param_name=worst, bar=tol["grad"],
+           dx_floor=f_dx, worst_param_floor=f_g[worst], dx_vs_f32_oracle=v_dx, worst_fraction_of_allowance=used)
     # stage 1's reconstructed input equals the codes of the subsampling block's output: recompute that output
     rec1 = r.tops[1].view(torch.int32).cpu().numpy().astype(np.int64)
     with oracle.conv_operands(conv):

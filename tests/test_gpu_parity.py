@@ -20,6 +20,7 @@ import pytest
 
 import synth_inputs as S
 from bf16_floor import bf16_grad_floor
+from parity_checks import assert_structure, record, PAIR_FACTOR
 
 pytestmark = pytest.mark.gpu
 
@@ -33,12 +34,15 @@ pytestmark = pytest.mark.gpu
 # than another correct summation order is.  That floor is measured, on the CPU
 # and with the oracle alone, as the distance between the oracle run in float32
 # and in float64 (both with bf16 operands); the GPU must stay within the 2e-2 bar
-# or, where the floor is above it, within 3x the floor.
+# or, where the floor is above it, within 1.5x the floor of both oracle runs.
+FLOOR_FACTOR = 1.5
+
+
 def bf16_grad_tol(oracle, cfg, x, params, dy, ref):
-    floor = bf16_grad_floor(oracle, cfg, x, params, dy, ref)
-    tol = max(TOL["bf16"]["grad"], 3.0 * floor)
-    print("  bf16 floor (oracle float32 vs float64, dx): %.2e -> gradient tolerance %.2e" % (floor, tol), flush=True)
-    return tol
+    """(floor of dx, the float32 oracle's outputs): see check_against_oracle."""
+    floor, r32 = bf16_grad_floor(oracle, cfg, x, params, dy, ref, want32=True)
+    print("  bf16 floor (oracle float32 vs float64, dx): %.2e" % floor, flush=True)
+    return floor, r32
 
 
 TOL = {"f32": dict(fwd=1e-5, grad=1e-4, recon=1e-5), "bf16": dict(fwd=1e-2, grad=2e-2, recon=1e-2)}
@@ -109,7 +113,12 @@ def error_table(oracle, out, ref, x, scale_grads=1.0):
     return err
 
 
-def check_against_oracle(oracle, out, ref, x, conv, scale_grads=1.0, tol=None):
+def check_against_oracle(oracle, out, ref, x, conv, scale_grads=1.0, tol=None, case=None, floor=None, ref32=None):
+    """Every output tensor against the float64 oracle at the bars of `tol`.
+    With `ref32` (the float32 oracle's outputs, bf16 cases) a gradient tensor
+    that misses the fixed bar may still pass at FLOOR_FACTOR x its own floor
+    -- the distance between the two oracle runs for that same tensor -- if the
+    GPU is also within PAIR_FACTOR floors of the float32 oracle."""
     tol = tol or TOL[conv]
     err = error_table(oracle, out, ref, x, scale_grads)
     gerr = {k: v for k, v in err.items() if "." in k}
@@ -118,8 +127,36 @@ def check_against_oracle(oracle, out, ref, x, conv, scale_grads=1.0, tol=None):
           (err["y"], err["x_rec"], err["dx"], worst, gerr[worst]), flush=True)
     assert err["y"] < tol["fwd"], ("y", err["y"])
     assert err["x_rec"] < tol["recon"], ("x_rec", err["x_rec"])
-    assert err["dx"] < tol["grad"], ("dx", err["dx"])
-    assert gerr[worst] < tol["grad"], (worst, gerr[worst])
+    bar = TOL[conv]["grad"] if ref32 is not None else tol["grad"]
+    floors, vs32 = {}, {}
+    if ref32 is not None:
+        as_out = lambda r: dict(y=r["y"], x_rec=x, dx=r["dx"], grads=r["grads"])
+        floors = error_table(oracle, as_out(ref32), ref, x, scale_grads)
+        vs32 = error_table(oracle, out, dict(y=ref32["y"], dx=ref32["dx"], grads=ref32["grads"]), x, scale_grads)
+    worst_ratio = 0.0
+    for key in ["dx"] + sorted(gerr):
+        e = err[key]
+        if e < bar:
+            worst_ratio = max(worst_ratio, e / bar)
+            continue
+        fl = floors.get(key)
+        assert fl is not None, (key, e, "above the bar", bar)
+        print("  %s: %.2e is above the %.0e bar; floor of this tensor %.2e, GPU against the float32 oracle %.2e" %
+              (key, e, bar, fl, vs32[key]), flush=True)
+        assert e < FLOOR_FACTOR * fl, (key, e, "floor", fl)
+        assert vs32[key] < PAIR_FACTOR * fl, (key, "against the float32 oracle", vs32[key], "floor", fl)
+        worst_ratio = max(worst_ratio, e / (FLOOR_FACTOR * fl))
+    # inside the tensors: images, channels, border slices, single elements
+    dx_bar = max(bar, FLOOR_FACTOR * floors.get("dx", 0.0))
+    st = dict(y=assert_structure("y", out["y"], ref["y"], tol["fwd"], smooth=True),
+              x_rec=assert_structure("x_rec", out["x_rec"], x, tol["recon"], smooth=True),
+              dx=assert_structure("dx", out["dx"], ref["dx"], dx_bar, smooth=False))
+    if case:
+        record(case, conv=conv, y=err["y"], x_rec=err["x_rec"], dx=err["dx"], worst_param=gerr[worst],
+               worst_param_name=worst, bar=bar, dx_floor=floors.get("dx"), worst_param_floor=floors.get(worst),
+               dx_vs_f32_oracle=vs32.get("dx"), worst_fraction_of_allowance=worst_ratio,
+               dx_per_image=st["dx"]["per_image"], dx_per_channel=st["dx"]["per_channel"], dx_border=st["dx"]["border"],
+               y_max_abs_over_rms=st["y"]["max_abs_over_rms"], dx_outliers=st["dx"]["outliers"])
     return err
 
 
@@ -141,16 +178,12 @@ SMALL_CASES = {
 @pytest.mark.parametrize("name", list(SMALL_CASES))
 def test_stack_matches_oracle(oracle, torch_cuda, name, conv):
     cfg = dict(SMALL_CASES[name], conv=conv)
-    if name.startswith("degenerate") and conv == "bf16":
-        pytest.skip("degenerate shapes are covered in fp32")
     print(f"case {name} conv={conv} cfg={cfg}", flush=True)
     x, params, dy = S.draw_stack(1234, **cfg)
     ref = oracle_reference(oracle, cfg, x, params, dy)
     out = gpu_run(cfg, x, params, dy)
-    tol = dict(TOL[conv])
-    if conv == "bf16":
-        tol["grad"] = bf16_grad_tol(oracle, cfg, x, params, dy, ref)
-    check_against_oracle(oracle, out, ref, x, conv, tol=tol)
+    r32 = bf16_grad_tol(oracle, cfg, x, params, dy, ref)[1] if conv == "bf16" else None
+    check_against_oracle(oracle, out, ref, x, conv, case=f"small/{name}/{conv}", ref32=r32)
 
 
 @pytest.mark.parametrize("kind,c,width,h,w,n", [
@@ -198,7 +231,7 @@ def test_bf16_every_block_of_a_stack_from_oracle_inputs(oracle, torch_cuda, kind
         out = dict(y=y_gpu, x_rec=r.to_host(Y[0]), dx=r.to_host(DY[0]), grads=[download_grads(r.grads)[k]])
         ref = dict(y=cat(outs[k]), dx=cat(downs[k]), grads=[grads[k]])
         print(f"block {k}:", end=" ")
-        check_against_oracle(oracle, out, ref, cat(inputs[k]), "bf16")
+        check_against_oracle(oracle, out, ref, cat(inputs[k]), "bf16", case=f"block_by_block/{kind}_c{c}_{h}x{w}_n{n}/block{k}")
 
 
 def test_block_entry_points_c1(oracle, torch_cuda):
@@ -320,7 +353,7 @@ def test_deep_stack_activation_memory_flat_and_drift_small(oracle, torch_cuda):
     same workspace and same peak device memory around forward + backward (the
     library allocates nothing).  The drift bar comes from the oracle alone: its
     float32 run of Algorithm 1 on the same inputs, against its float64
-    stored-activation gradients; the GPU has to stay within 3x of that for the
+    stored-activation gradients; the GPU has to stay within 1.5x of that for the
     reconstructed input, the input gradient and the parameter-gradient angle."""
     import torch
     from paper_1707_04585_amd.torch_harness import StackRunner, download_grads
@@ -355,9 +388,44 @@ def test_deep_stack_activation_memory_flat_and_drift_small(oracle, torch_cuda):
             o_ang = oracle.angle_deg(oracle.flatten_grads(g32), oracle.flatten_grads(ref["grads"]))
             print("depth 72: x_rec %.2e  dx %.2e  gradient angle %.3f deg  (oracle float32 Algorithm 1: %.2e %.2e %.3f)" %
                   (e_rec, e_dx, ang, o_rec, o_dx, o_ang), flush=True)
-            assert e_rec < 3 * o_rec and e_dx < 3 * o_dx and ang < 3 * o_ang
+            assert e_rec < 1.5 * o_rec and e_dx < 1.5 * o_dx and ang < 1.5 * o_ang
+            record("deep_stack_72_blocks/f32", conv="f32", x_rec=e_rec, dx=e_dx, angle_deg=ang, oracle_f32_x_rec=o_rec,
+                   oracle_f32_dx=o_dx, oracle_f32_angle_deg=o_ang)
     assert ws[2] == ws[72], ws
     assert peaks[2] == 0 and peaks[72] == 0, peaks
+
+
+def expected_relu_flips(params, stored64, sigmas=4.0):
+    """From the float64 oracle alone: how many of the stack's ReLU decisions a
+    correct float32 evaluation can take differently, per image.
+
+    A pre-activation u = scale * h + shift inherits the rounding of the
+    convolution sum h behind it: K = c_in * k * k products accumulated in
+    float32 leave a relative error of about eps * sqrt(K) of the result's scale
+    (eps = 2^-24; random-walk growth of the rounding errors), so the float32
+    value is u + d with d ~ N(0, sigma^2), sigma = eps * sqrt(K) * rms(u) per
+    channel.  (The stream tensors that layer 0 reads carry the error of the
+    previous function's last convolution, hence that layer's K.)  Such a value
+    decides differently from u with probability Phi(-|u| / sigma); the sum over
+    an image's elements is the expected number of differing decisions there.
+    Returns (expected count per image, per-image flag: some |u| < sigmas * sigma)."""
+    from scipy.special import ndtr
+    eps = 2.0 ** -24
+    n = stored64[0]["F"][0]["u"].shape[0]
+    expected = np.zeros(n)
+    flagged = np.zeros(n, dtype=bool)
+    for k, st in enumerate(stored64):
+        for fn in ("F", "G"):
+            layers = params[k][fn]
+            for l, s64 in enumerate(st[fn]):
+                w = layers[l - 1]["w"] if l > 0 else layers[-1]["w"]   # the convolution that produced this layer's input
+                K = w.shape[1] * w.shape[2] * w.shape[3]
+                u = s64["u"]
+                sigma = eps * np.sqrt(K) * np.sqrt((u ** 2).mean(axis=(0, 2, 3), keepdims=True))
+                t = np.abs(u) / np.maximum(sigma, 1e-300)
+                expected += ndtr(-t).sum(axis=(1, 2, 3))
+                flagged |= (t < sigmas).any(axis=(1, 2, 3))
+    return expected, flagged
 
 
 def test_c2_full_size_with_drift_report(oracle, torch_cuda):
@@ -366,14 +434,15 @@ def test_c2_full_size_with_drift_report(oracle, torch_cuda):
     'Numerical error': it accumulates but stays small).
 
     Tolerance at this size.  The stack takes 9*4*N*c*H*W = 7.5e7 ReLU
-    decisions u > 0.  fp32 sums of 144 products put u about 3e-7 (relative to
-    its unit scale) away from the float64 value, so a decision differs with
-    probability 2 * 3e-7 * pdf(0) = 2.4e-7: about 18 of them, whatever the
-    kernel.  Each one changes its gradient element by O(1) and that error
-    travels, norm roughly preserved, through the layers below but stays inside
-    its own image.  Expected ||error|| / ||dx|| = sqrt(18 / 4.2e6) = 2e-3.  So:
-      * images without a differing decision must meet the 1e-4 bar, and at
-        least 60% of the 128 images must be such images;
+    decisions u > 0.  Float32 sums put u a few 1e-7 (more after several blocks
+    of reconstruction drift) away from the float64 value, so a handful of
+    decisions differ whatever the kernel.  Each one changes its gradient
+    element by O(1), and that error stays inside its own image:
+      * an image either meets the 1e-4 bar, or it holds a pre-activation within
+        4 sigma of zero in the float64 oracle (sigma: the rounding error of a
+        float32 convolution sum, see expected_relu_flips);
+      * the number of images above the bar is at most E + 4 sqrt(E) + 2, E the
+        expected number of differing decisions computed from the oracle alone;
       * whole tensors: dx within 5e-3, parameter gradients within 1e-2, and the
         angle between the parameter-gradient vectors (the quantity of the
         paper's figure on stored versus reconstructed activations) < 0.2 deg.
@@ -383,18 +452,37 @@ def test_c2_full_size_with_drift_report(oracle, torch_cuda):
     from paper_1707_04585_amd.torch_harness import StackRunner
     cfg, x, params, dy = S.draw_named("c2_stack9")
     print("oracle reference for c2_stack9 ...", flush=True)
-    ref = oracle_reference(oracle, cfg, x, params, dy)
+    x1, x2 = split(x)
+    y1, y2, inputs, stored = oracle.stack_fwd(x1, x2, params, keep=True)
+    dx1, dx2, grads = oracle.stack_bwd_stored(stored, params, *split(dy))
+    ref = dict(y=np.concatenate([y1, y2], 1), dx=np.concatenate([dx1, dx2], 1), grads=grads, inputs=inputs)
+    expected, flagged = expected_relu_flips(params, stored)
+    del stored
     print("gpu run ...", flush=True)
     out = gpu_run(cfg, x, params, dy)
-    check_against_oracle(oracle, out, ref, x, "f32", tol=dict(fwd=1e-5, recon=1e-5, grad=1e-2))
-    assert oracle.rel_l2(out["dx"], ref["dx"]) < 5e-3
+    err = error_table(oracle, out, ref, x)
+    gerr = {k: v for k, v in err.items() if "." in k}
+    worst = max(gerr, key=gerr.get)
+    print("rel. errors: y %.2e  x_rec %.2e  dx %.2e  worst parameter gradient %s %.2e" %
+          (err["y"], err["x_rec"], err["dx"], worst, gerr[worst]), flush=True)
+    assert err["y"] < 1e-5 and err["x_rec"] < 1e-5
+    assert err["dx"] < 5e-3 and gerr[worst] < 1e-2
+    assert_structure("y", out["y"], ref["y"], 1e-5, smooth=True)
+    assert_structure("x_rec", out["x_rec"], x, 1e-5, smooth=True)
     per_image = np.array([oracle.rel_l2(out["dx"][i], ref["dx"][i]) for i in range(cfg["n"])])
-    clean = float((per_image < 1e-4).mean())
-    print("images whose dx meets 1e-4: %.0f%%; median per-image error %.2e" % (100 * clean, np.median(per_image)), flush=True)
-    assert clean >= 0.6
+    above = per_image >= 1e-4
+    E = float(expected.sum())
+    print("images whose dx meets 1e-4: %d of %d; median per-image error %.2e; expected differing decisions %.1f; "
+          "images with a pre-activation within 4 sigma of zero: %d" %
+          (int((~above).sum()), cfg["n"], np.median(per_image), E, int(flagged.sum())), flush=True)
+    assert not (above & ~flagged).any(), ("images above 1e-4 without a near-zero pre-activation", np.nonzero(above & ~flagged)[0])
+    assert above.sum() <= E + 4.0 * np.sqrt(E) + 2.0, (int(above.sum()), E)
     ang = oracle.angle_deg(oracle.flatten_grads(out["grads"]), oracle.flatten_grads(ref["grads"]))
     print("angle between GPU and stored-activation parameter gradients: %.3e degrees" % ang, flush=True)
     assert ang < 0.2
+    record("c2_stack9/full", conv="f32", y=err["y"], x_rec=err["x_rec"], dx=err["dx"], worst_param=gerr[worst],
+           worst_param_name=worst, images_above_bar=int(above.sum()), expected_flips=E, flagged_images=int(flagged.sum()),
+           median_per_image_dx=float(np.median(per_image)), angle_deg=ang)
     # drift per depth: peel the stack one block at a time with the block entry point
     r = StackRunner(**cfg)
     r.set_params(params)
@@ -436,8 +524,8 @@ def test_reduced_batch_real_shapes_bf16(oracle, torch_cuda):
         x, params, dy = S.draw_stack(81, **cfg)
         ref = oracle_reference(oracle, cfg, x, params, dy)
         out = gpu_run(cfg, x, params, dy)
-        gtol = bf16_grad_tol(oracle, cfg, x, params, dy, ref)
-        check_against_oracle(oracle, out, ref, x, "bf16", tol=dict(TOL["bf16"], grad=gtol))
+        _, r32 = bf16_grad_tol(oracle, cfg, x, params, dy, ref)
+        check_against_oracle(oracle, out, ref, x, "bf16", case=f"reduced_batch/{name}_n{n}", ref32=r32)
         with oracle.conv_operands("exact"):
             exact = oracle_reference(oracle, dict(cfg, conv="f32"), x, params, dy)
         print("  for information, against unrounded float64: dx %.2e" % oracle.rel_l2(out["dx"], exact["dx"]), flush=True)

@@ -120,8 +120,8 @@ def test_whole_network_matches_oracle_fp32(oracle, torch_cuda, name, n):
     batch: last stage's top and every parameter derivative (stem filter
     included) against ordinary stored-activation backprop in float64.  The bar
     allows for the few 0/1 ReLU decisions that fp32 sums take differently (see
-    test_body_real_shapes_reduced_batch): 3x the oracle's own float32-to-float64
-    distance where that exceeds 1e-4."""
+    test_body_real_shapes_reduced_batch): a tensor above 1e-4 must be within
+    1.5x the largest float32-to-float64 oracle distance of the case."""
     import torch
     import synth_inputs as S
     from paper_1707_04585_amd.torch_harness import NetRunner, download_grads, download_down, _dev
@@ -145,9 +145,8 @@ def test_whole_network_matches_oracle_fp32(oracle, torch_cuda, name, n):
     _, t32, dx32, sg32, dg32, dws32 = oracle_run(np.float32)
     o32 = dict(tops=t32, x_rec=x0, dx=dx32, stage_grads=sg32, down_grads=dg32)
     f_fwd, _, f_dx, f_g = body_errors(oracle, o32, tops_ref, dx_ref, sg_ref, dg_ref, x0)
-    floor = max(f_dx, max(f_g.values()), oracle.rel_l2(dws32, dws_ref))
-    tol = max(1e-4, 3.0 * floor)
-    print(f"{name}: floor (oracle float32 vs float64) {floor:.2e} -> gradient tolerance {tol:.2e}", flush=True)
+    floors = dict(f_g, dx=f_dx, stem_w=oracle.rel_l2(dws32, dws_ref))
+    print(f"{name}: largest floor (oracle float32 vs float64) {max(floors.values()):.2e}", flush=True)
 
     r = NetRunner(cfg, stem)
     r.set_params(stages, downs)
@@ -166,8 +165,14 @@ def test_whole_network_matches_oracle_fp32(oracle, torch_cuda, name, n):
     worst = max(g, key=g.get)
     print("  rel. errors: tops %.2e  stem output reconstructed %.2e  dx %.2e  stem filter gradient %.2e  worst other %s %.2e" %
           (fwd, rec, dx, e_stem, worst, g[worst]), flush=True)
-    assert fwd < max(1e-5, 3.0 * f_fwd) and rec < 1e-5
-    assert dx < tol and e_stem < tol and g[worst] < tol
+    assert fwd < max(1e-5, 1.5 * f_fwd) and rec < 1e-5
+    _, _, v_dx, v_g = body_errors(oracle, out, t32, dx32, sg32, dg32, x0)
+    from parity_checks import check_with_floors, record
+    vs32 = dict(v_g, dx=v_dx, stem_w=oracle.rel_l2(r.stem_dw.cpu().numpy(), dws32))
+    used = check_with_floors(dict(g, dx=dx, stem_w=e_stem), floors, vs32, 1e-4, pooled=True)
+    record(f"whole_network/{name}_n{n}/f32", conv="f32", y=fwd, x_rec=rec, dx=dx, worst_param=g[worst], worst_param_name=worst,
+           bar=1e-4, dx_floor=f_dx, worst_param_floor=floors[worst], dx_vs_f32_oracle=v_dx, stem_w=e_stem,
+           worst_fraction_of_allowance=used)
 
 
 def test_stem_with_gapped_planes(oracle, torch_cuda):
