@@ -129,19 +129,38 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
     // x = r - conv, negated again when stored), so its loads are in flight
     // together with the first activation loads and cost no registers.  r may
     // alias out element for element: a lane reads an address before it writes it.
+    // The loads are unconditional (a lane with nothing to fetch re-reads its own first valid address, or
+    // the tensor base, and the value is discarded afterwards): a load inside a divergent branch makes the
+    // compiler wait for it before the next one is issued, one memory round trip per register.
     float16_t acc[MTW][4];
+    if (p.ep != EP_STORE) {
+        const bool fetch = live && !idle && kw == 0;
+        const float sign = p.ep == EP_SUB ? -1.f : 1.f;
+        F4 t[MTW][16];
 #pragma unroll
-    for (int m = 0; m < MTW; ++m)
+        for (int m = 0; m < MTW; ++m)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            F4 t = {0.f, 0.f, 0.f, 0.f};
-            if (p.ep != EP_STORE && live && !idle && kw == 0 && chan(m, i) + 4 * kg < p.CO) {
-                t = *reinterpret_cast<const F4 *>(r_base + (int64_t)chan(m, i) * p.rsc * 4 + r_off);
-                if (p.ep == EP_SUB) t = -t;
+            for (int i = 0; i < 16; ++i) {
+                const bool ok = fetch && chan(m, i) + 4 * kg < p.CO;
+                const int64_t off = ok ? (int64_t)chan(m, i) * p.rsc * 4 + r_off : 0;
+                t[m][i] = *reinterpret_cast<const F4 *>(r_base + off);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[m][j][i] = t[j];
-        }
+        for (int m = 0; m < MTW; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const bool ok = fetch && chan(m, i) + 4 * kg < p.CO;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[m][j][i] = ok ? sign * t[m][i][j] : 0.f;
+            }
+    } else {
+#pragma unroll
+        for (int m = 0; m < MTW; ++m)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[m][j][i] = 0.f;
+    }
 
     struct Buf {
         F4 v[8];
@@ -158,6 +177,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
     };
     auto compute = [&](Buf &b, int ks) {
+#if defined(RVN_C1_ABL) && (RVN_C1_ABL & 1)
+        {   // ablation: consume the loads, no conversion, no matrix instructions
+            float t = 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) t += (b.v[k][0] + b.v[k][1]) + (b.v[k][2] + b.v[k][3]);
+#pragma unroll
+            for (int m = 0; m < MTW; ++m) acc[m][0][0] += t + __uint_as_float(b.a[m][0]);
+            return;
+        }
+#endif
         float v[8][4];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -264,6 +293,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
             F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
             if (p.ep == EP_SUB) t = -t;
             float *op = reinterpret_cast<float *>(o_base + (int64_t)chan(m, i) * p.osc * 4 + o_off);
+#if defined(RVN_C1_ABL) && (RVN_C1_ABL & 2)
+            if (p.HW == -1 || (i == 0 && m == 0))   // ablation: one store per wavefront tile instead of all
+#endif
             if (!GEN || dup == 0) {
                 *reinterpret_cast<F4 *>(op) = t;
             } else {  // the first dup pixels belong to the previous group

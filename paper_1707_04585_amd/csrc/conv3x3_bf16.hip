@@ -377,9 +377,10 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
     pl.ok = false;
     if (ci % 8 != 0 || g.w < 4 || ci > 4096) return pl;
     // Output channels per workgroup and the wavefront arrangement.
-    if (co <= 32) { pl.WM = 1; pl.MTW = 1; pl.NTW = 2; }
-    else if (co <= 64) { pl.WM = 1; pl.MTW = 2; pl.NTW = 2; }
-    else { pl.WM = 2; pl.MTW = 2; pl.NTW = 2; }
+    // 64 output channels per workgroup at most, the four wavefronts side by side along the pixels: with
+    // 128 channels (two wavefronts stacked) the wide layers were 5-10 % slower (twice the filter tile per
+    // workgroup, half as many pixel slots).
+    pl.WM = 1; pl.MTW = co <= 32 ? 1 : 2; pl.NTW = 2;
     const int ch = pl.WM * pl.MTW * 32, slots = (4 / pl.WM) * pl.NTW * 32;
     // One chunk of 32 channels when that is the whole input; otherwise chunks of
     // 16, which pipeline better (measured on 64-, 56- and 32-channel layers).
@@ -484,7 +485,6 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     else if (pl.WM == 1 && pl.MTW == 1 && pl.KC == 32) launch_c3<1, 1, 2, 32>(cx, pl, a, grid);
     else if (pl.WM == 1 && pl.MTW == 2 && pl.KC == 16) launch_c3<1, 2, 2, 16>(cx, pl, a, grid);
     else if (pl.WM == 1 && pl.MTW == 2 && pl.KC == 32) launch_c3<1, 2, 2, 32>(cx, pl, a, grid);
-    else if (pl.WM == 2 && pl.MTW == 2 && pl.KC == 16) launch_c3<2, 2, 2, 16>(cx, pl, a, grid);
     else launched = false;
     if (!launched) {
         cx.emitted = EmittedStats{};

@@ -330,7 +330,9 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     w.units = ((g.n + w.IMGS - 1) / w.IMGS) * w.bands;
     const int groups = w.tiles_ko * w.tiles_c;
     w.part_stride = groups * w.MT * w.CT * ks * ks * 1024;
-    int s = 512 / groups;  // two workgroups per compute unit
+    // Two workgroups per compute unit.  Fewer slices or 32 x 32 tiles would write fewer partial results, but
+    // measured slower on every workload (the launch is bound by staging and the multiply chain, not by those bytes).
+    int s = 512 / groups;
     if (s < 1) s = 1;
     if (s > w.units) s = w.units;
     w.upw = (w.units + s - 1) / s;
