@@ -379,7 +379,9 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         const int64_t tiles = (int64_t)ptiles * a.mtiles;
         a.KW = 1;
         if (tiles < 1024 && a.ksteps >= 8) a.KW = tiles < 512 && a.ksteps >= 16 ? 4 : 2;
-        int mtw = a.KW == 1 && a.mtiles >= 2 && (int64_t)ptiles * ((a.mtiles + 1) / 2) >= 2048 ? 2 : 1;
+        // (1024 wavefront tiles: at the 56x56 bottleneck layers two tiles per wavefront took 5-13 % off the
+        // launch, at 28x28 -- 784 tiles left -- they cost 3 %)
+        int mtw = a.KW == 1 && a.mtiles >= 2 && (int64_t)ptiles * ((a.mtiles + 1) / 2) >= 1024 ? 2 : 1;
         const int cot = (a.mtiles + mtw - 1) / mtw;
         const int rest = 4 / a.KW;
         a.CW = cot >= rest ? rest : cot >= 2 ? 2 : 1;

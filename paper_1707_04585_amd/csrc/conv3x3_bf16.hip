@@ -75,6 +75,13 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     return *reinterpret_cast<const uint32_t *>(&b);
 }
 
+// Buffer resource over `bytes` bytes at `base` (raw, no stride, dword data): accesses through it take a
+// 32-bit per-lane byte offset and a 32-bit wavefront-uniform byte offset from scalar registers, so no
+// vector instruction is spent on addresses.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
+
 // WM x WN wavefronts (WM * WN = 4), each MTW x NTW tiles of 32 output channels
 // x 32 pixels; KC input channels per chunk.
 template <int WM, int MTW, int NTW, int KC, bool EMIT = false>
@@ -252,39 +259,54 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
         }
     }
 
-    // ---- epilogue: register i of a lane is channel 8*(i/4) + 4*kg + i%4 of its pixel
+    // ---- epilogue: register i of a lane is channel 8*(i/4) + 4*kg + i%4 of its pixel.
+    //      Every access is a buffer access: a 32-bit per-lane byte offset (image, pixel, 4*kg channels)
+    //      plus a wavefront-uniform byte offset (the channel without the lane's 4*kg) that lives in scalar
+    //      registers; the host keeps every tensor handed to one launch below 4 GB.  With a 64-bit address
+    //      per lane and access, address arithmetic was half of the kernel's vector instructions.
     const bool partial = gridDim.z > 1;
+    const uint32_t HW4 = (uint32_t)(H * W) * 4u;
+    const uint32_t osc4 = (uint32_t)p.osc * 4u, rsc4 = (uint32_t)p.rsc * 4u;
+    const __amdgpu_buffer_rsrc_t out_rs = partial ? buffer_over(p.part + blockIdx.z * p.part_stride, (uint32_t)p.part_stride * 4u)
+                                                  : buffer_over(p.out, 0xfffffffcu);
+    const __amdgpu_buffer_rsrc_t r_rs = buffer_over(p.ep != EP_STORE ? p.r : p.out, 0xfffffffcu);
+    const uint32_t c_stride = partial ? HW4 : osc4;  // bytes from one output channel to the next
+    // channel counts that are multiples of 8 (the usual case) make the bound check uniform: register i exists
+    // for both halves of the wavefront or for neither
+    const bool whole8 = (CO & 7) == 0;
 #pragma unroll
     for (int t = 0; t < NTW; ++t) {
         if (o_img[t] < 0) continue;
+        const uint32_t o_off = partial ? (uint32_t)((((int64_t)o_img[t] * CO + 4 * kg) * (H * W) + o_pix[t]) * 4)
+                                       : (uint32_t)(((int64_t)o_img[t] * p.osn + o_pix[t] + (int64_t)(4 * kg) * p.osc) * 4);
+        const uint32_t r_off = (uint32_t)(((int64_t)o_img[t] * p.rsn + o_pix[t] + (int64_t)(4 * kg) * p.rsc) * 4);
 #pragma unroll
         for (int m = 0; m < MTW; ++m) {
-            const int kb = co0 + (wm * MTW + m) * 32 + 4 * kg;
-            if (partial) {
-                float *dst = p.part + blockIdx.z * p.part_stride + ((int64_t)o_img[t] * CO) * (H * W) + o_pix[t];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int ko = kb + 8 * (i >> 2) + (i & 3);
-                    if (ko < CO) dst[(int64_t)ko * (H * W)] = acc[m][t][i];
-                }
-                continue;
-            }
-            if (p.ep != EP_STORE) {  // all skip values first: r may alias out
-                const float *const rsrc = p.r + (int64_t)o_img[t] * p.rsn + o_pix[t];
+            const int ku0 = co0 + (wm * MTW + m) * 32;  // uniform; register i is channel ku0 + 8*(i/4) + i%4 (+ 4*kg)
+            if (!partial && p.ep != EP_STORE) {  // all skip values first: r may alias out
                 float rv[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int ko = kb + 8 * (i >> 2) + (i & 3);
-                    rv[i] = ko < CO ? rsrc[(int64_t)ko * p.rsc] : 0.f;
+                    const int ku = ku0 + 8 * (i >> 2) + (i & 3);
+                    // (a register without a channel re-reads the lane's first one; the value is not used)
+                    const bool has = whole8 ? ku < CO : ku + 4 * kg < CO;
+                    rv[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r_rs, has ? r_off : 0u, (uint32_t)(ku < CO ? ku : ku0) * rsc4, 0));
                 }
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[m][t][i] = p.ep == EP_ADD ? rv[i] + acc[m][t][i] : rv[i] - acc[m][t][i];
             }
-            float *const dst = p.out + (int64_t)o_img[t] * p.osn + o_pix[t];
+            if (whole8) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int ko = kb + 8 * (i >> 2) + (i & 3);
-                if (ko < CO) dst[(int64_t)ko * p.osc] = acc[m][t][i];
+                for (int i = 0; i < 16; ++i) {
+                    const int ku = ku0 + 8 * (i >> 2) + (i & 3);
+                    if (ku < CO) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[m][t][i]), out_rs, o_off, (uint32_t)ku * c_stride, 0);
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int ku = ku0 + 8 * (i >> 2) + (i & 3);
+                    if (ku + 4 * kg < CO) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[m][t][i]), out_rs, o_off, (uint32_t)ku * c_stride, 0);
+                }
             }
         }
     }
@@ -455,8 +477,11 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     if (!wq) return false;
     const C3Plan pl = plan_c3(ci, co, g);
     if (!pl.ok || (pl.S > 1 && !scratch)) return false;
-    // lane offsets into `in` are 32-bit byte offsets
-    if (((int64_t)g.n * in.sn + (int64_t)ci * in.sc) * 4 >= ((int64_t)1 << 32)) return false;
+    // lane offsets into `in`, `out`, `r` and the partial tiles are 32-bit byte offsets
+    const int64_t lim = (int64_t)1 << 32;
+    if (((int64_t)g.n * in.sn + (int64_t)ci * in.sc) * 4 >= lim || ((int64_t)g.n * out.sn + (int64_t)co * out.sc) * 4 >= lim ||
+        (r && ((int64_t)g.n * r->sn + (int64_t)co * r->sc) * 4 >= lim) || (int64_t)g.n * co * g.h * g.w * 4 >= lim)
+        return false;
     C3Args a{};
     a.in = in.p; a.isn = in.sn; a.isc = in.sc;
     a.scale_shift = scale_shift;
