@@ -22,6 +22,8 @@
 // formed (and rounded to bf16) on the way into LDS.  Partial results are summed
 // in a fixed order by wgrad_reduce_body, in a launch of its own or carried by
 // another kernel.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace rvn {
@@ -50,9 +52,8 @@ struct WgArgs {
     int Wq, cpr;                      // 4-pixel groups and 8-pixel chunks per image row
     int lrows, a_pitch, a_img, a_plane;  // LDS geometry of a (bf16 elements)
     int d_pitch, d_img, d_plane;         // LDS geometry of dh (bf16 elements)
-    int a_items, d_items;                // 4-pixel items per unit
     int chunks;                          // 8-pixel chunks per unit = IMGS * TH * cpr
-    uint32_t m_wq, m_lrows, m_imgs, m_th;  // fast-division multipliers (see fdiv)
+    uint32_t m_wq;                       // fast-division multiplier (see fdiv)
     int part_stride;                     // floats of one workgroup column's partial results
 };
 
@@ -120,68 +121,125 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p)
     for (int e = tid; e < (CT * 32 * p.a_plane + MT * 32 * p.d_plane) / 8; e += kThreads)
         reinterpret_cast<uint4_t *>(smem16)[e] = uint4_t{0u, 0u, 0u, 0u};
 
-    // Stage unit u: a = max(x*scale + shift, 0) (zero outside the image) and dh,
-    // both as bf16, 4 pixels per item.  Several workgroups share a compute unit,
-    // so one's loads overlap another's matrix instructions.
-    // Items are handled kBatch at a time: all loads of a batch are issued (from a
-    // safe address where the item is outside the tensor) before any is converted,
-    // so a unit costs a few memory round trips instead of one per item.
-    auto stage = [&](int u) {
+    // ---- staging.  A channel plane of a unit holds Q = IMGS * rows * Wq items of 4 pixels; lane l of a
+    //      wavefront owns items l and l + 64 of every plane (the host keeps Q <= 128), and the wavefront
+    //      walks over the channels w, w + 4, ...  What depends on the item -- image, row, column, where it
+    //      sits in the LDS plane, how many of its pixels exist -- is worked out once per kernel; per unit a
+    //      lane only checks its image and row against the tensor, and per channel everything that changes
+    //      is wavefront-uniform (plane base, scale, shift).  (With one flat index per item, decoded by
+    //      division for every item of every unit, index arithmetic was three quarters of the kernel's
+    //      vector instructions.)
+    constexpr int kPass = 2;
+    struct Item {
+        int off;   // element offset from (first image, first row of the unit, column 0) of a channel plane; pulled back by sh
+        int lds;   // element offset in the LDS plane
+        int meta;  // image | row << 8 | sh << 20 | valid pixels << 22 | live << 25
+    };
+    auto make_item = [&](int q, int rows, int row_bias, int pitch, int img_stride_lds, int64_t sn, int lead) {
+        Item it{0, 0, 0};
+        if (q < IMGS * rows * p.Wq) {
+            const int t = fdiv(q, p.m_wq), qx = q - t * p.Wq;
+            const int img = t / rows, r = t - img * rows;
+            const int col = qx * 4;
+            const int sh = VEC ? 0 : col - min(col, W - 4);  // a quad that would run over the row end starts early
+            it.off = (int)((int64_t)img * sn) + (r - row_bias) * W + col - sh;
+            it.lds = img * img_stride_lds + r * pitch + lead + col;
+            it.meta = img | (r << 8) | (sh << 20) | (min(4, W - col) << 22) | (1 << 25);
+        }
+        return it;
+    };
+    Item ia[kPass], id[kPass];
+#pragma unroll
+    for (int ps = 0; ps < kPass; ++ps) {
+        ia[ps] = make_item(ps * 64 + lane, p.lrows, PAD, p.a_pitch, p.a_img, xsn, LP);
+        id[ps] = make_item(ps * 64 + lane, TH, 0, p.d_pitch, p.d_img, dsn, 0);
+    }
+    const int nch_a = min(CT * 32, p.CI - c0), nch_d = min(MT * 32, p.CO - ko0);  // channels of the tiles that exist
+
+    // One loaded item of channel cl: BN + ReLU (a only), tail and outside zeros, rounding to bf16, into LDS.
+    auto convert_store = [&](f4u_t x, int cl, const Item &it, bool inside, bool bn, uint16_t *lds, int plane) {
+        const int meta = it.meta;
+        const int sh = (meta >> 20) & 3, nv = (meta >> 22) & 7;
+        const float4 q = quad_fix(x, VEC ? 0 : sh, !inside);
+        float v0 = q.x, v1 = q.y, v2 = q.z, v3 = q.w;
+        if (bn) {
+            const float scl = ss_lds[cl], sft = ss_lds[CT * 32 + cl];
+            v0 = fmaxf(fmaf(v0, scl, sft), 0.f);
+            v1 = fmaxf(fmaf(v1, scl, sft), 0.f);
+            v2 = fmaxf(fmaf(v2, scl, sft), 0.f);
+            v3 = fmaxf(fmaf(v3, scl, sft), 0.f);
+            if (!inside) v0 = v1 = v2 = v3 = 0.f;  // zero outside the image is a(x) = 0, not a(0)
+        }
+        if (nv < 2) v1 = 0.f;
+        if (nv < 3) v2 = 0.f;
+        if (nv < 4) v3 = 0.f;
+        if ((meta >> 25) & 1) *reinterpret_cast<uint2 *>(lds + cl * plane + it.lds) = make_uint2(pack2(v0, v1), pack2(v2, v3));
+    };
+    auto item_inside = [&](const Item &it, int n0, int row0, int row_bias) {
+        const int meta = it.meta;
+        return ((meta >> 25) & 1) && n0 + (meta & 0xff) < N && (unsigned)(row0 + ((meta >> 8) & 0xfff) - row_bias) < (unsigned)H;
+    };
+    // One tensor of unit (n0, row0), kBatch channels in flight per lane.
+    auto stage_planes = [&](const float *base, int64_t sc, int64_t sn, const Item (&items)[kPass], int nch, int quads,
+                            int row_bias, int n0, int row0, uint16_t *lds, int plane, bool bn) {
+        const float *const ubase = base + (int64_t)n0 * sn + (int64_t)row0 * W;
+#pragma unroll
+        for (int ps = 0; ps < kPass; ++ps) {
+            if (ps * 64 >= quads) break;  // no second item per lane in this plane
+            const bool inside = item_inside(items[ps], n0, row0, row_bias);
+            const int64_t lo = inside ? (int64_t)items[ps].off : 0;  // (outside: the unit's first element, not used)
+            for (int cb = wave; cb < nch; cb += 4 * kBatch) {
+                f4u_t x[kBatch];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b)
+                    x[b] = *reinterpret_cast<const f4u_t *>(ubase + (int64_t)min(cb + 4 * b, nch - 1) * sc + lo);
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (cb + 4 * b >= nch) break;
+                    convert_store(x[b], cb + 4 * b, items[ps], inside, bn, lds, plane);
+                }
+            }
+        }
+    };
+    auto origin = [&](int u, int &n0, int &row0) {
         const int g = u / bands;
-        const int n0 = g * IMGS, row0 = (u - g * bands) * TH;
-        for (int e0 = tid; e0 < p.a_items; e0 += kThreads * kBatch) {
-            f4u_t x[kBatch];
-            int where[kBatch];  // LDS offset (elements) | sh << 20 | outside << 30; negative: no item
+        n0 = g * IMGS;
+        row0 = (u - g * bands) * TH;
+    };
+    auto stage = [&](int u) {
+        int n0, row0;
+        origin(u, n0, row0);
+        stage_planes(xp + (int64_t)c0 * p.xsc, p.xsc, xsn, ia, nch_a, IMGS * p.lrows * p.Wq, PAD, n0, row0, a_lds, p.a_plane, true);
+        stage_planes(dp + (int64_t)ko0 * p.dsc, p.dsc, dsn, id, nch_d, IMGS * TH * p.Wq, 0, n0, row0, d_lds, p.d_plane, false);
+    };
+    // 1x1 filters (16 accumulator registers): when a plane is one item per lane, every load of a unit is
+    // requested at once, one unit ahead, and arrives under the matrix instructions of the unit before.
+    constexpr bool kCanPrefetch = KS == 1;
+    constexpr int NBA = kCanPrefetch ? CT * 8 : 1, NBD = kCanPrefetch ? MT * 8 : 1;  // channels per wavefront and tile
+    const bool prefetch = kCanPrefetch && IMGS * p.lrows * p.Wq <= 64 && IMGS * TH * p.Wq <= 64;
+    f4u_t pa[NBA], pd[NBD];
+    auto request_unit = [&](int u) {
+        int n0, row0;
+        origin(u, n0, row0);
+        const float *const ua = xp + (int64_t)c0 * p.xsc + (int64_t)n0 * xsn + (int64_t)row0 * W +
+                                (item_inside(ia[0], n0, row0, PAD) ? (int64_t)ia[0].off : 0);
+        const float *const ud = dp + (int64_t)ko0 * p.dsc + (int64_t)n0 * dsn + (int64_t)row0 * W +
+                                (item_inside(id[0], n0, row0, 0) ? (int64_t)id[0].off : 0);
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const int e = e0 + b * kThreads;
-                const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
-                const int t2 = fdiv(t, p.m_lrows), lr = t - t2 * p.lrows;
-                const int cl = fdiv(t2, p.m_imgs), img = t2 - cl * IMGS;
-                const int col = qx * 4, ch = c0 + cl, n = n0 + img, row = row0 - PAD + lr;
-                const bool in = e < p.a_items && ch < p.CI && n < N && row >= 0 && row < H;
-                int sh;
-                x[b] = quad_load<VEC>(xp + (int64_t)n * xsn + (int64_t)ch * p.xsc + row * W + col, in, xp, col, W, sh);
-                where[b] = e < p.a_items ? (cl * p.a_plane + img * p.a_img + lr * p.a_pitch + LP + col) | (sh << 20) | (in ? 0 : 1 << 30) : -1;
-            }
+        for (int b = 0; b < NBA; ++b) pa[b] = *reinterpret_cast<const f4u_t *>(ua + (int64_t)min(wave + 4 * b, nch_a - 1) * p.xsc);
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const int off = where[b] & 0xfffff;
-                const float4 q = quad_fix(x[b], VEC ? 0 : (where[b] >> 20) & 3, false);
-                const bool zero = (where[b] >> 30) & 1;
-                const int e = e0 + b * kThreads;
-                const int t = fdiv(e, p.m_wq), col = (e - t * p.Wq) * 4;
-                const int cl = min(fdiv(fdiv(t, p.m_lrows), p.m_imgs), CT * 32 - 1);
-                const float sc = ss_lds[cl], sh = ss_lds[CT * 32 + cl];
-                const float v0 = zero ? 0.f : fmaxf(fmaf(q.x, sc, sh), 0.f);
-                const float v1 = zero || col + 1 >= W ? 0.f : fmaxf(fmaf(q.y, sc, sh), 0.f);
-                const float v2 = zero || col + 2 >= W ? 0.f : fmaxf(fmaf(q.z, sc, sh), 0.f);
-                const float v3 = zero || col + 3 >= W ? 0.f : fmaxf(fmaf(q.w, sc, sh), 0.f);
-                if (where[b] >= 0) *reinterpret_cast<uint2 *>(a_lds + off) = make_uint2(pack2(v0, v1), pack2(v2, v3));
-            }
-        }
-        for (int e0 = tid; e0 < p.d_items; e0 += kThreads * kBatch) {
-            f4u_t x[kBatch];
-            int where[kBatch];
+        for (int b = 0; b < NBD; ++b) pd[b] = *reinterpret_cast<const f4u_t *>(ud + (int64_t)min(wave + 4 * b, nch_d - 1) * p.dsc);
+    };
+    auto commit_unit = [&](int u) {
+        int n0, row0;
+        origin(u, n0, row0);
+        const bool ina = item_inside(ia[0], n0, row0, PAD), ind = item_inside(id[0], n0, row0, 0);
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const int e = e0 + b * kThreads;
-                const int t = fdiv(e, p.m_wq), qx = e - t * p.Wq;
-                const int t2 = fdiv(t, p.m_th), r = t - t2 * TH;
-                const int ml = fdiv(t2, p.m_imgs), img = t2 - ml * IMGS;
-                const int col = qx * 4, ko = ko0 + ml, n = n0 + img, row = row0 + r;
-                const bool in = e < p.d_items && ko < p.CO && n < N && row < H;
-                int sh;
-                x[b] = quad_load<VEC>(dp + (int64_t)n * dsn + (int64_t)ko * p.dsc + row * W + col, in, dp, col, W, sh);
-                where[b] = e < p.d_items ? (ml * p.d_plane + img * p.d_img + r * p.d_pitch + col) | (sh << 20) | (in ? 0 : 1 << 30) : -1;
-            }
+        for (int b = 0; b < NBA; ++b)
+            if (wave + 4 * b < nch_a) convert_store(pa[b], wave + 4 * b, ia[0], ina, true, a_lds, p.a_plane);
 #pragma unroll
-            for (int b = 0; b < kBatch; ++b) {
-                const float4 q = quad_fix(x[b], VEC ? 0 : (where[b] >> 20) & 3, (where[b] >> 30) & 1);
-                const uint2 v = make_uint2(pack2(q.x, q.y), pack2(q.z, q.w));
-                if (where[b] >= 0) *reinterpret_cast<uint2 *>(d_lds + (where[b] & 0xfffff)) = v;
-            }
-        }
+        for (int b = 0; b < NBD; ++b)
+            if (wave + 4 * b < nch_d) convert_store(pd[b], wave + 4 * b, id[0], ind, false, d_lds, p.d_plane);
     };
 
     // ---- this wavefront's tile and share of the steps
@@ -198,10 +256,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_bf16_k(const WgArgs p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 
+    if (prefetch && u_begin < u_end) request_unit(u_begin);
     for (int u = u_begin; u < u_end; ++u) {
         __syncthreads();  // the previous unit has been consumed (first pass: tiles zeroed, ss_lds written)
-        stage(u);
+        if (prefetch) commit_unit(u);
+        else stage(u);
         __syncthreads();
+        if (prefetch && u + 1 < u_end) request_unit(u + 1);
         // This lane's chunk in step t is q = 2*t + kg -> (image, row, chunk in row).
         int q = 2 * kw + kg, img = 0, row = 0, cr = q;
         for (int t = kw; t < steps; t += KW) {
@@ -312,6 +373,7 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
         const int d_items = w.MT * 32 * imgs * th * w.Wq;
         const size_t bytes = ((size_t)w.CT * 32 * a_plane + (size_t)w.MT * 32 * d_plane) * 2;
         if (bytes > 64 * 1024 || imgs > 255 || lrows > 4000) return false;
+        if (imgs * lrows * w.Wq > 128) return false;  // staging: at most two 4-pixel items per lane and channel plane
         w.TH = th; w.IMGS = imgs; w.lrows = lrows;
         w.a_img = a_img; w.d_img = d_img; w.a_plane = a_plane; w.d_plane = d_plane;
         w.a_items = a_items; w.d_items = d_items;
@@ -351,6 +413,8 @@ bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin
                      float *scratch, float *dw, bool accumulate, double bytes, double flops, WgradReduce *defer) {
     const WgPlan w = plan_wg(cin, cout, ks, g);
     if (!w.ok) return false;
+    // a lane's item offsets (image, row, column within a channel plane of a unit) are 32-bit
+    if ((int64_t)w.IMGS * std::max(x.sn, dh.sn) + (int64_t)(w.lrows + 1) * g.w >= ((int64_t)1 << 30)) return false;
     WgArgs a{};
     a.x = x.p; a.xsn = x.sn; a.xsc = x.sc;
     a.scale_shift = scale_shift;
@@ -361,9 +425,8 @@ bool conv_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, int cin
     a.Wq = w.Wq; a.cpr = w.cpr; a.lrows = w.lrows;
     a.a_pitch = w.a_pitch; a.a_img = w.a_img; a.a_plane = w.a_plane;
     a.d_pitch = w.d_pitch; a.d_img = w.d_img; a.d_plane = w.d_plane;
-    a.a_items = w.a_items; a.d_items = w.d_items;
     a.chunks = w.IMGS * w.TH * w.cpr;
-    a.m_wq = fdiv_magic(w.Wq); a.m_lrows = fdiv_magic(w.lrows); a.m_imgs = fdiv_magic(w.IMGS); a.m_th = fdiv_magic(w.TH);
+    a.m_wq = fdiv_magic(w.Wq);
     a.part_stride = w.part_stride;
     const dim3 grid((unsigned)w.S, (unsigned)w.tiles_ko, (unsigned)w.tiles_c);
     const bool vec = (g.w & 3) == 0 && (x.sn & 3) == 0 && (x.sc & 3) == 0 && (dh.sn & 3) == 0 && (dh.sc & 3) == 0 &&
