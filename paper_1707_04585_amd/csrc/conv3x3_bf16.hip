@@ -83,8 +83,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, 
 }
 
 // WM x WN wavefronts (WM * WN = 4), each MTW x NTW tiles of 32 output channels
-// x 32 pixels; KC input channels per chunk.
-template <int WM, int MTW, int NTW, int KC, bool EMIT = false>
+// x 32 pixels; KC input channels per chunk.  NI: activation staging items per
+// thread and chunk.  With NI == 1 the activation loads run two chunks ahead of the
+// matrix instructions (two register sets): a chunk's matrix work is well below one
+// memory round trip, so with one chunk of lookahead every chunk paid for one.
+template <int WM, int MTW, int NTW, int KC, bool EMIT = false, int NI = kInItems>
 __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
     constexpr int WN = 4 / WM;
     constexpr int REC = KC + kPadK, OCTS = KC / 8;
@@ -117,10 +120,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
     // ---- this thread's activation items: (image, quad of the band's pixel range, channel octet)
     const int start_row = max(0, row0 - 1), end_row = min(H, row0 + p.TR + 1);
     const int range = (end_row - start_row) * W;  // contiguous pixels of the plane this block reads
-    uint32_t it_off[kInItems];                    // byte offset of (image, pixel) in a plane (dead items: 0)
-    int it_rec[kInItems], it_info[kInItems];      // LDS record of pixel 0; col | nvalid << 16 | oc << 24
+    uint32_t it_off[NI];                          // byte offset of (image, pixel) in a plane (dead items: 0)
+    int it_rec[NI], it_info[NI];                  // LDS record of pixel 0; col | nvalid << 16 | oc << 24
 #pragma unroll
-    for (int i = 0; i < kInItems; ++i) {
+    for (int i = 0; i < NI; ++i) {
         const int e = tid + i * kThreads;
         const int oc = e % OCTS, t = e / OCTS;
         const int q = t % p.q_per_img, img = t / p.q_per_img;
@@ -157,21 +160,25 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.f;
 
-    f4u_t gin[kInItems][8];
+    constexpr int SETS = NI == 1 ? 2 : 1;  // register sets of activation loads
+    f4u_t gin[SETS][NI][8];
     uint4_t gw[W_PER];
     const char *const in_base = reinterpret_cast<const char *>(p.in);
     const int64_t isc_b = p.isc * 4;
 
-    auto g2r = [&](int c0) {
+    // global -> registers: the activations of chunk c0 into register set `set`, the filter of chunk c0
+    auto g2r_act = [&](f4u_t (&g)[NI][8], int c0) {
 #pragma unroll
-        for (int i = 0; i < kInItems; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int oc = it_info[i] >> 24;
             // octets past the last channel read the chunk's first octet instead and are zeroed later
             const uint32_t off = it_off[i] + (c0 + oc * 8 < CI ? (uint32_t)(oc * 8 * isc_b) : 0u);
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                gin[i][k] = *reinterpret_cast<const f4u_t *>(in_base + (int64_t)(c0 + k) * isc_b + off);
+                g[i][k] = *reinterpret_cast<const f4u_t *>(in_base + (int64_t)(c0 + k) * isc_b + off);
         }
+    };
+    auto g2r_w = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < W_PER; ++i) {
             const int e = tid + i * kThreads;
@@ -181,9 +188,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
             if (!ok) gw[i] = uint4_t{0u, 0u, 0u, 0u};
         }
     };
-    auto r2l = [&](int c0) {
+    // registers -> LDS: BN + ReLU + rounding of the activations of chunk c0; the filter as loaded
+    auto r2l_act = [&](const f4u_t (&g)[NI][8], int c0) {
 #pragma unroll
-        for (int i = 0; i < kInItems; ++i) {
+        for (int i = 0; i < NI; ++i) {
             const int info = it_info[i];
             const int col = info & 0xffff, nvalid = (info >> 16) & 15, oc = info >> 24;
             if (nvalid == 0) continue;
@@ -191,7 +199,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
             float v[8][4];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const f4u_t x = gin[i][k];
+                const f4u_t x = g[i][k];
                 float x0 = x[0], x1 = x[1], x2 = x[2], x3 = x[3];
                 if (bn) {
                     const int ch = chan_ok ? c0 + oc * 8 + k : 0;
@@ -215,20 +223,15 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
                 *reinterpret_cast<uint4_t *>(in_lds + rec * REC + oc * 8) = q;
             }
         }
+    };
+    auto r2l_w = [&]() {
 #pragma unroll
         for (int i = 0; i < W_PER; ++i) {
             const int e = tid + i * kThreads;
             if (e < W_ITEMS) *reinterpret_cast<uint4_t *>(w_lds + (e / OCTS) * REC + (e % OCTS) * 8) = gw[i];
         }
     };
-
-    const int chunk0 = blockIdx.z * p.cps, chunk1 = min(p.chunks, chunk0 + p.cps);
-    g2r(chunk0 * KC);
-    __syncthreads();  // tile zeroed, scale/shift in LDS
-    r2l(chunk0 * KC);
-    __syncthreads();
-    for (int ch = chunk0; ch < chunk1; ++ch) {
-        if (ch + 1 < chunk1) g2r((ch + 1) * KC);
+    auto multiply = [&]() {
 #pragma unroll
         for (int rr = 0; rr < 3; ++rr) {
 #pragma unroll
@@ -252,10 +255,52 @@ __global__ __launch_bounds__(kThreads, 2) void conv3x3_bf16_k(const C3Args p) {
                 }
             }
         }
-        if (ch + 1 < chunk1) {
+    };
+
+    const int chunk0 = blockIdx.z * p.cps, chunk1 = min(p.chunks, chunk0 + p.cps);
+    g2r_w(chunk0 * KC);
+    g2r_act(gin[0], chunk0 * KC);
+    if (SETS == 2 && chunk0 + 1 < chunk1) g2r_act(gin[SETS - 1], (chunk0 + 1) * KC);
+    __syncthreads();  // tile zeroed, scale/shift in LDS
+    r2l_w();
+    r2l_act(gin[0], chunk0 * KC);
+    __syncthreads();
+    if constexpr (SETS == 1) {
+        for (int ch = chunk0; ch < chunk1; ++ch) {
+            if (ch + 1 < chunk1) {
+                g2r_w((ch + 1) * KC);
+                g2r_act(gin[0], (ch + 1) * KC);
+            }
+            multiply();
+            if (ch + 1 < chunk1) {
+                __syncthreads();  // every wavefront has read chunk ch
+                r2l_w();
+                r2l_act(gin[0], (ch + 1) * KC);
+                __syncthreads();
+            }
+        }
+    } else {
+        // LDS holds chunk ch; set 1 holds chunk ch + 1 (in flight), set 0 is free -- and the other way
+        // round one chunk later.  The filter (small, cached) keeps one chunk of lookahead and is requested
+        // before the activations two chunks ahead, so that waiting for it does not wait for them.
+        for (int ch = chunk0; ch < chunk1; ch += 2) {
+            if (ch + 1 < chunk1) g2r_w((ch + 1) * KC);
+            if (ch + 2 < chunk1) g2r_act(gin[0], (ch + 2) * KC);
+            multiply();
+            if (ch + 1 >= chunk1) break;
             __syncthreads();  // every wavefront has read chunk ch
-            r2l((ch + 1) * KC);
+            r2l_w();
+            r2l_act(gin[SETS - 1], (ch + 1) * KC);
             __syncthreads();
+            if (ch + 2 < chunk1) g2r_w((ch + 2) * KC);
+            if (ch + 3 < chunk1) g2r_act(gin[SETS - 1], (ch + 3) * KC);
+            multiply();
+            if (ch + 2 < chunk1) {
+                __syncthreads();
+                r2l_w();
+                r2l_act(gin[0], (ch + 2) * KC);
+                __syncthreads();
+            }
         }
     }
 
@@ -442,11 +487,11 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
     return pl;
 }
 
-template <int WM, int MTW, int NTW, int KC, bool EMIT>
-void launch_c3_variant(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
+template <int WM, int MTW, int NTW, int KC, bool EMIT, int NI>
+void launch_c3_items(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be asked for once
     if (!raised && !cx.dry) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT, NI>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (e != hipSuccess) {
             cx.fail(e);
@@ -454,7 +499,14 @@ void launch_c3_variant(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
         }
         raised = true;
     }
-    cx.run(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT>, grid, dim3(kThreads), pl.lds_bytes, a);
+    cx.run(conv3x3_bf16_k<WM, MTW, NTW, KC, EMIT, NI>, grid, dim3(kThreads), pl.lds_bytes, a);
+}
+
+template <int WM, int MTW, int NTW, int KC, bool EMIT>
+void launch_c3_variant(Ctx &cx, const C3Plan &pl, const C3Args &a, dim3 grid) {
+    // one staging item per thread at most: the variant whose activation loads run two chunks ahead
+    if (pl.in_items <= kThreads) launch_c3_items<WM, MTW, NTW, KC, EMIT, 1>(cx, pl, a, grid);
+    else launch_c3_items<WM, MTW, NTW, KC, EMIT, kInItems>(cx, pl, a, grid);
 }
 
 template <int WM, int MTW, int NTW, int KC>
