@@ -177,16 +177,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
         }
     };
     auto compute = [&](Buf &b, int ks) {
-#if defined(RVN_C1_ABL) && (RVN_C1_ABL & 1)
-        {   // ablation: consume the loads, no conversion, no matrix instructions
-            float t = 0.f;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) t += (b.v[k][0] + b.v[k][1]) + (b.v[k][2] + b.v[k][3]);
-#pragma unroll
-            for (int m = 0; m < MTW; ++m) acc[m][0][0] += t + __uint_as_float(b.a[m][0]);
-            return;
-        }
-#endif
         float v[8][4];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -293,9 +283,6 @@ __global__ __launch_bounds__(kThreads, 2) void conv1x1_bf16_k(const C1Args p) {
             F4 t = {acc[m][0][i], acc[m][1][i], acc[m][2][i], acc[m][3][i]};
             if (p.ep == EP_SUB) t = -t;
             float *op = reinterpret_cast<float *>(o_base + (int64_t)chan(m, i) * p.osc * 4 + o_off);
-#if defined(RVN_C1_ABL) && (RVN_C1_ABL & 2)
-            if (p.HW == -1 || (i == 0 && m == 0))   // ablation: one store per wavefront tile instead of all
-#endif
             if (!GEN || dup == 0) {
                 *reinterpret_cast<F4 *>(op) = t;
             } else {  // the first dup pixels belong to the previous group
@@ -374,8 +361,8 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
         a.ptiles = ptiles;
         // With few tiles, the wavefronts of a workgroup split the input channels
         // (shorter dependent chains, more loads in flight).  Otherwise two output
-        // tiles per wavefront halve the passes over the input, as long as that
-        // still leaves two wavefronts for every SIMD.
+        // tiles per wavefront halve the passes over the input, once the halved
+        // tile count still fills the chip four times over.
         const int64_t tiles = (int64_t)ptiles * a.mtiles;
         a.KW = 1;
         if (tiles < 1024 && a.ksteps >= 8) a.KW = tiles < 512 && a.ksteps >= 16 ? 4 : 2;
