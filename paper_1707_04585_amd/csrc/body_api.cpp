@@ -245,14 +245,27 @@ void down_backward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const Do
             // a0's second child, the shortcut; first, because its filter gradient's
             // partial sums share the scratch with those of this layer, which stay
             // pending until the BN backward below
-            conv_wgrad(cx, dense_view(b.xs, d.c_in, pl.low), scale_shift, d.conv_dtype, dy, d.c_in, d.c_out, 1, pl.low,
-                       b.wgrad_scratch, gr.d_shortcut_w, accumulate);
-            conv_dgrad(cx, dy, d.conv_dtype, p.shortcut_w, b.wq_b[kShortcut], d.c_in, d.c_out, 1, pl.low, b.t, b.conv_scratch);
+            const View xs = dense_view(b.xs, d.c_in, pl.low);
+            WgradReduce sred;
+            if (d.conv_dtype == RVN_BF16 &&
+                conv_dgrad_wgrad_bf16(cx, xs, scale_shift, dy, b.wq_b[kShortcut], d.c_in, d.c_out, 1, pl.low, b.wgrad_scratch,
+                                      gr.d_shortcut_w, accumulate, b.t, b.conv_scratch, &sred)) {
+                wgrad_reduce(cx, sred);
+            } else {
+                conv_wgrad(cx, xs, scale_shift, d.conv_dtype, dy, d.c_in, d.c_out, 1, pl.low, b.wgrad_scratch,
+                           gr.d_shortcut_w, accumulate);
+                conv_dgrad(cx, dy, d.conv_dtype, p.shortcut_w, b.wq_b[kShortcut], d.c_in, d.c_out, 1, pl.low, b.t,
+                           b.conv_scratch);
+            }
         }
         WgradReduce red;
-        conv_wgrad(cx, xl, scale_shift, d.conv_dtype, dcur, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch, gr.R.d_conv_w[l],
-                   accumulate, &red);
-        conv_dgrad(cx, dcur, d.conv_dtype, p.R.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
+        if (d.conv_dtype != RVN_BF16 ||
+            !conv_dgrad_wgrad_bf16(cx, xl, scale_shift, dcur, b.wq_b[l], ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
+                                   gr.R.d_conv_w[l], accumulate, da, b.conv_scratch, &red)) {
+            conv_wgrad(cx, xl, scale_shift, d.conv_dtype, dcur, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch, gr.R.d_conv_w[l],
+                       accumulate, &red);
+            conv_dgrad(cx, dcur, d.conv_dtype, p.R.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
+        }
         if (l == 0) upsample2_add(cx, b.t, d.c_in, pl.full, da);
         const View out = l == 0 ? dx : dense_view(da, ly.cin, g);
         bn_relu_bwd(cx, xl, da, ly.cin, g, b.stats[l], b.bn_scratch, b.counters, gr.R.d_bn_gamma[l], gr.R.d_bn_beta[l],

@@ -276,7 +276,15 @@ void wgrad_reduce(Ctx &cx, const WgradReduce &r);
 bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, const float *w, int cin, int cout,
                           int ks, Geo g, float *scratch, float *dw, bool accumulate, float *da, WgradReduce *defer);
 
-// The same with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
+// conv_dgrad and conv_wgrad of one layer with bf16 operands (1x1 or 3x3) in a single launch; wq_b is the
+// filter prepared for the data gradient.  The ordered sum of the filter gradient is left in *defer; a
+// channel-split data gradient is followed by its reduce launch.  Returns false (nothing launched,
+// nothing accounted) for the shapes it does not take.
+bool conv_dgrad_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, const uint16_t *wq_b, int cin, int cout,
+                           int ks, Geo g, float *wgrad_scratch, float *dw, bool accumulate, float *da,
+                           float *conv_scratch, WgradReduce *defer);
+
+// The filter gradient with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
 // to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the
 // caller accounts for the launch.  Returns false (nothing launched) when no
 // plan fits; scratch must hold wgrad_bf16_scratch_floats(...) floats.

@@ -378,9 +378,13 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
         // BN-backward apply launch below.
         WgradReduce red;
         float *da = b.g[cur];
-        if (d.conv_dtype != RVN_F32 ||
-            !conv_dgrad_wgrad_f32(cx, xl, st + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
-                                  b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, &red)) {
+        const bool paired =
+            d.conv_dtype == RVN_F32
+                ? conv_dgrad_wgrad_f32(cx, xl, st + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
+                                       b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, &red)
+                : conv_dgrad_wgrad_bf16(cx, xl, st + 2 * ly.cin, dh, b.wq_b[l], ly.cin, ly.cout, ly.ks, g,
+                                        b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, b.conv_scratch, &red);
+        if (!paired) {
             conv_wgrad(cx, xl, st + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                        gr.d_conv_w[l], accumulate, &red);
             conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
