@@ -60,6 +60,11 @@
  *           (x + g) - g (Section 3.2, "Numerical error").  The fixed-point
  *           entry points further down take every statistic of a stream tensor
  *           from one algorithm in both passes and reconstruct bit for bit.
+ * Diagnostics. While the environment variable RVN_SEPARATE_LAUNCHES is "1" the
+ *           backward pass gives the data gradient and the filter gradient of
+ *           a layer a launch each instead of one shared launch (the default).
+ *           It is read at every call; results are the same bits either way,
+ *           the launch counts of the cost queries follow it.
  */
 #ifndef REVNET_H
 #define REVNET_H

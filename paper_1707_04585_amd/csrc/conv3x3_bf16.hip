@@ -127,7 +127,8 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
     const int64_t wgs = (int64_t)((g.n + pl.IMGS - 1) / pl.IMGS) * pl.bands * ((co + ch - 1) / ch);
     pl.S = 1;
     // Too few workgroups for the chip (measured: at most one per two compute
-    // units): split the input channels over gridDim.z as well.
+    // units): split the input channels over gridDim.z as well.  (56 -> 56 channels at 8x8, N=128: the
+    // 32 unsplit workgroups take 18.5 us, the 64 split ones 10.1 us plus 4.2 us for the sum.)
     if (wgs <= 128 && pl.chunks >= 4) pl.S = (int)std::min<int64_t>(pl.chunks / 2, (512 + wgs - 1) / wgs);
     pl.cps = (pl.chunks + pl.S - 1) / pl.S;
     pl.S = (pl.chunks + pl.cps - 1) / pl.cps;

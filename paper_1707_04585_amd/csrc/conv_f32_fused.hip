@@ -6,6 +6,8 @@
 // workgroups of both (filter gradient first: it has the longer dependent chain),
 // which saves a launch and lets the matrix phases of one overlap the load and
 // store phases of the other on the same compute units.
+#include <cstdlib>
+
 #include "conv_mfma_body.h"
 #include "conv_wgrad_body.h"
 #include "kernels.h"
@@ -32,9 +34,14 @@ __global__ __launch_bounds__(kThreads) void dgrad_wgrad_f32_k(const ConvArgs c, 
 
 }  // namespace
 
+bool separate_launches() {
+    const char *e = std::getenv("RVN_SEPARATE_LAUNCHES");
+    return e && e[0] == '1' && e[1] == 0;
+}
+
 bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, const float *w, int cin, int cout,
                           int ks, Geo g, float *scratch, float *dw, bool accumulate, float *da, WgradReduce *defer) {
-    if (ks != 3 || !defer) return false;
+    if (ks != 3 || !defer || separate_launches()) return false;
     ConvLaunch C;
     WgradLaunch W;
     WgradReduce red{};

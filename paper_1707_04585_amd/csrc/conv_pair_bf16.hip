@@ -158,7 +158,7 @@ bool pair_small(Ctx &cx, View x, const float *scale_shift, View dh, const uint16
 bool conv_dgrad_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, const uint16_t *wq_b, int cin, int cout,
                            int ks, Geo g, float *wgrad_scratch, float *dw, bool accumulate, float *da,
                            float *conv_scratch, WgradReduce *defer) {
-    if (!defer || !wq_b || (ks != 1 && ks != 3)) return false;
+    if (!defer || !wq_b || (ks != 1 && ks != 3) || separate_launches()) return false;
     WgLaunch W;
     if (!conv_wgrad_bf16_plan(x, scale_shift, dh, cin, cout, ks, g, wgrad_scratch, dw, accumulate, W))
         return ks == 3 && pair_small(cx, x, scale_shift, dh, wq_b, cin, cout, g, wgrad_scratch, dw, accumulate, da,

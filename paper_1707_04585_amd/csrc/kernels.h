@@ -270,6 +270,11 @@ void conv_wgrad(Ctx &cx, View x, const float *scale_shift, rvn_dtype dt, View dh
                 int ks, Geo g, float *scratch, float *dw, bool accumulate, WgradReduce *defer = nullptr);
 void wgrad_reduce(Ctx &cx, const WgradReduce &r);
 
+// True while the environment variable RVN_SEPARATE_LAUNCHES is "1": the data gradient and the filter
+// gradient of a layer then always get a launch each (a diagnostic switch, read at every call; the
+// results do not depend on it, bit for bit).
+bool separate_launches();
+
 // conv_dgrad and conv_wgrad of one fp32 3x3 layer in a single launch (both need
 // only dh); the ordered sum of the filter gradient is left in *defer.  Returns
 // false (nothing launched, nothing accounted) for the shapes it does not take.
