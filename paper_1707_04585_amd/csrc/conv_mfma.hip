@@ -40,6 +40,8 @@ __global__ __launch_bounds__(kThreads) void conv_mfma_f32_k(const ConvArgs p) {
     conv_mfma_f32_body<KS, MT, NT, KC, EMIT>(p, blockIdx.x, blockIdx.y, smem);
 }
 
+uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
+
 int ilog2(int v) {
     int l = 0;
     while ((1 << l) < v) ++l;
@@ -132,8 +134,7 @@ void conv_mfma(Ctx &cx, View in, const float *scale_shift, const float *w, bool 
     // Statistics of the output for the BN layer that reads it next (fp32 operands, 3x3, up to 32 output
     // channels, 4 tiles per wavefront): every tile slot of every workgroup must be a whole, valid tile.
     const int tiles = (int)L.grid.x * kWaves;
-    const bool whole = a.n_tiles == kWaves * L.nt && g.h % a.TH == 0 && a.TH % a.trows == 0 &&
-                       g.w % (1 << a.tcols_log2) == 0 && g.n % a.IMGS == 0;
+    const bool whole = a.whole != 0;
     if (cx.want_emit && cx.emit_buf && !bf16 && !transposed && ks == 3 && L.kc == 16 && L.nt == 4 && L.mt <= 2 &&
         whole && (size_t)co * tiles * 2 <= cx.emit_floats) {
         a.emit = cx.emit_buf;
@@ -159,6 +160,7 @@ bool conv_mfma_plan(View in, const float *scale_shift, const float *w, bool tran
     const int kc = ks == 3 ? (mt == 4 ? 8 : 16) : 16;
     const Tiling tl = choose_tiling(g, ks, kc, mt);
     if (tl.NT == 0) return false;
+    if ((int64_t)ci * co * ks * ks >= ((int64_t)1 << 30)) return false;  // filter elements are indexed in 32 bits
     ConvArgs a{};
     a.in = in.p; a.isn = in.sn; a.isc = in.sc;
     a.scale_shift = scale_shift;
@@ -172,6 +174,16 @@ bool conv_mfma_plan(View in, const float *scale_shift, const float *w, bool tran
     a.tiles_per_img = tl.tiles_per_img; a.n_tiles = tl.n_tiles;
     a.lrows = tl.lrows; a.pitch = tl.pitch; a.plane = tl.plane;
     a.img_stride = kc * tl.plane;
+    a.m_tpi = fdiv_magic(a.tiles_per_img);
+    a.m_ctl = fdiv_magic(a.ctl);
+    const int64_t lim = (int64_t)1 << 30;
+    auto fits = [&](const View &v, int c) {
+        return (v.sn & 3) == 0 && (v.sc & 3) == 0 && (reinterpret_cast<uintptr_t>(v.p) & 15) == 0 &&
+               (int64_t)g.n * v.sn + (int64_t)c * v.sc + (int64_t)g.h * g.w < lim;
+    };
+    a.vec32 = (g.w & 3) == 0 && fits(in, ci) && fits(out, co) && (!r || fits(*r, co));
+    a.whole = a.n_tiles == kWaves * tl.NT && g.h % a.TH == 0 && a.TH % a.trows == 0 && g.w % (1 << a.tcols_log2) == 0 &&
+              g.n % a.IMGS == 0;
     a.tpr_log2 = ilog2((g.w + 3) / 4);
     a.inv_lrows = 1.0f / (float)a.lrows;
     L.a = a;

@@ -24,6 +24,12 @@ struct ConvArgs {
     int lrows, pitch, plane, img_stride;  // LDS geometry (floats)
     int tpr_log2;                 // threads per staged row
     float inv_lrows;
+    // vec32: every plane of `in`, `r`, `out` is 16-byte aligned with rows of whole 4-pixel groups, and the
+    // tensors are small enough for 32-bit element offsets (below 2^30; the filter always is): staging and
+    // epilogue then address with a uniform base and one 32-bit lane offset, and load unconditionally.
+    // whole: every tile slot of every workgroup is a valid tile (no pixel checks in the epilogue).
+    int vec32, whole;
+    uint32_t m_tpi, m_ctl;        // fast-division multipliers of tiles_per_img and ctl (see fdiv_u)
     // EMIT instances (every tile slot of every workgroup a whole, valid tile): per channel and
     // wavefront the mean and centred sum of squares of the 16 * NT pixels it stores, at
     // emit[(channel * emit_tiles + workgroup * 4 + wavefront) * 2]
@@ -58,6 +64,9 @@ __device__ __forceinline__ float bf16_round_dev(float f) {
     return __uint_as_float(u & 0xffff0000u);
 }
 
+// e / d for 0 <= e, e * d < 2^32, with m = 2^32 / d + 1 computed on the host (m = 0 stands for d = 1).
+__device__ __forceinline__ int fdiv_u(int e, uint32_t m) { return m ? (int)__umulhi((uint32_t)e, m) : e; }
+
 // Workgroup (bx, by) of the convolution; `smem` is the workgroup's dynamic LDS.
 template <int KS, int MT, int NT, int KC, bool EMIT = false>
 __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, int by, float *smem) {
@@ -82,8 +91,8 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int tile = wave + kWaves * t;
-        const int img = tile / p.tiles_per_img, rem = tile - img * p.tiles_per_img;
-        const int tr = rem / p.ctl, tc = rem - tr * p.ctl;
+        const int img = fdiv_u(tile, p.m_tpi), rem = tile - img * p.tiles_per_img;
+        const int tr = fdiv_u(rem, p.m_ctl), tc = rem - tr * p.ctl;
         b_base[t] = img * p.img_stride + kq * p.plane + (tr * p.trows + dr) * p.pitch + (LP - PAD) +
                     (tc << p.tcols_log2) + dc;
         if (tile >= p.n_tiles) b_base[t] = kq * p.plane;  // idle slot: any valid address
@@ -121,12 +130,40 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
     constexpr bool kEarlySkip = MT * NT <= 8;
     int64_t e_off[NT];  // offset of (image, pixel) in out, -1: nothing to write
     float rv[NT][MT][4];
+    // Lean form (uniform): no pixel or channel can fall outside, offsets fit 32 bits.  A result's address
+    // is then a wavefront-uniform channel base plus one lane offset per tile, with no vector arithmetic
+    // per access and no branch.
+    const bool lean_ep = p.vec32 && p.whole && co0 + MT * 16 <= p.CO;
+    uint32_t o_lane[NT], r_lane[NT];  // byte offsets
     auto locate_and_request = [&]() {
+        if (lean_ep) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int tile = wave + kWaves * t;
+                const int img = fdiv_u(tile, p.m_tpi), rem = tile - img * p.tiles_per_img;
+                const int tr = fdiv_u(rem, p.m_ctl), tc = rem - tr * p.ctl;
+                const int n = n0 + img, row = row0 + tr * p.trows + dr, col = (tc << p.tcols_log2) + dc;
+                const uint32_t pix = (uint32_t)(row * p.W + col);
+                o_lane[t] = ((uint32_t)n * (uint32_t)p.osn + pix + (uint32_t)(kq * 4) * (uint32_t)p.osc) * 4u;
+                r_lane[t] = ((uint32_t)n * (uint32_t)p.rsn + pix + (uint32_t)(kq * 4) * (uint32_t)p.rsc) * 4u;
+            }
+            if (p.ep != EP_STORE) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const char *rb = reinterpret_cast<const char *>(p.r + (int64_t)(co0 + m * 16 + j) * p.rsc);  // uniform
+#pragma unroll
+                        for (int t = 0; t < NT; ++t) rv[t][m][j] = *reinterpret_cast<const float *>(rb + r_lane[t]);
+                    }
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int tile = wave + kWaves * t;
-            const int img = tile / p.tiles_per_img, rem = tile - img * p.tiles_per_img;
-            const int tr = rem / p.ctl, tc = rem - tr * p.ctl;
+            const int img = fdiv_u(tile, p.m_tpi), rem = tile - img * p.tiles_per_img;
+            const int tr = fdiv_u(rem, p.m_ctl), tc = rem - tr * p.ctl;
             const int n = n0 + img, row = row0 + tr * p.trows + dr, col = (tc << p.tcols_log2) + dc;
             const bool ok = tile < p.n_tiles && n < p.N && row < p.H && row < row0 + p.TH && col < p.W;
             const int pix = row * p.W + col;
@@ -150,31 +187,28 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
         //      when transposed), all loads in flight before the first store.
         float wv[WITER];
         int wdst[WITER];
+        {
+            // element e of the chunk is (output channel, input channel, tap) in the order of global memory:
+            // the input channel is the slower index when the filter is read transposed.  Every load is
+            // issued, from the filter's first element where e lies outside (the value is discarded).
+            const bool tr = p.transposed != 0;
+            const uint32_t s_ko = tr ? (uint32_t)KS2 : (uint32_t)p.CI * KS2, s_ch = tr ? (uint32_t)p.CO * KS2 : (uint32_t)KS2;
+            const char *const wb = reinterpret_cast<const char *>(p.w);
 #pragma unroll
-        for (int i = 0; i < WITER; ++i) {
-            const int e = tid + i * kConvThreads;
-            int kol, cl, t;
-            if (p.transposed) {
-                cl = e / (MT * 16 * KS2);
-                const int rem = e - cl * (MT * 16 * KS2);
-                kol = rem / KS2;
-                t = rem - kol * KS2;
-            } else {
-                kol = e / (KC * KS2);
-                const int rem = e - kol * (KC * KS2);
-                cl = rem / KS2;
-                t = rem - cl * KS2;
+            for (int i = 0; i < WITER; ++i) {
+                const int e = tid + i * kConvThreads;
+                const int o1 = e / (KC * KS2), r1 = e - o1 * (KC * KS2), i1 = r1 / KS2, t1 = r1 - i1 * KS2;
+                const int o2 = e / (MT * 16 * KS2), r2 = e - o2 * (MT * 16 * KS2), i2 = r2 / KS2, t2 = r2 - i2 * KS2;
+                const int kol = tr ? i2 : o1, cl = tr ? o2 : i1, t = tr ? t2 : t1;
+                const int ko = co0 + kol, ch = c0 + cl;
+                const bool in = e < WCHUNK && ko < p.CO && ch < p.CI;
+                const uint32_t idx = (uint32_t)ko * s_ko + (uint32_t)ch * s_ch + (uint32_t)t;
+                const float v = *reinterpret_cast<const float *>(wb + (in ? idx * 4u : 0u));
+                wv[i] = in ? v : 0.f;
+                // A-operand order; the transposed (data-gradient) filter is also flipped.
+                const int tt = tr ? KS2 - 1 - t : t;
+                wdst[i] = e < WCHUNK ? ((((cl >> 2) * KS2 + tt) * MT + (kol >> 4)) * 64 + (cl & 3) * 16 + (kol & 15)) : -1;
             }
-            const int ko = co0 + kol, ch = c0 + cl;
-            float v = 0.f;
-            if (e < WCHUNK && ko < p.CO && ch < p.CI) {
-                v = p.transposed ? p.w[((int64_t)ch * p.CO + ko) * KS2 + t]
-                                 : p.w[((int64_t)ko * p.CI + ch) * KS2 + t];
-            }
-            wv[i] = v;
-            // A-operand order; the transposed (data-gradient) filter is also flipped.
-            const int tt = p.transposed ? KS2 - 1 - t : t;
-            wdst[i] = e < WCHUNK ? ((((cl >> 2) * KS2 + tt) * MT + (kol >> 4)) * 64 + (cl & 3) * 16 + (kol & 15)) : -1;
         }
         // ---- input band: a = max(x*scale + shift, 0), zero outside the image
         for (int rbase = 0; rbase < total_rows; rbase += RB * rows_per_pass) {
@@ -195,7 +229,15 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
                 q[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                 sc[i] = 1.f;
                 sh[i] = 0.f;
-                if (live[i]) {
+                if (p.vec32) {  // (uniform) every load issued, from the tensor's first element where the item is outside
+                    const uint32_t off = (uint32_t)n * (uint32_t)p.isn + (uint32_t)ch * (uint32_t)p.isc + (uint32_t)(row * p.W + col);
+                    q[i] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(p.in) + (live[i] ? off * 4u : 0u));
+                    if (p.scale_shift) {
+                        const uint32_t sidx = live[i] ? (uint32_t)ch * 4u : 0u;
+                        sc[i] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(p.scale_shift) + sidx);
+                        sh[i] = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(p.scale_shift + p.CI) + sidx);
+                    }
+                } else if (live[i]) {
                     const float *src = p.in + (int64_t)n * p.isn + (int64_t)ch * p.isc + row * p.W + col;
                     if (vec) {
                         q[i] = *reinterpret_cast<const float4 *>(src);
@@ -215,22 +257,23 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
             for (int i = 0; i < RB; ++i) {
                 if (dsti[i] < 0) continue;
                 float v[4] = {q[i].x, q[i].y, q[i].z, q[i].w};
-                if (live[i]) {
-                    if (p.scale_shift) {
+                if (p.scale_shift) {
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) v[j] = fmaxf(fmaf(v[j], sc[i], sh[i]), 0.f);
-                    }
-                    if (p.round_bf16) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) v[j] = bf16_round_dev(v[j]);
-                    }
-                    if (!vec) {
-                        const int col = tx * 4;
-#pragma unroll
-                        for (int j = 1; j < 4; ++j)
-                            if (col + j >= p.W) v[j] = 0.f;
-                    }
+                    for (int j = 0; j < 4; ++j) v[j] = fmaxf(fmaf(v[j], sc[i], sh[i]), 0.f);
                 }
+                if (p.round_bf16) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = bf16_round_dev(v[j]);
+                }
+                if (!vec) {
+                    const int col = tx * 4;
+#pragma unroll
+                    for (int j = 1; j < 4; ++j)
+                        if (col + j >= p.W) v[j] = 0.f;
+                }
+                // an item outside the tensor is zero in a(x) (whatever was loaded for it)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = live[i] ? v[j] : 0.f;
                 float *dst = in_lds + dsti[i];
                 *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
                 if (KS == 3) {
@@ -280,15 +323,26 @@ __device__ __forceinline__ void conv_mfma_f32_body(const ConvArgs &p, int bx, in
                 for (int j = 0; j < 4; ++j)
                     acc[m][t][j] = p.ep == EP_ADD ? rv[t][m][j] + acc[m][t][j] : rv[t][m][j] - acc[m][t][j];
     }
+    if (lean_ep) {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        if (e_off[t] < 0) continue;
-#pragma unroll
-        for (int m = 0; m < MT; ++m) {
+        for (int m = 0; m < MT; ++m)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int ko = co0 + m * 16 + kq * 4 + j;
-                if (ko < p.CO) p.out[e_off[t] + (int64_t)ko * p.osc] = acc[m][t][j];
+                char *ob = reinterpret_cast<char *>(p.out + (int64_t)(co0 + m * 16 + j) * p.osc);  // uniform
+#pragma unroll
+                for (int t = 0; t < NT; ++t) *reinterpret_cast<float *>(ob + o_lane[t]) = acc[m][t][j];
+            }
+    } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if (e_off[t] < 0) continue;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ko = co0 + m * 16 + kq * 4 + j;
+                    if (ko < p.CO) p.out[e_off[t] + (int64_t)ko * p.osc] = acc[m][t][j];
+                }
             }
         }
     }

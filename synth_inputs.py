@@ -48,6 +48,9 @@ STACKS = {
     "c5_stage2":  dict(kind="bottleneck", n=32, c=512, h=28, w=28, depth=4, width=128, conv="bf16", affine="random"),
     "c5_stage3":  dict(kind="bottleneck", n=32, c=1024, h=14, w=14, depth=6, width=256, conv="bf16", affine="random"),
     "c5_stage4":  dict(kind="bottleneck", n=32, c=2048, h=7, w=7, depth=3, width=512, conv="bf16", affine="random"),
+    # Not one of the paper's workloads: one block whose 3x3 layer (512 -> 512 channels at 28x28) is wide enough
+    # to be bound by the matrix unit rather than by HBM, for the utilisation figures of the kernel profiles.
+    "wide_bneck1": dict(kind="bottleneck", n=32, c=2048, h=28, w=28, depth=1, width=512, conv="bf16", affine="random"),
 }
 
 
