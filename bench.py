@@ -145,6 +145,19 @@ def oracle_sample(run_pass, n, sample_n, what):
                 sample=f"first {ns} of {n} images, same shapes and depths, {passes} pass(es) of {what}")
 
 
+def copy_probe(args, torch, device):
+    """--copy-probe-mib M: one elementwise kernel that reads and writes M MiB, the known-size
+    copy that the HBM counters of a rocprofv3 run are scaled by."""
+    if not args.copy_probe_mib:
+        return
+    src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device=device).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.mul(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_body(args, workload, primary) -> dict:
     """A multi-stage body or whole network (reversible stages joined by subsampling
     blocks, optionally behind the stem): one step = forward, then backward from
@@ -197,6 +210,7 @@ def bench_body(args, workload, primary) -> dict:
         out["kernels_ms_per_step"] = {k: v["ms_per_step"] for k, v in kern.items()}
         return out
 
+    copy_probe(args, torch, r.device)
     if is_net:   # the body's input is the stem's output: compare the reconstruction with a fresh stem forward
         ref0 = torch.empty_like(r.tops[0])
         rv.revnet_stem_fwd(net.stem_desc, X, net.stem_w, net.conv_out, ref0, stream)
@@ -317,13 +331,7 @@ def bench_stack(args, workload, primary) -> dict:
         out["kernels_ms_per_step"] = {k: v["ms_per_step"] for k, v in kern.items()}
         return out
 
-    if args.copy_probe_mib:
-        src = torch.empty(args.copy_probe_mib * (1 << 20) // 4, dtype=torch.float32, device=r.device).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)   # one elementwise kernel: reads and writes copy_probe_mib MiB
-        torch.cuda.synchronize()
-        del src, dst
+    copy_probe(args, torch, r.device)
 
     # ---- the same totals against the rooflines, whole step
     fwd_cost, bwd_cost = rv.revnet_stack_cost(r.desc, depth, n, h, w)
