@@ -351,7 +351,7 @@ __device__ __forceinline__ void bn_bwd_apply_body(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
     int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce &carry, const StatsMerge &merge,
-    const PrepArgs &prep) {
+    const PrepArgs &prep, uint16_t *out16) {
     // The first workgroups do independent work that would otherwise be launches of their own (first,
     // so that their dependent loads run under the streaming of the others): merge.blocks of them merge
     // the partial statistics of a tensor that a later BN layer reads, carry.blocks sum a filter
@@ -403,7 +403,16 @@ __device__ __forceinline__ void bn_bwd_apply_body(
             const float dx = scale * ((dy - c1) - xh * c2);
             r[j] = SKIP ? ks[j] + dx : dx;
         }
-        *reinterpret_cast<float4 *>(po) = make_float4(r[0], r[1], r[2], r[3]);
+        if (out16) {  // (uniform) dense bf16, nearest even: what the convolutions that read it would round it to
+            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+            typedef float float2_t __attribute__((ext_vector_type(2)));
+            const float2_t lo = {r[0], r[1]}, hi = {r[2], r[3]};
+            const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+            *reinterpret_cast<uint2 *>(out16 + plane * HW + i) =
+                make_uint2(*reinterpret_cast<const uint32_t *>(&blo), *reinterpret_cast<const uint32_t *>(&bhi));
+        } else {
+            *reinterpret_cast<float4 *>(po) = make_float4(r[0], r[1], r[2], r[3]);
+        }
     } else {
         const float xv = *px;
         const float dy = fmaf(xv, scale, shift) > 0.f ? *pd : 0.f;
@@ -417,9 +426,10 @@ template <bool VEC, bool SKIP>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int C, int HW,
     int64_t total, const float *__restrict__ stats, const float *__restrict__ coef, const float *skip,
-    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge) {
+    int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge,
+    uint16_t *out16) {
     bn_bwd_apply_body<VEC, SKIP, false>(x, sn, sc, da, C, HW, total, stats, coef, skip, ksn, ksc, out, osn, osc, carry,
-                                        merge, PrepArgs{});
+                                        merge, PrepArgs{}, out16);
 }
 
 // The same with a filter conversion among the carried work (a large argument block: kept out of the
@@ -431,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_prep_k(
     int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, const WgradReduce carry, const StatsMerge merge,
     const PrepArgs prep) {
     bn_bwd_apply_body<VEC, SKIP, true>(x, sn, sc, da, C, HW, total, stats, coef, skip, ksn, ksc, out, osn, osc, carry,
-                                       merge, prep);
+                                       merge, prep, nullptr);
 }
 
 __global__ void clear_counters_k(int *p, int n) {
@@ -499,7 +509,7 @@ void bn_stats(Ctx &cx, View x, int c, Geo g, float eps, const float *gamma, cons
 
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
                  int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out,
-                 const WgradReduce *carry) {
+                 const WgradReduce *carry, uint16_t *out16) {
     const int S = reduce_splits(c, g);
     const int ipw = (g.n + S - 1) / S;
     const double t = 4.0 * (double)g.pixels() * c;
@@ -513,8 +523,12 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
         else
             cx.run(bn_bwd_reduce_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, div_magic(ipw, g.hw()), stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
     }
-    if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : 3.0) * t)) {
-        const bool vec = vec_in && vec_ok(out, g.hw()) && (!skip || vec_ok(*skip, g.hw()));
+    if (out16 && (skip || !vec_in || cx.carry_now)) {  // a caller's mistake: nothing sensible to launch
+        cx.fail(hipErrorInvalidValue);
+        return;
+    }
+    if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : out16 ? 2.5 : 3.0) * t)) {
+        const bool vec = vec_in && (out16 || vec_ok(out, g.hw())) && (!skip || vec_ok(*skip, g.hw()));
         const int64_t total = (int64_t)g.n * c * (g.hw() / (vec ? 4 : 1));
         const unsigned blocks = (unsigned)((total + kThreads - 1) / kThreads);
         const float *kp = skip ? skip->p : nullptr;
@@ -539,7 +553,7 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
                    total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep);                         \
         else                                                                                                          \
             cx.run(bn_bwd_apply_k<V, K>, dim3(blocks + extra), dim3(kThreads), 0, x.p, x.sn, x.sc, da, c, g.hw(),      \
-                   total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge);                               \
+                   total, stats, coef, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, out16);                        \
     } while (0)
         if (vec && skip) RVN_LAUNCH(true, true);
         else if (vec) RVN_LAUNCH(true, false);

@@ -248,7 +248,7 @@ void down_backward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const Do
             const View xs = dense_view(b.xs, d.c_in, pl.low);
             WgradReduce sred;
             if (d.conv_dtype == RVN_BF16 &&
-                conv_dgrad_wgrad_bf16(cx, xs, scale_shift, dy, b.wq_b[kShortcut], d.c_in, d.c_out, 1, pl.low, b.wgrad_scratch,
+                conv_dgrad_wgrad_bf16(cx, xs, scale_shift, dy, nullptr, b.wq_b[kShortcut], d.c_in, d.c_out, 1, pl.low, b.wgrad_scratch,
                                       gr.d_shortcut_w, accumulate, b.t, b.conv_scratch, &sred)) {
                 wgrad_reduce(cx, sred);
             } else {
@@ -260,7 +260,7 @@ void down_backward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const Do
         }
         WgradReduce red;
         if (d.conv_dtype != RVN_BF16 ||
-            !conv_dgrad_wgrad_bf16(cx, xl, scale_shift, dcur, b.wq_b[l], ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
+            !conv_dgrad_wgrad_bf16(cx, xl, scale_shift, dcur, nullptr, b.wq_b[l], ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                                    gr.R.d_conv_w[l], accumulate, da, b.conv_scratch, &red)) {
             conv_wgrad(cx, xl, scale_shift, d.conv_dtype, dcur, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch, gr.R.d_conv_w[l],
                        accumulate, &red);

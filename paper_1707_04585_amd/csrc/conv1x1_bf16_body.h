@@ -56,6 +56,7 @@ typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float f4a_t __attribute__((ext_vector_type(4)));              // 16-byte aligned
 typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));  // only element aligned
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2a_t __attribute__((ext_vector_type(2)));  // four bf16, 8-byte aligned
 
 constexpr int kThreads = 256;
 
@@ -73,7 +74,9 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 // (1 or 2).  GEN: planes need not be 16-byte
 // aligned and H*W need not be a multiple of 4 (the last group of an image then
 // starts at H*W - 4 and leaves the pixels it shares with its neighbour to it).
-template <int MTW, int DEPTH, bool GEN, bool EMIT = false>
+// IN16 (aligned variant only): `in` holds bf16 already (dense planes, same element strides; no BN
+// prologue): the values a conversion on load would produce, so results are the same bits at half the bytes.
+template <int MTW, int DEPTH, bool GEN, bool EMIT = false, bool IN16 = false>
 __device__ __forceinline__ void conv1x1_bf16_body(const C1Args &p, int bx, int gx, float *red) {
     using F4 = typename std::conditional<GEN, f4u_t, f4a_t>::type;
     const int lane = threadIdx.x & 63;
@@ -105,9 +108,11 @@ __device__ __forceinline__ void conv1x1_bf16_body(const C1Args &p, int bx, int g
     // Addresses are a wavefront-uniform 64-bit part (channel, step) plus a 32-bit
     // per-lane byte offset (image, pixel, channel octet half): the host keeps
     // every tensor slice handed to one launch below 4 GB.
-    const uint32_t in_off = (uint32_t)(((int64_t)n * p.isn + pix + (int64_t)(kg * 8) * p.isc) * 4);
+    static_assert(!(IN16 && GEN), "bf16 input: aligned planes only");
+    constexpr int kInBytes = IN16 ? 2 : 4;
+    const uint32_t in_off = (uint32_t)(((int64_t)n * p.isn + pix + (int64_t)(kg * 8) * p.isc) * kInBytes);
     const char *const in_base = reinterpret_cast<const char *>(p.in);
-    const int64_t isc_b = p.isc * 4;
+    const int64_t isc_b = p.isc * kInBytes;
     const char *const w_base = reinterpret_cast<const char *>(p.wq) + (int64_t)mt0 * p.ksteps * 1024;
     const uint32_t w_off = (uint32_t)lane * 16;
     const int64_t tile_w = (int64_t)p.ksteps * 1024;
@@ -159,14 +164,15 @@ __device__ __forceinline__ void conv1x1_bf16_body(const C1Args &p, int bx, int g
                 for (int i = 0; i < 16; ++i) acc[m][j][i] = 0.f;
     }
 
+    using Quad = typename std::conditional<IN16, u2a_t, F4>::type;  // four pixels of one channel as loaded
     struct Buf {
-        F4 v[8];
+        Quad v[8];
         uint4_t a[MTW];
     };
     auto load = [&](Buf &b, int ks) {
 #pragma unroll
         for (int k = 0; k < 8; ++k)
-            b.v[k] = *reinterpret_cast<const F4 *>(in_base + (int64_t)(ks * 16 + k) * isc_b + in_off);
+            b.v[k] = *reinterpret_cast<const Quad *>(in_base + (int64_t)(ks * 16 + k) * isc_b + in_off);
 #pragma unroll
         for (int m = 0; m < MTW; ++m) {
             const bool has = mt0 + m < p.mtiles;
@@ -174,6 +180,24 @@ __device__ __forceinline__ void conv1x1_bf16_body(const C1Args &p, int bx, int g
         }
     };
     auto compute = [&](Buf &b, int ks) {
+        if constexpr (IN16) {
+            // dword w of channel k holds pixels 2w, 2w + 1; the operand of pixel j wants the 8 channels in
+            // pairs: one byte permute per dword (low halves for even pixels, high halves for odd ones)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                uint4_t bq;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) bq[d] = __builtin_amdgcn_perm(b.v[2 * d + 1][j >> 1], b.v[2 * d][j >> 1], sel);
+                const bf16x8_t bo = *reinterpret_cast<const bf16x8_t *>(&bq);
+#pragma unroll
+                for (int m = 0; m < MTW; ++m)
+                    acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t *>(&b.a[m]), bo,
+                                                                        acc[m][j], 0, 0, 0);
+            }
+            (void)ks;
+            return;
+        } else {
         float v[8][4];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -199,6 +223,7 @@ __device__ __forceinline__ void conv1x1_bf16_body(const C1Args &p, int bx, int g
             for (int m = 0; m < MTW; ++m)
                 acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8_t *>(&b.a[m]), bo,
                                                                     acc[m][j], 0, 0, 0);
+        }
         }
     };
 

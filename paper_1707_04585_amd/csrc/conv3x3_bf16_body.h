@@ -3,6 +3,8 @@
 // hold it next to another body.  Device code only.
 #pragma once
 
+#include <type_traits>
+
 #include "kernels.h"
 #include "stats_fold.h"
 
@@ -62,6 +64,7 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2u_t __attribute__((ext_vector_type(2), aligned(4)));  // four bf16, only element aligned
 
 constexpr int kThreads = 256;
 constexpr int kPadK = 8;     // bf16 elements of padding per LDS record
@@ -86,7 +89,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_over(const void *base, 
 // thread and chunk.  With NI == 1 the activation loads run two chunks ahead of the
 // matrix instructions (two register sets): a chunk's matrix work is well below one
 // memory round trip, so with one chunk of lookahead every chunk paid for one.
-template <int WM, int MTW, int NTW, int KC, bool EMIT = false, int NI = kInItems>
+// IN16: `in` holds bf16 already (dense planes, same element strides; no BN prologue): the values a
+// conversion on load would produce, so results are the same bits at half the bytes.
+template <int WM, int MTW, int NTW, int KC, bool EMIT = false, int NI = kInItems, bool IN16 = false>
 __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int by, int bz, int gz, uint16_t *smem16) {
     constexpr int WN = 4 / WM;
     constexpr int REC = KC + kPadK, OCTS = KC / 8;
@@ -105,6 +110,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
     const int N = p.N, H = p.H, W = p.W, CI = p.CI, CO = p.CO;
     const int l32 = lane & 31, kg = lane >> 5;
     const bool bn = p.scale_shift != nullptr;
+    constexpr int kInBytes = IN16 ? 2 : 4;
 
     // ---- zero the activation tile once (halo, rows outside the image, unused
     //      slots stay zero) and fetch scale/shift
@@ -131,7 +137,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
         // with its neighbour are written twice, with the same values
         const int ld = min(start, range - 4);
         const int lin = start_row * W + ld, row = lin / W, col = lin - row * W;
-        it_off[i] = live ? (uint32_t)(((int64_t)n * p.isn + start_row * W + ld) * 4) : 0u;
+        it_off[i] = live ? (uint32_t)(((int64_t)n * p.isn + start_row * W + ld) * kInBytes) : 0u;
         it_rec[i] = (img * p.lrows + (row - (row0 - 1))) * p.lcols + 1 + col;
         const int nvalid = live ? 4 : 0;
         it_info[i] = col | (nvalid << 16) | (oc << 24);
@@ -159,13 +165,14 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
             for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.f;
 
     constexpr int SETS = NI == 1 ? 2 : 1;  // register sets of activation loads
-    f4u_t gin[SETS][NI][8];
+    using Quad = typename std::conditional<IN16, u2u_t, f4u_t>::type;  // four pixels of one channel as loaded
+    Quad gin[SETS][NI][8];
     uint4_t gw[W_PER];
     const char *const in_base = reinterpret_cast<const char *>(p.in);
-    const int64_t isc_b = p.isc * 4;
+    const int64_t isc_b = p.isc * kInBytes;
 
     // global -> registers: the activations of chunk c0 into register set `set`, the filter of chunk c0
-    auto g2r_act = [&](f4u_t (&g)[NI][8], int c0) {
+    auto g2r_act = [&](Quad (&g)[NI][8], int c0) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int oc = it_info[i] >> 24;
@@ -173,7 +180,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
             const uint32_t off = it_off[i] + (c0 + oc * 8 < CI ? (uint32_t)(oc * 8 * isc_b) : 0u);
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                g[i][k] = *reinterpret_cast<const f4u_t *>(in_base + (int64_t)(c0 + k) * isc_b + off);
+                g[i][k] = *reinterpret_cast<const Quad *>(in_base + (int64_t)(c0 + k) * isc_b + off);
         }
     };
     auto g2r_w = [&](int c0) {
@@ -187,13 +194,30 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
         }
     };
     // registers -> LDS: BN + ReLU + rounding of the activations of chunk c0; the filter as loaded
-    auto r2l_act = [&](const f4u_t (&g)[NI][8], int c0) {
+    auto r2l_act = [&](const Quad (&g)[NI][8], int c0) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int info = it_info[i];
             const int col = info & 0xffff, nvalid = (info >> 16) & 15, oc = info >> 24;
             if (nvalid == 0) continue;
             const bool chan_ok = c0 + oc * 8 < CI;
+            if constexpr (IN16) {
+                // dword w of channel k holds pixels 2w, 2w + 1; a record wants, per pixel, the channels in
+                // pairs: one byte permute per dword (low halves for even pixels, high halves for odd ones)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int rec = it_rec[i] + j + (col + j >= W ? 2 : 0);
+                    const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+                    uint4_t q;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t pr = __builtin_amdgcn_perm(g[i][2 * d + 1][j >> 1], g[i][2 * d][j >> 1], sel);
+                        q[d] = chan_ok ? pr : 0u;
+                    }
+                    *reinterpret_cast<uint4_t *>(in_lds + rec * REC + oc * 8) = q;
+                }
+                continue;
+            } else {
             float v[8][4];
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
@@ -219,6 +243,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx, int b
                 const uint4_t q = {pack2(v[0][j], v[1][j]), pack2(v[2][j], v[3][j]), pack2(v[4][j], v[5][j]),
                                    pack2(v[6][j], v[7][j])};
                 *reinterpret_cast<uint4_t *>(in_lds + rec * REC + oc * 8) = q;
+            }
             }
         }
     };

@@ -3,6 +3,8 @@
 // hold it next to another body.  Device code only.
 #pragma once
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace rvn {
@@ -50,6 +52,7 @@ typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 typedef float f4u_t __attribute__((ext_vector_type(4), aligned(4)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u2w_t __attribute__((ext_vector_type(2)));  // four bf16, 8-byte aligned
 
 constexpr int kThreads = 256;
 
@@ -90,12 +93,15 @@ __device__ __forceinline__ float4 quad_fix(f4u_t x, int sh, bool zero) {
     return q;
 }
 
-template <int KS, int MT, int CT, bool VEC>
+// DH16 (VEC only): `dh` holds bf16 already (dense planes, same element strides): the values the
+// conversion while staging would produce, so results are the same bits at half the bytes.
+template <int KS, int MT, int CT, bool VEC, bool DH16 = false>
 __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, int by, int bz, int gz, uint16_t *smem16) {
     constexpr int KS2 = KS * KS, PAD = KS / 2, LP = KS == 3 ? 8 : 0;  // 3x3: image column 0 sits 8 elements into a tile row
     constexpr int WT = MT * CT, KW = 4 / WT;            // tile owners, pixel shares
     constexpr int kBatch = KS == 3 ? 4 : 8;             // staging items a thread has in flight
     static_assert(WT == 1 || WT == 2 || WT == 4, "one tile per wavefront");
+    static_assert(VEC || !DH16, "bf16 upstream gradient: aligned planes only");
     uint16_t *a_lds = smem16;
     uint16_t *d_lds = smem16 + CT * 32 * p.a_plane;
     __shared__ float ss_lds[2 * CT * 32];  // scale, shift of this workgroup's input channels
@@ -197,6 +203,33 @@ __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, in
             }
         }
     };
+    // The same for a tensor that is bf16 already: straight into LDS, zeros for an outside item.
+    auto store16 = [&](u2w_t v, int cl, const Item &it, bool inside, uint16_t *lds, int plane) {
+        if (!inside) v = u2w_t{0u, 0u};
+        if ((it.meta >> 25) & 1) *reinterpret_cast<uint2 *>(lds + cl * plane + it.lds) = make_uint2(v[0], v[1]);
+    };
+    auto stage_planes16 = [&](const uint16_t *base, int64_t sc, int64_t sn, const Item (&items)[kPass], int nch, int quads,
+                              int n0, int row0, uint16_t *lds, int plane) {
+        const uint16_t *const ubase = base + (int64_t)n0 * sn + (int64_t)row0 * W;
+#pragma unroll
+        for (int ps = 0; ps < kPass; ++ps) {
+            if (ps * 64 >= quads) break;
+            const bool inside = item_inside(items[ps], n0, row0, 0);
+            const int64_t lo = inside ? (int64_t)items[ps].off : 0;
+            for (int cb = wave; cb < nch; cb += 4 * kBatch) {
+                u2w_t x[kBatch];
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b)
+                    x[b] = *reinterpret_cast<const u2w_t *>(ubase + (int64_t)min(cb + 4 * b, nch - 1) * sc + lo);
+#pragma unroll
+                for (int b = 0; b < kBatch; ++b) {
+                    if (cb + 4 * b >= nch) break;
+                    store16(x[b], cb + 4 * b, items[ps], inside, lds, plane);
+                }
+            }
+        }
+    };
+    const uint16_t *const dp16 = reinterpret_cast<const uint16_t *>(p.dh);
     auto origin = [&](int u, int &n0, int &row0) {
         const int g = u / bands;
         n0 = g * IMGS;
@@ -206,25 +239,34 @@ __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, in
         int n0, row0;
         origin(u, n0, row0);
         stage_planes(xp + (int64_t)c0 * p.xsc, p.xsc, xsn, ia, nch_a, IMGS * p.lrows * p.Wq, PAD, n0, row0, a_lds, p.a_plane, true);
-        stage_planes(dp + (int64_t)ko0 * p.dsc, p.dsc, dsn, id, nch_d, IMGS * TH * p.Wq, 0, n0, row0, d_lds, p.d_plane, false);
+        if constexpr (DH16)
+            stage_planes16(dp16 + (int64_t)ko0 * p.dsc, p.dsc, dsn, id, nch_d, IMGS * TH * p.Wq, n0, row0, d_lds, p.d_plane);
+        else
+            stage_planes(dp + (int64_t)ko0 * p.dsc, p.dsc, dsn, id, nch_d, IMGS * TH * p.Wq, 0, n0, row0, d_lds, p.d_plane, false);
     };
     // 1x1 filters (16 accumulator registers): when a plane is one item per lane, every load of a unit is
     // requested at once, one unit ahead, and arrives under the matrix instructions of the unit before.
     constexpr bool kCanPrefetch = KS == 1;
     constexpr int NBA = kCanPrefetch ? CT * 8 : 1, NBD = kCanPrefetch ? MT * 8 : 1;  // channels per wavefront and tile
     const bool prefetch = kCanPrefetch && IMGS * p.lrows * p.Wq <= 64 && IMGS * TH * p.Wq <= 64;
-    f4u_t pa[NBA], pd[NBD];
+    using DQuad = typename std::conditional<DH16, u2w_t, f4u_t>::type;
+    f4u_t pa[NBA];
+    DQuad pd[NBD];
     auto request_unit = [&](int u) {
         int n0, row0;
         origin(u, n0, row0);
         const float *const ua = xp + (int64_t)c0 * p.xsc + (int64_t)n0 * xsn + (int64_t)row0 * W +
                                 (item_inside(ia[0], n0, row0, PAD) ? (int64_t)ia[0].off : 0);
-        const float *const ud = dp + (int64_t)ko0 * p.dsc + (int64_t)n0 * dsn + (int64_t)row0 * W +
-                                (item_inside(id[0], n0, row0, 0) ? (int64_t)id[0].off : 0);
+        const int64_t ud_off = (int64_t)ko0 * p.dsc + (int64_t)n0 * dsn + (int64_t)row0 * W +
+                               (item_inside(id[0], n0, row0, 0) ? (int64_t)id[0].off : 0);
 #pragma unroll
         for (int b = 0; b < NBA; ++b) pa[b] = *reinterpret_cast<const f4u_t *>(ua + (int64_t)min(wave + 4 * b, nch_a - 1) * p.xsc);
 #pragma unroll
-        for (int b = 0; b < NBD; ++b) pd[b] = *reinterpret_cast<const f4u_t *>(ud + (int64_t)min(wave + 4 * b, nch_d - 1) * p.dsc);
+        for (int b = 0; b < NBD; ++b) {
+            const int64_t o = ud_off + (int64_t)min(wave + 4 * b, nch_d - 1) * p.dsc;
+            if constexpr (DH16) pd[b] = *reinterpret_cast<const u2w_t *>(dp16 + o);
+            else pd[b] = *reinterpret_cast<const f4u_t *>(dp + o);
+        }
     };
     auto commit_unit = [&](int u) {
         int n0, row0;
@@ -235,7 +277,10 @@ __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, in
             if (wave + 4 * b < nch_a) convert_store(pa[b], wave + 4 * b, ia[0], ina, true, a_lds, p.a_plane);
 #pragma unroll
         for (int b = 0; b < NBD; ++b)
-            if (wave + 4 * b < nch_d) convert_store(pd[b], wave + 4 * b, id[0], ind, false, d_lds, p.d_plane);
+            if (wave + 4 * b < nch_d) {
+                if constexpr (DH16) store16(pd[b], wave + 4 * b, id[0], ind, d_lds, p.d_plane);
+                else convert_store(pd[b], wave + 4 * b, id[0], ind, false, d_lds, p.d_plane);
+            }
     };
 
     // ---- this wavefront's tile and share of the steps

@@ -215,9 +215,11 @@ void clear_counters(Ctx &cx, int *counters, int n);
 // accumulate) and out = [skip +] dx.  `skip` may be null.  `out` may alias
 // `da` (dense in-place) or `skip`.  `carry`: a pending filter-gradient sum that
 // rides in the apply launch (extra workgroups).
+// out16 != null (needs h*w % 4 == 0 and 16-byte aligned x, da; no skip): the result goes there as
+// dense bf16 [n][c][h*w], rounded to nearest even, and `out` is not written; out16 must not overlap da.
 void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *stats, float *scratch,
                  int *counters, float *dgamma, float *dbeta, bool accumulate, const View *skip, View out,
-                 const WgradReduce *carry = nullptr);
+                 const WgradReduce *carry = nullptr, uint16_t *out16 = nullptr);
 
 // ---- convolutions (Section 2.2: c_k(x) = Conv_kxk(a(x)), k in {1,3}) -------
 // out = ep(r, conv(a(x), w)) with a(x) = max(x*scale + shift, 0) formed on the
@@ -285,9 +287,14 @@ bool conv_dgrad_wgrad_f32(Ctx &cx, View x, const float *scale_shift, View dh, co
 // filter prepared for the data gradient.  The ordered sum of the filter gradient is left in *defer; a
 // channel-split data gradient is followed by its reduce launch.  Returns false (nothing launched,
 // nothing accounted) for the shapes it does not take.
-bool conv_dgrad_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, const uint16_t *wq_b, int cin, int cout,
-                           int ks, Geo g, float *wgrad_scratch, float *dw, bool accumulate, float *da,
-                           float *conv_scratch, WgradReduce *defer);
+// dh16 != null: the upstream gradient is there as dense bf16 [n][cout][h*w] (what rounding dh on load
+// would give, so the results are the same bits) and `dh` is ignored; only for layers for which
+// conv_dgrad_wgrad_takes_bf16_dh says yes.
+bool conv_dgrad_wgrad_bf16(Ctx &cx, View x, const float *scale_shift, View dh, const uint16_t *dh16, const uint16_t *wq_b,
+                           int cin, int cout, int ks, Geo g, float *wgrad_scratch, float *dw, bool accumulate,
+                           float *da, float *conv_scratch, WgradReduce *defer);
+bool conv_dgrad_wgrad_takes_bf16_dh(View x, const uint16_t *dh16, const uint16_t *wq_b, int cin, int cout, int ks, Geo g,
+                                    float *wgrad_scratch, float *da, float *conv_scratch);
 
 // The filter gradient with bf16 operands on v_mfma_f32_32x32x16_bf16 (a(x) and dh rounded
 // to bf16 while staged, fp32 accumulation); `bytes` and `flops` are what the

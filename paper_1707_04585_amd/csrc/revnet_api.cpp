@@ -369,6 +369,7 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
                    const rvn_func_params &p, View upstream, const rvn_func_grads &gr, bool accumulate,
                    View skip, View out, const float *stats0) {
     View dh = upstream;
+    const uint16_t *dh16 = nullptr;  // the upstream gradient of the layer at hand as bf16, when the layer above left it so
     int cur = 0;
     for (int l = pl.L - 1; l >= 0; --l) {
         const Layer &ly = pl.layers[l];
@@ -382,19 +383,38 @@ void func_backward(Ctx &cx, const rvn_block_desc &d, const Plan &pl, const Bufs 
             d.conv_dtype == RVN_F32
                 ? conv_dgrad_wgrad_f32(cx, xl, st + 2 * ly.cin, dh, p.conv_w[l], ly.cin, ly.cout, ly.ks, g,
                                        b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, &red)
-                : conv_dgrad_wgrad_bf16(cx, xl, st + 2 * ly.cin, dh, b.wq_b[l], ly.cin, ly.cout, ly.ks, g,
+                : conv_dgrad_wgrad_bf16(cx, xl, st + 2 * ly.cin, dh, dh16, b.wq_b[l], ly.cin, ly.cout, ly.ks, g,
                                         b.wgrad_scratch, gr.d_conv_w[l], accumulate, da, b.conv_scratch, &red);
         if (!paired) {
+            if (dh16) {  // cannot happen: the layer above asked before it wrote bf16
+                cx.fail(hipErrorInvalidValue);
+                return;
+            }
             conv_wgrad(cx, xl, st + 2 * ly.cin, d.conv_dtype, dh, ly.cin, ly.cout, ly.ks, g, b.wgrad_scratch,
                        gr.d_conv_w[l], accumulate, &red);
             conv_dgrad(cx, dh, d.conv_dtype, p.conv_w[l], b.wq_b[l], ly.cin, ly.cout, ly.ks, g, da, b.conv_scratch);
         }
         if (l > 0) {
             View dx = dense_view(da, ly.cin, g);
+            // The gradient this BN backward produces is read only by the two gradient kernels of the layer
+            // below, which round it to bf16 on load: where their shared launch takes it that way, it is
+            // written rounded (same bits downstream, half the bytes three times over), into the other
+            // ping-pong buffer, whose content (this layer's upstream gradient) is dead by now.
+            const Layer &below = pl.layers[l - 1];
+            const View x_below = l - 1 > 0 ? dense_view(b.h[l - 2], below.cin, g) : x;
+            uint16_t *const as16 = reinterpret_cast<uint16_t *>(b.g[cur ^ 1]);
+            const bool to16 = d.conv_dtype == RVN_BF16 && g.hw() % 4 == 0 &&
+                              conv_dgrad_wgrad_takes_bf16_dh(x_below, as16, b.wq_b[l - 1], below.cin, below.cout, below.ks, g,
+                                                             b.wgrad_scratch, da, b.conv_scratch);
             bn_relu_bwd(cx, xl, da, ly.cin, g, st, b.bn_scratch, b.counters, gr.d_bn_gamma[l], gr.d_bn_beta[l],
-                        accumulate, nullptr, dx, &red);
-            dh = dx;
-            cur ^= 1;
+                        accumulate, nullptr, dx, &red, to16 ? as16 : nullptr);
+            if (to16) {
+                dh16 = as16;  // (da of this layer is dead after the launch above: the next layer reuses b.g[cur])
+            } else {
+                dh = dx;
+                dh16 = nullptr;
+                cur ^= 1;
+            }
         } else {
             // the last launch of this function's backward pass: every use of its converted filters is
             // behind it, so what arm_merge prepared for the next function can ride here
