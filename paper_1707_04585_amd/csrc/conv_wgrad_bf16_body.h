@@ -99,7 +99,9 @@ template <int KS, int MT, int CT, bool VEC, bool DH16 = false>
 __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, int by, int bz, int gz, uint16_t *smem16) {
     constexpr int KS2 = KS * KS, PAD = KS / 2, LP = KS == 3 ? 8 : 0;  // 3x3: image column 0 sits 8 elements into a tile row
     constexpr int WT = MT * CT, KW = 4 / WT;            // tile owners, pixel shares
-    constexpr int kBatch = KS == 3 ? 4 : 8;             // staging items a thread has in flight
+    // staging items a thread has in flight: 16-byte fp32 quads, 8-byte bf16 quads (at the 64 -> 64 3x3 layer
+    // of the 56x56 bottleneck stack 4 / 4 gave 67.2 us for the shared gradient launch, 8 / 16 65.6, 16 / 16 73.1)
+    constexpr int kBatch = 8, kBatch16 = 16;
     static_assert(WT == 1 || WT == 2 || WT == 4, "one tile per wavefront");
     static_assert(VEC || !DH16, "bf16 upstream gradient: aligned planes only");
     uint16_t *a_lds = smem16;
@@ -216,13 +218,13 @@ __device__ __forceinline__ void conv_wgrad_bf16_body(const WgArgs &p, int bx, in
             if (ps * 64 >= quads) break;
             const bool inside = item_inside(items[ps], n0, row0, 0);
             const int64_t lo = inside ? (int64_t)items[ps].off : 0;
-            for (int cb = wave; cb < nch; cb += 4 * kBatch) {
-                u2w_t x[kBatch];
+            for (int cb = wave; cb < nch; cb += 4 * kBatch16) {
+                u2w_t x[kBatch16];
 #pragma unroll
-                for (int b = 0; b < kBatch; ++b)
+                for (int b = 0; b < kBatch16; ++b)
                     x[b] = *reinterpret_cast<const u2w_t *>(ubase + (int64_t)min(cb + 4 * b, nch - 1) * sc + lo);
 #pragma unroll
-                for (int b = 0; b < kBatch; ++b) {
+                for (int b = 0; b < kBatch16; ++b) {
                     if (cb + 4 * b >= nch) break;
                     store16(x[b], cb + 4 * b, items[ps], inside, lds, plane);
                 }
