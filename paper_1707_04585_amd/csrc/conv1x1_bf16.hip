@@ -128,6 +128,9 @@ bool conv1x1_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     }
     for (int n0 = 0; n0 < g.n; n0 += slice_n) {
         const int ns = std::min(slice_n, g.n - n0);
+        // (the caller has recorded the first launch; further slices are launches of the same family, their
+        // bytes and flops already counted with the first)
+        if (n0 > 0 && !cx.launch(cx.last_id, 0.0) && !cx.dry) return true;
         C1Launch L = plan_slice(in, scale_shift, wq, ci, co, g, ep, r, out, n0, ns);
         C1Args &a = L.a;
         // Statistics of the output for the BN layer that reads it next: whole 128-pixel tiles, aligned

@@ -205,7 +205,9 @@ bool conv3x3_bf16_plan(View in, const float *scale_shift, const uint16_t *wq, in
     L.MTW = pl.MTW; L.KC = pl.KC; L.S = pl.S;
     // one staging item per thread at most: the variant whose activation loads run two chunks ahead
     L.NI = pl.in_items <= kThreads ? 1 : kInItems;
-    L.grid = dim3((unsigned)(pl.bands * ((g.n + pl.IMGS - 1) / pl.IMGS)), (unsigned)((co + ch - 1) / ch), (unsigned)pl.S);
+    L.a.wg_x = pl.bands * ((g.n + pl.IMGS - 1) / pl.IMGS);
+    L.a.wg_x8 = (L.a.wg_x + 7) / 8 * 8;
+    L.grid = dim3((unsigned)L.a.wg_x8, (unsigned)((co + ch - 1) / ch), (unsigned)pl.S);
     L.lds_bytes = pl.lds_bytes;
     L.scratch = scratch;
     return true;
@@ -241,7 +243,7 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     C3Args &a = L.a;
     // Statistics of the output for the BN layer that reads it next: no split (for split launches see
     // conv3x3_bf16_finish), and every pixel slot of every workgroup a valid pixel (whole blocks of rows or images).
-    const int slots = 4 * 2 * 32, tiles = (int)L.grid.x * 4;
+    const int slots = 4 * 2 * 32, tiles = a.wg_x * 4;
     const bool whole = a.n_pix == slots && g.n % a.IMGS == 0 && g.h % a.TR == 0;
     if (cx.want_emit && cx.emit_buf && L.S == 1 && whole && (size_t)co * tiles * 2 <= cx.emit_floats) {
         a.emit = cx.emit_buf;

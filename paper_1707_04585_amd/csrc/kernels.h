@@ -136,11 +136,14 @@ struct Ctx {
     rvn_cost cost = {};
     hipError_t err = hipSuccess;
     hipEvent_t ev_start = nullptr, ev_stop = nullptr;  // set while a profiled launch is pending
+    int last_id = 0;  // family of the latest launch(): a wrapper that needs further launches for the same
+                      // operation (image slices of a tensor beyond 4 GB) records them under it, with no bytes
 
     // Record one kernel launch of family `id` that must move `bytes`
     // algorithmic bytes and perform `flops`; returns true if the kernel should
     // really be launched (then call run() for it).
     bool launch(int id, double bytes, double flops = 0.0) {
+        last_id = id;
         cost.kernel_launches += 1;
         cost.algorithmic_bytes += bytes;
         const bool go = !dry && err == hipSuccess;
