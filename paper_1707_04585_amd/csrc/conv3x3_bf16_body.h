@@ -172,7 +172,9 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][t][i] = 0.f;
 
-    constexpr int SETS = NI == 1 ? 2 : 1;  // register sets of activation loads
+    // register sets of activation loads (with bf16 input four half-size sets, four chunks ahead, measured the
+    // same as two: in the shared gradient launch the filter gradient is the longer part)
+    constexpr int SETS = NI == 1 ? 2 : 1;
     using Quad = typename std::conditional<IN16, u2u_t, f4u_t>::type;  // four pixels of one channel as loaded
     Quad gin[SETS][NI][8];
     uint4_t gw[W_PER];
@@ -291,45 +293,29 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
     const int chunk0 = bz * p.cps, chunk1 = min(p.chunks, chunk0 + p.cps);
     g2r_w(chunk0 * KC);
     g2r_act(gin[0], chunk0 * KC);
-    if (SETS == 2 && chunk0 + 1 < chunk1) g2r_act(gin[SETS - 1], (chunk0 + 1) * KC);
+#pragma unroll
+    for (int st = 1; st < SETS; ++st)
+        if (chunk0 + st < chunk1) g2r_act(gin[st], (chunk0 + st) * KC);
     __syncthreads();  // tile zeroed, scale/shift in LDS
     r2l_w();
     r2l_act(gin[0], chunk0 * KC);
     __syncthreads();
-    if constexpr (SETS == 1) {
-        for (int ch = chunk0; ch < chunk1; ++ch) {
-            if (ch + 1 < chunk1) {
-                g2r_w((ch + 1) * KC);
-                g2r_act(gin[0], (ch + 1) * KC);
-            }
+    // LDS holds chunk ch, which came from register set st; that set is free and takes the loads of chunk
+    // ch + SETS, the chunks in between are in flight in the other sets.  The filter (small, cached) keeps
+    // one chunk of lookahead and is requested before the activations, so that waiting for it does not
+    // wait for them.
+    for (int base = chunk0; base < chunk1; base += SETS) {
+#pragma unroll
+        for (int st = 0; st < SETS; ++st) {
+            const int ch = base + st;
+            if (ch >= chunk1) break;
+            if (ch + 1 < chunk1) g2r_w((ch + 1) * KC);
+            if (ch + SETS < chunk1) g2r_act(gin[st], (ch + SETS) * KC);
             multiply();
             if (ch + 1 < chunk1) {
                 __syncthreads();  // every wavefront has read chunk ch
                 r2l_w();
-                r2l_act(gin[0], (ch + 1) * KC);
-                __syncthreads();
-            }
-        }
-    } else {
-        // LDS holds chunk ch; set 1 holds chunk ch + 1 (in flight), set 0 is free -- and the other way
-        // round one chunk later.  The filter (small, cached) keeps one chunk of lookahead and is requested
-        // before the activations two chunks ahead, so that waiting for it does not wait for them.
-        for (int ch = chunk0; ch < chunk1; ch += 2) {
-            if (ch + 1 < chunk1) g2r_w((ch + 1) * KC);
-            if (ch + 2 < chunk1) g2r_act(gin[0], (ch + 2) * KC);
-            multiply();
-            if (ch + 1 >= chunk1) break;
-            __syncthreads();  // every wavefront has read chunk ch
-            r2l_w();
-            r2l_act(gin[SETS - 1], (ch + 1) * KC);
-            __syncthreads();
-            if (ch + 2 < chunk1) g2r_w((ch + 2) * KC);
-            if (ch + 3 < chunk1) g2r_act(gin[SETS - 1], (ch + 3) * KC);
-            multiply();
-            if (ch + 2 < chunk1) {
-                __syncthreads();
-                r2l_w();
-                r2l_act(gin[0], (ch + 2) * KC);
+                r2l_act(gin[(st + 1) % SETS], (ch + 1) * KC);
                 __syncthreads();
             }
         }
