@@ -77,6 +77,9 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
         const int a_items = w.CT * 32 * imgs * lrows * w.Wq;
         const int d_items = w.MT * 32 * imgs * th * w.Wq;
         const size_t bytes = ((size_t)w.CT * 32 * a_plane + (size_t)w.MT * 32 * d_plane) * 2;
+        // (64 KB: two workgroups per compute unit would hold 78 KB each, but the taller units that buys -- 3 rows
+        // for 5 staged instead of 2 for 4 at 56 columns and 64 + 64 channels -- leave 406 slices for 512 slots
+        // and fewer units per slice to pipeline: the shared gradient launch took 77.9 us against 65.7)
         if (bytes > 64 * 1024 || imgs > 255 || lrows > 4000) return false;
         if (imgs * lrows * w.Wq > 128) return false;  // staging: at most two 4-pixel items per lane and channel plane
         w.TH = th; w.IMGS = imgs; w.lrows = lrows;
