@@ -13,7 +13,7 @@ launch stream, in a separate profiled pass of the same steps), the CPU oracle
 timed beside it on a bounded sample (stored-activation backprop, and the
 literal Algorithm 1), peak activation bytes versus depth, reconstruction error
 versus depth, and under "secondary" the same throughput / roofline figures for
-the other workloads the design notes quote.
+the fp32 stack and the two multi-stage bodies.
 """
 from __future__ import annotations
 

@@ -55,7 +55,7 @@ batch norm and its unfused chain-rule backward) are plain C in
 ``layer_ops_impl.h``; the precision is that of the arrays passed in
 (float64 for reference values, float32 to mimic the paper's setting).
 
-Readings of points the paper leaves open (all stated in the design notes):
+Readings of points the paper leaves open:
 BN uses batch statistics with the biased variance and ``eps`` added inside the
 square root; ReLU'(0) = 0; every unit, including the first of F and G, is
 BN -> ReLU -> conv; convolutions are zero padded by (k-1)/2 with no bias.

@@ -1,6 +1,6 @@
 """Shared pieces of the GPU parity tests: error measures that look inside a
 tensor (a whole-tensor norm can hide one wrong pixel per plane), and a log of
-every measured error for the tolerance table of the design notes.
+every measured error (one line per parity case, for tabulating).
 
 Uses numpy only; the reference values always come from the oracle."""
 import json
@@ -101,7 +101,7 @@ def check_with_floors(errs, floors, vs32, bar, pooled=False):
 
 def record(case, **values):
     """Append one line to the file named by RVN_PARITY_LOG (if set): the
-    measured errors of a parity case, for the table in the design notes."""
+    measured errors of a parity case."""
     path = os.environ.get("RVN_PARITY_LOG")
     if not path:
         return
