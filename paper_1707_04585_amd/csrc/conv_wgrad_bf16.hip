@@ -53,7 +53,7 @@ uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uin
 // of 16 bytes apart put the 16-byte reads of 8 neighbouring lanes on distinct banks.
 int bank_pad(int plane) { return plane + ((8 - plane % 16) + 16) % 16; }
 
-WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
+WgPlan plan_wg_tiles(int cin, int cout, int ks, const Geo &g, int ct_max) {
     WgPlan w{};
     w.ok = false;
     if (g.w < 4) return w;  // staging loads 4 pixels of a row at a time
@@ -61,7 +61,7 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     // kernel (16 x 16 tiles, operands rounded to bf16 on the way in) is faster there.
     if (cin <= 16 && cout <= 16) return w;
     w.MT = cout <= 32 ? 1 : 2;
-    w.CT = cin <= 32 ? 1 : 2;
+    w.CT = cin <= 32 || ct_max < 2 ? 1 : 2;
     w.Wq = (g.w + 3) / 4;
     w.cpr = (g.w + 7) / 8;
     w.a_pitch = ks == 3 ? 8 + w.cpr * 8 + 8 : w.cpr * 8;  // 3x3: 8 zero elements before and after every row
@@ -100,14 +100,27 @@ WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
     w.units = ((g.n + w.IMGS - 1) / w.IMGS) * w.bands;
     const int groups = w.tiles_ko * w.tiles_c;
     w.part_stride = groups * w.MT * w.CT * ks * ks * 1024;
-    // Two workgroups per compute unit.  Fewer slices or 32 x 32 tiles would write fewer partial results, but
-    // measured slower on every workload (the launch is bound by staging and the multiply chain, not by those bytes).
+    // Two workgroups per compute unit.  Fewer slices would write fewer partial results, but measured slower
+    // on every workload (the launch is bound by staging and the multiply chain, not by those bytes).
     int s = 512 / groups;
     if (s < 1) s = 1;
     if (s > w.units) s = w.units;
     w.upw = (w.units + s - 1) / s;
     w.S = (w.units + w.upw - 1) / w.upw;
     return w;
+}
+
+// 64 x 64 tiles per workgroup; for a 3x3 layer with more units than slices to give them to, 64 x 32: the
+// same 512 workgroups then write half the partial results (a workgroup's partial filter is its whole
+// tile times nine taps, whatever it summed over) for one more read of the upstream gradient, which the
+// tile groups of a slice share in their die's L2.  Measured at the 56x56 bottleneck stack: step 15.98 ->
+// 15.82 ms, the four-stage body 14.81 -> 14.50; 32 x 32, 32 x 64 and any split of the 1x1 layers were
+// slower, and so was the split on the small layers whose slices are limited by their units.
+WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
+    const WgPlan w = plan_wg_tiles(cin, cout, ks, g, 2);
+    if (!w.ok || ks != 3 || w.CT != 2 || w.units <= 512 / (w.tiles_ko * w.tiles_c)) return w;
+    const WgPlan n = plan_wg_tiles(cin, cout, ks, g, 1);
+    return n.ok ? n : w;
 }
 
 }  // namespace
