@@ -100,8 +100,8 @@ WgPlan plan_wg_tiles(int cin, int cout, int ks, const Geo &g, int ct_max) {
     w.units = ((g.n + w.IMGS - 1) / w.IMGS) * w.bands;
     const int groups = w.tiles_ko * w.tiles_c;
     w.part_stride = groups * w.MT * w.CT * ks * ks * 1024;
-    // Two workgroups per compute unit.  Fewer slices would write fewer partial results, but measured slower
-    // on every workload (the launch is bound by staging and the multiply chain, not by those bytes).
+    // Two workgroups per compute unit (512 in all: 384 measured the same, 768 and 1024 4-10 % slower per
+    // launch; half and a quarter were slower on every workload).
     int s = 512 / groups;
     if (s < 1) s = 1;
     if (s > w.units) s = w.units;
