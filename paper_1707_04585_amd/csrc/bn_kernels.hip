@@ -444,6 +444,131 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_prep_k(
                                        merge, prep, nullptr);
 }
 
+// Both passes in one launch, for layers whose channels are small: one workgroup per channel keeps the
+// channel's x and da in registers (at most kFusedQuads 16-byte quads per thread), sums, and applies --
+// x and da are read once, and there is no ticket and no second launch.  (Aligned planes of whole quads
+// only; the sums are formed per thread, then per wavefront, then over the four wavefronts, in double
+// from the wavefront sums on: a fixed order.)
+constexpr int kFusedQuads = 8;
+
+template <bool SKIP, bool PREP>
+__device__ __forceinline__ void bn_bwd_fused_body(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
+    const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
+    int accumulate, const float *skip, int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, uint16_t *out16,
+    const WgradReduce &carry, const StatsMerge &merge, const PrepArgs &prep) {
+    // carried work first, as in bn_bwd_apply_body
+    if ((int)blockIdx.x < merge.blocks) {
+        bn_stats_merge_body(merge.partials, merge.tiles, merge.count, merge.eps, merge.gamma, merge.beta, merge.stats,
+                            merge.C, (int)blockIdx.x);
+        return;
+    }
+    const int prep_blocks = PREP ? prep.blocks : 0;
+    if (PREP && (int)blockIdx.x < merge.blocks + prep_blocks) {
+        prep_filter_body(prep, (int)blockIdx.x - merge.blocks);
+        return;
+    }
+    const int bx = (int)blockIdx.x - merge.blocks - prep_blocks;
+    if (bx < carry.blocks) {
+        __shared__ float lds[kThreads];
+        wgrad_reduce_body(carry, bx, lds);
+        return;
+    }
+    __shared__ double sums[8];
+    const int ch = bx - carry.blocks;
+    const int per = HW / 4, total = N * per;
+    const float mean = stats[ch], rstd = stats[C + ch];
+    const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
+    float4 xv[kFusedQuads], dv[kFusedQuads];
+    int nn[kFusedQuads], ii[kFusedQuads];  // image and first pixel of the quad
+    bool ok[kFusedQuads];
+#pragma unroll
+    for (int k = 0; k < kFusedQuads; ++k) {
+        const int q = (int)threadIdx.x + k * kThreads;
+        ok[k] = q < total;
+        const int qc = ok[k] ? q : 0;
+        nn[k] = idiv(qc, per, m_per);
+        ii[k] = (qc - nn[k] * per) * 4;
+        xv[k] = *reinterpret_cast<const float4 *>(x + (int64_t)nn[k] * sn + (int64_t)ch * sc + ii[k]);
+        dv[k] = *reinterpret_cast<const float4 *>(da + ((int64_t)nn[k] * C + ch) * HW + ii[k]);
+    }
+    float dy[kFusedQuads][4], xh[kFusedQuads][4];
+    float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+    for (int k = 0; k < kFusedQuads; ++k) {
+        const float xs[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
+        const float ds[4] = {dv[k].x, dv[k].y, dv[k].z, dv[k].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            dy[k][j] = ok[k] && fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
+            xh[k][j] = (xs[j] - mean) * rstd;
+            a0 += dy[k][j];
+            a1 += dy[k][j] * xh[k][j];
+        }
+    }
+    a0 = wave_sum(a0);
+    a1 = wave_sum(a1);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) {
+        sums[wave * 2] = (double)a0;
+        sums[wave * 2 + 1] = (double)a1;
+    }
+    __syncthreads();
+    const double sb = (sums[0] + sums[2]) + (sums[4] + sums[6]), sg = (sums[1] + sums[3]) + (sums[5] + sums[7]);
+    if (threadIdx.x == 0) {
+        if (accumulate) {
+            dbeta[ch] += (float)sb;
+            dgamma[ch] += (float)sg;
+        } else {
+            dbeta[ch] = (float)sb;
+            dgamma[ch] = (float)sg;
+        }
+    }
+    const float c1 = (float)(sb * inv_m), c2 = (float)(sg * inv_m);
+#pragma unroll
+    for (int k = 0; k < kFusedQuads; ++k) {
+        if (!ok[k]) continue;
+        float r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r[j] = scale * ((dy[k][j] - c1) - xh[k][j] * c2);
+        const int n = nn[k], i = ii[k];
+        if (SKIP) {
+            const float4 kv = *reinterpret_cast<const float4 *>(skip + (int64_t)n * ksn + (int64_t)ch * ksc + i);
+            r[0] += kv.x; r[1] += kv.y; r[2] += kv.z; r[3] += kv.w;
+            *reinterpret_cast<float4 *>(out + (int64_t)n * osn + (int64_t)ch * osc + i) = make_float4(r[0], r[1], r[2], r[3]);
+        } else if (out16) {  // (uniform) dense bf16, nearest even
+            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+            typedef float float2_t __attribute__((ext_vector_type(2)));
+            const float2_t lo = {r[0], r[1]}, hi = {r[2], r[3]};
+            const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+            *reinterpret_cast<uint2 *>(out16 + ((int64_t)n * C + ch) * HW + i) =
+                make_uint2(*reinterpret_cast<const uint32_t *>(&blo), *reinterpret_cast<const uint32_t *>(&bhi));
+        } else {
+            *reinterpret_cast<float4 *>(out + (int64_t)n * osn + (int64_t)ch * osc + i) = make_float4(r[0], r[1], r[2], r[3]);
+        }
+    }
+}
+
+template <bool SKIP>
+__global__ __launch_bounds__(kThreads) void bn_bwd_fused_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
+    const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
+    int accumulate, const float *skip, int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, uint16_t *out16,
+    const WgradReduce carry, const StatsMerge merge) {
+    bn_bwd_fused_body<SKIP, false>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn, ksc,
+                                   out, osn, osc, out16, carry, merge, PrepArgs{});
+}
+
+template <bool SKIP>
+__global__ __launch_bounds__(kThreads) void bn_bwd_fused_prep_k(
+    const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
+    const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
+    int accumulate, const float *skip, int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc,
+    const WgradReduce carry, const StatsMerge merge, const PrepArgs prep) {
+    bn_bwd_fused_body<SKIP, true>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn, ksc,
+                                  out, osn, osc, nullptr, carry, merge, prep);
+}
+
 __global__ void clear_counters_k(int *p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
@@ -515,6 +640,46 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
     const double t = 4.0 * (double)g.pixels() * c;
     float *coef = scratch + (size_t)c * S * 3;
     const bool vec_in = vec_ok(x, g.hw()) && (reinterpret_cast<uintptr_t>(da) & 15) == 0;
+    if (out16 && (skip || !vec_in || cx.carry_now)) {  // a caller's mistake: nothing sensible to launch
+        cx.fail(hipErrorInvalidValue);
+        return;
+    }
+    // Small channels: both passes in one launch.
+    const bool vec_all = vec_in && (out16 || vec_ok(out, g.hw())) && (!skip || vec_ok(*skip, g.hw()));
+    if (vec_all && (int64_t)g.n * (g.hw() / 4) <= (int64_t)kFusedQuads * kThreads) {
+        if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : out16 ? 2.5 : 3.0) * t)) {
+            WgradReduce red{};
+            if (carry) red = *carry;
+            if (red.blocks < 0) red.blocks = 0;
+            // a waiting merge and filter conversion ride along when the caller says this is the launch
+            StatsMerge merge{};
+            PrepArgs prep{};
+            if (cx.carry_now) {
+                merge = cx.merge_carry;
+                prep = cx.prep_carry;
+                cx.merge_carry = StatsMerge{};
+                cx.prep_carry = PrepArgs{};
+            }
+            const dim3 grid((unsigned)(c + red.blocks + merge.blocks + prep.blocks));
+            const double inv_m = 1.0 / (double)g.pixels();
+            const uint32_t m_per = div_magic(g.n, g.hw() / 4);
+            const float *kp = skip ? skip->p : nullptr;
+            const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
+#define RVN_LAUNCH(K)                                                                                                   \
+    do {                                                                                                                \
+        if (prep.blocks > 0)                                                                                            \
+            cx.run(bn_bwd_fused_prep_k<K>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats,   \
+                   inv_m, dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep);     \
+        else                                                                                                            \
+            cx.run(bn_bwd_fused_k<K>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats, inv_m, \
+                   dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, out16, red, merge);           \
+    } while (0)
+            if (skip) RVN_LAUNCH(true);
+            else RVN_LAUNCH(false);
+#undef RVN_LAUNCH
+        }
+        return;
+    }
     if (cx.launch(K_BN_BWD_REDUCE, 2.0 * t)) {
         dim3 grid(S, c);
         const double inv_m = 1.0 / (double)g.pixels();
@@ -522,10 +687,6 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
             cx.run(bn_bwd_reduce_k<true>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, div_magic(ipw, g.hw() / 4), stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
         else
             cx.run(bn_bwd_reduce_k<false>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), ipw, div_magic(ipw, g.hw()), stats, scratch, counters, inv_m, dgamma, dbeta, accumulate ? 1 : 0, coef);
-    }
-    if (out16 && (skip || !vec_in || cx.carry_now)) {  // a caller's mistake: nothing sensible to launch
-        cx.fail(hipErrorInvalidValue);
-        return;
     }
     if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : out16 ? 2.5 : 3.0) * t)) {
         const bool vec = vec_in && (out16 || vec_ok(out, g.hw())) && (!skip || vec_ok(*skip, g.hw()));
