@@ -11,9 +11,10 @@
 // What this kernel adds to that scheme:
 //  * register tiling: a wavefront owns MTW x NTW tiles of 32 x 32 results, so
 //    an LDS read feeds NTW (filter) or MTW (activation) matrix instructions;
-//  * software pipelining: the global loads of channel chunk i+1 (activations as
-//    fp32, filter as prepared bf16) are issued before the matrix instructions
-//    of chunk i and are converted and written to LDS after them;
+//  * software pipelining: the global loads of the next channel chunk (the next
+//    two, where a thread holds one staging item; activations as fp32, filter as
+//    prepared bf16) are issued before the matrix instructions of chunk i and
+//    are converted and written to LDS after them;
 //  * staging by linear quads: an item is 4 consecutive pixels of the band's
 //    contiguous range in the image plane, times 8 channels, so the loads are
 //    16 bytes whatever the image width; BN scale/shift, ReLU and the bf16
@@ -21,7 +22,10 @@
 //  * optional split of the input channels over gridDim.z: partial tiles go to
 //    scratch and a second kernel sums them in a fixed order and applies the
 //    coupling y = r + conv / reconstruction x = r - conv of Section 3.1
-//    (otherwise that is done in the accumulator registers here).
+//    (otherwise that is done in the accumulator registers here);
+//  * an epilogue through buffer resources (scalar channel offsets, one uniform
+//    bound check), and workgroup ids remapped so that a die gets a contiguous
+//    range of bands (neighbouring bands share input rows).
 #include <algorithm>
 
 #include "conv3x3_bf16_body.h"

@@ -6,9 +6,15 @@
 // workgroup slots), and each pays its own launch and its own ramp; one launch
 // holds the workgroups of both, filter gradient first (it has the longer
 // dependent chain), so that the two run side by side on the same compute units
-// and the load phases of one overlap the matrix phases of the other.  The
-// bodies are the ones of the separate kernels, unchanged: results are bit for
-// bit those of two launches.
+// and the load phases of one overlap the matrix phases of the other (which also
+// pays at the large layers: the workgroups of a launch otherwise run in step).
+// The bodies are the ones of the separate kernels, unchanged: results are bit
+// for bit those of two launches.
+//
+// DH16 variants: the upstream gradient arrives as bf16 -- the BN backward of the
+// layer above wrote it rounded, since both bodies here would round it on load
+// anyway -- and is moved to the operand layouts with byte permutes.  Same bits,
+// half the bytes of that tensor.
 #include <algorithm>
 
 #include "conv1x1_bf16_body.h"
