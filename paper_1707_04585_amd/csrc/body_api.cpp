@@ -173,15 +173,6 @@ DownBufs bind(const DownPlan &p, void *ws, bool backward) {
     return o;
 }
 
-// One filter to bf16, in the order the convolutions at geometry g read it.
-void prep_one(Ctx &cx, const float *w, int cin, int cout, int ks, const Geo &g, uint16_t *qf, uint16_t *qb) {
-    if (!qf && !qb) return;
-    const FilterPrep fp{w, cin, cout, ks, qf, qb};
-    double bytes = 0.0;
-    const PrepArgs pa = plan_filter_prep(&fp, 1, g, &bytes);
-    prep_filters_bf16(cx, pa, bytes);
-}
-
 // With recompute_only the internals (statistics, h_l, subsampled x) are left
 // in `b` for down_backward and y is not formed.
 void down_forward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const DownBufs &b, View x,
@@ -189,9 +180,24 @@ void down_forward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const Dow
     clear_counters(cx, b.counters, pl.n_counters);
     cx.emit_buf = nullptr;  // the statistics of this block's tensors are always read from the tensors
     cx.emit_floats = 0;
-    for (int l = 0; l < pl.L; ++l)
-        prep_one(cx, p.R.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, pl.gin[l], b.wq_f[l], b.wq_b[l]);
-    prep_one(cx, p.shortcut_w, d.c_in, d.c_out, 1, pl.low, b.wq_f[kShortcut], b.wq_b[kShortcut]);
+    // bf16 filters: one conversion launch per geometry (the order a 1x1 filter is stored in depends on
+    // the geometry its layer runs at): the layers before and including the strided one, then the rest
+    // and the shortcut.
+    for (int pass = 0; pass < 2; ++pass) {
+        FilterPrep fp[3];
+        int nf = 0;
+        const Geo &gp = pass == 0 ? pl.full : pl.low;
+        for (int l = 0; l < pl.L; ++l) {
+            const bool at_full = pl.gin[l].h == pl.full.h;
+            if (at_full == (pass == 0))
+                fp[nf++] = FilterPrep{p.R.conv_w[l], pl.layers[l].cin, pl.layers[l].cout, pl.layers[l].ks, b.wq_f[l], b.wq_b[l]};
+        }
+        if (pass == 1) fp[nf++] = FilterPrep{p.shortcut_w, d.c_in, d.c_out, 1, b.wq_f[kShortcut], b.wq_b[kShortcut]};
+        if (nf == 0 || !pl.bf16) continue;
+        double bytes = 0.0;
+        const PrepArgs pa = plan_filter_prep(fp, nf, gp, &bytes);
+        prep_filters_bf16(cx, pa, bytes);
+    }
     View cur = x;
     for (int l = 0; l < pl.L; ++l) {
         const DownLayer &ly = pl.layers[l];
