@@ -91,6 +91,7 @@ DownPlan make_down_plan(const rvn_down_desc &d, const Geo &full, bool backward) 
         if (backward) wg_s = std::max(wg_s, wgrad_scratch_floats(cin, cout, ks, g));
         if (!p.bf16) return;
         cv_s = std::max(cv_s, conv_bf16_scratch_floats(cin, cout, ks, g));
+        if (ks == 3) cv_s = std::max(cv_s, conv3x3_bf16_scratch_floats(cin, cout, g, 2));  // (the strided layer's forward)
         p.wq_f[slot] = off;
         off = align_up(off + filter_bf16_elems(cout, cin, ks) * 2);
         if (backward) {
@@ -216,6 +217,10 @@ void down_forward(Ctx &cx, const rvn_down_desc &d, const DownPlan &pl, const Dow
             if (!recompute_only)
                 conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.R.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_ADD, &y,
                          y, b.conv_scratch);
+        } else if (ly.strided && ly.ks == 3 && d.conv_dtype == RVN_BF16 &&
+                   conv3x3_bf16_stride2(cx, cur, scale_shift, b.wq_f[l], ly.cin, ly.cout, g, dense_view(b.h[l], ly.cout, pl.low),
+                                        b.conv_scratch)) {
+            cur = dense_view(b.h[l], ly.cout, pl.low);  // only the outputs that exist were computed
         } else if (ly.strided) {
             const View hf = dense_view(b.hfull, ly.cout, pl.full);
             conv_fwd(cx, cur, scale_shift, d.conv_dtype, p.R.conv_w[l], b.wq_f[l], ly.cin, ly.cout, ly.ks, g, EP_STORE,

@@ -90,10 +90,12 @@ struct C3Plan {
     bool ok;
 };
 
-C3Plan plan_c3(int ci, int co, const Geo &g) {
+C3Plan plan_c3(int ci, int co, const Geo &g, int stride = 1) {
     C3Plan pl{};
     pl.ok = false;
     if (ci % 8 != 0 || g.w < 4 || ci > 4096) return pl;
+    if (stride != 1 && (stride != 2 || g.h % 2 || g.w % 2)) return pl;
+    const int oh = g.h / stride, ow = g.w / stride;  // the result's rows and columns
     // Output channels per workgroup and the wavefront arrangement.
     // 64 output channels per workgroup at most, the four wavefronts side by side along the pixels: with
     // 128 channels (two wavefronts stacked) the wide layers were 5-10 % slower (twice the filter tile per
@@ -107,16 +109,16 @@ C3Plan plan_c3(int ci, int co, const Geo &g) {
     // Pixel block: the fullest block of whole rows (or whole images) that fits.
     double best = -1.0;
     for (int imgs = 1; imgs <= 16 && imgs <= g.n; ++imgs) {
-        for (int tr = imgs > 1 ? g.h : 1; tr <= g.h; ++tr) {
-            const int npix = imgs * tr * g.w;
+        for (int tr = imgs > 1 ? oh : 1; tr <= oh; ++tr) {
+            const int npix = imgs * tr * ow;
             if (npix > slots) break;
-            const int lrows = tr + 2, lcols = g.w + 2;
-            const int q = ((tr + 2) * g.w + 3) / 4;
+            const int lrows = stride * (tr - 1) + 3, lcols = g.w + 2;
+            const int q = (lrows * g.w + 3) / 4;
             const int items = imgs * q * octs;
             const size_t bytes = ((size_t)imgs * lrows * lcols + (size_t)ch * 9) * rec * 2 + (size_t)ci * 8;
             if (items > kInItems * kThreads || bytes > 76 * 1024) break;
-            const int bands = (g.h + tr - 1) / tr, groups = (g.n + imgs - 1) / imgs;
-            const double useful = (double)g.n * g.h * g.w, issued = (double)groups * bands * slots;
+            const int bands = (oh + tr - 1) / tr, groups = (g.n + imgs - 1) / imgs;
+            const double useful = (double)g.n * oh * ow, issued = (double)groups * bands * slots;
             const double score = useful / issued;
             if (score > best) {
                 best = score;
@@ -176,21 +178,22 @@ void launch_c3(Ctx &cx, const C3Launch &L, dim3 grid) {
 
 bool conv3x3_bf16_ok(int ci, int co, const Geo &g) { return plan_c3(ci, co, g).ok; }
 
-size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g) {
-    const C3Plan pl = plan_c3(ci, co, g);
-    return pl.ok && pl.S > 1 ? (size_t)pl.S * g.n * co * g.h * g.w : 0;
+size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g, int stride) {
+    const C3Plan pl = plan_c3(ci, co, g, stride);
+    return pl.ok && pl.S > 1 ? (size_t)pl.S * g.n * co * (g.h / stride) * (g.w / stride) : 0;
 }
 
 bool conv3x3_bf16_plan(View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g, Epilogue ep,
-                       const View *r, View out, float *scratch, C3Launch &L) {
+                       const View *r, View out, float *scratch, C3Launch &L, int stride) {
     if (!wq) return false;
-    const C3Plan pl = plan_c3(ci, co, g);
+    const C3Plan pl = plan_c3(ci, co, g, stride);
+    const int oh = g.h / stride, ow = g.w / stride;  // `out`, `r` and the partial tiles have the result's geometry
     if (!pl.ok || (pl.S > 1 && !scratch)) return false;
     if (pl.WM != 1 || pl.NTW != 2 || (pl.MTW != 1 && pl.MTW != 2) || (pl.KC != 16 && pl.KC != 32)) return false;
     // lane offsets into `in`, `out`, `r` and the partial tiles are 32-bit byte offsets
     const int64_t lim = (int64_t)1 << 32;
     if (((int64_t)g.n * in.sn + (int64_t)ci * in.sc) * 4 >= lim || ((int64_t)g.n * out.sn + (int64_t)co * out.sc) * 4 >= lim ||
-        (r && ((int64_t)g.n * r->sn + (int64_t)co * r->sc) * 4 >= lim) || (int64_t)g.n * co * g.h * g.w * 4 >= lim)
+        (r && ((int64_t)g.n * r->sn + (int64_t)co * r->sc) * 4 >= lim) || (int64_t)g.n * co * oh * ow * 4 >= lim)
         return false;
     C3Args a{};
     a.in = in.p; a.isn = in.sn; a.isc = in.sc;
@@ -199,11 +202,12 @@ bool conv3x3_bf16_plan(View in, const float *scale_shift, const uint16_t *wq, in
     a.r = r ? r->p : nullptr; a.rsn = r ? r->sn : 0; a.rsc = r ? r->sc : 0;
     a.out = out.p; a.osn = out.sn; a.osc = out.sc;
     a.N = g.n; a.H = g.h; a.W = g.w; a.CI = ci; a.CO = co; a.ep = (int)ep;
+    a.stride = stride;
     a.TR = pl.TR; a.IMGS = pl.IMGS; a.bands = pl.bands;
-    a.pix_per_img = pl.TR * g.w; a.n_pix = pl.IMGS * pl.TR * g.w;
+    a.pix_per_img = pl.TR * ow; a.n_pix = pl.IMGS * pl.TR * ow;
     a.lrows = pl.lrows; a.lcols = pl.lcols; a.q_per_img = pl.q_per_img; a.in_items = pl.in_items;
     a.chunks = pl.chunks; a.cps = pl.cps;
-    a.part = scratch; a.part_stride = (int64_t)g.n * co * g.h * g.w;
+    a.part = scratch; a.part_stride = (int64_t)g.n * co * oh * ow;
     const int ch = pl.WM * pl.MTW * 32;
     L.a = a;
     L.MTW = pl.MTW; L.KC = pl.KC; L.S = pl.S;
@@ -259,6 +263,30 @@ bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq
     else if (L.MTW == 2 && L.KC == 16) launch_c3<1, 2, 2, 16>(cx, L, L.grid);
     else launch_c3<1, 2, 2, 32>(cx, L, L.grid);
     conv3x3_bf16_finish(cx, L, g);
+    return true;
+}
+
+// The same convolution with stride 2 (even h and w, zero padding 1): only the rows and columns of the
+// result that exist are computed -- the pixel block of a workgroup is a block of the result, its input band
+// twice as tall plus one row, and a result's operand records sit two rows and two columns apart.  `out`
+// is [n][co][h/2][w/2]; no epilogue coupling, no epilogue statistics.
+bool conv3x3_bf16_stride2(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g, View out,
+                          float *scratch) {
+    C3Launch L;
+    if (!conv3x3_bf16_plan(in, scale_shift, wq, ci, co, g, EP_STORE, nullptr, out, scratch, L, 2)) return false;
+    const Geo low{g.n, g.h / 2, g.w / 2};
+    const double P = (double)low.pixels();
+    const double flops = 2.0 * P * ci * co * 9;
+    cx.cost.conv_fwd_calls += 1;
+    cx.cost.conv_flops += flops;
+    cx.emitted = EmittedStats{};
+    if (cx.launch(K_CONV_FWD, (double)g.pixels() * ci * 4.0 + P * co * 4.0, flops)) {
+        if (L.MTW == 1 && L.KC == 16) launch_c3<1, 1, 2, 16>(cx, L, L.grid);
+        else if (L.MTW == 1 && L.KC == 32) launch_c3<1, 1, 2, 32>(cx, L, L.grid);
+        else if (L.MTW == 2 && L.KC == 16) launch_c3<1, 2, 2, 16>(cx, L, L.grid);
+        else launch_c3<1, 2, 2, 32>(cx, L, L.grid);
+    }
+    conv3x3_bf16_finish(cx, L, low);
     return true;
 }
 

@@ -21,6 +21,7 @@ struct C3Args {
     float *out;
     int64_t osn, osc;
     int N, H, W, CI, CO, ep;
+    int stride;           // 1, or 2 (H and W even): only every second row and column of the result exists, OH = H / 2, OW = W / 2
     int TR, IMGS, bands;  // rows and images per pixel block, blocks per image column
     int pix_per_img;      // TR * W
     int n_pix;            // IMGS * TR * W
@@ -51,8 +52,9 @@ struct C3Launch {
 // Tiling and arguments of a 3x3 convolution without epilogue statistics; false if the kernel does not
 // take the layer.  Defined in conv3x3_bf16.hip.
 bool conv3x3_bf16_plan(View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g, Epilogue ep,
-                       const View *r, View out, float *scratch, C3Launch &L);
-// The launch that sums the partial tiles of a split convolution (nothing to do when L.S == 1).
+                       const View *r, View out, float *scratch, C3Launch &L, int stride = 1);
+// The launch that sums the partial tiles of a split convolution (nothing to do when L.S == 1); g: the
+// geometry of the result.
 void conv3x3_bf16_finish(Ctx &cx, const C3Launch &L, Geo g);
 
 namespace {
@@ -113,7 +115,8 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
     const int bx = p.bands > 1 ? (bx_launch & 7) * (p.wg_x8 >> 3) + (bx_launch >> 3) : bx_launch;
     if (bx >= p.wg_x) return;
     const int band = bx % p.bands, img_grp = bx / p.bands;
-    const int n0 = img_grp * p.IMGS, row0 = band * p.TR;
+    const int n0 = img_grp * p.IMGS, row0 = band * p.TR;  // (row0, TR, bands: rows of the result)
+    const int st = p.stride, OH = p.H / st, OW = p.W / st;
     const int co0 = by * CH;
     const int N = p.N, H = p.H, W = p.W, CI = p.CI, CO = p.CO;
     const int l32 = lane & 31, kg = lane >> 5;
@@ -130,7 +133,8 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
     }
 
     // ---- this thread's activation items: (image, quad of the band's pixel range, channel octet)
-    const int start_row = max(0, row0 - 1), end_row = min(H, row0 + p.TR + 1);
+    const int in_row0 = st * row0 - 1;  // the input row of the tile's first row
+    const int start_row = max(0, in_row0), end_row = min(H, st * (row0 + p.TR - 1) + 2);
     const int range = (end_row - start_row) * W;  // contiguous pixels of the plane this block reads
     uint32_t it_off[NI];                          // byte offset of (image, pixel) in a plane (dead items: 0)
     int it_rec[NI], it_info[NI];                  // LDS record of pixel 0; col | nvalid << 16 | oc << 24
@@ -146,7 +150,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
         const int ld = min(start, range - 4);
         const int lin = start_row * W + ld, row = lin / W, col = lin - row * W;
         it_off[i] = live ? (uint32_t)(((int64_t)n * p.isn + start_row * W + ld) * kInBytes) : 0u;
-        it_rec[i] = (img * p.lrows + (row - (row0 - 1))) * p.lcols + 1 + col;
+        it_rec[i] = (img * p.lrows + (row - in_row0)) * p.lcols + 1 + col;
         const int nvalid = live ? 4 : 0;
         it_info[i] = col | (nvalid << 16) | (oc << 24);
     }
@@ -157,11 +161,11 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
     for (int t = 0; t < NTW; ++t) {
         const int f = (wn * NTW + t) * 32 + l32;
         const int img = f / p.pix_per_img, rem = f - img * p.pix_per_img;
-        const int rr = rem / W, cc = rem - rr * W;
-        const bool ok = f < p.n_pix && n0 + img < N && row0 + rr < H;
-        b_rec[t] = f < p.n_pix ? (img * p.lrows + rr) * p.lcols + cc : 0;
+        const int rr = rem / OW, cc = rem - rr * OW;
+        const bool ok = f < p.n_pix && n0 + img < N && row0 + rr < OH;
+        b_rec[t] = f < p.n_pix ? (img * p.lrows + st * rr) * p.lcols + st * cc : 0;
         o_img[t] = ok ? n0 + img : -1;
-        o_pix[t] = (row0 + rr) * W + cc;
+        o_pix[t] = (row0 + rr) * OW + cc;
     }
 
     float16_t acc[MTW][NTW];
@@ -327,7 +331,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
     //      registers; the host keeps every tensor handed to one launch below 4 GB.  With a 64-bit address
     //      per lane and access, address arithmetic was half of the kernel's vector instructions.
     const bool partial = gz > 1;
-    const uint32_t HW4 = (uint32_t)(H * W) * 4u;
+    const uint32_t HW4 = (uint32_t)(OH * OW) * 4u;
     const uint32_t osc4 = (uint32_t)p.osc * 4u, rsc4 = (uint32_t)p.rsc * 4u;
     const __amdgpu_buffer_rsrc_t out_rs = partial ? buffer_over(p.part + bz * p.part_stride, (uint32_t)p.part_stride * 4u)
                                                   : buffer_over(p.out, 0xfffffffcu);
@@ -339,7 +343,7 @@ __device__ __forceinline__ void conv3x3_bf16_body(const C3Args &p, int bx_launch
 #pragma unroll
     for (int t = 0; t < NTW; ++t) {
         if (o_img[t] < 0) continue;
-        const uint32_t o_off = partial ? (uint32_t)((((int64_t)o_img[t] * CO + 4 * kg) * (H * W) + o_pix[t]) * 4)
+        const uint32_t o_off = partial ? (uint32_t)((((int64_t)o_img[t] * CO + 4 * kg) * (OH * OW) + o_pix[t]) * 4)
                                        : (uint32_t)(((int64_t)o_img[t] * p.osn + o_pix[t] + (int64_t)(4 * kg) * p.osc) * 4);
         const uint32_t r_off = (uint32_t)(((int64_t)o_img[t] * p.rsn + o_pix[t] + (int64_t)(4 * kg) * p.rsc) * 4);
 #pragma unroll

@@ -245,7 +245,11 @@ size_t conv_bf16_scratch_floats(int ci, int co, int ks, const Geo &g);
 // Needs the filter prepared as [co][9][ci padded to 8]; returns false (nothing
 // launched) when conv3x3_bf16_ok(ci, co, g) does not hold.
 bool conv3x3_bf16_ok(int ci, int co, const Geo &g);
-size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g);
+size_t conv3x3_bf16_scratch_floats(int ci, int co, const Geo &g, int stride = 1);
+// The 3x3 convolution with stride 2 (g: the input's geometry, h and w even; out: [n][co][h/2][w/2], store only),
+// accounted as a forward convolution; false (nothing launched, nothing accounted) if the kernel does not take it.
+bool conv3x3_bf16_stride2(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g, View out,
+                          float *scratch);
 bool conv3x3_bf16(Ctx &cx, View in, const float *scale_shift, const uint16_t *wq, int ci, int co, Geo g,
                   Epilogue ep, const View *r, View out, float *scratch);
 
