@@ -53,6 +53,12 @@ DOWN_CASES = [
     ("basic", 8, 32, 64, 32, 32),        # the first subsampling block of the three-stage basic body
     ("bottleneck", 2, 64, 128, 28, 28),
     ("bottleneck", 4, 48, 40, 10, 6),     # ragged: half resolution 5x3, inner width 10
+    # shapes the stride-2 3x3 kernel of the bf16 path takes (input channels a multiple of 8) with ragged geometry:
+    # rows that are not whole 4-pixel groups, several bands per image with a short last one, odd half resolution
+    ("basic", 3, 16, 24, 12, 10),
+    ("bottleneck", 5, 64, 96, 20, 12),    # inner width 24
+    ("basic", 2, 40, 72, 36, 44),         # several bands per image
+    ("bottleneck", 3, 32, 64, 18, 14),    # inner width 16, half resolution 9x7
     # the other subsampling blocks of the two multi-stage workloads, at their real shapes
     ("basic", 8, 64, 112, 16, 16),
     ("bottleneck", 2, 256, 512, 56, 56),
