@@ -45,6 +45,7 @@ struct WgPlan {
     size_t lds_bytes;
     int tiles_ko, tiles_c, part_stride;
     bool ok;
+    Geo g;  // the geometry the plan is for (see wg_geometry)
 };
 
 uint32_t fdiv_magic(int d) { return d == 1 ? 0u : (uint32_t)((1ull << 32) / (uint64_t)d + 1ull); }
@@ -116,11 +117,30 @@ WgPlan plan_wg_tiles(int cin, int cout, int ks, const Geo &g, int ct_max) {
 // tile groups of a slice share in their die's L2.  Measured at the 56x56 bottleneck stack: step 15.98 ->
 // 15.82 ms, the four-stage body 14.81 -> 14.50; 32 x 32, 32 x 64 and any split of the 1x1 layers were
 // slower, and so was the split on the small layers whose slices are limited by their units.
-WgPlan plan_wg(int cin, int cout, int ks, const Geo &g) {
-    const WgPlan w = plan_wg_tiles(cin, cout, ks, g, 2);
+// A 1x1 filter's gradient has no spatial structure: where the rows are not whole 4-pixel groups but the
+// planes are (14x14), an image is taken as one row of h*w pixels, which puts the layer on the aligned
+// staging path (16-byte loads, whole-unit prefetch, bf16 upstream gradient).
+Geo wg_geometry(int ks, const Geo &g) {
+    if (ks == 1 && (g.w & 3) != 0 && ((int64_t)g.h * g.w) % 4 == 0 && (int64_t)g.h * g.w <= 512) return Geo{g.n, 1, g.h * g.w};
+    return g;
+}
+
+WgPlan plan_wg_for(int cin, int cout, int ks, const Geo &g) {
+    WgPlan w = plan_wg_tiles(cin, cout, ks, g, 2);
+    w.g = g;
     if (!w.ok || ks != 3 || w.CT != 2 || w.units <= 512 / (w.tiles_ko * w.tiles_c)) return w;
-    const WgPlan n = plan_wg_tiles(cin, cout, ks, g, 1);
+    WgPlan n = plan_wg_tiles(cin, cout, ks, g, 1);
+    n.g = g;
     return n.ok ? n : w;
+}
+
+WgPlan plan_wg(int cin, int cout, int ks, const Geo &g_layer) {
+    const Geo flat = wg_geometry(ks, g_layer);
+    if (flat.h != g_layer.h) {
+        const WgPlan w = plan_wg_for(cin, cout, ks, flat);
+        if (w.ok) return w;  // (else the one-row image does not fit a unit: the layer's own rows)
+    }
+    return plan_wg_for(cin, cout, ks, g_layer);
 }
 
 }  // namespace
@@ -130,9 +150,10 @@ size_t wgrad_bf16_scratch_floats(int cin, int cout, int ks, const Geo &g) {
     return w.ok ? (size_t)w.S * w.part_stride : 0;
 }
 
-bool conv_wgrad_bf16_plan(View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g, float *scratch,
+bool conv_wgrad_bf16_plan(View x, const float *scale_shift, View dh, int cin, int cout, int ks, Geo g_layer, float *scratch,
                           float *dw, bool accumulate, WgLaunch &L) {
-    const WgPlan w = plan_wg(cin, cout, ks, g);
+    const WgPlan w = plan_wg(cin, cout, ks, g_layer);
+    const Geo g = w.g;
     if (!w.ok) return false;
     // a lane's item offsets (image, row, column within a channel plane of a unit) are 32-bit
     if ((int64_t)w.IMGS * std::max(x.sn, dh.sn) + (int64_t)(w.lrows + 1) * g.w >= ((int64_t)1 << 30)) return false;
