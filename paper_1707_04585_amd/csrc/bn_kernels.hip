@@ -454,7 +454,9 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_prep_k(
 // 32 channels of 16x16 x 128: one workgroup per channel is then too little parallelism.)
 constexpr int kFusedQuads = 8;
 
-template <bool SKIP, bool PREP>
+// VEC: aligned planes of whole 4-pixel quads (16-byte accesses); otherwise element by element (7x7 planes;
+// channels of at most 2048 elements then: with 32 items per thread the launch was slower than two).
+template <bool SKIP, bool PREP, bool VEC>
 __device__ __forceinline__ void bn_bwd_fused_body(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
     const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
@@ -478,35 +480,43 @@ __device__ __forceinline__ void bn_bwd_fused_body(
         return;
     }
     __shared__ double sums[8];
+    constexpr int E = VEC ? 4 : 1, K = kFusedQuads;  // elements per item, items per thread
     const int ch = bx - carry.blocks;
-    const int per = HW / 4, total = N * per;
+    const int per = HW / E, total = N * per;
     const float mean = stats[ch], rstd = stats[C + ch];
     const float scale = stats[2 * C + ch], shift = stats[3 * C + ch];
-    float4 xv[kFusedQuads], dv[kFusedQuads];
-    int nn[kFusedQuads], ii[kFusedQuads];  // image and first pixel of the quad
-    bool ok[kFusedQuads];
+    float xs[K][E], ds[K][E];
+    int nn[K], ii[K];  // image and first pixel of the item
+    bool ok[K];
 #pragma unroll
-    for (int k = 0; k < kFusedQuads; ++k) {
+    for (int k = 0; k < K; ++k) {
         const int q = (int)threadIdx.x + k * kThreads;
         ok[k] = q < total;
         const int qc = ok[k] ? q : 0;
         nn[k] = idiv(qc, per, m_per);
-        ii[k] = (qc - nn[k] * per) * 4;
-        xv[k] = *reinterpret_cast<const float4 *>(x + (int64_t)nn[k] * sn + (int64_t)ch * sc + ii[k]);
-        dv[k] = *reinterpret_cast<const float4 *>(da + ((int64_t)nn[k] * C + ch) * HW + ii[k]);
+        ii[k] = (qc - nn[k] * per) * E;
+        const float *px = x + (int64_t)nn[k] * sn + (int64_t)ch * sc + ii[k];
+        const float *pd = da + ((int64_t)nn[k] * C + ch) * HW + ii[k];
+        if constexpr (VEC) {
+            const float4 xv = *reinterpret_cast<const float4 *>(px), dv = *reinterpret_cast<const float4 *>(pd);
+            xs[k][0] = xv.x; xs[k][1] = xv.y; xs[k][2] = xv.z; xs[k][3] = xv.w;
+            ds[k][0] = dv.x; ds[k][1] = dv.y; ds[k][2] = dv.z; ds[k][3] = dv.w;
+        } else {
+            xs[k][0] = *px;
+            ds[k][0] = *pd;
+        }
     }
-    float dy[kFusedQuads][4], xh[kFusedQuads][4];
     float a0 = 0.f, a1 = 0.f;
 #pragma unroll
-    for (int k = 0; k < kFusedQuads; ++k) {
-        const float xs[4] = {xv[k].x, xv[k].y, xv[k].z, xv[k].w};
-        const float ds[4] = {dv[k].x, dv[k].y, dv[k].z, dv[k].w};
+    for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            dy[k][j] = ok[k] && fmaf(xs[j], scale, shift) > 0.f ? ds[j] : 0.f;
-            xh[k][j] = (xs[j] - mean) * rstd;
-            a0 += dy[k][j];
-            a1 += dy[k][j] * xh[k][j];
+        for (int j = 0; j < E; ++j) {
+            const float dyv = ok[k] && fmaf(xs[k][j], scale, shift) > 0.f ? ds[k][j] : 0.f;
+            const float xhv = (xs[k][j] - mean) * rstd;
+            ds[k][j] = dyv;  // from here on: dy and xhat
+            xs[k][j] = xhv;
+            a0 += dyv;
+            a1 += dyv * xhv;
         }
     }
     a0 = wave_sum(a0);
@@ -529,47 +539,52 @@ __device__ __forceinline__ void bn_bwd_fused_body(
     }
     const float c1 = (float)(sb * inv_m), c2 = (float)(sg * inv_m);
 #pragma unroll
-    for (int k = 0; k < kFusedQuads; ++k) {
+    for (int k = 0; k < K; ++k) {
         if (!ok[k]) continue;
-        float r[4];
+        float r[E];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) r[j] = scale * ((dy[k][j] - c1) - xh[k][j] * c2);
+        for (int j = 0; j < E; ++j) r[j] = scale * ((ds[k][j] - c1) - xs[k][j] * c2);
         const int n = nn[k], i = ii[k];
-        if (SKIP) {
-            const float4 kv = *reinterpret_cast<const float4 *>(skip + (int64_t)n * ksn + (int64_t)ch * ksc + i);
-            r[0] += kv.x; r[1] += kv.y; r[2] += kv.z; r[3] += kv.w;
-            *reinterpret_cast<float4 *>(out + (int64_t)n * osn + (int64_t)ch * osc + i) = make_float4(r[0], r[1], r[2], r[3]);
-        } else if (out16) {  // (uniform) dense bf16, nearest even
-            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-            typedef float float2_t __attribute__((ext_vector_type(2)));
-            const float2_t lo = {r[0], r[1]}, hi = {r[2], r[3]};
-            const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
-            *reinterpret_cast<uint2 *>(out16 + ((int64_t)n * C + ch) * HW + i) =
-                make_uint2(*reinterpret_cast<const uint32_t *>(&blo), *reinterpret_cast<const uint32_t *>(&bhi));
+        float *po = out + (int64_t)n * osn + (int64_t)ch * osc + i;
+        if constexpr (VEC) {
+            if (SKIP) {
+                const float4 kv = *reinterpret_cast<const float4 *>(skip + (int64_t)n * ksn + (int64_t)ch * ksc + i);
+                r[0] += kv.x; r[1] += kv.y; r[2] += kv.z; r[3] += kv.w;
+                *reinterpret_cast<float4 *>(po) = make_float4(r[0], r[1], r[2], r[3]);
+            } else if (out16) {  // (uniform) dense bf16, nearest even
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                typedef float float2_t __attribute__((ext_vector_type(2)));
+                const float2_t lo = {r[0], r[1]}, hi = {r[2], r[3]};
+                const bf16x2_t blo = __builtin_convertvector(lo, bf16x2_t), bhi = __builtin_convertvector(hi, bf16x2_t);
+                *reinterpret_cast<uint2 *>(out16 + ((int64_t)n * C + ch) * HW + i) =
+                    make_uint2(*reinterpret_cast<const uint32_t *>(&blo), *reinterpret_cast<const uint32_t *>(&bhi));
+            } else {
+                *reinterpret_cast<float4 *>(po) = make_float4(r[0], r[1], r[2], r[3]);
+            }
         } else {
-            *reinterpret_cast<float4 *>(out + (int64_t)n * osn + (int64_t)ch * osc + i) = make_float4(r[0], r[1], r[2], r[3]);
+            *po = SKIP ? skip[(int64_t)n * ksn + (int64_t)ch * ksc + i] + r[0] : r[0];
         }
     }
 }
 
-template <bool SKIP>
+template <bool SKIP, bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_fused_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
     const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
     int accumulate, const float *skip, int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc, uint16_t *out16,
     const WgradReduce carry, const StatsMerge merge) {
-    bn_bwd_fused_body<SKIP, false>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn, ksc,
-                                   out, osn, osc, out16, carry, merge, PrepArgs{});
+    bn_bwd_fused_body<SKIP, false, VEC>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn,
+                                        ksc, out, osn, osc, out16, carry, merge, PrepArgs{});
 }
 
-template <bool SKIP>
+template <bool SKIP, bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_fused_prep_k(
     const float *__restrict__ x, int64_t sn, int64_t sc, const float *da, int N, int C, int HW, uint32_t m_per,
     const float *__restrict__ stats, double inv_m, float *__restrict__ dgamma, float *__restrict__ dbeta,
     int accumulate, const float *skip, int64_t ksn, int64_t ksc, float *out, int64_t osn, int64_t osc,
     const WgradReduce carry, const StatsMerge merge, const PrepArgs prep) {
-    bn_bwd_fused_body<SKIP, true>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn, ksc,
-                                  out, osn, osc, nullptr, carry, merge, prep);
+    bn_bwd_fused_body<SKIP, true, VEC>(x, sn, sc, da, N, C, HW, m_per, stats, inv_m, dgamma, dbeta, accumulate, skip, ksn, ksc,
+                                       out, osn, osc, nullptr, carry, merge, prep);
 }
 
 __global__ void clear_counters_k(int *p, int n) {
@@ -649,7 +664,8 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
     }
     // Small channels: both passes in one launch.
     const bool vec_all = vec_in && (out16 || vec_ok(out, g.hw())) && (!skip || vec_ok(*skip, g.hw()));
-    if (vec_all && (int64_t)g.n * (g.hw() / 4) <= (int64_t)kFusedQuads * kThreads) {
+    const int64_t items = vec_all ? (int64_t)g.n * (g.hw() / 4) : (int64_t)g.n * g.hw();
+    if (items <= (int64_t)kFusedQuads * kThreads) {
         if (cx.launch(K_BN_BWD_APPLY, (skip ? 4.0 : out16 ? 2.5 : 3.0) * t)) {
             WgradReduce red{};
             if (carry) red = *carry;
@@ -665,20 +681,22 @@ void bn_relu_bwd(Ctx &cx, View x, const float *da, int c, Geo g, const float *st
             }
             const dim3 grid((unsigned)(c + red.blocks + merge.blocks + prep.blocks));
             const double inv_m = 1.0 / (double)g.pixels();
-            const uint32_t m_per = div_magic(g.n, g.hw() / 4);
+            const uint32_t m_per = div_magic(g.n, vec_all ? g.hw() / 4 : g.hw());
             const float *kp = skip ? skip->p : nullptr;
             const int64_t ksn = skip ? skip->sn : 0, ksc = skip ? skip->sc : 0;
-#define RVN_LAUNCH(K)                                                                                                   \
-    do {                                                                                                                \
-        if (prep.blocks > 0)                                                                                            \
-            cx.run(bn_bwd_fused_prep_k<K>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats,   \
-                   inv_m, dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep);     \
-        else                                                                                                            \
-            cx.run(bn_bwd_fused_k<K>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats, inv_m, \
-                   dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, out16, red, merge);           \
+#define RVN_LAUNCH(K, V)                                                                                                 \
+    do {                                                                                                                 \
+        if (prep.blocks > 0)                                                                                             \
+            cx.run(bn_bwd_fused_prep_k<K, V>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats, \
+                   inv_m, dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, red, merge, prep);      \
+        else                                                                                                             \
+            cx.run(bn_bwd_fused_k<K, V>, grid, dim3(kThreads), 0, x.p, x.sn, x.sc, da, g.n, c, g.hw(), m_per, stats,      \
+                   inv_m, dgamma, dbeta, accumulate ? 1 : 0, kp, ksn, ksc, out.p, out.sn, out.sc, out16, red, merge);     \
     } while (0)
-            if (skip) RVN_LAUNCH(true);
-            else RVN_LAUNCH(false);
+            if (skip && vec_all) RVN_LAUNCH(true, true);
+            else if (skip) RVN_LAUNCH(true, false);
+            else if (vec_all) RVN_LAUNCH(false, true);
+            else RVN_LAUNCH(false, false);
 #undef RVN_LAUNCH
         }
         return;
