@@ -9,7 +9,9 @@
 // and the load phases of one overlap the matrix phases of the other (which also
 // pays at the large layers: the workgroups of a launch otherwise run in step).
 // The bodies are the ones of the separate kernels, unchanged: results are bit
-// for bit those of two launches.
+// for bit those of two launches.  (Order measured at the 56x56 bottleneck stack:
+// filter gradient first 65.4 us per launch, convolution first 72.2, alternating
+// groups of eight 88.3.)
 //
 // DH16 variants: the upstream gradient arrives as bf16 -- the BN backward of the
 // layer above wrote it rounded, since both bodies here would round it on load
